@@ -1,0 +1,14 @@
+"""CPU oracle for the direct-convolution forward pass.
+
+TEST INFRASTRUCTURE ONLY: imported by tests, the smoke check and the benchmark's
+cpu_baseline leg.  The product package never imports this.
+"""
+from .conv_ref import (  # noqa: F401
+    build,
+    conv_forward,
+    conv_forward_points,
+    conv_forward_reordered,
+    out_dim,
+    threads,
+    tolerance,
+)
