@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the zero-workspace direct convolution on one MI355X.
+
+A step is one forward pass of every layer of the chosen workload (one
+conv_direct_run per layer) on seeded synthetic tensors already resident in HBM.
+The default workload is the batched AlexNet-/VGG-shaped layer suite; `--workload
+NAME` times a single layer (names: paper_1809_10170_amd/workloads.py).
+
+Prints ONE JSON line: whole-workload TFLOP/s (2*N*K*C*R*S*P*Q per layer / time),
+per-layer figures, the roofline record of the kernel that takes the most time, and
+the CPU oracle timed on a bounded sample of the same workload on this host.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X: 256 CU x 256 flop/clk x 2.4 GHz
+PEAK_HBM_GBPS = 8000.0
+
+
+def suite(name, workloads):
+    if name == "suite_batched":
+        return [l for l in workloads.ALL_LAYERS if l.N >= 32]
+    if name == "suite_all":
+        return list(workloads.ALL_LAYERS)
+    return [workloads.BY_NAME[name]]
+
+
+def cpu_baseline(layers, budget_s=12.0):
+    """The oracle, as it stands, on whole images of the workload's first layers until
+    about budget_s seconds of CPU work are spent."""
+    import numpy as np
+    import oracle
+    from paper_1809_10170_amd import workloads
+    oracle.build()
+    flops, secs, parts = 0, 0.0, []
+    # take the heaviest layer of the workload: one image at a time
+    l = max(layers, key=lambda t: t.flops)
+    x, w = workloads.make_inputs(l, N=min(l.N, 4))
+    n_img = 0
+    while secs < budget_s and n_img < x.shape[0]:
+        t0 = time.perf_counter()
+        oracle.conv_forward(x[n_img:n_img + 1], w, l.stride, l.pad)
+        secs += time.perf_counter() - t0
+        flops += l.flops // l.N
+        n_img += 1
+    parts.append(f"{n_img} image(s) of {l.name}, full output")
+    return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(),
+            "kind": "oracle", "sample": "; ".join(parts), "seconds": round(secs, 2)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="suite_batched")
+    ap.add_argument("--variant", default=None, help="force a kernel variant (single-layer workloads)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--check", action="store_true", help="also verify sampled outputs against the oracle")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only; --gpus must be 1 "
+                 "(the path shards over batch with no exchange step, see DESIGN.md)")
+
+    import torch
+    from paper_1809_10170_amd import conv_direct as cd
+    from paper_1809_10170_amd import workloads
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    cd.lib()   # fail loudly if the HIP library is missing
+    layers = suite(args.workload, workloads)
+    dev = torch.device("cuda:0")
+
+    items = []
+    for l in layers:
+        x, w = workloads.make_inputs(l)
+        xd, wd = torch.from_numpy(x).to(dev), torch.from_numpy(w).to(dev)
+        plan = cd.Plan(*l.dims(), variant=args.variant)
+        out = torch.empty((l.N, l.K, l.P, l.Q), device=dev, dtype=torch.float32)
+        items.append((l, plan, xd, wd, out))
+        del x, w
+    torch.cuda.synchronize()
+    alloc_before = torch.cuda.memory_allocated()
+
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        for l, plan, xd, wd, out in items:
+            plan.run(xd, wd, out, stream.cuda_stream)
+    torch.cuda.synchronize()
+
+    # per-layer events inside the timed region, on the stream the kernels run on
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in items] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        for i, (l, plan, xd, wd, out) in enumerate(items):
+            ev[s][i][0].record(stream)
+            plan.run(xd, wd, out, stream.cuda_stream)
+            ev[s][i][1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    assert torch.cuda.memory_allocated() == alloc_before, "device memory was allocated during the timed region"
+
+    per_layer = []
+    for i, (l, plan, xd, wd, out) in enumerate(items):
+        ms = sorted(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(args.steps))
+        avg = sum(ms) / len(ms)
+        info = plan.info()
+        per_layer.append({
+            "layer": l.name, "variant": info["variant"], "grid": info["grid"],
+            "gflop": round(l.flops / 1e9, 3), "ms_avg": round(avg, 5), "ms_min": round(ms[0], 5),
+            "tflops": round(l.flops / (avg * 1e-3) / 1e12, 3),
+            "frac_fp32_mfma_peak": round(l.flops / (avg * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4),
+            "algorithmic_GBps": round(l.algorithmic_bytes / (avg * 1e-3) / 1e9, 1),
+            "workspace_bytes": plan.workspace_bytes(),
+        })
+    total_flops = sum(l.flops for l in layers)
+    ms_per_step = wall * 1e3 / args.steps
+    value = total_flops / (ms_per_step * 1e-3) / 1e12
+
+    dom = max(per_layer, key=lambda r: r["ms_avg"])
+    roofline = {"bound": "mfma", "kernel": f"conv_tile_kernel<{dom['variant']}>", "layer": dom["layer"],
+                "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, 4),
+                "launch_ms": dom["ms_avg"], "traffic": None}
+
+    if args.check:
+        import oracle
+        for l, plan, xd, wd, out in items:
+            pts = workloads.sample_points(l, 4000)
+            want = oracle.conv_forward_points(xd.cpu().numpy(), wd.cpu().numpy(), pts, l.stride, l.pad)
+            got = out.cpu().numpy()[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]]
+            err = float(abs(got - want).max())
+            assert err <= oracle.tolerance(l.C, l.R, l.S), (l.name, err)
+
+    rec = {
+        "metric": "conv fwd TFLOP/s (2*N*K*C*R*S*P*Q/t), fp32, zero workspace",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "layers": [l.name for l in layers],
+                   "frac_fp32_mfma_peak": round(value / PEAK_FP32_MFMA_TFLOPS, 4),
+                   "workspace_bytes": 0},
+        "roofline": roofline,
+        "layers": per_layer,
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(layers)
+    for _, plan, *_ in items:
+        plan.destroy()
+    print(json.dumps(rec), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,103 @@
+/*
+ * conv_direct.h -- C ABI of the MI355X (gfx950) zero-workspace direct convolution.
+ *
+ * The operation (paper: Section 3, Algorithm 1; "Input I, Kernel Weights F,
+ * stride s -> Output O"), with a batch dimension and symmetric zero padding added:
+ *
+ *   P = floor((H + 2*pad - R) / stride) + 1,  Q = floor((W + 2*pad - S) / stride) + 1
+ *   out[n][k][p][q] = sum over c, r, s of
+ *       in[n][c][p*stride + r - pad][q*stride + s - pad] * w[k][c][r][s]
+ *
+ * Taps outside the image contribute zero; the filter is not flipped; there is no
+ * bias, grouping or dilation; stride and pad are the same in both dimensions.
+ * The convolution is computed directly from the plain tensors (paper: Sections 1
+ * and 4, "zero memory overhead"): the library never allocates, frees or copies
+ * device memory, makes no packed or lowered copy of the input or the weights, and
+ * its kernels use no private scratch.  All arithmetic is fp32 (fp32 MFMA
+ * accumulation); the order of the C*R*S additions is unspecified.
+ *
+ * Layouts, row-major with the last index fastest, fp32:
+ *   in  [N][C][H][W]    w  [K][C][R][S]    out [N][K][P][Q]
+ *
+ * Every function returns 0 (CONV_DIRECT_OK) or a negative error code; nothing
+ * throws, aborts or sets errno.
+ */
+#ifndef CONV_DIRECT_H
+#define CONV_DIRECT_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CONV_DIRECT_OK            0
+#define CONV_DIRECT_EINVAL       (-1) /* a dimension <= 0, stride < 1, pad < 0, filter larger than padded input, NULL argument */
+#define CONV_DIRECT_EUNSUPPORTED (-2) /* a tensor has >= 2^31 elements, or no kernel variant can tile the shape */
+#define CONV_DIRECT_EALIGN       (-3) /* a device pointer is not 4-byte aligned */
+#define CONV_DIRECT_EHIP         (-4) /* the HIP runtime refused the launch; see conv_direct_last_hip_error */
+#define CONV_DIRECT_ENOMEM       (-5) /* host allocation of the plan failed */
+
+/* Opaque launch plan: host memory only, immutable after creation. */
+typedef struct conv_direct_plan conv_direct_plan;
+
+/*
+ * Validate a layer shape and choose the kernel variant, tile and grid for it
+ * (the per-layer blocking decision of the paper's Section 3.1.2, made for the
+ * GPU's register file and LDS instead of a CPU's registers and caches).
+ * Host only: touches no device, allocates only the plan.  *plan is set to NULL on
+ * error.  The caller releases the plan with conv_direct_destroy.
+ */
+int conv_direct_create(conv_direct_plan **plan,
+                       int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+
+/*
+ * Enqueue the forward convolution on `stream` (a hipStream_t; NULL = the default
+ * stream) and return without synchronising.
+ *   in  : device pointer, N*C*H*W floats, read only
+ *   w   : device pointer, K*C*R*S floats, read only
+ *   out : device pointer, N*K*P*Q floats, every element overwritten (beta = 0)
+ * The caller owns all three buffers and the stream; the buffers must not overlap
+ * and must stay valid until the stream has run the kernel.  Pointers need 4-byte
+ * alignment only.  A plan may be run any number of times.
+ */
+int conv_direct_run(const conv_direct_plan *plan,
+                    const float *in, const float *w, float *out, void *stream);
+
+/* Free the host plan.  conv_direct_destroy(NULL) is a no-op that returns OK. */
+int conv_direct_destroy(conv_direct_plan *plan);
+
+/* Output height and width of the planned layer. */
+int conv_direct_output_dims(const conv_direct_plan *plan, int *P, int *Q);
+
+/* Device workspace the plan needs: always 0.  Exists so callers can assert it. */
+size_t conv_direct_workspace_bytes(const conv_direct_plan *plan);
+
+/*
+ * Write a one-line, space-separated key=value description of the plan into buf
+ * (variant name, tile, grid, LDS bytes, threads ...), NUL-terminated and truncated
+ * to n bytes.  Returns the untruncated length, or a negative error code.
+ */
+int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n);
+
+/* Static text for an error code. */
+const char *conv_direct_strerror(int code);
+
+/* hipError_t value of the most recent failed launch on this thread (0 if none). */
+int conv_direct_last_hip_error(void);
+
+/*
+ * Testing / tuning aid: like conv_direct_create, but forces the kernel variant
+ * whose name is `variant` (as printed by conv_direct_plan_info) instead of asking
+ * the planner.  Returns CONV_DIRECT_EUNSUPPORTED if that variant cannot run the
+ * shape.  conv_direct_variant_name(i) enumerates the names (NULL past the end).
+ */
+int conv_direct_create_with_variant(conv_direct_plan **plan, const char *variant,
+                                    int N, int C, int H, int W, int K, int R, int S,
+                                    int stride, int pad);
+const char *conv_direct_variant_name(int index);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONV_DIRECT_H */

@@ -1,0 +1,234 @@
+// C ABI and per-layer planner of the direct-convolution library (see
+// include/conv_direct.h for the contract).  Host code only: the planner picks, for
+// one layer shape, the compiled kernel variant, its tile and the grid -- the GPU
+// counterpart of choosing the block sizes C_o,b, W_o,b and C_i,b in the paper's
+// Section 3.1.2.  Nothing here allocates, frees or copies device memory.
+#include <hip/hip_runtime_api.h>
+
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "../../include/conv_direct.h"
+#include "variant.h"
+
+using convd::Shape;
+using convd::Variant;
+
+struct conv_direct_plan {
+    Shape s;
+    const Variant *v;
+    int tilesP, tilesQ, ktiles;
+    unsigned grid;
+    size_t lds_bytes;
+    double mfma_efficiency;   // useful / issued multiply-accumulates
+};
+
+namespace {
+
+constexpr int kNumCU = 256;                   // MI355X
+constexpr size_t kLdsPerCU = 160 * 1024;
+constexpr int64_t kMaxElems = (int64_t)1 << 31;
+thread_local int t_last_hip_error = 0;
+
+int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+int validate(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, Shape *out)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0 || R <= 0 || S <= 0 || stride < 1 || pad < 0)
+        return CONV_DIRECT_EINVAL;
+    const int64_t spanH = (int64_t)H + 2 * (int64_t)pad - R, spanW = (int64_t)W + 2 * (int64_t)pad - S;
+    if (spanH < 0 || spanW < 0) return CONV_DIRECT_EINVAL;
+    const int64_t P = spanH / stride + 1, Q = spanW / stride + 1;
+    const int64_t nin = (int64_t)N * C * H * W, nw = (int64_t)K * C * R * S, nout = (int64_t)N * K * P * Q;
+    // the kernels index each tensor with 32-bit element offsets inside one image
+    if (nin >= kMaxElems || nw >= kMaxElems || nout >= kMaxElems || (int64_t)pad * 2 + H >= kMaxElems / 4)
+        return CONV_DIRECT_EUNSUPPORTED;
+    *out = Shape{N, C, H, W, K, R, S, stride, pad, (int)P, (int)Q};
+    return CONV_DIRECT_OK;
+}
+
+// Can variant v run shape s at all?
+bool applicable(const Variant &v, const Shape &s)
+{
+    if (v.R != 0 && (v.R != s.R || v.S != s.S || v.stride != s.stride)) return false;
+    if (v.lds_bytes(s) > kLdsPerCU) return false;
+    const int64_t grid = (int64_t)cdiv(s.K, v.KT) * cdiv(s.P, v.TP) * cdiv(s.Q, v.TQ) * s.N;
+    return grid > 0 && grid < kMaxElems;
+}
+
+void fill(conv_direct_plan *p, const Shape &s, const Variant &v)
+{
+    p->s = s;
+    p->v = &v;
+    p->tilesP = cdiv(s.P, v.TP);
+    p->tilesQ = cdiv(s.Q, v.TQ);
+    p->ktiles = cdiv(s.K, v.KT);
+    p->grid = (unsigned)((int64_t)p->ktiles * p->tilesP * p->tilesQ * s.N);
+    p->lds_bytes = v.lds_bytes(s);
+    // issued MACs: every workgroup runs KT x (NPB*32) outputs over the padded reduction
+    double red;
+    if (v.R == 0) {
+        red = 2.0 * cdiv(s.C, 2) * s.R * s.S;
+    } else if (v.pair == convd::PAIR_C) {
+        red = (double)cdiv(s.C, v.CB) * v.CB * s.R * s.S;
+    } else {
+        red = (double)cdiv(s.C, v.CB) * v.CB * s.R * (2 * ((s.S + 1) / 2));
+    }
+    const double issued = (double)p->grid * v.KT * (v.NPB * 32.0) * red;
+    const double useful = (double)s.N * s.K * s.P * s.Q * ((double)s.C * s.R * s.S);
+    p->mfma_efficiency = useful / issued;
+}
+
+// Estimated time, in arbitrary units, of running the plan: workgroups are dealt
+// evenly to the CUs; a CU works through its share with up to `occupancy` of them
+// resident, and its four matrix pipes are busy only as far as resident waves cover
+// them.  Waves that have a pipe to themselves cannot hide their own staging and
+// barriers, which the last factor charges for.
+double cost(const conv_direct_plan &p)
+{
+    const Variant &v = *p.v;
+    const double useful = (double)p.s.N * p.s.K * p.s.P * p.s.Q * ((double)p.s.C * p.s.R * p.s.S);
+    const double macs_per_wg = useful / p.mfma_efficiency / p.grid;
+    const int waves_per_wg = v.threads / 64;
+    const int wg_per_cu = cdiv((int)p.grid, kNumCU);
+    const int resident = wg_per_cu < v.occupancy ? wg_per_cu : v.occupancy;
+    const int resident_waves = resident * waves_per_wg;
+    const double pipes = resident_waves < 4 ? resident_waves : 4;
+    double c = wg_per_cu * macs_per_wg / pipes;
+    c *= 1.0 + 0.25 * 4.0 / (resident_waves < 4 ? 4 : resident_waves);
+    if (v.R == 0) c *= 3.0;   // the runtime-shape fallback synchronises far more often
+    return c;
+}
+
+int make_plan(conv_direct_plan **plan, const char *forced, int N, int C, int H, int W, int K, int R,
+              int S, int stride, int pad)
+{
+    if (!plan) return CONV_DIRECT_EINVAL;
+    *plan = nullptr;
+    Shape s;
+    const int rc = validate(N, C, H, W, K, R, S, stride, pad, &s);
+    if (rc != CONV_DIRECT_OK) return rc;
+
+    conv_direct_plan best;
+    bool have = false;
+    double best_cost = 0.0;
+    int count = 0;
+    const Variant *table = convd::variant_table(&count);
+    for (int i = 0; i < count; ++i) {
+        const Variant &v = table[i];
+        if (forced && std::strcmp(forced, v.name) != 0) continue;
+        if (!applicable(v, s)) continue;
+        conv_direct_plan cand;
+        fill(&cand, s, v);
+        const double c = cost(cand);
+        if (!have || c < best_cost) {
+            best = cand;
+            best_cost = c;
+            have = true;
+        }
+    }
+    if (!have) return CONV_DIRECT_EUNSUPPORTED;
+    conv_direct_plan *p = new (std::nothrow) conv_direct_plan(best);
+    if (!p) return CONV_DIRECT_ENOMEM;
+    *plan = p;
+    return CONV_DIRECT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int conv_direct_create(conv_direct_plan **plan, int N, int C, int H, int W, int K, int R, int S,
+                       int stride, int pad)
+{
+    return make_plan(plan, nullptr, N, C, H, W, K, R, S, stride, pad);
+}
+
+int conv_direct_create_with_variant(conv_direct_plan **plan, const char *variant, int N, int C, int H,
+                                    int W, int K, int R, int S, int stride, int pad)
+{
+    if (!variant) {
+        if (plan) *plan = nullptr;
+        return CONV_DIRECT_EINVAL;
+    }
+    return make_plan(plan, variant, N, C, H, W, K, R, S, stride, pad);
+}
+
+const char *conv_direct_variant_name(int index)
+{
+    int count = 0;
+    const Variant *table = convd::variant_table(&count);
+    return (index >= 0 && index < count) ? table[index].name : nullptr;
+}
+
+int conv_direct_run(const conv_direct_plan *plan, const float *in, const float *w, float *out,
+                    void *stream)
+{
+    if (!plan || !in || !w || !out) return CONV_DIRECT_EINVAL;
+    if (((uintptr_t)in | (uintptr_t)w | (uintptr_t)out) & 3u) return CONV_DIRECT_EALIGN;
+    convd::KernelArgs a;
+    a.in = in;
+    a.w = w;
+    a.out = out;
+    a.s = plan->s;
+    a.tilesP = plan->tilesP;
+    a.tilesQ = plan->tilesQ;
+    a.ktiles = plan->ktiles;
+    const hipError_t e = plan->v->launch(a, plan->grid, (hipStream_t)stream);
+    if (e != hipSuccess) {
+        t_last_hip_error = (int)e;
+        return CONV_DIRECT_EHIP;
+    }
+    return CONV_DIRECT_OK;
+}
+
+int conv_direct_destroy(conv_direct_plan *plan)
+{
+    delete plan;
+    return CONV_DIRECT_OK;
+}
+
+int conv_direct_output_dims(const conv_direct_plan *plan, int *P, int *Q)
+{
+    if (!plan || !P || !Q) return CONV_DIRECT_EINVAL;
+    *P = plan->s.P;
+    *Q = plan->s.Q;
+    return CONV_DIRECT_OK;
+}
+
+size_t conv_direct_workspace_bytes(const conv_direct_plan *) { return 0; }
+
+int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
+{
+    if (!plan || (!buf && n)) return CONV_DIRECT_EINVAL;
+    const Variant &v = *plan->v;
+    const Shape &s = plan->s;
+    return std::snprintf(buf, n,
+                         "variant=%s N=%d C=%d H=%d W=%d K=%d R=%d S=%d stride=%d pad=%d P=%d Q=%d "
+                         "TP=%d TQ=%d KT=%d NPB=%d CB=%d pair=%s tilesP=%d tilesQ=%d ktiles=%d grid=%u "
+                         "threads=%d lds_bytes=%zu occupancy=%d mfma_efficiency=%.4f workspace_bytes=0",
+                         v.name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, v.TP, v.TQ,
+                         v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : "s", plan->tilesP,
+                         plan->tilesQ, plan->ktiles, plan->grid, v.threads, plan->lds_bytes, v.occupancy,
+                         plan->mfma_efficiency);
+}
+
+const char *conv_direct_strerror(int code)
+{
+    switch (code) {
+        case CONV_DIRECT_OK: return "ok";
+        case CONV_DIRECT_EINVAL: return "invalid argument (dimension, stride, pad or NULL pointer)";
+        case CONV_DIRECT_EUNSUPPORTED: return "shape not supported (tensor too large or no variant fits)";
+        case CONV_DIRECT_EALIGN: return "device pointer not 4-byte aligned";
+        case CONV_DIRECT_EHIP: return "HIP launch failed (see conv_direct_last_hip_error)";
+        case CONV_DIRECT_ENOMEM: return "host allocation failed";
+        default: return "unknown error code";
+    }
+}
+
+int conv_direct_last_hip_error(void) { return t_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,391 @@
+// Direct-convolution forward kernels for gfx950 (MI355X): fp32 MFMA, LDS-staged
+// halo tiles, no workspace.
+//
+// The computation is the paper's Algorithm 1 (Section 3): six loops around one
+// multiply-accumulate.  The paper blocks the output-channel and output-column loops
+// for the register file, the input-channel loop for the cache, and runs output
+// channels in parallel (Section 3.1.2, Section 3.2, Algorithm 3).  On this GPU the
+// same three decisions become:
+//   * register block  -> a (32*KBW) x (32*PBW) accumulator tile per wave, held in
+//     VGPRs as 32x32 MFMA results; rows are output channels, columns output pixels;
+//   * cache block     -> CB input channels staged per step into LDS: the input
+//     halo window of the workgroup's pixel tile and the matching filter slice;
+//   * parallel loop   -> the grid: every (image, pixel tile, channel tile) is an
+//     independent workgroup.
+// Because the halo window sits in LDS once and every filter tap reads it at a
+// different constant offset, nothing like an im2col matrix ever exists: that is
+// the paper's "zero memory overhead" (Sections 1, 2.2) carried over.
+//
+// v_mfma_f32_32x32x2_f32 operand layout used here: lane l supplies A[i = l%32][kk = l/32]
+// and B[kk = l/32][j = l%32]; accumulator register v of lane l holds
+// D[i = 8*(v/4) + 4*(l/32) + v%4][j = l%32].  A = filter slice (i = output channel),
+// B = input values (j = output pixel).  The two kk lanes of one instruction take two
+// neighbouring input channels at one filter tap (PAIR_C), or, for layers with very
+// few input channels, two neighbouring filter columns of one channel (PAIR_S, an odd
+// filter width being padded with a zero weight).  Any order of the C*R*S additions
+// is a correct convolution (Section 3, "any permutation of the loops").
+#include <hip/hip_runtime.h>
+
+#include "variant.h"
+
+namespace convd {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+template <int R_, int S_, int ST_, int TP_, int TQ_, int KBW_, int PBW_, int WK_, int WP_, int CB_,
+          int PAIR_, int OCC_>
+struct Geom {
+    static constexpr int R = R_, S = S_, ST = ST_, TP = TP_, TQ = TQ_;
+    static constexpr int KBW = KBW_, PBW = PBW_, WK = WK_, WP = WP_, CB = CB_, PAIR = PAIR_, OCC = OCC_;
+    static constexpr int NT = 64 * WK * WP;            // threads per workgroup
+    static constexpr int WPE = (OCC * WK * WP + 3) / 4; // waves per SIMD the register budget must allow
+    static constexpr int SB = 8;                       // staging loads in flight per thread
+    static constexpr int KT = 32 * KBW * WK;           // output channels per workgroup
+    static constexpr int NPB = PBW * WP;               // 32-pixel blocks per workgroup
+    static constexpr int NPIX = TP * TQ;               // real pixels in the tile
+    static constexpr int S2 = (S + 1) / 2;
+    static constexpr int SPAN = PAIR == PAIR_S ? 2 * S2 : S;
+    static constexpr int LH = (TP - 1) * ST + R;       // halo window rows
+    static constexpr int LW = (TQ - 1) * ST + SPAN;    // halo window columns
+    static constexpr int LWP = LW;                     // LDS row pitch
+    static constexpr int PS = LH * LWP;                // LDS channel-plane stride
+    static constexpr int RS = R * S;
+    static constexpr int STEPS = PAIR == PAIR_C ? (CB / 2) * RS : CB * R * S2;   // MFMA k-steps per chunk
+    static constexpr int KP = KT + 1;                  // LDS pitch of one filter k-row (odd: spreads banks)
+    static constexpr int LDS_A = STEPS * 2 * KP;       // floats
+    static constexpr int LDS_B = CB * PS;              // floats
+    static constexpr size_t LDS_BYTES = sizeof(float) * (size_t)(LDS_A + LDS_B);
+    static_assert(NPB * 32 >= NPIX, "pixel blocks must cover the tile");
+    static_assert(PAIR == PAIR_S || CB % 2 == 0, "channel pairing needs an even chunk");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
+};
+
+// Global -> LDS staging helper: N_IT elements per thread, BATCH loads in flight
+// before their LDS stores (bounds the registers the staging needs).
+template <int N_IT, int BATCH, class LoadF, class StoreF>
+__device__ __forceinline__ void stage(LoadF ld, StoreF st)
+{
+#pragma unroll
+    for (int i0 = 0; i0 < N_IT; i0 += BATCH) {
+        float v[BATCH];
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b)
+            if (i0 + b < N_IT) v[b] = ld(i0 + b);
+#pragma unroll
+        for (int b = 0; b < BATCH; ++b)
+            if (i0 + b < N_IT) st(i0 + b, v[b]);
+    }
+}
+
+template <class G>
+__global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelArgs a)
+{
+    extern __shared__ __align__(16) float lds[];
+    float *ldsA = lds;                 // [STEPS][2][KP]   filter slice, k-lane major
+    float *ldsB = lds + G::LDS_A;      // [CB][LH][LWP]    input halo window
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wk = wave % G::WK, wp = wave / G::WK;
+    const int h = lane >> 5, j = lane & 31;
+
+    const int C = a.s.C, H = a.s.H, W = a.s.W, K = a.s.K, P = a.s.P, Q = a.s.Q;
+
+    // workgroup -> (channel tile, pixel tile column, pixel tile row, image)
+    unsigned bid = blockIdx.x;
+    const int kt = bid % a.ktiles;  bid /= a.ktiles;
+    const int tq = bid % a.tilesQ;  bid /= a.tilesQ;
+    const int tp = bid % a.tilesP;
+    const int n = bid / a.tilesP;
+    const int p0 = tp * G::TP, q0 = tq * G::TQ, k0 = kt * G::KT;
+    const int ih0 = p0 * G::ST - a.s.pad, iw0 = q0 * G::ST - a.s.pad;
+
+    const float *in_n = a.in + (size_t)n * C * H * W;
+    const float *w_k = a.w + (size_t)k0 * C * G::RS;
+
+    // per-lane LDS read bases
+    int bbase[G::PBW];
+#pragma unroll
+    for (int pb = 0; pb < G::PBW; ++pb) {
+        const int t = (wp * G::PBW + pb) * 32 + j;
+        const int py = t / G::TQ, px = t - py * G::TQ;
+        const int pix = t < G::NPIX ? py * G::ST * G::LWP + px * G::ST : 0;
+        bbase[pb] = pix + h * (G::PAIR == PAIR_C ? G::PS : 1);
+    }
+    const int abase = h * G::KP + wk * G::KBW * 32 + j;
+
+    floatx16 acc[G::KBW][G::PBW];
+#pragma unroll
+    for (int kb = 0; kb < G::KBW; ++kb)
+#pragma unroll
+        for (int pb = 0; pb < G::PBW; ++pb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[kb][pb][v] = 0.f;
+
+    if (G::PAIR == PAIR_S && (G::S & 1)) {
+        // the zero weight that pads an odd filter width is written once
+        for (int e = tid; e < G::LDS_A; e += G::NT) ldsA[e] = 0.f;
+    }
+
+    constexpr int NB = G::CB * G::LH * G::LW;          // input elements per chunk
+    constexpr int NB_IT = (NB + G::NT - 1) / G::NT;
+    constexpr int NA = G::KT * G::CB * G::RS;          // filter elements per chunk
+    constexpr int NA_IT = (NA + G::NT - 1) / G::NT;
+
+    for (int c0 = 0; c0 < C; c0 += G::CB) {
+        // Keep the per-element index arithmetic inside the loop: hoisted out, it would
+        // occupy more registers than the accumulators leave free.
+        int t = tid;
+        asm volatile("" : "+v"(t));
+        // ---- stage the chunk: global -> registers -> LDS, a batch of loads at a time ----
+        stage<NB_IT, G::SB>(
+            [&](int i) {
+                const int e = t + i * G::NT;
+                const int cc = e / (G::LH * G::LW);
+                const int rem = e - cc * (G::LH * G::LW);
+                const int hh = rem / G::LW, ww = rem - hh * G::LW;
+                const int ih = ih0 + hh, iw = iw0 + ww, c = c0 + cc;
+                const bool ok = e < NB && c < C && (unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W;
+                const float v = in_n[ok ? (c * H + ih) * W + iw : 0];
+                return ok ? v : 0.f;
+            },
+            [&](int i, float v) {
+                const int e = t + i * G::NT;
+                const int cc = e / (G::LH * G::LW);
+                const int rem = e - cc * (G::LH * G::LW);
+                const int hh = rem / G::LW, ww = rem - hh * G::LW;
+                if ((i + 1) * G::NT <= NB || e < NB) ldsB[cc * G::PS + hh * G::LWP + ww] = v;
+            });
+        stage<NA_IT, G::SB>(
+            [&](int i) {
+                const int e = t + i * G::NT;
+                const int kk = e / (G::CB * G::RS);
+                const int jj = e - kk * (G::CB * G::RS);
+                const int cc = jj / G::RS;
+                const bool ok = e < NA && k0 + kk < K && c0 + cc < C;
+                const float v = w_k[ok ? (kk * C + c0) * G::RS + jj : 0];
+                return ok ? v : 0.f;
+            },
+            [&](int i, float v) {
+                const int e = t + i * G::NT;
+                const int kk = e / (G::CB * G::RS);
+                const int jj = e - kk * (G::CB * G::RS);
+                const int cc = jj / G::RS, rs = jj - cc * G::RS;
+                int slot;
+                if (G::PAIR == PAIR_C) {
+                    slot = ((cc >> 1) * G::RS + rs) * 2 + (cc & 1);
+                } else {
+                    const int r = rs / G::S, s = rs - r * G::S;
+                    slot = ((cc * G::R + r) * G::S2 + (s >> 1)) * 2 + (s & 1);
+                }
+                if ((i + 1) * G::NT <= NA || e < NA) ldsA[slot * G::KP + kk] = v;
+            });
+        __syncthreads();
+
+        // ---- the reduction over this chunk: STEPS rank-2 updates of the tile ----
+#pragma unroll
+        for (int step = 0; step < G::STEPS; ++step) {
+            int boff;
+            if (G::PAIR == PAIR_C) {
+                const int c2 = step / G::RS, rs = step - c2 * G::RS;
+                const int r = rs / G::S, s = rs - r * G::S;
+                boff = c2 * 2 * G::PS + r * G::LWP + s;
+            } else {
+                const int cc = step / (G::R * G::S2), rem = step - cc * (G::R * G::S2);
+                const int r = rem / G::S2, s2 = rem - r * G::S2;
+                boff = cc * G::PS + r * G::LWP + 2 * s2;
+            }
+            float av[G::KBW], bv[G::PBW];
+#pragma unroll
+            for (int kb = 0; kb < G::KBW; ++kb) av[kb] = ldsA[abase + step * 2 * G::KP + kb * 32];
+#pragma unroll
+            for (int pb = 0; pb < G::PBW; ++pb) bv[pb] = ldsB[bbase[pb] + boff];
+#pragma unroll
+            for (int kb = 0; kb < G::KBW; ++kb)
+#pragma unroll
+                for (int pb = 0; pb < G::PBW; ++pb)
+                    acc[kb][pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[kb], bv[pb], acc[kb][pb], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: each output element is written exactly once ----
+    float *out_n = a.out + (size_t)n * K * P * Q;
+#pragma unroll
+    for (int pb = 0; pb < G::PBW; ++pb) {
+        const int t = (wp * G::PBW + pb) * 32 + j;
+        const int py = t / G::TQ, px = t - py * G::TQ;
+        const int p = p0 + py, q = q0 + px;
+        if (t < G::NPIX && p < P && q < Q) {
+#pragma unroll
+            for (int kb = 0; kb < G::KBW; ++kb) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int k = k0 + (wk * G::KBW + kb) * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (k < K) out_n[((size_t)k * P + p) * Q + q] = acc[kb][pb][v];
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Fallback for any filter size and stride (runtime R, S, stride).  Same operand
+// mapping; one chunk is one pair of input channels at one filter row, so the LDS
+// need is independent of R.  Tile: 2 output rows x 32 columns x 64 channels,
+// four waves each owning one 32x32 accumulator block.
+// ---------------------------------------------------------------------------
+struct GenericGeom {
+    static constexpr int TP = 2, TQ = 32, KT = 64, NT = 256, KP = KT + 1;
+    static __host__ __device__ int lw(int S, int st) { return (TQ - 1) * st + S; }
+    static __host__ __device__ size_t lds_floats(int S, int st) { return (size_t)S * 2 * KP + 2 * TP * lw(S, st); }
+};
+
+__global__ void __launch_bounds__(GenericGeom::NT) conv_generic_kernel(const KernelArgs a)
+{
+    using G = GenericGeom;
+    extern __shared__ __align__(16) float lds[];
+    const int C = a.s.C, H = a.s.H, W = a.s.W, K = a.s.K, P = a.s.P, Q = a.s.Q;
+    const int R = a.s.R, S = a.s.S, st = a.s.stride;
+    const int LW = G::lw(S, st);
+    float *ldsA = lds;                       // [S][2][KP]
+    float *ldsB = lds + S * 2 * G::KP;       // [2][TP][LW]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wk = wave & 1, wp = wave >> 1;   // wp = output row of the tile
+    const int h = lane >> 5, j = lane & 31;
+
+    unsigned bid = blockIdx.x;
+    const int kt = bid % a.ktiles;  bid /= a.ktiles;
+    const int tq = bid % a.tilesQ;  bid /= a.tilesQ;
+    const int tp = bid % a.tilesP;
+    const int n = bid / a.tilesP;
+    const int p0 = tp * G::TP, q0 = tq * G::TQ, k0 = kt * G::KT;
+    const int iw0 = q0 * st - a.s.pad;
+    const float *in_n = a.in + (size_t)n * C * H * W;
+
+    const int bbase = (h * G::TP + wp) * LW + j * st;
+    const int abase = h * G::KP + wk * 32 + j;
+
+    floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+
+    const int nB = 2 * G::TP * LW, nA = G::KT * 2 * S;
+    for (int c0 = 0; c0 < C; c0 += 2) {
+        for (int r = 0; r < R; ++r) {
+            for (int e = tid; e < nB; e += G::NT) {
+                const int cc = e / (G::TP * LW), rem = e - cc * (G::TP * LW);
+                const int py = rem / LW, ww = rem - py * LW;
+                const int ih = (p0 + py) * st + r - a.s.pad, iw = iw0 + ww, c = c0 + cc;
+                float v = 0.f;
+                if (c < C && (unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W)
+                    v = in_n[((size_t)c * H + ih) * W + iw];
+                ldsB[e] = v;
+            }
+            for (int e = tid; e < nA; e += G::NT) {
+                const int kk = e / (2 * S), rem = e - kk * (2 * S);
+                const int cc = rem / S, s = rem - cc * S;
+                float v = 0.f;
+                if (k0 + kk < K && c0 + cc < C)
+                    v = a.w[(((size_t)(k0 + kk) * C + c0 + cc) * R + r) * S + s];
+                ldsA[(s * 2 + cc) * G::KP + kk] = v;
+            }
+            __syncthreads();
+            for (int s = 0; s < S; ++s) {
+                const float av = ldsA[abase + s * 2 * G::KP];
+                const float bv = ldsB[bbase + s];
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc, 0, 0, 0);
+            }
+            __syncthreads();
+        }
+    }
+
+    const int p = p0 + wp, q = q0 + j;
+    if (p < P && q < Q) {
+        float *out_n = a.out + (size_t)n * K * P * Q;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int k = k0 + wk * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+            if (k < K) out_n[((size_t)k * P + p) * Q + q] = acc[v];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Host side of this translation unit: launchers and the variant table.
+// ---------------------------------------------------------------------------
+static hipError_t allow_lds(const void *fn, size_t bytes)
+{
+    // Workgroups above the 64 KB default need the limit raised (no allocation involved).
+    if (bytes <= 64 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+template <class G>
+static hipError_t launch_tile(const KernelArgs &a, unsigned grid, hipStream_t stream)
+{
+    hipError_t e = allow_lds(reinterpret_cast<const void *>(&conv_tile_kernel<G>), G::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(conv_tile_kernel<G>, dim3(grid), dim3(G::NT), G::LDS_BYTES, stream, a);
+    return hipGetLastError();
+}
+
+template <class G>
+static size_t lds_tile(const Shape &) { return G::LDS_BYTES; }
+
+static size_t lds_generic(const Shape &s)
+{
+    return sizeof(float) * GenericGeom::lds_floats(s.S, s.stride);
+}
+
+static hipError_t launch_generic(const KernelArgs &a, unsigned grid, hipStream_t stream)
+{
+    const size_t bytes = lds_generic(a.s);
+    hipError_t e = allow_lds(reinterpret_cast<const void *>(&conv_generic_kernel), bytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(conv_generic_kernel, dim3(grid), dim3(GenericGeom::NT), bytes, stream, a);
+    return hipGetLastError();
+}
+
+#define TILE_VARIANT(NAME, R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC)                        \
+    {                                                                                               \
+        NAME, R, S, ST, TP, TQ, Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC>::KT,       \
+            Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC>::NPB, CB, PAIR,                \
+            Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC>::NT, OCC,                      \
+            &lds_tile<Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC>>,                    \
+            &launch_tile<Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC>>                  \
+    }
+
+// name, R, S, stride, TP, TQ, KBW, PBW, WK, WP, CB, pair, workgroups/CU
+static const Variant k_variants[] = {
+    // 3x3 stride 1: 224-pixel tiles (7 blocks), 128 or 64 output channels
+    TILE_VARIANT("f3s1_1x224_k128", 3, 3, 1, 1, 224, 1, 7, 4, 1, 8, PAIR_C, 2),
+    TILE_VARIANT("f3s1_2x112_k128", 3, 3, 1, 2, 112, 1, 7, 4, 1, 8, PAIR_C, 2),
+    TILE_VARIANT("f3s1_4x56_k128", 3, 3, 1, 4, 56, 1, 7, 4, 1, 8, PAIR_C, 2),
+    TILE_VARIANT("f3s1_8x28_k128", 3, 3, 1, 8, 28, 1, 7, 4, 1, 8, PAIR_C, 2),
+    TILE_VARIANT("f3s1_14x14_k128", 3, 3, 1, 14, 14, 1, 7, 4, 1, 8, PAIR_C, 2),
+    TILE_VARIANT("f3s1_13x13_k128", 3, 3, 1, 13, 13, 1, 6, 4, 1, 8, PAIR_C, 2),
+    TILE_VARIANT("f3s1_2x224_k64", 3, 3, 1, 2, 224, 1, 7, 2, 2, 8, PAIR_C, 2),
+    TILE_VARIANT("f3s1_7x32_k32_c3", 3, 3, 1, 7, 32, 1, 7, 1, 1, 3, PAIR_S, 4),
+    // 5x5 stride 1
+    TILE_VARIANT("f5s1_9x27_k128", 5, 5, 1, 9, 27, 1, 8, 4, 1, 4, PAIR_C, 2),
+    // 1x1
+    TILE_VARIANT("f1s1_4x56_k64", 1, 1, 1, 4, 56, 1, 7, 2, 1, 32, PAIR_C, 4),
+    TILE_VARIANT("f1s1_4x56_k128", 1, 1, 1, 4, 56, 1, 7, 4, 1, 32, PAIR_C, 2),
+    // 3x3 stride 2
+    TILE_VARIANT("f3s2_8x28_k128", 3, 3, 2, 8, 28, 1, 7, 4, 1, 8, PAIR_C, 2),
+    // first layers (3 input channels): pairs of filter columns
+    TILE_VARIANT("f7s2_2x112_k64_c3", 7, 7, 2, 2, 112, 1, 7, 2, 1, 3, PAIR_S, 2),
+    TILE_VARIANT("f11s4_4x55_k96_c3", 11, 11, 4, 4, 55, 1, 7, 3, 1, 1, PAIR_S, 2),
+    // any shape
+    {"generic_2x32_k64", 0, 0, 0, GenericGeom::TP, GenericGeom::TQ, GenericGeom::KT, 2, 2, PAIR_C,
+     GenericGeom::NT, 2, &lds_generic, &launch_generic},
+};
+const Variant *variant_table(int *count)
+{
+    *count = (int)(sizeof(k_variants) / sizeof(k_variants[0]));
+    return k_variants;
+}
+
+}  // namespace convd

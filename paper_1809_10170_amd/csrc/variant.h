@@ -1,0 +1,41 @@
+// Host-side description of the compiled kernel variants, shared by the kernel
+// translation unit (which fills the table) and the planner / C ABI (which reads it).
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <stddef.h>
+
+namespace convd {
+
+struct Shape {
+    int N, C, H, W, K, R, S, stride, pad, P, Q;
+};
+
+// Everything a kernel needs; passed by value as the kernel argument.
+struct KernelArgs {
+    const float *in;
+    const float *w;
+    float *out;
+    Shape s;
+    int tilesP, tilesQ, ktiles;   // grid = ktiles * tilesQ * tilesP * N workgroups
+};
+
+enum Pair { PAIR_C = 0, PAIR_S = 1 };
+
+struct Variant {
+    const char *name;
+    int R, S, stride;     // filter and stride the variant is compiled for; 0 = any (runtime)
+    int TP, TQ;           // output tile of one workgroup: TP rows x TQ columns of one image
+    int KT;               // output channels per workgroup
+    int NPB;              // 32-pixel MFMA column blocks per workgroup (NPB*32 >= TP*TQ)
+    int CB;               // input channels staged per LDS chunk
+    int pair;             // which reduction index the two k-lanes of one MFMA span
+    int threads;          // workgroup size
+    int occupancy;        // workgroups per CU the variant is sized for
+    size_t (*lds_bytes)(const Shape &);
+    hipError_t (*launch)(const KernelArgs &, unsigned grid, hipStream_t stream);
+};
+
+// The compiled variants (host table; lives in the kernel translation unit).
+const Variant *variant_table(int *count);
+
+}  // namespace convd

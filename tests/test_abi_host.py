@@ -1,0 +1,128 @@
+"""Host-side checks of the C ABI and the planner.  No GPU: nothing here launches a kernel.
+
+The library must load, export every symbol the header declares, reject bad arguments
+with the documented codes, and plan a tiling that covers every output exactly once.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1809_10170_amd import conv_direct as cd
+from paper_1809_10170_amd import workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    with open(os.path.join(ROOT, "include", "conv_direct.h")) as f:
+        text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
+    names = set(re.findall(r"\b(conv_direct_[a-z_]+)\s*\(", text))
+    assert {"conv_direct_create", "conv_direct_run", "conv_direct_destroy"} <= names
+    raw = ctypes.CDLL(cd.LIB_PATH)
+    for nm in sorted(names):
+        assert hasattr(raw, nm), f"{nm} declared in the header but not exported"
+
+
+def test_error_codes():
+    L = cd.lib()
+    p = ctypes.c_void_p()
+    good = [1, 3, 8, 8, 4, 3, 3, 1, 1]
+    for pos, bad in [(0, 0), (1, -1), (2, 0), (3, 0), (4, 0), (5, 0), (6, 0), (7, 0), (8, -1)]:
+        args = list(good)
+        args[pos] = bad
+        assert L.conv_direct_create(ctypes.byref(p), *args) == cd.EINVAL
+        assert not p.value
+    # filter larger than the padded input
+    assert L.conv_direct_create(ctypes.byref(p), 1, 1, 2, 2, 1, 3, 3, 1, 0) == cd.EINVAL
+    assert L.conv_direct_create(ctypes.byref(p), 1, 1, 2, 2, 1, 3, 3, 1, 1) == cd.OK
+    assert L.conv_direct_destroy(p) == cd.OK
+    # NULL plan pointer
+    assert L.conv_direct_create(None, *good) == cd.EINVAL
+    # a tensor with 2^31 or more elements
+    assert L.conv_direct_create(ctypes.byref(p), 4096, 1024, 32, 32, 8, 1, 1, 1, 0) == cd.EUNSUPPORTED
+    assert L.conv_direct_destroy(None) == cd.OK
+    assert L.conv_direct_create_with_variant(ctypes.byref(p), b"no_such_variant", *good) == cd.EUNSUPPORTED
+    assert L.conv_direct_create_with_variant(ctypes.byref(p), None, *good) == cd.EINVAL
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        assert cd.strerror(code)
+    assert L.conv_direct_last_hip_error() == 0
+
+
+def test_run_rejects_null_and_misaligned_pointers_before_any_launch():
+    plan = cd.Plan(1, 3, 8, 8, 4, 3, 3, 1, 1)
+    L = cd.lib()
+    assert L.conv_direct_run(plan._p, None, 4096, 8192, None) == cd.EINVAL
+    assert L.conv_direct_run(plan._p, 4096, None, 8192, None) == cd.EINVAL
+    assert L.conv_direct_run(plan._p, 4096, 8192, None, None) == cd.EINVAL
+    assert L.conv_direct_run(None, 4096, 8192, 12288, None) == cd.EINVAL
+    assert L.conv_direct_run(plan._p, 4097, 8192, 12288, None) == cd.EALIGN
+    assert L.conv_direct_run(plan._p, 4096, 8194, 12288, None) == cd.EALIGN
+    assert L.conv_direct_run(plan._p, 4096, 8192, 12291, None) == cd.EALIGN
+    assert L.conv_direct_output_dims(None, None, None) == cd.EINVAL
+    plan.destroy()
+    plan.destroy()   # idempotent
+
+
+def _check_cover(info, exhaustive):
+    N, K, P, Q = info["N"], info["K"], info["P"], info["Q"]
+    TP, TQ, KT = info["TP"], info["TQ"], info["KT"]
+    tP, tQ, tK = info["tilesP"], info["tilesQ"], info["ktiles"]
+    assert info["grid"] == tP * tQ * tK * N
+    assert info["NPB"] * 32 >= TP * TQ
+    assert (tP - 1) * TP < P <= tP * TP
+    assert (tQ - 1) * TQ < Q <= tQ * TQ
+    assert (tK - 1) * KT < K <= tK * KT
+    assert info["lds_bytes"] <= 160 * 1024
+    assert info["threads"] % 64 == 0 and 64 <= info["threads"] <= 1024
+    assert info["workspace_bytes"] == 0
+    assert 0.0 < info["mfma_efficiency"] <= 1.0
+    if exhaustive:
+        # replay the kernel's workgroup -> tile decode and count writers per output
+        hits = np.zeros((N, K, P, Q), np.int32)
+        for bid in range(info["grid"]):
+            b = bid
+            kt, b = b % tK, b // tK
+            tq, b = b % tQ, b // tQ
+            tp, n = b % tP, b // tP
+            hits[n, kt * KT:(kt + 1) * KT, tp * TP:(tp + 1) * TP, tq * TQ:(tq + 1) * TQ] += 1
+        assert hits.min() == 1 and hits.max() == 1
+
+
+@pytest.mark.parametrize("layer", workloads.ALL_LAYERS, ids=lambda l: l.name)
+def test_plan_for_every_benchmark_layer(layer):
+    plan = cd.Plan(*layer.dims())
+    assert plan.output_dims() == (layer.P, layer.Q)
+    assert plan.workspace_bytes() == 0
+    info = plan.info()
+    for k in ("N", "C", "H", "W", "K", "R", "S", "stride", "pad"):
+        assert info[k] == getattr(layer, k)
+    # a compiled (not runtime-shape) variant serves every benchmark layer
+    assert not info["variant"].startswith("generic")
+    _check_cover(info, exhaustive=layer.N * layer.K * layer.P * layer.Q <= 2_000_000)
+    plan.destroy()
+
+
+@pytest.mark.parametrize("shape", [
+    (1, 1, 1, 1, 1, 1, 1, 1, 0), (2, 5, 9, 7, 33, 2, 4, 3, 2), (3, 4, 40, 70, 65, 4, 4, 1, 0),
+    (1, 7, 33, 35, 130, 3, 3, 1, 1), (2, 3, 50, 50, 20, 9, 9, 5, 4), (1, 2, 5, 300, 3, 1, 7, 1, 3),
+])
+def test_plan_for_odd_shapes(shape):
+    plan = cd.Plan(*shape)
+    _check_cover(plan.info(), exhaustive=True)
+    plan.destroy()
+
+
+def test_every_variant_plans_a_matching_shape():
+    names = cd.variant_names()
+    assert len(names) == len(set(names)) and any(n.startswith("generic") for n in names)
+    for nm in names:
+        m = re.match(r"f(\d+)s(\d+)_", nm)
+        R, st = (int(m.group(1)), int(m.group(2))) if m else (4, 3)
+        plan = cd.Plan(2, 6, 37, 41, 70, R, R, st, R // 2, variant=nm)
+        info = plan.info()
+        assert info["variant"] == nm
+        _check_cover(info, exhaustive=True)
+        plan.destroy()

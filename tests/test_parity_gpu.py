@@ -1,0 +1,200 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded host arrays.  Floating point bar: max |gpu - oracle| <= 1e-4*sqrt(C*R*S)
+(inputs of magnitude <= 1), written `not (err <= tol)` so NaN fails.  Integer-valued
+inputs whose partial sums are exact in fp32 must match bit for bit in any order.
+"""
+import re
+
+import numpy as np
+import pytest
+import torch
+
+from paper_1809_10170_amd import conv_direct as cd
+from paper_1809_10170_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(x, w, stride, pad, variant=None):
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    N, C, H, W = x.shape
+    K, _, R, S = w.shape
+    plan = cd.Plan(N, C, H, W, K, R, S, stride, pad, variant)
+    P, Q = plan.output_dims()
+    out = torch.full((N, K, P, Q), float("nan"), device="cuda", dtype=torch.float32)
+    plan.run(xd, wd, out)
+    torch.cuda.synchronize()
+    info = plan.info()
+    plan.destroy()
+    return out.cpu().numpy(), info
+
+
+def _assert_close(got, want, tol, what):
+    err = np.abs(got.astype(np.float64) - want).max() if want.size else 0.0
+    assert not np.isnan(got).any(), f"{what}: NaN in output (an element was not written)"
+    assert err <= tol, f"{what}: max err {err:.3e} > tol {tol:.3e}"
+
+
+SMALL = [
+    # N, C, H, W, K, R, S, stride, pad
+    (1, 1, 1, 1, 1, 1, 1, 1, 0),
+    (1, 3, 5, 5, 2, 3, 3, 1, 0),
+    (2, 3, 33, 47, 35, 3, 3, 1, 1),
+    (2, 7, 30, 61, 70, 3, 3, 1, 1),
+    (3, 16, 29, 31, 130, 3, 3, 1, 1),
+    (1, 9, 40, 40, 33, 5, 5, 1, 2),
+    (2, 10, 27, 27, 129, 5, 5, 1, 2),
+    (2, 37, 19, 23, 65, 1, 1, 1, 0),
+    (1, 64, 57, 59, 96, 1, 1, 1, 0),
+    (2, 12, 57, 55, 130, 3, 3, 2, 1),
+    (2, 3, 75, 230, 64, 7, 7, 2, 3),
+    (2, 3, 99, 227, 96, 11, 11, 4, 0),
+    (1, 4, 50, 50, 20, 11, 11, 4, 5),
+    (2, 5, 9, 7, 33, 2, 4, 3, 2),
+    (1, 2, 5, 300, 3, 1, 7, 1, 3),
+    (2, 3, 50, 50, 20, 9, 9, 5, 4),
+    (1, 1, 4, 4, 1, 3, 3, 1, 3),
+    (1, 6, 20, 20, 8, 4, 2, 2, 0),
+]
+
+
+@pytest.mark.parametrize("shape", SMALL)
+def test_small_shapes_full_output(oracle, shape):
+    N, C, H, W, K, R, S, st, pd = shape
+    rng = np.random.default_rng(100 + sum(shape))
+    x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    w = rng.uniform(-1, 1, (K, C, R, S)).astype(np.float32)
+    got, info = _run(x, w, st, pd)
+    want = oracle.conv_forward(x, w, st, pd)
+    assert got.shape == want.shape
+    _assert_close(got, want, oracle.tolerance(C, R, S), f"{shape} via {info['variant']}")
+
+
+@pytest.mark.parametrize("shape", SMALL)
+def test_small_shapes_integer_inputs_bit_exact(oracle, shape):
+    N, C, H, W, K, R, S, st, pd = shape
+    rng = np.random.default_rng(200 + sum(shape))
+    x = rng.integers(-4, 5, (N, C, H, W)).astype(np.float32)
+    w = rng.integers(-4, 5, (K, C, R, S)).astype(np.float32)
+    assert C * R * S * 16 < 2 ** 24
+    got, info = _run(x, w, st, pd)
+    want = oracle.conv_forward(x, w, st, pd)
+    assert np.array_equal(got.astype(np.float64), want), f"{shape} via {info['variant']}"
+
+
+def _variant_shape(name):
+    m = re.match(r"f(\d+)s(\d+)_", name)
+    R, st = (int(m.group(1)), int(m.group(2))) if m else (4, 3)
+    return R, st
+
+
+@pytest.mark.parametrize("name", cd.variant_names())
+def test_every_variant_on_ragged_shape(oracle, name):
+    """Each compiled variant, forced, on a shape that leaves ragged tiles in every
+    dimension (K, C, rows, columns) and spans several tiles."""
+    R, st = _variant_shape(name)
+    N, C, K = 2, 11, 161
+    H, W = 61, 67
+    if R >= 7:
+        C = 3
+        H, W = 83, 241
+    pd = R // 2
+    rng = np.random.default_rng(300 + R + st)
+    x = rng.integers(-4, 5, (N, C, H, W)).astype(np.float32)
+    w = rng.integers(-4, 5, (K, C, R, R)).astype(np.float32)
+    got, info = _run(x, w, st, pd, variant=name)
+    assert info["variant"] == name
+    want = oracle.conv_forward(x, w, st, pd)
+    assert np.array_equal(got.astype(np.float64), want), name
+    xr = rng.uniform(-1, 1, x.shape).astype(np.float32)
+    wr = rng.uniform(-1, 1, w.shape).astype(np.float32)
+    got, _ = _run(xr, wr, st, pd, variant=name)
+    _assert_close(got, oracle.conv_forward(xr, wr, st, pd), oracle.tolerance(C, R, R), name)
+
+
+def test_toy_config_full(oracle):
+    l = workloads.TOY
+    x, w = workloads.make_inputs(l)
+    got, info = _run(x, w, l.stride, l.pad)
+    _assert_close(got, oracle.conv_forward(x, w, l.stride, l.pad), oracle.tolerance(l.C, l.R, l.S), l.name)
+
+
+@pytest.mark.parametrize("layer", [l for l in workloads.ALL_LAYERS if l is not workloads.TOY],
+                         ids=lambda l: l.name)
+def test_benchmark_layers_full_size(oracle, layer):
+    """Full-size layers in the launch configuration the benchmark times: the first and
+    last image in full where that is cheap, and a seeded sample of outputs everywhere."""
+    l = layer
+    x, w = workloads.make_inputs(l)
+    got, info = _run(x, w, l.stride, l.pad)
+    assert got.shape == (l.N, l.K, l.P, l.Q)
+    tol = oracle.tolerance(l.C, l.R, l.S)
+    pts = workloads.sample_points(l, 20000)
+    want = oracle.conv_forward_points(x, w, pts, l.stride, l.pad)
+    _assert_close(got[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]], want, tol, f"{l.name} sample")
+    per_image_flops = l.flops // l.N
+    if per_image_flops <= 1.0e9:
+        for n in sorted({0, l.N - 1}):
+            want = oracle.conv_forward(x[n:n + 1], w, l.stride, l.pad)
+            _assert_close(got[n:n + 1], want, tol, f"{l.name} image {n} via {info['variant']}")
+    assert not np.isnan(got).any(), "an output element was never written"
+
+
+def test_zero_workspace_and_no_allocation():
+    l = workloads.BY_NAME["alex_conv3_n64"]
+    x, w = workloads.make_inputs(l, N=4)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    out = torch.empty((4, l.K, l.P, l.Q), device="cuda")
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    alloc0, res0 = torch.cuda.memory_allocated(), torch.cuda.memory_reserved()
+    plan = cd.Plan(4, l.C, l.H, l.W, l.K, l.R, l.S, l.stride, l.pad)
+    assert plan.workspace_bytes() == 0
+    for _ in range(3):
+        plan.run(xd, wd, out)
+    torch.cuda.synchronize()
+    plan.destroy()
+    free1, _ = torch.cuda.mem_get_info()
+    assert torch.cuda.memory_allocated() == alloc0 and torch.cuda.memory_reserved() == res0
+    # the first launch may load the code object; nothing beyond that may be taken
+    assert free0 - free1 <= 64 * 1024 * 1024
+
+
+def test_runs_on_a_side_stream_and_is_repeatable(oracle):
+    l = workloads.TOY
+    x, w = workloads.make_inputs(l)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    out1 = torch.zeros((1, l.K, l.P, l.Q), device="cuda")
+    out2 = torch.zeros_like(out1)
+    plan = cd.Plan(*l.dims())
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    plan.run(xd, wd, out1, stream=st.cuda_stream)
+    plan.run(xd, wd, out2, stream=st.cuda_stream)
+    st.synchronize()
+    assert torch.equal(out1, out2)
+    _assert_close(out1.cpu().numpy(), oracle.conv_forward(x, w, l.stride, l.pad),
+                  oracle.tolerance(l.C, l.R, l.S), "side stream")
+    plan.destroy()
+
+
+def test_unaligned_by_four_bytes_pointers(oracle):
+    """Pointers need 4-byte alignment only: offset every tensor by one float."""
+    N, C, H, W, K, R, S, st, pd = 2, 8, 20, 22, 40, 3, 3, 1, 1
+    rng = np.random.default_rng(7)
+    x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    w = rng.uniform(-1, 1, (K, C, R, S)).astype(np.float32)
+    xb = torch.zeros(x.size + 1, device="cuda")
+    wb = torch.zeros(w.size + 1, device="cuda")
+    xb[1:] = torch.from_numpy(x).cuda().reshape(-1)
+    wb[1:] = torch.from_numpy(w).cuda().reshape(-1)
+    plan = cd.Plan(N, C, H, W, K, R, S, st, pd)
+    P, Q = plan.output_dims()
+    ob = torch.full((N * K * P * Q + 1,), float("nan"), device="cuda")
+    plan.run_ptr(xb.data_ptr() + 4, wb.data_ptr() + 4, ob.data_ptr() + 4,
+                 torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    plan.destroy()
+    got = ob[1:].reshape(N, K, P, Q).cpu().numpy()
+    _assert_close(got, oracle.conv_forward(x, w, st, pd), oracle.tolerance(C, R, S), "offset pointers")
+    assert torch.isnan(ob[0]).item()   # the float before the output was not touched
