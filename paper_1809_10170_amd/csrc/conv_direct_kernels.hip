@@ -125,6 +125,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
     if (G::PAIR == PAIR_S && (G::S & 1)) {
         // the zero weight that pads an odd filter width is written once
         for (int e = tid; e < G::LDS_A; e += G::NT) ldsA[e] = 0.f;
+        __syncthreads();   // other threads stage real weights into these rows next
     }
 
     constexpr int NB = G::CB * G::LH * G::LW;          // input elements per chunk
