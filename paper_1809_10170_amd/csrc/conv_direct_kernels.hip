@@ -26,6 +26,8 @@
 // is a correct convolution (Section 3, "any permutation of the loops").
 #include <hip/hip_runtime.h>
 
+#include <cstdint>
+
 #include "variant.h"
 
 namespace convd {
@@ -33,8 +35,9 @@ namespace convd {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 template <int R_, int S_, int ST_, int TP_, int TQ_, int KBW_, int PBW_, int WK_, int WP_, int CB_,
-          int PAIR_, int OCC_>
+          int PAIR_, int OCC_, int PREF_>
 struct Geom {
+    static constexpr int PREF = PREF_;                 // 1: prefetch the next chunk into registers
     static constexpr int R = R_, S = S_, ST = ST_, TP = TP_, TQ = TQ_;
     static constexpr int KBW = KBW_, PBW = PBW_, WK = WK_, WP = WP_, CB = CB_, PAIR = PAIR_, OCC = OCC_;
     static constexpr int NT = 64 * WK * WP;            // threads per workgroup
@@ -60,24 +63,25 @@ struct Geom {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
 };
 
-// Global -> LDS staging helper: N_IT elements per thread, BATCH loads in flight
-// before their LDS stores (bounds the registers the staging needs).
-template <int N_IT, int BATCH, class LoadF, class StoreF>
-__device__ __forceinline__ void stage(LoadF ld, StoreF st)
-{
-#pragma unroll
-    for (int i0 = 0; i0 < N_IT; i0 += BATCH) {
-        float v[BATCH];
-#pragma unroll
-        for (int b = 0; b < BATCH; ++b)
-            if (i0 + b < N_IT) v[b] = ld(i0 + b);
-#pragma unroll
-        for (int b = 0; b < BATCH; ++b)
-            if (i0 + b < N_IT) st(i0 + b, v[b]);
-    }
-}
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-template <class G>
+// One global load of WV consecutive filter values (WV = 1 or 4).
+template <int WV> struct WLoad;
+template <> struct WLoad<1> {
+    typedef float type;
+    static __device__ __forceinline__ float ld(const float *p) { return *p; }
+    static __device__ __forceinline__ float get(float v, int) { return v; }
+};
+template <> struct WLoad<4> {
+    typedef floatx4 type;
+    static __device__ __forceinline__ floatx4 ld(const float *p) { return *reinterpret_cast<const floatx4 *>(p); }
+    static __device__ __forceinline__ float get(floatx4 v, int u) { return v[u]; }
+};
+
+// G: tile geometry.  WV: filter values per global load; 4 needs a 16-byte aligned
+// filter pointer, C*R*S and CB*R*S multiples of 4 and C a multiple of CB (the launcher
+// checks), 1 works for anything.
+template <class G, int WV>
 __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelArgs a)
 {
     extern __shared__ __align__(16) float lds[];
@@ -128,49 +132,50 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
         __syncthreads();   // other threads stage real weights into these rows next
     }
 
+    constexpr int CRS = G::CB * G::RS;                 // filter values per output channel and chunk
     constexpr int NB = G::CB * G::LH * G::LW;          // input elements per chunk
     constexpr int NB_IT = (NB + G::NT - 1) / G::NT;
-    constexpr int NA = G::KT * G::CB * G::RS;          // filter elements per chunk
+    constexpr int NA = G::KT * CRS / WV;               // filter loads per chunk
     constexpr int NA_IT = (NA + G::NT - 1) / G::NT;
+    static_assert(CRS % WV == 0, "vector filter loads must not straddle output channels");
+    typedef typename WLoad<WV>::type wvec;
 
-    for (int c0 = 0; c0 < C; c0 += G::CB) {
-        // Keep the per-element index arithmetic inside the loop: hoisted out, it would
-        // occupy more registers than the accumulators leave free.
-        int t = tid;
-        asm volatile("" : "+v"(t));
-        // ---- stage the chunk: global -> registers -> LDS, a batch of loads at a time ----
-        stage<NB_IT, G::SB>(
-            [&](int i) {
-                const int e = t + i * G::NT;
-                const int cc = e / (G::LH * G::LW);
-                const int rem = e - cc * (G::LH * G::LW);
-                const int hh = rem / G::LW, ww = rem - hh * G::LW;
-                const int ih = ih0 + hh, iw = iw0 + ww, c = c0 + cc;
-                const bool ok = e < NB && c < C && (unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W;
-                const float v = in_n[ok ? (c * H + ih) * W + iw : 0];
-                return ok ? v : 0.f;
-            },
-            [&](int i, float v) {
-                const int e = t + i * G::NT;
-                const int cc = e / (G::LH * G::LW);
-                const int rem = e - cc * (G::LH * G::LW);
-                const int hh = rem / G::LW, ww = rem - hh * G::LW;
-                if ((i + 1) * G::NT <= NB || e < NB) ldsB[cc * G::PS + hh * G::LWP + ww] = v;
-            });
-        stage<NA_IT, G::SB>(
-            [&](int i) {
-                const int e = t + i * G::NT;
-                const int kk = e / (G::CB * G::RS);
-                const int jj = e - kk * (G::CB * G::RS);
-                const int cc = jj / G::RS;
-                const bool ok = e < NA && k0 + kk < K && c0 + cc < C;
-                const float v = w_k[ok ? (kk * C + c0) * G::RS + jj : 0];
-                return ok ? v : 0.f;
-            },
-            [&](int i, float v) {
-                const int e = t + i * G::NT;
-                const int kk = e / (G::CB * G::RS);
-                const int jj = e - kk * (G::CB * G::RS);
+    // ---- staging primitives: element i of thread t (index math stays inside the loop) ----
+    auto in_load = [&](int t, int c0, int i) -> float {
+        const int e = t + i * G::NT;
+        const int cc = e / (G::LH * G::LW);
+        const int rem = e - cc * (G::LH * G::LW);
+        const int hh = rem / G::LW, ww = rem - hh * G::LW;
+        const int ih = ih0 + hh, iw = iw0 + ww, c = c0 + cc;
+        const bool ok = e < NB && c < C && (unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W;
+        const float v = in_n[ok ? (unsigned)((c * H + ih) * W + iw) : 0u];
+        return ok ? v : 0.f;
+    };
+    auto in_store = [&](int t, int i, float v) {
+        const int e = t + i * G::NT;
+        const int cc = e / (G::LH * G::LW);
+        const int rem = e - cc * (G::LH * G::LW);
+        const int hh = rem / G::LW, ww = rem - hh * G::LW;
+        if ((i + 1) * G::NT <= NB || e < NB) ldsB[cc * G::PS + hh * G::LWP + ww] = v;
+    };
+    auto w_load = [&](int t, int c0, int i) -> wvec {
+        const int e = (t + i * G::NT) * WV;
+        const int kk = e / CRS;
+        const int jj = e - kk * CRS;
+        // with WV = 4 the launcher guarantees C % CB == 0, so the channel test is uniform
+        const bool ok = e < NA * WV && k0 + kk < K && c0 + jj / G::RS < C;
+        wvec v = WLoad<WV>::ld(w_k + (ok ? (unsigned)((kk * C + c0) * G::RS + jj) : 0u));
+        if (!ok) v = wvec(0.f);
+        return v;
+    };
+    auto w_store = [&](int t, int i, wvec v) {
+        const int e = (t + i * G::NT) * WV;
+        const int kk = e / CRS;
+        const int jj0 = e - kk * CRS;
+        if ((i + 1) * G::NT <= NA || e < NA * WV) {
+#pragma unroll
+            for (int u = 0; u < WV; ++u) {
+                const int jj = jj0 + u;
                 const int cc = jj / G::RS, rs = jj - cc * G::RS;
                 int slot;
                 if (G::PAIR == PAIR_C) {
@@ -179,11 +184,16 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
                     const int r = rs / G::S, s = rs - r * G::S;
                     slot = ((cc * G::R + r) * G::S2 + (s >> 1)) * 2 + (s & 1);
                 }
-                if ((i + 1) * G::NT <= NA || e < NA) ldsA[slot * G::KP + kk] = v;
-            });
-        __syncthreads();
+                ldsA[slot * G::KP + kk] = WLoad<WV>::get(v, u);
+            }
+        }
+    };
+    // Hoisted out of the chunk loop, the per-element index arithmetic would occupy more
+    // registers than the accumulators leave free: this keeps it inside.
+    auto opaque_tid = [&]() { int t = tid; asm volatile("" : "+v"(t)); return t; };
 
-        // ---- the reduction over this chunk: STEPS rank-2 updates of the tile ----
+    // ---- the reduction over one staged chunk: STEPS rank-2 updates of the tile ----
+    auto compute = [&]() {
 #pragma unroll
         for (int step = 0; step < G::STEPS; ++step) {
             int boff;
@@ -207,7 +217,67 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
                 for (int pb = 0; pb < G::PBW; ++pb)
                     acc[kb][pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[kb], bv[pb], acc[kb][pb], 0, 0, 0);
         }
-        __syncthreads();
+    };
+
+    if (G::PREF) {
+        // Software pipeline: the next chunk's global loads are in flight while this
+        // chunk's MFMAs run; their LDS stores follow the barrier that ends the reads.
+        float vb[NB_IT];
+        wvec va[NA_IT];
+        {
+            const int t = opaque_tid();
+#pragma unroll
+            for (int i = 0; i < NB_IT; ++i) vb[i] = in_load(t, 0, i);
+#pragma unroll
+            for (int i = 0; i < NA_IT; ++i) va[i] = w_load(t, 0, i);
+        }
+        for (int c0 = 0; c0 < C; c0 += G::CB) {
+            {
+                const int t = opaque_tid();
+#pragma unroll
+                for (int i = 0; i < NB_IT; ++i) in_store(t, i, vb[i]);
+#pragma unroll
+                for (int i = 0; i < NA_IT; ++i) w_store(t, i, va[i]);
+            }
+            __syncthreads();
+            if (c0 + G::CB < C) {
+                const int t = opaque_tid();
+#pragma unroll
+                for (int i = 0; i < NB_IT; ++i) vb[i] = in_load(t, c0 + G::CB, i);
+#pragma unroll
+                for (int i = 0; i < NA_IT; ++i) va[i] = w_load(t, c0 + G::CB, i);
+            }
+            compute();
+            __syncthreads();
+        }
+    } else {
+        for (int c0 = 0; c0 < C; c0 += G::CB) {
+            const int t = opaque_tid();
+            // global -> registers -> LDS, a bounded batch of loads at a time
+#pragma unroll
+            for (int i0 = 0; i0 < NB_IT; i0 += G::SB) {
+                float v[G::SB];
+#pragma unroll
+                for (int b = 0; b < G::SB; ++b)
+                    if (i0 + b < NB_IT) v[b] = in_load(t, c0, i0 + b);
+#pragma unroll
+                for (int b = 0; b < G::SB; ++b)
+                    if (i0 + b < NB_IT) in_store(t, i0 + b, v[b]);
+            }
+#pragma unroll
+            for (int i0 = 0; i0 < NA_IT; i0 += G::SB) {
+                wvec v[G::SB];
+#pragma unroll
+                for (int b = 0; b < G::SB; ++b)
+                    if (i0 + b < NA_IT) v[b] = w_load(t, c0, i0 + b);
+#pragma unroll
+                for (int b = 0; b < G::SB; ++b)
+                    if (i0 + b < NA_IT) w_store(t, i0 + b, v[b]);
+            }
+            __syncthreads();
+            compute();
+            __syncthreads();
+        }
     }
 
     // ---- epilogue: each output element is written exactly once ----
@@ -323,13 +393,26 @@ static hipError_t allow_lds(const void *fn, size_t bytes)
     return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
+template <class G, int WV>
+static hipError_t launch_tile_wv(const KernelArgs &a, unsigned grid, hipStream_t stream)
+{
+    hipError_t e = allow_lds(reinterpret_cast<const void *>(&conv_tile_kernel<G, WV>), G::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((conv_tile_kernel<G, WV>), dim3(grid), dim3(G::NT), G::LDS_BYTES, stream, a);
+    return hipGetLastError();
+}
+
 template <class G>
 static hipError_t launch_tile(const KernelArgs &a, unsigned grid, hipStream_t stream)
 {
-    hipError_t e = allow_lds(reinterpret_cast<const void *>(&conv_tile_kernel<G>), G::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(conv_tile_kernel<G>, dim3(grid), dim3(G::NT), G::LDS_BYTES, stream, a);
-    return hipGetLastError();
+    // 16-byte filter loads when every one of them is aligned and stays inside one
+    // output channel's row; plain 4-byte loads otherwise (any pointer, any C).
+    constexpr bool can4 = G::PAIR == PAIR_C && (G::CB * G::RS) % 4 == 0;
+    if (can4) {
+        const bool ok4 = ((uintptr_t)a.w & 15u) == 0 && (a.s.C * G::RS) % 4 == 0 && a.s.C % G::CB == 0;
+        if (ok4) return launch_tile_wv<G, can4 ? 4 : 1>(a, grid, stream);
+    }
+    return launch_tile_wv<G, 1>(a, grid, stream);
 }
 
 template <class G>
@@ -349,36 +432,36 @@ static hipError_t launch_generic(const KernelArgs &a, unsigned grid, hipStream_t
     return hipGetLastError();
 }
 
-#define TILE_VARIANT(NAME, R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC)                        \
+#define TILE_VARIANT(NAME, R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC, PREF)                        \
     {                                                                                               \
-        NAME, R, S, ST, TP, TQ, Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC>::KT,       \
-            Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC>::NPB, CB, PAIR,                \
-            Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC>::NT, OCC,                      \
-            &lds_tile<Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC>>,                    \
-            &launch_tile<Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC>>                  \
+        NAME, R, S, ST, TP, TQ, Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC, PREF>::KT,       \
+            Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC, PREF>::NPB, CB, PAIR,                \
+            Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC, PREF>::NT, OCC,                      \
+            &lds_tile<Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC, PREF>>,                    \
+            &launch_tile<Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC, PREF>>                  \
     }
 
-// name, R, S, stride, TP, TQ, KBW, PBW, WK, WP, CB, pair, workgroups/CU
+// name, R, S, stride, TP, TQ, KBW, PBW, WK, WP, CB, pair, workgroups/CU, prefetch
 static const Variant k_variants[] = {
     // 3x3 stride 1: 224-pixel tiles (7 blocks), 128 or 64 output channels
-    TILE_VARIANT("f3s1_1x224_k128", 3, 3, 1, 1, 224, 1, 7, 4, 1, 8, PAIR_C, 2),
-    TILE_VARIANT("f3s1_2x112_k128", 3, 3, 1, 2, 112, 1, 7, 4, 1, 8, PAIR_C, 2),
-    TILE_VARIANT("f3s1_4x56_k128", 3, 3, 1, 4, 56, 1, 7, 4, 1, 8, PAIR_C, 2),
-    TILE_VARIANT("f3s1_8x28_k128", 3, 3, 1, 8, 28, 1, 7, 4, 1, 8, PAIR_C, 2),
-    TILE_VARIANT("f3s1_14x14_k128", 3, 3, 1, 14, 14, 1, 7, 4, 1, 8, PAIR_C, 2),
-    TILE_VARIANT("f3s1_13x13_k128", 3, 3, 1, 13, 13, 1, 6, 4, 1, 8, PAIR_C, 2),
-    TILE_VARIANT("f3s1_2x224_k64", 3, 3, 1, 2, 224, 1, 7, 2, 2, 8, PAIR_C, 2),
-    TILE_VARIANT("f3s1_7x32_k32_c3", 3, 3, 1, 7, 32, 1, 7, 1, 1, 3, PAIR_S, 4),
+    TILE_VARIANT("f3s1_1x224_k128", 3, 3, 1, 1, 224, 1, 7, 4, 1, 8, PAIR_C, 2, 1),
+    TILE_VARIANT("f3s1_2x112_k128", 3, 3, 1, 2, 112, 1, 7, 4, 1, 8, PAIR_C, 2, 1),
+    TILE_VARIANT("f3s1_4x56_k128", 3, 3, 1, 4, 56, 1, 7, 4, 1, 8, PAIR_C, 2, 1),
+    TILE_VARIANT("f3s1_8x28_k128", 3, 3, 1, 8, 28, 1, 7, 4, 1, 8, PAIR_C, 2, 1),
+    TILE_VARIANT("f3s1_14x14_k128", 3, 3, 1, 14, 14, 1, 7, 4, 1, 8, PAIR_C, 2, 1),
+    TILE_VARIANT("f3s1_13x13_k128", 3, 3, 1, 13, 13, 1, 6, 4, 1, 8, PAIR_C, 2, 1),
+    TILE_VARIANT("f3s1_2x224_k64", 3, 3, 1, 2, 224, 1, 7, 2, 2, 8, PAIR_C, 2, 1),
+    TILE_VARIANT("f3s1_7x32_k32_c3", 3, 3, 1, 7, 32, 1, 7, 1, 1, 3, PAIR_S, 4, 0),
     // 5x5 stride 1
-    TILE_VARIANT("f5s1_9x27_k128", 5, 5, 1, 9, 27, 1, 8, 4, 1, 4, PAIR_C, 2),
+    TILE_VARIANT("f5s1_9x27_k128", 5, 5, 1, 9, 27, 1, 8, 4, 1, 2, PAIR_C, 2, 1),
     // 1x1
-    TILE_VARIANT("f1s1_4x56_k64", 1, 1, 1, 4, 56, 1, 7, 2, 1, 32, PAIR_C, 4),
-    TILE_VARIANT("f1s1_4x56_k128", 1, 1, 1, 4, 56, 1, 7, 4, 1, 32, PAIR_C, 2),
+    TILE_VARIANT("f1s1_4x56_k64", 1, 1, 1, 4, 56, 1, 7, 2, 1, 32, PAIR_C, 4, 1),
+    TILE_VARIANT("f1s1_4x56_k128", 1, 1, 1, 4, 56, 1, 7, 4, 1, 32, PAIR_C, 2, 1),
     // 3x3 stride 2
-    TILE_VARIANT("f3s2_8x28_k128", 3, 3, 2, 8, 28, 1, 7, 4, 1, 8, PAIR_C, 2),
+    TILE_VARIANT("f3s2_8x28_k128", 3, 3, 2, 8, 28, 1, 7, 4, 1, 4, PAIR_C, 2, 1),
     // first layers (3 input channels): pairs of filter columns
-    TILE_VARIANT("f7s2_2x112_k64_c3", 7, 7, 2, 2, 112, 1, 7, 2, 1, 3, PAIR_S, 2),
-    TILE_VARIANT("f11s4_4x55_k96_c3", 11, 11, 4, 4, 55, 1, 7, 3, 1, 1, PAIR_S, 2),
+    TILE_VARIANT("f7s2_2x112_k64_c3", 7, 7, 2, 2, 112, 1, 7, 2, 1, 3, PAIR_S, 2, 0),
+    TILE_VARIANT("f11s4_4x55_k96_c3", 11, 11, 4, 4, 55, 1, 7, 3, 1, 1, PAIR_S, 2, 0),
     // any shape
     {"generic_2x32_k64", 0, 0, 0, GenericGeom::TP, GenericGeom::TQ, GenericGeom::KT, 2, 2, PAIR_C,
      GenericGeom::NT, 2, &lds_generic, &launch_generic},
