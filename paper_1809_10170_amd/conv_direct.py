@@ -10,7 +10,8 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libconv_direct.so")
+# CONV_DIRECT_LIB overrides the library path (e.g. an experimental build of the same ABI)
+LIB_PATH = os.environ.get("CONV_DIRECT_LIB") or os.path.join(_HERE, "libconv_direct.so")
 
 OK, EINVAL, EUNSUPPORTED, EALIGN, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5
 

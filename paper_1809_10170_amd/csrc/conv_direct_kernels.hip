@@ -42,6 +42,7 @@ struct Geom {
     static constexpr int KBW = KBW_, PBW = PBW_, WK = WK_, WP = WP_, CB = CB_, PAIR = PAIR_, OCC = OCC_;
     static constexpr int NT = 64 * WK * WP;            // threads per workgroup
     static constexpr int WPE = (OCC * WK * WP + 3) / 4; // waves per SIMD the register budget must allow
+    static constexpr int UNROLL_OUTER = 1;             // unroll factor of the channel loop inside a chunk
     static constexpr int SB = 8;                       // staging loads in flight per thread
     static constexpr int KT = 32 * KBW * WK;           // output channels per workgroup
     static constexpr int NPB = PBW * WP;               // 32-pixel blocks per workgroup
@@ -132,147 +133,236 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
         __syncthreads();   // other threads stage real weights into these rows next
     }
 
-    constexpr int CRS = G::CB * G::RS;                 // filter values per output channel and chunk
-    constexpr int NB = G::CB * G::LH * G::LW;          // input elements per chunk
-    constexpr int NB_IT = (NB + G::NT - 1) / G::NT;
-    constexpr int NA = G::KT * CRS / WV;               // filter loads per chunk
-    constexpr int NA_IT = (NA + G::NT - 1) / G::NT;
+    // ---- staging: global -> registers -> LDS ----
+    // Work is dealt to waves by rows, so that everything about an element except its
+    // column is wave-uniform (scalar registers) or a compile-time constant: an input
+    // row is one (channel, halo row) pair read by consecutive lanes; a filter row is
+    // the CB*R*S contiguous values of one output channel.
+    constexpr int NW = G::NT / 64;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    // Re-read through an opaque scalar wherever elements are enumerated: hoisted out of
+    // the chunk loop, the per-element scalars would not fit the scalar register file.
+    auto wave_id = [&]() { int t = wave_u; asm volatile("" : "+s"(t)); return t; };
+
+    // input halo window: ROWS rows of LW columns, SEGS lane-segments per row; narrow
+    // windows put two channels (sub = 0, 1) side by side in one 64-lane access
+    constexpr int SUBS = (G::LW <= 32 && G::CB % 2 == 0) ? 2 : 1;
+    constexpr int SEGW = 64 / SUBS;
+    constexpr int SEGS = (G::LW + SEGW - 1) / SEGW;
+    constexpr int ROWS = (G::CB / SUBS) * G::LH;
+    constexpr int ROW_IT = (ROWS + NW - 1) / NW;
+    constexpr int NB_IT = ROW_IT * SEGS;
+    const int sub = SUBS == 2 ? (lane >> 5) : 0;
+    const int lcol = SUBS == 2 ? (lane & 31) : lane;
+    const int in_lane_goff = sub * H * W + lcol;
+    const int in_lane_loff = sub * G::PS + lcol;
+
+    // Validity and address of input element i of this lane; loads return the raw
+    // value (from a safe address when invalid) and the zero fill happens at store
+    // time, so that nothing has to touch a prefetched register before its store.
+    auto in_addr = [&](int wave_s, int c0, int i, bool &ok) -> unsigned {
+        const int ir = i / SEGS, seg = i - ir * SEGS;
+        const int rowg = ir * NW + wave_s;
+        const int cg = rowg / G::LH, hh = rowg - cg * G::LH;
+        const int ih = ih0 + hh;
+        const int col = seg * SEGW + lcol;
+        const int iw = iw0 + col;
+        ok = rowg < ROWS && (unsigned)ih < (unsigned)H && c0 + cg * SUBS + sub < C &&
+             col < G::LW && (unsigned)iw < (unsigned)W;
+        const int off = ((c0 + cg * SUBS) * H + ih) * W + iw0 + seg * SEGW + in_lane_goff;
+        return ok ? (unsigned)off : 0u;
+    };
+    auto in_load = [&](int wave_s, int c0, int i) -> float {
+        bool ok;
+        return in_n[in_addr(wave_s, c0, i, ok)];
+    };
+    auto in_store = [&](int wave_s, int c0, int i, float v) {
+        bool ok;
+        (void)in_addr(wave_s, c0, i, ok);
+        const int ir = i / SEGS, seg = i - ir * SEGS;
+        const int rowg = ir * NW + wave_s;
+        const int cg = rowg / G::LH, hh = rowg - cg * G::LH;
+        if (rowg < ROWS && seg * SEGW + lcol < G::LW)
+            ldsB[cg * SUBS * G::PS + hh * G::LWP + seg * SEGW + in_lane_loff] = ok ? v : 0.f;
+    };
+
+    // filter slice: KT rows of CRS values, read WV at a time; short rows are packed
+    // RPI to a 64-lane access, long rows take WSEGS accesses
+    constexpr int CRS = G::CB * G::RS;
     static_assert(CRS % WV == 0, "vector filter loads must not straddle output channels");
     typedef typename WLoad<WV>::type wvec;
-
-    // ---- staging primitives: element i of thread t (index math stays inside the loop) ----
-    auto in_load = [&](int t, int c0, int i) -> float {
-        const int e = t + i * G::NT;
-        const int cc = e / (G::LH * G::LW);
-        const int rem = e - cc * (G::LH * G::LW);
-        const int hh = rem / G::LW, ww = rem - hh * G::LW;
-        const int ih = ih0 + hh, iw = iw0 + ww, c = c0 + cc;
-        const bool ok = e < NB && c < C && (unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W;
-        const float v = in_n[ok ? (unsigned)((c * H + ih) * W + iw) : 0u];
-        return ok ? v : 0.f;
-    };
-    auto in_store = [&](int t, int i, float v) {
-        const int e = t + i * G::NT;
-        const int cc = e / (G::LH * G::LW);
-        const int rem = e - cc * (G::LH * G::LW);
-        const int hh = rem / G::LW, ww = rem - hh * G::LW;
-        if ((i + 1) * G::NT <= NB || e < NB) ldsB[cc * G::PS + hh * G::LWP + ww] = v;
-    };
-    auto w_load = [&](int t, int c0, int i) -> wvec {
-        const int e = (t + i * G::NT) * WV;
-        const int kk = e / CRS;
-        const int jj = e - kk * CRS;
-        // with WV = 4 the launcher guarantees C % CB == 0, so the channel test is uniform
-        const bool ok = e < NA * WV && k0 + kk < K && c0 + jj / G::RS < C;
-        wvec v = WLoad<WV>::ld(w_k + (ok ? (unsigned)((kk * C + c0) * G::RS + jj) : 0u));
-        if (!ok) v = wvec(0.f);
-        return v;
-    };
-    auto w_store = [&](int t, int i, wvec v) {
-        const int e = (t + i * G::NT) * WV;
-        const int kk = e / CRS;
-        const int jj0 = e - kk * CRS;
-        if ((i + 1) * G::NT <= NA || e < NA * WV) {
+    constexpr int V = CRS / WV;
+    constexpr int RPI = V <= 64 ? 64 / V : 1;
+    constexpr int WSEGS = V <= 64 ? 1 : (V + 63) / 64;
+    constexpr int KGRPS = (G::KT + RPI - 1) / RPI;
+    constexpr int KG_IT = (KGRPS + NW - 1) / NW;
+    constexpr int NA_IT = KG_IT * WSEGS;
+    const int ksub = V <= 64 ? lane / V : 0;
+    const int jl = V <= 64 ? lane - ksub * V : lane;
+    const bool wlane_ok = ksub < RPI;
+    const int w_lane_goff = ksub * C * G::RS + jl * WV;
+    int aslot[WSEGS][WV];   // LDS position of each value this lane loads, per segment
 #pragma unroll
-            for (int u = 0; u < WV; ++u) {
-                const int jj = jj0 + u;
-                const int cc = jj / G::RS, rs = jj - cc * G::RS;
-                int slot;
-                if (G::PAIR == PAIR_C) {
-                    slot = ((cc >> 1) * G::RS + rs) * 2 + (cc & 1);
-                } else {
-                    const int r = rs / G::S, s = rs - r * G::S;
-                    slot = ((cc * G::R + r) * G::S2 + (s >> 1)) * 2 + (s & 1);
-                }
-                ldsA[slot * G::KP + kk] = WLoad<WV>::get(v, u);
+    for (int seg = 0; seg < WSEGS; ++seg)
+#pragma unroll
+        for (int u = 0; u < WV; ++u) {
+            const int jj = (seg * 64 + jl) * WV + u;
+            const int cc = jj / G::RS, rs = jj - cc * G::RS;
+            int slot;
+            if (G::PAIR == PAIR_C) {
+                slot = ((cc >> 1) * G::RS + rs) * 2 + (cc & 1);
+            } else {
+                const int r = rs / G::S, ss = rs - r * G::S;
+                slot = ((cc * G::R + r) * G::S2 + (ss >> 1)) * 2 + (ss & 1);
             }
+            aslot[seg][u] = jj < CRS ? slot * G::KP + ksub : 0;
+        }
+
+    auto w_addr = [&](int wave_s, int c0, int i, bool &ok) -> unsigned {
+        const int ik = i / WSEGS, seg = i - ik * WSEGS;
+        const int kg = ik * NW + wave_s;
+        const int kk = kg * RPI + ksub;
+        const int jj = (seg * 64 + jl) * WV;
+        // with WV = 4 the launcher guarantees C % CB == 0, so a load never straddles the
+        // end of the channels; with WV = 1 the last test cuts the channel tail
+        ok = wlane_ok && kk < G::KT && k0 + kk < K && jj < CRS && jj < (C - c0) * G::RS;
+        const int off = (kg * RPI * C + c0) * G::RS + seg * 64 * WV + w_lane_goff;
+        return ok ? (unsigned)off : 0u;
+    };
+    auto w_load = [&](int wave_s, int c0, int i) -> wvec {
+        bool ok;
+        return WLoad<WV>::ld(w_k + w_addr(wave_s, c0, i, ok));
+    };
+    auto w_store = [&](int wave_s, int c0, int i, wvec v) {
+        bool ok;
+        (void)w_addr(wave_s, c0, i, ok);
+        const int ik = i / WSEGS, seg = i - ik * WSEGS;
+        const int kg = ik * NW + wave_s;
+        const int kk = kg * RPI + ksub;
+        if (wlane_ok && kk < G::KT) {
+#pragma unroll
+            for (int u = 0; u < WV; ++u)
+                if ((seg * 64 + jl) * WV + u < CRS)
+                    ldsA[aslot[seg][u] + kg * RPI] = ok ? WLoad<WV>::get(v, u) : 0.f;
         }
     };
-    // Hoisted out of the chunk loop, the per-element index arithmetic would occupy more
-    // registers than the accumulators leave free: this keeps it inside.
-    auto opaque_tid = [&]() { int t = tid; asm volatile("" : "+v"(t)); return t; };
 
     // ---- the reduction over one staged chunk: STEPS rank-2 updates of the tile ----
+    // Outer loop over channel pairs (PAIR_C) or channels (PAIR_S) is a real loop, the
+    // filter taps inside it are unrolled with constant LDS offsets.
+    constexpr int OUTER = G::PAIR == PAIR_C ? G::CB / 2 : G::CB;
+    constexpr int INNER = G::STEPS / OUTER;                       // taps (PAIR_C) or tap pairs (PAIR_S)
+    constexpr int B_OUTER = G::PAIR == PAIR_C ? 2 * G::PS : G::PS; // LDS floats per outer step, input
+    constexpr int A_OUTER = INNER * 2 * G::KP;                    // LDS floats per outer step, filter
+    // LDS -> register operand fetches for tap t of outer step o
+    auto fetch_a = [&](int o, int t, float (&av)[G::KBW]) {
+        const float *pa = ldsA + abase + o * A_OUTER;
+#pragma unroll
+        for (int kb = 0; kb < G::KBW; ++kb) av[kb] = pa[t * 2 * G::KP + kb * 32];
+    };
+    auto fetch_b = [&](int o, int t, float (&bv)[G::PBW]) {
+        const float *pbase = ldsB + o * B_OUTER;
+        int boff;
+        if (G::PAIR == PAIR_C) {
+            const int r = t / G::S, ss = t - r * G::S;
+            boff = r * G::LWP + ss;
+        } else {
+            const int r = t / G::S2, s2 = t - r * G::S2;
+            boff = r * G::LWP + 2 * s2;
+        }
+#pragma unroll
+        for (int pb = 0; pb < G::PBW; ++pb) bv[pb] = pbase[bbase[pb] + boff];
+    };
+    // Software-pipelined: while the MFMAs of one tap issue, the input operands of the
+    // next tap and the filter operand of the tap after it are fetched; the scheduling
+    // hints pin one LDS read behind each MFMA.  Fetches past the end of the chunk are
+    // clamped to its last outer step (their values are never used).
     auto compute = [&]() {
+        float a0[G::KBW], a1[G::KBW], b0[G::PBW];
+        fetch_a(0, 0, a0);
+        fetch_b(0, 0, b0);
+        fetch_a((1 / INNER) < OUTER ? 1 / INNER : OUTER - 1, 1 % INNER, a1);
+#pragma unroll G::UNROLL_OUTER
+        for (int o = 0; o < OUTER; ++o) {
 #pragma unroll
-        for (int step = 0; step < G::STEPS; ++step) {
-            int boff;
-            if (G::PAIR == PAIR_C) {
-                const int c2 = step / G::RS, rs = step - c2 * G::RS;
-                const int r = rs / G::S, s = rs - r * G::S;
-                boff = c2 * 2 * G::PS + r * G::LWP + s;
-            } else {
-                const int cc = step / (G::R * G::S2), rem = step - cc * (G::R * G::S2);
-                const int r = rem / G::S2, s2 = rem - r * G::S2;
-                boff = cc * G::PS + r * G::LWP + 2 * s2;
+            for (int t = 0; t < INNER; ++t) {
+                float a2[G::KBW], b1[G::PBW];
+                // taps are numbered o*INNER + t; fetch tap +1 (input) and tap +2 (filter)
+                const int o1 = o + (t + 1) / INNER, o2 = o + (t + 2) / INNER;
+                fetch_b(o1 < OUTER ? o1 : OUTER - 1, (t + 1) % INNER, b1);
+                fetch_a(o2 < OUTER ? o2 : OUTER - 1, (t + 2) % INNER, a2);
+#pragma unroll
+                for (int kb = 0; kb < G::KBW; ++kb)
+#pragma unroll
+                    for (int pb = 0; pb < G::PBW; ++pb)
+                        acc[kb][pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[kb], b0[pb], acc[kb][pb], 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < G::KBW * G::PBW; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                }
+#pragma unroll
+                for (int kb = 0; kb < G::KBW; ++kb) { a0[kb] = a1[kb]; a1[kb] = a2[kb]; }
+#pragma unroll
+                for (int pb = 0; pb < G::PBW; ++pb) b0[pb] = b1[pb];
             }
-            float av[G::KBW], bv[G::PBW];
-#pragma unroll
-            for (int kb = 0; kb < G::KBW; ++kb) av[kb] = ldsA[abase + step * 2 * G::KP + kb * 32];
-#pragma unroll
-            for (int pb = 0; pb < G::PBW; ++pb) bv[pb] = ldsB[bbase[pb] + boff];
-#pragma unroll
-            for (int kb = 0; kb < G::KBW; ++kb)
-#pragma unroll
-                for (int pb = 0; pb < G::PBW; ++pb)
-                    acc[kb][pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[kb], bv[pb], acc[kb][pb], 0, 0, 0);
         }
     };
 
-    if (G::PREF) {
+    if (G::PREF && WV == 4) {
         // Software pipeline: the next chunk's global loads are in flight while this
         // chunk's MFMAs run; their LDS stores follow the barrier that ends the reads.
         float vb[NB_IT];
         wvec va[NA_IT];
         {
-            const int t = opaque_tid();
+            const int ws = wave_id();
 #pragma unroll
-            for (int i = 0; i < NB_IT; ++i) vb[i] = in_load(t, 0, i);
+            for (int i = 0; i < NB_IT; ++i) vb[i] = in_load(ws, 0, i);
 #pragma unroll
-            for (int i = 0; i < NA_IT; ++i) va[i] = w_load(t, 0, i);
+            for (int i = 0; i < NA_IT; ++i) va[i] = w_load(ws, 0, i);
         }
         for (int c0 = 0; c0 < C; c0 += G::CB) {
             {
-                const int t = opaque_tid();
+                const int ws = wave_id();
 #pragma unroll
-                for (int i = 0; i < NB_IT; ++i) in_store(t, i, vb[i]);
+                for (int i = 0; i < NB_IT; ++i) in_store(ws, c0, i, vb[i]);
 #pragma unroll
-                for (int i = 0; i < NA_IT; ++i) w_store(t, i, va[i]);
+                for (int i = 0; i < NA_IT; ++i) w_store(ws, c0, i, va[i]);
             }
             __syncthreads();
             if (c0 + G::CB < C) {
-                const int t = opaque_tid();
+                const int ws = wave_id();
 #pragma unroll
-                for (int i = 0; i < NB_IT; ++i) vb[i] = in_load(t, c0 + G::CB, i);
+                for (int i = 0; i < NB_IT; ++i) vb[i] = in_load(ws, c0 + G::CB, i);
 #pragma unroll
-                for (int i = 0; i < NA_IT; ++i) va[i] = w_load(t, c0 + G::CB, i);
+                for (int i = 0; i < NA_IT; ++i) va[i] = w_load(ws, c0 + G::CB, i);
             }
             compute();
             __syncthreads();
         }
     } else {
         for (int c0 = 0; c0 < C; c0 += G::CB) {
-            const int t = opaque_tid();
-            // global -> registers -> LDS, a bounded batch of loads at a time
+            const int ws = wave_id();
+            // a bounded batch of loads at a time (bounds the registers staging needs)
 #pragma unroll
             for (int i0 = 0; i0 < NB_IT; i0 += G::SB) {
                 float v[G::SB];
 #pragma unroll
                 for (int b = 0; b < G::SB; ++b)
-                    if (i0 + b < NB_IT) v[b] = in_load(t, c0, i0 + b);
+                    if (i0 + b < NB_IT) v[b] = in_load(ws, c0, i0 + b);
 #pragma unroll
                 for (int b = 0; b < G::SB; ++b)
-                    if (i0 + b < NB_IT) in_store(t, i0 + b, v[b]);
+                    if (i0 + b < NB_IT) in_store(ws, c0, i0 + b, v[b]);
             }
 #pragma unroll
             for (int i0 = 0; i0 < NA_IT; i0 += G::SB) {
                 wvec v[G::SB];
 #pragma unroll
                 for (int b = 0; b < G::SB; ++b)
-                    if (i0 + b < NA_IT) v[b] = w_load(t, c0, i0 + b);
+                    if (i0 + b < NA_IT) v[b] = w_load(ws, c0, i0 + b);
 #pragma unroll
                 for (int b = 0; b < G::SB; ++b)
-                    if (i0 + b < NA_IT) w_store(t, i0 + b, v[b]);
+                    if (i0 + b < NA_IT) w_store(ws, c0, i0 + b, v[b]);
             }
             __syncthreads();
             compute();
@@ -444,7 +534,6 @@ static hipError_t launch_generic(const KernelArgs &a, unsigned grid, hipStream_t
 // name, R, S, stride, TP, TQ, KBW, PBW, WK, WP, CB, pair, workgroups/CU, prefetch
 static const Variant k_variants[] = {
     // 3x3 stride 1: 224-pixel tiles (7 blocks), 128 or 64 output channels
-    TILE_VARIANT("f3s1_1x224_k128", 3, 3, 1, 1, 224, 1, 7, 4, 1, 8, PAIR_C, 2, 1),
     TILE_VARIANT("f3s1_2x112_k128", 3, 3, 1, 2, 112, 1, 7, 4, 1, 8, PAIR_C, 2, 1),
     TILE_VARIANT("f3s1_4x56_k128", 3, 3, 1, 4, 56, 1, 7, 4, 1, 8, PAIR_C, 2, 1),
     TILE_VARIANT("f3s1_8x28_k128", 3, 3, 1, 8, 28, 1, 7, 4, 1, 8, PAIR_C, 2, 1),
@@ -453,7 +542,7 @@ static const Variant k_variants[] = {
     TILE_VARIANT("f3s1_2x224_k64", 3, 3, 1, 2, 224, 1, 7, 2, 2, 8, PAIR_C, 2, 1),
     TILE_VARIANT("f3s1_7x32_k32_c3", 3, 3, 1, 7, 32, 1, 7, 1, 1, 3, PAIR_S, 4, 0),
     // 5x5 stride 1
-    TILE_VARIANT("f5s1_9x27_k128", 5, 5, 1, 9, 27, 1, 8, 4, 1, 2, PAIR_C, 2, 1),
+    TILE_VARIANT("f5s1_9x27_k128", 5, 5, 1, 9, 27, 1, 8, 4, 1, 4, PAIR_C, 2, 0),
     // 1x1
     TILE_VARIANT("f1s1_4x56_k64", 1, 1, 1, 4, 56, 1, 7, 2, 1, 32, PAIR_C, 4, 1),
     TILE_VARIANT("f1s1_4x56_k128", 1, 1, 1, 4, 56, 1, 7, 4, 1, 32, PAIR_C, 2, 1),
