@@ -37,12 +37,14 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 template <int R_, int S_, int ST_, int TP_, int TQ_, int KBW_, int PBW_, int WK_, int WP_, int CB_,
           int PAIR_, int OCC_, int PREF_>
 struct Geom {
-    static constexpr int PREF = PREF_;                 // 1: prefetch the next chunk into registers
+    static constexpr int PREF = PREF_;                 // 0: load-store-compute; 1: next chunk prefetched into registers;
+                                                       // 2: two LDS buffers, staging interleaved with the MFMAs
     static constexpr int R = R_, S = S_, ST = ST_, TP = TP_, TQ = TQ_;
     static constexpr int KBW = KBW_, PBW = PBW_, WK = WK_, WP = WP_, CB = CB_, PAIR = PAIR_, OCC = OCC_;
     static constexpr int NT = 64 * WK * WP;            // threads per workgroup
     static constexpr int WPE = (OCC * WK * WP + 3) / 4; // waves per SIMD the register budget must allow
-    static constexpr int UNROLL_OUTER = 1;             // unroll factor of the channel loop inside a chunk
+    // unroll factor of the channel loop inside a chunk (full when staging is interleaved tap by tap)
+    static constexpr int UNROLL_OUTER = PREF_ == 2 ? (PAIR_ == PAIR_C ? CB_ / 2 : CB_) : 1;
     static constexpr int SB = 8;                       // staging loads in flight per thread
     static constexpr int KT = 32 * KBW * WK;           // output channels per workgroup
     static constexpr int NPB = PBW * WP;               // 32-pixel blocks per workgroup
@@ -58,7 +60,10 @@ struct Geom {
     static constexpr int KP = KT + 1;                  // LDS pitch of one filter k-row (odd: spreads banks)
     static constexpr int LDS_A = STEPS * 2 * KP;       // floats
     static constexpr int LDS_B = CB * PS;              // floats
-    static constexpr size_t LDS_BYTES = sizeof(float) * (size_t)(LDS_A + LDS_B);
+    static constexpr int NBUF = PREF_ == 2 ? 2 : 1;     // LDS stage buffers
+    static constexpr int LDS_DUMP = 64;                // one word per lane: where masked-off lanes store
+    static constexpr int LDS_BUF = LDS_A + LDS_B + LDS_DUMP;   // floats per stage buffer: filter, input, dump
+    static constexpr size_t LDS_BYTES = sizeof(float) * (size_t)LDS_BUF * NBUF;
     static_assert(NPB * 32 >= NPIX, "pixel blocks must cover the tile");
     static_assert(PAIR == PAIR_S || CB % 2 == 0, "channel pairing needs an even chunk");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
@@ -167,8 +172,8 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
         const int ih = ih0 + hh;
         const int col = seg * SEGW + lcol;
         const int iw = iw0 + col;
-        ok = rowg < ROWS && (unsigned)ih < (unsigned)H && c0 + cg * SUBS + sub < C &&
-             col < G::LW && (unsigned)iw < (unsigned)W;
+        ok = (rowg < ROWS) & ((unsigned)ih < (unsigned)H) & (c0 + cg * SUBS + sub < C) &
+             (col < G::LW) & ((unsigned)iw < (unsigned)W);
         const int off = ((c0 + cg * SUBS) * H + ih) * W + iw0 + seg * SEGW + in_lane_goff;
         return ok ? (unsigned)off : 0u;
     };
@@ -176,14 +181,16 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
         bool ok;
         return in_n[in_addr(wave_s, c0, i, ok)];
     };
-    auto in_store = [&](int wave_s, int c0, int i, float v) {
+    auto in_store = [&](float *dstB, int wave_s, int c0, int i, float v) {
         bool ok;
         (void)in_addr(wave_s, c0, i, ok);
         const int ir = i / SEGS, seg = i - ir * SEGS;
         const int rowg = ir * NW + wave_s;
         const int cg = rowg / G::LH, hh = rowg - cg * G::LH;
-        if (rowg < ROWS && seg * SEGW + lcol < G::LW)
-            ldsB[cg * SUBS * G::PS + hh * G::LWP + seg * SEGW + in_lane_loff] = ok ? v : 0.f;
+        // masked-off lanes store to their dump word: no branch, the chunk stays one block
+        const bool act = (rowg < ROWS) & (seg * SEGW + lcol < G::LW);
+        const int idx = cg * SUBS * G::PS + hh * G::LWP + seg * SEGW + in_lane_loff;
+        dstB[act ? idx : G::LDS_B + lane] = ok ? v : 0.f;
     };
 
     // filter slice: KT rows of CRS values, read WV at a time; short rows are packed
@@ -225,7 +232,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
         const int jj = (seg * 64 + jl) * WV;
         // with WV = 4 the launcher guarantees C % CB == 0, so a load never straddles the
         // end of the channels; with WV = 1 the last test cuts the channel tail
-        ok = wlane_ok && kk < G::KT && k0 + kk < K && jj < CRS && jj < (C - c0) * G::RS;
+        ok = wlane_ok & (kk < G::KT) & (k0 + kk < K) & (jj < CRS) & (jj < (C - c0) * G::RS);
         const int off = (kg * RPI * C + c0) * G::RS + seg * 64 * WV + w_lane_goff;
         return ok ? (unsigned)off : 0u;
     };
@@ -233,17 +240,16 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
         bool ok;
         return WLoad<WV>::ld(w_k + w_addr(wave_s, c0, i, ok));
     };
-    auto w_store = [&](int wave_s, int c0, int i, wvec v) {
+    auto w_store = [&](float *dstA, int wave_s, int c0, int i, wvec v) {
         bool ok;
         (void)w_addr(wave_s, c0, i, ok);
         const int ik = i / WSEGS, seg = i - ik * WSEGS;
         const int kg = ik * NW + wave_s;
         const int kk = kg * RPI + ksub;
-        if (wlane_ok && kk < G::KT) {
 #pragma unroll
-            for (int u = 0; u < WV; ++u)
-                if ((seg * 64 + jl) * WV + u < CRS)
-                    ldsA[aslot[seg][u] + kg * RPI] = ok ? WLoad<WV>::get(v, u) : 0.f;
+        for (int u = 0; u < WV; ++u) {
+            const bool act = wlane_ok & (kk < G::KT) & ((seg * 64 + jl) * WV + u < CRS);
+            dstA[act ? aslot[seg][u] + kg * RPI : G::LDS_A + G::LDS_B + lane] = ok ? WLoad<WV>::get(v, u) : 0.f;
         }
     };
 
@@ -255,13 +261,13 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
     constexpr int B_OUTER = G::PAIR == PAIR_C ? 2 * G::PS : G::PS; // LDS floats per outer step, input
     constexpr int A_OUTER = INNER * 2 * G::KP;                    // LDS floats per outer step, filter
     // LDS -> register operand fetches for tap t of outer step o
-    auto fetch_a = [&](int o, int t, float (&av)[G::KBW]) {
-        const float *pa = ldsA + abase + o * A_OUTER;
+    auto fetch_a = [&](const float *srcA, int o, int t, float (&av)[G::KBW]) {
+        const float *pa = srcA + abase + o * A_OUTER;
 #pragma unroll
         for (int kb = 0; kb < G::KBW; ++kb) av[kb] = pa[t * 2 * G::KP + kb * 32];
     };
-    auto fetch_b = [&](int o, int t, float (&bv)[G::PBW]) {
-        const float *pbase = ldsB + o * B_OUTER;
+    auto fetch_b = [&](const float *srcB, int o, int t, float (&bv)[G::PBW]) {
+        const float *pbase = srcB + o * B_OUTER;
         int boff;
         if (G::PAIR == PAIR_C) {
             const int r = t / G::S, ss = t - r * G::S;
@@ -277,20 +283,21 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
     // next tap and the filter operand of the tap after it are fetched; the scheduling
     // hints pin one LDS read behind each MFMA.  Fetches past the end of the chunk are
     // clamped to its last outer step (their values are never used).
-    auto compute = [&]() {
+    auto compute = [&](const float *srcA, const float *srcB, auto &&side_work) {
         float a0[G::KBW], a1[G::KBW], b0[G::PBW];
-        fetch_a(0, 0, a0);
-        fetch_b(0, 0, b0);
-        fetch_a((1 / INNER) < OUTER ? 1 / INNER : OUTER - 1, 1 % INNER, a1);
+        fetch_a(srcA, 0, 0, a0);
+        fetch_b(srcB, 0, 0, b0);
+        fetch_a(srcA, (1 / INNER) < OUTER ? 1 / INNER : OUTER - 1, 1 % INNER, a1);
 #pragma unroll G::UNROLL_OUTER
         for (int o = 0; o < OUTER; ++o) {
 #pragma unroll
             for (int t = 0; t < INNER; ++t) {
                 float a2[G::KBW], b1[G::PBW];
+                side_work(o, t);
                 // taps are numbered o*INNER + t; fetch tap +1 (input) and tap +2 (filter)
                 const int o1 = o + (t + 1) / INNER, o2 = o + (t + 2) / INNER;
-                fetch_b(o1 < OUTER ? o1 : OUTER - 1, (t + 1) % INNER, b1);
-                fetch_a(o2 < OUTER ? o2 : OUTER - 1, (t + 2) % INNER, a2);
+                fetch_b(srcB, o1 < OUTER ? o1 : OUTER - 1, (t + 1) % INNER, b1);
+                fetch_a(srcA, o2 < OUTER ? o2 : OUTER - 1, (t + 2) % INNER, a2);
 #pragma unroll
                 for (int kb = 0; kb < G::KBW; ++kb)
 #pragma unroll
@@ -300,6 +307,11 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
                 for (int i = 0; i < G::KBW * G::PBW; ++i) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                    if (G::PREF == 2) {
+                        __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // a little address arithmetic
+                        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one global load
+                        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS store
+                    }
                 }
 #pragma unroll
                 for (int kb = 0; kb < G::KBW; ++kb) { a0[kb] = a1[kb]; a1[kb] = a2[kb]; }
@@ -308,7 +320,68 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
             }
         }
     };
+    auto no_side_work = [](int, int) {};
 
+    if (G::PREF == 2 && WV == 4) {
+        // Two LDS stage buffers.  A wave that shares its SIMD with a wave issuing MFMAs
+        // back to back gets almost no issue slots, so staging cannot be left to "the
+        // other" wave: every wave stages in the shadow of its own MFMAs.  During the
+        // taps of chunk i a wave first stores the registers holding chunk i+1 into the
+        // other buffer, then reloads them from global memory with chunk i+2.  Past the
+        // last chunk the chunk index is clamped: redundant loads of valid memory and
+        // stores into a buffer nobody reads again, in exchange for branch-free code.
+        constexpr int BUF = G::LDS_BUF;                    // floats per stage buffer
+        constexpr int NEL = NB_IT + NA_IT;                 // staged elements per thread
+        constexpr int ST_TAPS = G::STEPS / 3 > 0 ? G::STEPS / 3 : 1;   // taps that carry stores
+        constexpr int SPT = (NEL + ST_TAPS - 1) / ST_TAPS;             // elements per such tap
+        constexpr int LD_TAPS = ST_TAPS;                               // taps that carry loads
+        constexpr int LPT = (NEL + LD_TAPS - 1) / LD_TAPS;
+        constexpr int LD_T0 = (NEL + SPT - 1) / SPT;                   // first tap with loads
+        static_assert(LD_T0 + (NEL + LPT - 1) / LPT <= G::STEPS, "staging does not fit the taps of a chunk");
+        const int c_last = ((C - 1) / G::CB) * G::CB;
+        float vb[NB_IT];
+        wvec va[NA_IT];
+        {
+            const int ws = wave_id();
+#pragma unroll
+            for (int i = 0; i < NB_IT; ++i) vb[i] = in_load(ws, 0, i);
+#pragma unroll
+            for (int i = 0; i < NA_IT; ++i) va[i] = w_load(ws, 0, i);
+#pragma unroll
+            for (int i = 0; i < NB_IT; ++i) in_store(ldsB, ws, 0, i, vb[i]);
+#pragma unroll
+            for (int i = 0; i < NA_IT; ++i) w_store(ldsA, ws, 0, i, va[i]);
+            const int c1 = G::CB < C ? G::CB : c_last;
+#pragma unroll
+            for (int i = 0; i < NB_IT; ++i) vb[i] = in_load(ws, c1, i);
+#pragma unroll
+            for (int i = 0; i < NA_IT; ++i) va[i] = w_load(ws, c1, i);
+        }
+        __syncthreads();
+        int cur = 0;
+        for (int c0 = 0; c0 < C; c0 += G::CB, cur ^= 1) {
+            const int c1 = c0 + G::CB < C ? c0 + G::CB : c_last;           // chunk held in registers
+            const int c2 = c0 + 2 * G::CB < C ? c0 + 2 * G::CB : c_last;   // chunk to load next
+            float *curA = ldsA + cur * BUF, *curB = ldsB + cur * BUF;
+            float *nxtA = ldsA + (cur ^ 1) * BUF, *nxtB = ldsB + (cur ^ 1) * BUF;
+            const int ws = wave_id();
+            compute(curA, curB, [&](int o, int t) {
+                const int tap = o * INNER + t;   // compile-time when the outer loop is unrolled
+#pragma unroll
+                for (int e = 0; e < NEL; ++e) {
+                    if (e / SPT == tap) {
+                        if (e < NB_IT) in_store(nxtB, ws, c1, e, vb[e]);
+                        else w_store(nxtA, ws, c1, e - NB_IT, va[e - NB_IT]);
+                    }
+                    if (e / LPT + LD_T0 == tap) {
+                        if (e < NB_IT) vb[e] = in_load(ws, c2, e);
+                        else va[e - NB_IT] = w_load(ws, c2, e - NB_IT);
+                    }
+                }
+            });
+            __syncthreads();
+        }
+    } else
     if (G::PREF && WV == 4) {
         // Software pipeline: the next chunk's global loads are in flight while this
         // chunk's MFMAs run; their LDS stores follow the barrier that ends the reads.
@@ -325,9 +398,9 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
             {
                 const int ws = wave_id();
 #pragma unroll
-                for (int i = 0; i < NB_IT; ++i) in_store(ws, c0, i, vb[i]);
+                for (int i = 0; i < NB_IT; ++i) in_store(ldsB, ws, c0, i, vb[i]);
 #pragma unroll
-                for (int i = 0; i < NA_IT; ++i) w_store(ws, c0, i, va[i]);
+                for (int i = 0; i < NA_IT; ++i) w_store(ldsA, ws, c0, i, va[i]);
             }
             __syncthreads();
             if (c0 + G::CB < C) {
@@ -337,7 +410,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
 #pragma unroll
                 for (int i = 0; i < NA_IT; ++i) va[i] = w_load(ws, c0 + G::CB, i);
             }
-            compute();
+            compute(ldsA, ldsB, no_side_work);
             __syncthreads();
         }
     } else {
@@ -352,7 +425,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
                     if (i0 + b < NB_IT) v[b] = in_load(ws, c0, i0 + b);
 #pragma unroll
                 for (int b = 0; b < G::SB; ++b)
-                    if (i0 + b < NB_IT) in_store(ws, c0, i0 + b, v[b]);
+                    if (i0 + b < NB_IT) in_store(ldsB, ws, c0, i0 + b, v[b]);
             }
 #pragma unroll
             for (int i0 = 0; i0 < NA_IT; i0 += G::SB) {
@@ -362,10 +435,10 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
                     if (i0 + b < NA_IT) v[b] = w_load(ws, c0, i0 + b);
 #pragma unroll
                 for (int b = 0; b < G::SB; ++b)
-                    if (i0 + b < NA_IT) w_store(ws, c0, i0 + b, v[b]);
+                    if (i0 + b < NA_IT) w_store(ldsA, ws, c0, i0 + b, v[b]);
             }
             __syncthreads();
-            compute();
+            compute(ldsA, ldsB, no_side_work);
             __syncthreads();
         }
     }
@@ -534,12 +607,13 @@ static hipError_t launch_generic(const KernelArgs &a, unsigned grid, hipStream_t
 // name, R, S, stride, TP, TQ, KBW, PBW, WK, WP, CB, pair, workgroups/CU, prefetch
 static const Variant k_variants[] = {
     // 3x3 stride 1: 224-pixel tiles (7 blocks), 128 or 64 output channels
-    TILE_VARIANT("f3s1_2x112_k128", 3, 3, 1, 2, 112, 1, 7, 4, 1, 8, PAIR_C, 2, 1),
-    TILE_VARIANT("f3s1_4x56_k128", 3, 3, 1, 4, 56, 1, 7, 4, 1, 8, PAIR_C, 2, 1),
-    TILE_VARIANT("f3s1_8x28_k128", 3, 3, 1, 8, 28, 1, 7, 4, 1, 8, PAIR_C, 2, 1),
-    TILE_VARIANT("f3s1_14x14_k128", 3, 3, 1, 14, 14, 1, 7, 4, 1, 8, PAIR_C, 2, 1),
-    TILE_VARIANT("f3s1_13x13_k128", 3, 3, 1, 13, 13, 1, 6, 4, 1, 8, PAIR_C, 2, 1),
-    TILE_VARIANT("f3s1_2x224_k64", 3, 3, 1, 2, 224, 1, 7, 2, 2, 8, PAIR_C, 2, 1),
+    TILE_VARIANT("f3s1_2x112_k128", 3, 3, 1, 2, 112, 1, 7, 4, 1, 4, PAIR_C, 2, 2),
+    TILE_VARIANT("f3s1_4x56_k128", 3, 3, 1, 4, 56, 1, 7, 4, 1, 4, PAIR_C, 2, 2),
+    TILE_VARIANT("f3s1_8x28_k128", 3, 3, 1, 8, 28, 1, 7, 4, 1, 4, PAIR_C, 2, 2),
+    TILE_VARIANT("f3s1_14x14_k128", 3, 3, 1, 14, 14, 1, 7, 4, 1, 4, PAIR_C, 2, 2),
+    TILE_VARIANT("f3s1_13x13_k128", 3, 3, 1, 13, 13, 1, 6, 4, 1, 4, PAIR_C, 2, 2),
+    TILE_VARIANT("f3s1_2x224_k64", 3, 3, 1, 2, 224, 1, 7, 2, 2, 4, PAIR_C, 2, 2),
+    TILE_VARIANT("f3s1_4x56_k128_p1", 3, 3, 1, 4, 56, 1, 7, 4, 1, 8, PAIR_C, 2, 1),
     TILE_VARIANT("f3s1_7x32_k32_c3", 3, 3, 1, 7, 32, 1, 7, 1, 1, 3, PAIR_S, 4, 0),
     // 5x5 stride 1
     TILE_VARIANT("f5s1_9x27_k128", 5, 5, 1, 9, 27, 1, 8, 4, 1, 4, PAIR_C, 2, 0),
