@@ -1,44 +1,119 @@
-"""Compile the HIP kernels and the C ABI into libconv_direct.so (gfx950 only)."""
+"""Compile the HIP kernels and the C ABI into libconv_direct.so (gfx950 only).
+
+Every row of csrc/variants.def is one translation unit (conv_tile_variant.hip compiled
+with that row's parameters); the units compile in parallel and are linked with the
+fallback kernel and the C ABI.  Objects are cached under csrc/_build/ by a hash of
+their inputs; build(force=True) ignores the cache.
+"""
 from __future__ import annotations
 
+import concurrent.futures as cf
+import hashlib
 import os
+import re
 import subprocess
+import time
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
+OBJDIR = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libconv_direct.so")
-SOURCES = ["conv_direct_kernels.hip", "conv_direct_api.cpp"]
-HEADERS = [os.path.join(CSRC, "variant.h"),
-           os.path.join(os.path.dirname(HERE), "include", "conv_direct.h")]
+INCLUDE = os.path.join(os.path.dirname(HERE), "include")
+COMMON_DEPS = [os.path.join(CSRC, "variant.h"), os.path.join(CSRC, "variants.def"),
+               os.path.join(INCLUDE, "conv_direct.h")]
 
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]
 
 
-def is_stale() -> bool:
-    if not os.path.exists(LIB):
-        return True
-    t = os.path.getmtime(LIB)
-    deps = [os.path.join(CSRC, s) for s in SOURCES] + HEADERS
-    return any(os.path.getmtime(d) > t for d in deps)
+def variants():
+    """(name, params) for every X(...) row of variants.def."""
+    out = []
+    with open(os.path.join(CSRC, "variants.def")) as f:
+        for ln in f:
+            m = re.match(r"\s*X\(\s*(\w+)\s*,(.*)\)\s*$", ln)
+            if m:
+                out.append((m.group(1), re.sub(r"\s+", "", m.group(2))))
+    return out
 
 
-def build(force: bool = True, extra_flags=(), verbose: bool = False) -> str:
-    """Run hipcc; returns the library path.  With force=False an up-to-date library is kept."""
-    if not force and not is_stale():
-        return LIB
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + list(extra_flags) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+def _units(only=None):
+    """(object stem, source, extra defines, dependency files) per translation unit."""
+    units = []
+    for name, params in variants():
+        if only and name not in only:
+            continue
+        units.append((f"tile_{name}", "conv_tile_variant.hip", [f"-DV_NAME={name}", f"-DV_PARAMS={params}"],
+                      [os.path.join(CSRC, "conv_tile_kernel.h"), os.path.join(CSRC, "variant.h")], params))
+    defs = []
+    if only:
+        # a reduced table: the chosen rows only
+        sub = os.path.join(OBJDIR, "variants_subset.def")
+        with open(os.path.join(CSRC, "variants.def")) as f, open(sub, "w") as g:
+            g.writelines(ln for ln in f if (m := re.match(r"\s*X\(\s*(\w+)", ln)) and m.group(1) in only)
+        defs = [f'-DCONVD_VARIANTS_DEF="{sub}"']
+    units.append(("generic", "conv_generic_kernel.hip", defs, COMMON_DEPS, ",".join(sorted(only or []))))
+    units.append(("api", "conv_direct_api.cpp", [], COMMON_DEPS, ""))
+    return units
+
+
+def _hipcc():
+    return os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+
+def _compile(unit, extra_flags, force, verbose):
+    stem, src, defs, deps, salt = unit
+    srcp = os.path.join(CSRC, src)
+    h = hashlib.sha256()
+    for p in [srcp] + list(deps):
+        with open(p, "rb") as f:
+            h.update(f.read())
+    h.update(" ".join(FLAGS + list(extra_flags) + defs + [salt]).encode())
+    obj = os.path.join(OBJDIR, f"{stem}-{h.hexdigest()[:16]}.o")
+    if force or not os.path.exists(obj):
+        for old in os.listdir(OBJDIR):
+            if old.startswith(stem + "-") and old.endswith(".o"):
+                os.remove(os.path.join(OBJDIR, old))
+        cmd = [_hipcc()] + FLAGS + list(extra_flags) + defs + ["-c", srcp, "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        t0 = time.perf_counter()
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if verbose:
+            print(f"[build] {stem}: {time.perf_counter() - t0:.1f} s", flush=True)
+        msg = "\n".join(l for l in r.stdout.splitlines() if "is not a recognized feature" not in l)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {stem}:\n{msg}")
+        if msg.strip():
+            print(msg, flush=True)
+    return obj
+
+
+def build(force: bool = True, extra_flags=(), verbose: bool = False, only=None, lib: str = LIB,
+          jobs: int | None = None) -> str:
+    """Compile and link; returns the library path.  `only` (a set of variant names)
+    builds a reduced library for experiments (the fallback kernel is always included)."""
+    os.makedirs(OBJDIR, exist_ok=True)
+    units = _units(set(only) if only else None)
+    jobs = jobs or min(len(units), os.cpu_count() or 1, 16)
+    with cf.ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(lambda u: _compile(u, extra_flags, force, verbose), units))
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", lib]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
-    import sys
-    build(True, extra_flags=sys.argv[1:], verbose=True)
-    print(LIB)
+    import argparse
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--only", nargs="*", help="variant names for a reduced experimental library")
+    ap.add_argument("--lib", default=LIB)
+    ap.add_argument("--cached", action="store_true", help="reuse objects whose inputs did not change")
+    ap.add_argument("flags", nargs="*", help="extra hipcc flags (after --)")
+    a = ap.parse_args()
+    print(build(force=not a.cached, extra_flags=a.flags, verbose=True, only=a.only, lib=a.lib))

@@ -116,9 +116,9 @@ int make_plan(conv_direct_plan **plan, const char *forced, int N, int C, int H, 
     bool have = false;
     double best_cost = 0.0;
     int count = 0;
-    const Variant *table = convd::variant_table(&count);
+    const Variant *const *table = convd::variant_table(&count);
     for (int i = 0; i < count; ++i) {
-        const Variant &v = table[i];
+        const Variant &v = *table[i];
         if (forced && std::strcmp(forced, v.name) != 0) continue;
         if (!applicable(v, s)) continue;
         conv_direct_plan cand;
@@ -160,8 +160,8 @@ int conv_direct_create_with_variant(conv_direct_plan **plan, const char *variant
 const char *conv_direct_variant_name(int index)
 {
     int count = 0;
-    const Variant *table = convd::variant_table(&count);
-    return (index >= 0 && index < count) ? table[index].name : nullptr;
+    const Variant *const *table = convd::variant_table(&count);
+    return (index >= 0 && index < count) ? table[index]->name : nullptr;
 }
 
 int conv_direct_run(const conv_direct_plan *plan, const float *in, const float *w, float *out,

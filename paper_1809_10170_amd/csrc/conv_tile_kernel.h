@@ -24,6 +24,7 @@
 // few input channels, two neighbouring filter columns of one channel (PAIR_S, an odd
 // filter width being padded with a zero weight).  Any order of the C*R*S additions
 // is a correct convolution (Section 3, "any permutation of the loops").
+#pragma once
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -464,92 +465,9 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_tile_kernel(const KernelAr
 }
 
 // ---------------------------------------------------------------------------
-// Fallback for any filter size and stride (runtime R, S, stride).  Same operand
-// mapping; one chunk is one pair of input channels at one filter row, so the LDS
-// need is independent of R.  Tile: 2 output rows x 32 columns x 64 channels,
-// four waves each owning one 32x32 accumulator block.
+// Host side: launcher and the table entry of one compiled tile variant.
 // ---------------------------------------------------------------------------
-struct GenericGeom {
-    static constexpr int TP = 2, TQ = 32, KT = 64, NT = 256, KP = KT + 1;
-    static __host__ __device__ int lw(int S, int st) { return (TQ - 1) * st + S; }
-    static __host__ __device__ size_t lds_floats(int S, int st) { return (size_t)S * 2 * KP + 2 * TP * lw(S, st); }
-};
-
-__global__ void __launch_bounds__(GenericGeom::NT) conv_generic_kernel(const KernelArgs a)
-{
-    using G = GenericGeom;
-    extern __shared__ __align__(16) float lds[];
-    const int C = a.s.C, H = a.s.H, W = a.s.W, K = a.s.K, P = a.s.P, Q = a.s.Q;
-    const int R = a.s.R, S = a.s.S, st = a.s.stride;
-    const int LW = G::lw(S, st);
-    float *ldsA = lds;                       // [S][2][KP]
-    float *ldsB = lds + S * 2 * G::KP;       // [2][TP][LW]
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wk = wave & 1, wp = wave >> 1;   // wp = output row of the tile
-    const int h = lane >> 5, j = lane & 31;
-
-    unsigned bid = blockIdx.x;
-    const int kt = bid % a.ktiles;  bid /= a.ktiles;
-    const int tq = bid % a.tilesQ;  bid /= a.tilesQ;
-    const int tp = bid % a.tilesP;
-    const int n = bid / a.tilesP;
-    const int p0 = tp * G::TP, q0 = tq * G::TQ, k0 = kt * G::KT;
-    const int iw0 = q0 * st - a.s.pad;
-    const float *in_n = a.in + (size_t)n * C * H * W;
-
-    const int bbase = (h * G::TP + wp) * LW + j * st;
-    const int abase = h * G::KP + wk * 32 + j;
-
-    floatx16 acc;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-
-    const int nB = 2 * G::TP * LW, nA = G::KT * 2 * S;
-    for (int c0 = 0; c0 < C; c0 += 2) {
-        for (int r = 0; r < R; ++r) {
-            for (int e = tid; e < nB; e += G::NT) {
-                const int cc = e / (G::TP * LW), rem = e - cc * (G::TP * LW);
-                const int py = rem / LW, ww = rem - py * LW;
-                const int ih = (p0 + py) * st + r - a.s.pad, iw = iw0 + ww, c = c0 + cc;
-                float v = 0.f;
-                if (c < C && (unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W)
-                    v = in_n[((size_t)c * H + ih) * W + iw];
-                ldsB[e] = v;
-            }
-            for (int e = tid; e < nA; e += G::NT) {
-                const int kk = e / (2 * S), rem = e - kk * (2 * S);
-                const int cc = rem / S, s = rem - cc * S;
-                float v = 0.f;
-                if (k0 + kk < K && c0 + cc < C)
-                    v = a.w[(((size_t)(k0 + kk) * C + c0 + cc) * R + r) * S + s];
-                ldsA[(s * 2 + cc) * G::KP + kk] = v;
-            }
-            __syncthreads();
-            for (int s = 0; s < S; ++s) {
-                const float av = ldsA[abase + s * 2 * G::KP];
-                const float bv = ldsB[bbase + s];
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc, 0, 0, 0);
-            }
-            __syncthreads();
-        }
-    }
-
-    const int p = p0 + wp, q = q0 + j;
-    if (p < P && q < Q) {
-        float *out_n = a.out + (size_t)n * K * P * Q;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int k = k0 + wk * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-            if (k < K) out_n[((size_t)k * P + p) * Q + q] = acc[v];
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Host side of this translation unit: launchers and the variant table.
-// ---------------------------------------------------------------------------
-static hipError_t allow_lds(const void *fn, size_t bytes)
+inline hipError_t allow_lds(const void *fn, size_t bytes)
 {
     // Workgroups above the 64 KB default need the limit raised (no allocation involved).
     if (bytes <= 64 * 1024) return hipSuccess;
@@ -581,58 +499,11 @@ static hipError_t launch_tile(const KernelArgs &a, unsigned grid, hipStream_t st
 template <class G>
 static size_t lds_tile(const Shape &) { return G::LDS_BYTES; }
 
-static size_t lds_generic(const Shape &s)
+template <class G>
+constexpr Variant make_variant(const char *name)
 {
-    return sizeof(float) * GenericGeom::lds_floats(s.S, s.stride);
-}
-
-static hipError_t launch_generic(const KernelArgs &a, unsigned grid, hipStream_t stream)
-{
-    const size_t bytes = lds_generic(a.s);
-    hipError_t e = allow_lds(reinterpret_cast<const void *>(&conv_generic_kernel), bytes);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(conv_generic_kernel, dim3(grid), dim3(GenericGeom::NT), bytes, stream, a);
-    return hipGetLastError();
-}
-
-#define TILE_VARIANT(NAME, R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC, PREF)                        \
-    {                                                                                               \
-        NAME, R, S, ST, TP, TQ, Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC, PREF>::KT,       \
-            Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC, PREF>::NPB, CB, PAIR,                \
-            Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC, PREF>::NT, OCC,                      \
-            &lds_tile<Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC, PREF>>,                    \
-            &launch_tile<Geom<R, S, ST, TP, TQ, KBW, PBW, WK, WP, CB, PAIR, OCC, PREF>>                  \
-    }
-
-// name, R, S, stride, TP, TQ, KBW, PBW, WK, WP, CB, pair, workgroups/CU, prefetch
-static const Variant k_variants[] = {
-    // 3x3 stride 1: 224-pixel tiles (7 blocks), 128 or 64 output channels
-    TILE_VARIANT("f3s1_2x112_k128", 3, 3, 1, 2, 112, 1, 7, 4, 1, 4, PAIR_C, 2, 2),
-    TILE_VARIANT("f3s1_4x56_k128", 3, 3, 1, 4, 56, 1, 7, 4, 1, 4, PAIR_C, 2, 2),
-    TILE_VARIANT("f3s1_8x28_k128", 3, 3, 1, 8, 28, 1, 7, 4, 1, 4, PAIR_C, 2, 2),
-    TILE_VARIANT("f3s1_14x14_k128", 3, 3, 1, 14, 14, 1, 7, 4, 1, 4, PAIR_C, 2, 2),
-    TILE_VARIANT("f3s1_13x13_k128", 3, 3, 1, 13, 13, 1, 6, 4, 1, 4, PAIR_C, 2, 2),
-    TILE_VARIANT("f3s1_2x224_k64", 3, 3, 1, 2, 224, 1, 7, 2, 2, 4, PAIR_C, 2, 2),
-    TILE_VARIANT("f3s1_4x56_k128_p1", 3, 3, 1, 4, 56, 1, 7, 4, 1, 8, PAIR_C, 2, 1),
-    TILE_VARIANT("f3s1_7x32_k32_c3", 3, 3, 1, 7, 32, 1, 7, 1, 1, 3, PAIR_S, 4, 0),
-    // 5x5 stride 1
-    TILE_VARIANT("f5s1_9x27_k128", 5, 5, 1, 9, 27, 1, 8, 4, 1, 4, PAIR_C, 2, 0),
-    // 1x1
-    TILE_VARIANT("f1s1_4x56_k64", 1, 1, 1, 4, 56, 1, 7, 2, 1, 32, PAIR_C, 4, 1),
-    TILE_VARIANT("f1s1_4x56_k128", 1, 1, 1, 4, 56, 1, 7, 4, 1, 32, PAIR_C, 2, 1),
-    // 3x3 stride 2
-    TILE_VARIANT("f3s2_8x28_k128", 3, 3, 2, 8, 28, 1, 7, 4, 1, 4, PAIR_C, 2, 1),
-    // first layers (3 input channels): pairs of filter columns
-    TILE_VARIANT("f7s2_2x112_k64_c3", 7, 7, 2, 2, 112, 1, 7, 2, 1, 3, PAIR_S, 2, 0),
-    TILE_VARIANT("f11s4_4x55_k96_c3", 11, 11, 4, 4, 55, 1, 7, 3, 1, 1, PAIR_S, 2, 0),
-    // any shape
-    {"generic_2x32_k64", 0, 0, 0, GenericGeom::TP, GenericGeom::TQ, GenericGeom::KT, 2, 2, PAIR_C,
-     GenericGeom::NT, 2, &lds_generic, &launch_generic},
-};
-const Variant *variant_table(int *count)
-{
-    *count = (int)(sizeof(k_variants) / sizeof(k_variants[0]));
-    return k_variants;
+    return Variant{name, G::R, G::S, G::ST, G::TP, G::TQ, G::KT, G::NPB, G::CB, G::PAIR, G::NT, G::OCC,
+                   &lds_tile<G>, &launch_tile<G>};
 }
 
 }  // namespace convd

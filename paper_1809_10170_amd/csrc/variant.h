@@ -35,7 +35,7 @@ struct Variant {
     hipError_t (*launch)(const KernelArgs &, unsigned grid, hipStream_t stream);
 };
 
-// The compiled variants (host table; lives in the kernel translation unit).
-const Variant *variant_table(int *count);
+// The compiled variants (host table of pointers; lives beside the fallback kernel).
+const Variant *const *variant_table(int *count);
 
 }  // namespace convd
