@@ -129,7 +129,8 @@ def main():
     value = total_flops / (ms_per_step * 1e-3) / 1e12
 
     dom = max(per_layer, key=lambda r: r["ms_avg"])
-    roofline = {"bound": "mfma", "kernel": f"conv_tile_kernel<{dom['variant']}>", "layer": dom["layer"],
+    kern = "conv_rows_kernel" if dom["variant"].startswith("r") else "conv_dma_kernel"
+    roofline = {"bound": "mfma", "kernel": f"{kern}<{dom['variant']}>", "layer": dom["layer"],
                 "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, 4),
                 "launch_ms": dom["ms_avg"], "traffic": None}

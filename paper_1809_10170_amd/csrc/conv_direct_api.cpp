@@ -54,6 +54,7 @@ int validate(int N, int C, int H, int W, int K, int R, int S, int stride, int pa
 bool applicable(const Variant &v, const Shape &s)
 {
     if (v.R != 0 && (v.R != s.R || v.S != s.S || v.stride != s.stride)) return false;
+    if (v.pair == convd::PAIR_R && s.C > v.CB) return false;   // stages all channels at once
     if (v.lds_bytes(s) > kLdsPerCU) return false;
     const int64_t grid = (int64_t)cdiv(s.K, v.KT) * cdiv(s.P, v.TP) * cdiv(s.Q, v.TQ) * s.N;
     return grid > 0 && grid < kMaxElems;
@@ -75,7 +76,7 @@ void fill(conv_direct_plan *p, const Shape &s, const Variant &v)
     } else if (v.pair == convd::PAIR_C) {
         red = (double)cdiv(s.C, v.CB) * v.CB * s.R * s.S;
     } else {
-        red = (double)cdiv(s.C, v.CB) * v.CB * s.R * (2 * ((s.S + 1) / 2));
+        red = (double)s.C * (2 * ((s.R + 1) / 2)) * s.S;
     }
     const double issued = (double)p->grid * v.KT * (v.NPB * 32.0) * red;
     const double useful = (double)s.N * s.K * s.P * s.Q * ((double)s.C * s.R * s.S);
@@ -211,7 +212,7 @@ int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
                          "TP=%d TQ=%d KT=%d NPB=%d CB=%d pair=%s tilesP=%d tilesQ=%d ktiles=%d grid=%u "
                          "threads=%d lds_bytes=%zu occupancy=%d mfma_efficiency=%.4f workspace_bytes=0",
                          v.name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, v.TP, v.TQ,
-                         v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : "s", plan->tilesP,
+                         v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : "r", plan->tilesP,
                          plan->tilesQ, plan->ktiles, plan->grid, v.threads, plan->lds_bytes, v.occupancy,
                          plan->mfma_efficiency);
 }

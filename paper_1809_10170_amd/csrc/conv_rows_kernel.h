@@ -1,0 +1,239 @@
+// Direct-convolution forward kernel for gfx950 (MI355X), row-pair family: layers
+// with very few input channels (the first layer of a network: C <= CM, large
+// filters, stride 1, 2 or 4).  Same computation and operand mapping as
+// conv_dma_kernel.h (paper: Section 3, Algorithm 1; blocking after Section 3.1.2),
+// with two differences that keep the MFMA reduction depth useful when C is tiny:
+//
+//   * the two k-lanes of v_mfma_f32_32x32x2_f32 take filter rows r and r + R2
+//     (R2 = ceil(R/2)) of one input channel; for odd R the row past the filter has
+//     zero weights.  The reduction runs over (channel, row pair, filter column);
+//   * the input window of ALL channels of the workgroup's pixel tile is staged into
+//     LDS once (it is small when C is small), so the main loop has no barrier at
+//     all; the filter streams through registers, RG rows per lane at a time.
+//
+// For stride > 1 the window is stored split by column phase, [phase][row][col/stride],
+// so that the 32 pixels of an MFMA column block read consecutive LDS words for every
+// tap (stride-ST words would collide on the LDS banks).  The split costs nothing:
+// LDS-direct loads take an arbitrary global address per lane.
+#pragma once
+#include "conv_dma_kernel.h"
+
+namespace convd {
+
+template <int R_, int S_, int ST_, int TP_, int TQ_, int KBW_, int PBW_, int WK_, int WP_, int CM_, int RG_, int OCC_>
+struct RowGeom {
+    static constexpr int R = R_, S = S_, ST = ST_, TP = TP_, TQ = TQ_;
+    static constexpr int KBW = KBW_, PBW = PBW_, WK = WK_, WP = WP_, CM = CM_, RG = RG_, OCC = OCC_;
+    static constexpr int CB = CM;                        // reported as the channel block
+    static constexpr int PAIR = PAIR_R;
+    static constexpr int NT = 64 * WK * WP;
+    static constexpr int WPE = (OCC * WK * WP + 3) / 4;
+    static constexpr int KT = 32 * KBW * WK;            // a wave owns KBW x PBW 32x32 results
+    static constexpr int NPB = PBW * WP;
+    static constexpr int NPIX = TP * TQ;
+    static constexpr int R2 = (R + 1) / 2;               // filter rows per k-lane half
+    static constexpr int NSUB = R2 / RG;                 // register sub-chunks per channel
+    static constexpr int LHV = (TP - 1) * ST + R;        // window rows that hold image data
+    static constexpr int LH = (TP - 1) * ST + 2 * R2;    // window rows addressed (odd R: one zero row more)
+    static constexpr int LW = (TQ - 1) * ST + S;         // window columns
+    static constexpr int LWQ = (LW + ST - 1) / ST;       // columns per phase = LDS row pitch
+    static constexpr int PH = LH * LWQ;                  // floats of one phase plane
+    static constexpr int PS = ST * PH;                   // floats of one channel's window
+    static constexpr int PSP = (PS + 63) / 64 * 64;      // LDS stride between channels
+    static constexpr int HOFF = R2 * LWQ;                // LDS offset of the second k-lane half
+    static constexpr int NA = RG * S;                    // filter values per lane and sub-chunk
+    static constexpr int ITEMS = (CM * PSP + NT - 1) / NT;
+    static constexpr size_t LDS_BYTES = sizeof(float) * (size_t)CM * PSP;
+    static_assert(R2 % RG == 0 && NSUB % 2 == 0, "row groups must tile R2 an even number of times");
+    static_assert(NPB * 32 >= NPIX, "pixel blocks must cover the tile");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
+};
+
+template <class G>
+__global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelArgs a)
+{
+    extern __shared__ __align__(16) float lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    __builtin_assume(wave >= 0 && wave < G::NT / 64);
+    const int wk = wave % G::WK, wp = wave / G::WK;
+    const int h = lane >> 5, j = lane & 31;
+
+    const int C = a.s.C, H = a.s.H, W = a.s.W, K = a.s.K, P = a.s.P, Q = a.s.Q;
+
+    unsigned bid = blockIdx.x;
+    {
+        const unsigned g8 = gridDim.x & ~7u;
+        if (bid < g8) bid = (bid & 7u) * (g8 >> 3) + (bid >> 3);
+    }
+    const int kt = bid % a.ktiles;  bid /= a.ktiles;
+    const int tq = bid % a.tilesQ;  bid /= a.tilesQ;
+    const int tp = bid % a.tilesP;
+    const int n = bid / a.tilesP;
+    const int p0 = tp * G::TP, q0 = tq * G::TQ, k0 = kt * G::KT;
+    const int ih0 = p0 * G::ST - a.s.pad, iw0 = q0 * G::ST - a.s.pad;
+
+    // ---- stage the whole window (all channels) once ----
+    {
+        const float *in_n = a.in + (size_t)n * C * H * W;
+        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)in_n, 0, (int)((unsigned)(C * H * W) * 4u), 0x00020000);
+#pragma unroll 4
+        for (int i = 0; i < G::ITEMS; ++i) {
+            const int f0 = i * G::NT + wave * 64;
+            if (f0 < G::CM * G::PSP) {
+                const int f = f0 + lane;
+                const int cc = f / G::PSP, pos = f - cc * G::PSP;
+                const int ph = pos / G::PH, rem = pos - ph * G::PH;
+                const int hh = rem / G::LWQ, cq = rem - hh * G::LWQ;
+                const int ih = ih0 + hh, iw = iw0 + cq * G::ST + ph;
+                // rows past the filter (odd R) meet zero weights; they are stored as zeros
+                // too, so that no value outside the true window can reach an output
+                const bool ok = (pos < G::PS) & (hh < G::LHV) & (cc < C) & ((unsigned)ih < (unsigned)H) &
+                                ((unsigned)iw < (unsigned)W);
+                const unsigned off = ok ? (unsigned)(((cc * H + ih) * W + iw) * 4) : 0x80000000u;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, CONVD_LDS(lds + f0), 4, off, 0, 0, 0);
+            }
+        }
+    }
+
+    // per-lane LDS read offsets (floats): pixel position (phase 0) plus the k-lane half
+    int bbase[G::PBW];
+#pragma unroll
+    for (int pb = 0; pb < G::PBW; ++pb) {
+        const int t = (wp * G::PBW + pb) * 32 + j;
+        const int py = t / G::TQ, px = t - py * G::TQ;
+        const int pix = t < G::NPIX ? py * G::ST * G::LWQ + px : 0;
+        bbase[pb] = pix + h * G::HOFF;
+    }
+
+    // Filter values of this lane for sub-chunk (c, g): rows g*RG + h*R2 .. + RG of
+    // w[k][c], RG*S consecutive floats.  Rows past R (second half, odd R) are zeros and
+    // are not read.
+    const float *w_lane[G::KBW];
+#pragma unroll
+    for (int kb = 0; kb < G::KBW; ++kb) {
+        int krow = k0 + (wk * G::KBW + kb) * 32 + j;
+        krow = krow < K ? krow : K - 1;
+        w_lane[kb] = a.w + (size_t)krow * C * G::R * G::S + h * G::R2 * G::S;
+    }
+    auto load_a = [&](float (&dst)[G::KBW][G::NA], int c, int g) {
+#pragma unroll
+        for (int kb = 0; kb < G::KBW; ++kb) {
+        const float *p = w_lane[kb] + ((size_t)c * G::R + g * G::RG) * G::S;
+#pragma unroll
+        for (int i = 0; i < G::RG; ++i) {
+            const float *pr = p + i * G::S;
+            float *d = dst[kb] + i * G::S;
+            // row g*RG + i + h*R2 exists for both halves iff it exists for the second
+            const bool both = g * G::RG + i + G::R2 < G::R;
+            const bool ok = both | (h == 0);
+            const float *q = ok ? pr : a.w;     // lanes without a row read a valid address
+            constexpr int N4 = G::S / 4, REM = G::S % 4;
+#pragma unroll
+            for (int u = 0; u < N4; ++u) {
+                const dma_f4u v = *reinterpret_cast<const dma_f4u *>(q + 4 * u);
+                d[4 * u] = v[0]; d[4 * u + 1] = v[1]; d[4 * u + 2] = v[2]; d[4 * u + 3] = v[3];
+            }
+            if (REM >= 2) {
+                const dma_f2u v = *reinterpret_cast<const dma_f2u *>(q + 4 * N4);
+                d[4 * N4] = v[0]; d[4 * N4 + 1] = v[1];
+            }
+            if (REM & 1) d[G::S - 1] = q[G::S - 1];
+            if (!both) {
+#pragma unroll
+                for (int u = 0; u < G::S; ++u) d[u] = ok ? d[u] : 0.f;
+            }
+        }
+        }
+    };
+
+    dma_floatx16 acc[G::KBW][G::PBW];
+#pragma unroll
+    for (int kb = 0; kb < G::KBW; ++kb)
+#pragma unroll
+        for (int pb = 0; pb < G::PBW; ++pb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[kb][pb][v] = 0.f;
+
+    // RG*S rank-2 updates: rows g*RG .. of the first half, columns 0 .. S-1
+    auto compute = [&](const float *chan, int g, const float (&av)[G::KBW][G::NA]) {
+#pragma unroll
+        for (int i = 0; i < G::RG; ++i)
+#pragma unroll
+            for (int s = 0; s < G::S; ++s) {
+                const int boff = (s % G::ST) * G::PH + (g * G::RG + i) * G::LWQ + s / G::ST;
+                float bv[G::PBW];
+#pragma unroll
+                for (int pb = 0; pb < G::PBW; ++pb) bv[pb] = chan[bbase[pb] + boff];
+#pragma unroll
+                for (int kb = 0; kb < G::KBW; ++kb)
+#pragma unroll
+                    for (int pb = 0; pb < G::PBW; ++pb)
+                        acc[kb][pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[kb][i * G::S + s], bv[pb], acc[kb][pb], 0, 0, 0);
+            }
+    };
+
+    float a0[G::KBW][G::NA], a1[G::KBW][G::NA];
+    load_a(a0, 0, 0);
+    __syncthreads();   // the staged window is complete (the compiler waits for the LDS-direct loads)
+    for (int c = 0; c < C; ++c) {
+        const float *chan = lds + c * G::PSP;
+#pragma unroll
+        for (int g = 0; g < G::NSUB; g += 2) {
+            load_a(a1, c, g + 1);
+            compute(chan, g, a0);
+            {
+                // next sub-chunk: same channel, or the first of the next channel (clamped at the end)
+                const bool last = g + 2 == G::NSUB;
+                const int cn = last ? (c + 1 < C ? c + 1 : c) : c;
+                load_a(a0, cn, last ? 0 : g + 2);
+            }
+            compute(chan, g + 1, a1);
+        }
+    }
+
+    // ---- epilogue: each output element is written exactly once ----
+    float *out_n = a.out + (size_t)n * K * P * Q;
+#pragma unroll
+    for (int pb = 0; pb < G::PBW; ++pb) {
+        const int t = (wp * G::PBW + pb) * 32 + j;
+        const int py = t / G::TQ, px = t - py * G::TQ;
+        const int p = p0 + py, q = q0 + px;
+        if (t < G::NPIX && p < P && q < Q) {
+#pragma unroll
+            for (int kb = 0; kb < G::KBW; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int k = k0 + (wk * G::KBW + kb) * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (k < K) out_n[((size_t)k * P + p) * Q + q] = acc[kb][pb][v];
+                }
+        }
+    }
+}
+
+template <class G>
+static hipError_t launch_rows(const KernelArgs &a, unsigned grid, hipStream_t stream)
+{
+    if (a.s.C > G::CM) return hipErrorInvalidValue;   // the planner never asks for this
+    if (G::LDS_BYTES > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_rows_kernel<G>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((conv_rows_kernel<G>), dim3(grid), dim3(G::NT), G::LDS_BYTES, stream, a);
+    return hipGetLastError();
+}
+
+template <class G>
+static size_t lds_rows(const Shape &) { return G::LDS_BYTES; }
+
+template <class G>
+constexpr Variant make_rows_variant(const char *name)
+{
+    return Variant{name, G::R, G::S, G::ST, G::TP, G::TQ, G::KT, G::NPB, G::CM, G::PAIR, G::NT, G::OCC,
+                   &lds_rows<G>, &launch_rows<G>};
+}
+
+}  // namespace convd

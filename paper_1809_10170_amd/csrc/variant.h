@@ -19,7 +19,9 @@ struct KernelArgs {
     int tilesP, tilesQ, ktiles;   // grid = ktiles * tilesQ * tilesP * N workgroups
 };
 
-enum Pair { PAIR_C = 0, PAIR_S = 1 };
+// which reduction index the two k-lanes of one MFMA span: two input channels, or
+// filter rows r and r + ceil(R/2) of one channel
+enum Pair { PAIR_C = 0, PAIR_R = 2 };
 
 struct Variant {
     const char *name;
@@ -27,7 +29,7 @@ struct Variant {
     int TP, TQ;           // output tile of one workgroup: TP rows x TQ columns of one image
     int KT;               // output channels per workgroup
     int NPB;              // 32-pixel MFMA column blocks per workgroup (NPB*32 >= TP*TQ)
-    int CB;               // input channels staged per LDS chunk
+    int CB;               // input channels staged per LDS chunk (PAIR_R: most channels the variant takes)
     int pair;             // which reduction index the two k-lanes of one MFMA span
     int threads;          // workgroup size
     int occupancy;        // workgroups per CU the variant is sized for

@@ -120,10 +120,23 @@ def test_every_variant_plans_a_matching_shape():
     names = cd.variant_names()
     assert len(names) == len(set(names)) and any(n.startswith("generic") for n in names)
     for nm in names:
-        m = re.match(r"f(\d+)s(\d+)_", nm)
+        m = re.match(r"[fdr](\d+)s(\d+)_", nm)
         R, st = (int(m.group(1)), int(m.group(2))) if m else (4, 3)
-        plan = cd.Plan(2, 6, 37, 41, 70, R, R, st, R // 2, variant=nm)
+        C = 3 if nm.startswith("r") else 6   # the row-pair family takes only a few channels
+        plan = cd.Plan(2, C, 37, 41, 70, R, R, st, R // 2, variant=nm)
         info = plan.info()
         assert info["variant"] == nm
         _check_cover(info, exhaustive=True)
         plan.destroy()
+
+
+def test_no_kernel_uses_private_scratch():
+    """Zero workspace includes hidden memory: no kernel may spill registers to scratch
+    or use a dynamic stack (read from the compiler's resource report of the last build)."""
+    from paper_1809_10170_amd import build
+    recs = [r for r in build.kernel_resources() if "conv_" in r["kernel"]]
+    assert recs, "no resource report: build with `python -m paper_1809_10170_amd.build`"
+    for r in recs:
+        assert int(r["ScratchSize [bytes/lane]"]) == 0, r
+        assert r["Dynamic Stack"] == "False", r
+        assert int(r["VGPRs Spill"]) == 0, r
