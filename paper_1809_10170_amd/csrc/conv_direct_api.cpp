@@ -55,8 +55,11 @@ bool applicable(const Variant &v, const Shape &s)
 {
     if (v.R != 0 && (v.R != s.R || v.S != s.S || v.stride != s.stride)) return false;
     if (v.pair == convd::PAIR_R && s.C > v.CB) return false;   // stages all channels at once
+    if (v.img != 0 && (s.H != v.img || s.W != v.img || s.pad != v.pad)) return false;   // flat tiling
     if (v.lds_bytes(s) > kLdsPerCU) return false;
-    const int64_t grid = (int64_t)cdiv(s.K, v.KT) * cdiv(s.P, v.TP) * cdiv(s.Q, v.TQ) * s.N;
+    const int64_t grid = v.img != 0
+                             ? (int64_t)cdiv(s.K, v.KT) * ((((int64_t)s.N * s.P * s.Q) + v.NPB * 32 - 1) / (v.NPB * 32))
+                             : (int64_t)cdiv(s.K, v.KT) * cdiv(s.P, v.TP) * cdiv(s.Q, v.TQ) * s.N;
     return grid > 0 && grid < kMaxElems;
 }
 
@@ -64,10 +67,17 @@ void fill(conv_direct_plan *p, const Shape &s, const Variant &v)
 {
     p->s = s;
     p->v = &v;
-    p->tilesP = cdiv(s.P, v.TP);
-    p->tilesQ = cdiv(s.Q, v.TQ);
     p->ktiles = cdiv(s.K, v.KT);
-    p->grid = (unsigned)((int64_t)p->ktiles * p->tilesP * p->tilesQ * s.N);
+    if (v.img != 0) {
+        // flat tiling: tilesQ pixel tiles of NPB*32 consecutive pixels over all images
+        p->tilesP = 1;
+        p->tilesQ = (int)((((int64_t)s.N * s.P * s.Q) + v.NPB * 32 - 1) / (v.NPB * 32));
+        p->grid = (unsigned)((int64_t)p->ktiles * p->tilesQ);
+    } else {
+        p->tilesP = cdiv(s.P, v.TP);
+        p->tilesQ = cdiv(s.Q, v.TQ);
+        p->grid = (unsigned)((int64_t)p->ktiles * p->tilesP * p->tilesQ * s.N);
+    }
     p->lds_bytes = v.lds_bytes(s);
     // issued MACs: every workgroup runs KT x (NPB*32) outputs over the padded reduction
     double red;
@@ -210,11 +220,11 @@ int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
     return std::snprintf(buf, n,
                          "variant=%s N=%d C=%d H=%d W=%d K=%d R=%d S=%d stride=%d pad=%d P=%d Q=%d "
                          "TP=%d TQ=%d KT=%d NPB=%d CB=%d pair=%s tilesP=%d tilesQ=%d ktiles=%d grid=%u "
-                         "threads=%d lds_bytes=%zu occupancy=%d mfma_efficiency=%.4f workspace_bytes=0",
+                         "threads=%d lds_bytes=%zu occupancy=%d flat=%d mfma_efficiency=%.4f workspace_bytes=0",
                          v.name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, v.TP, v.TQ,
                          v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : "r", plan->tilesP,
                          plan->tilesQ, plan->ktiles, plan->grid, v.threads, plan->lds_bytes, v.occupancy,
-                         plan->mfma_efficiency);
+                         v.img != 0 ? 1 : 0, plan->mfma_efficiency);
 }
 
 const char *conv_direct_strerror(int code)

@@ -41,18 +41,37 @@ typedef float dma_floatx16 __attribute__((ext_vector_type(16)));
 typedef float dma_f4u __attribute__((ext_vector_type(4), aligned(4)));
 typedef float dma_f2u __attribute__((ext_vector_type(2), aligned(4)));
 
-template <int R_, int S_, int ST_, int TP_, int TQ_, int PBW_, int WK_, int WP_, int CB_, int OCC_>
+// Two tilings of the output pixels:
+//   rectangular (IMG_ = 0): a workgroup owns TP x TQ pixels of one image;
+//   flat (IMG_ > 0): for small square images of IMG_ x IMG_ pixels and padding PADC_
+//     (both fixed at compile time) the pixels of ALL images are numbered
+//     m = (n*P + p)*Q + q and a workgroup owns 32*PBW*WP consecutive ones, whatever
+//     image or row they fall in.  Its LDS window holds every input row those pixels
+//     touch, the rows of one image after those of the previous one.  No MFMA column
+//     is wasted on tile edges and the grid can be cut to fit the machine.
+template <int R_, int S_, int ST_, int TP_, int TQ_, int PBW_, int WK_, int WP_, int CB_, int OCC_, int IMG_ = 0,
+          int PADC_ = 0>
 struct DmaGeom {
-    static constexpr int R = R_, S = S_, ST = ST_, TP = TP_, TQ = TQ_;
+    static constexpr int R = R_, S = S_, ST = ST_;
     static constexpr int PBW = PBW_, WK = WK_, WP = WP_, CB = CB_, OCC = OCC_;
+    static constexpr int IMG = IMG_, PADC = PADC_;
+    static constexpr bool FLAT = IMG_ > 0;
+    static constexpr int OQ = FLAT ? (IMG + 2 * PADC - S) / ST + 1 : 0;       // flat: output width
+    static constexpr int OP = FLAT ? (IMG + 2 * PADC - R) / ST + 1 : 0;       // flat: output height
+    static constexpr int NPIXF = 32 * PBW * WP;                                // flat: pixels per workgroup
+    static constexpr int NRMAX = FLAT ? (NPIXF + OQ - 2) / OQ + 1 : 0;         // flat: output rows a tile can touch
+    static constexpr int NSI = FLAT ? (NRMAX + OP - 2) / OP + 1 : 1;           // flat: images a tile can touch
+    static constexpr int TP = FLAT ? 0 : TP_, TQ = FLAT ? OQ : TQ_;
     static constexpr int PAIR = PAIR_C;
     static constexpr int NT = 64 * WK * WP;              // threads per workgroup
     static constexpr int WPE = (OCC * WK * WP + 3) / 4;  // waves per SIMD the register budget must allow
     static constexpr int KT = 32 * WK;                   // output channels per workgroup
     static constexpr int NPB = PBW * WP;                 // 32-pixel blocks per workgroup
-    static constexpr int NPIX = TP * TQ;                 // real pixels in the tile
+    static constexpr int NPIX = FLAT ? NPIXF : TP * TQ;  // real pixels in the tile
     static constexpr int RS = R * S;
-    static constexpr int LH = (TP - 1) * ST + R;         // halo window rows
+    // halo window rows; flat: consecutive output rows of one image share input rows as
+    // usual, a new image starts R - ST rows further down
+    static constexpr int LH = FLAT ? (NRMAX - 1) * ST + R + (NSI - 1) * (R - ST) : (TP - 1) * ST + R;
     static constexpr int LW = (TQ - 1) * ST + S;         // halo window columns = LDS row pitch
     static constexpr int PS = LH * LW;                   // floats of one channel's window
     static constexpr int NSEG = (PS + 63) / 64;          // 64-lane loads per channel
@@ -63,8 +82,9 @@ struct DmaGeom {
     static constexpr int ITEMS = (CB * PSP + NT - 1) / NT;   // 64-lane loads per wave and chunk
     static constexpr int NA = HC * RS;                   // filter values per lane and chunk
     static constexpr int STEPS = HC * RS;                // MFMA k-steps per chunk
-    static constexpr size_t LDS_BYTES = sizeof(float) * 2 * (size_t)BUF;
+    static constexpr size_t LDS_BYTES = sizeof(float) * 3 * (size_t)BUF;   // three stage buffers
     static_assert(CB % 2 == 0, "channel pairing needs an even chunk");
+    static_assert(!FLAT || R >= ST, "flat tiling stacks image windows R - ST rows apart");
     static_assert(NPB * 32 >= NPIX, "pixel blocks must cover the tile");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
 };
@@ -93,10 +113,22 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
         if (bid < g8) bid = (bid & 7u) * (g8 >> 3) + (bid >> 3);
     }
     const int kt = bid % a.ktiles;  bid /= a.ktiles;
-    const int tq = bid % a.tilesQ;  bid /= a.tilesQ;
-    const int tp = bid % a.tilesP;
-    const int n = bid / a.tilesP;
-    const int p0 = tp * G::TP, q0 = tq * G::TQ, k0 = kt * G::KT;
+    const int k0 = kt * G::KT;
+    // rectangular: image n, tile origin (p0, q0).  flat: first pixel m0 of M, which
+    // lies in output row g0 (rows of all images numbered through) of image n
+    int n, p0 = 0, q0 = 0, m0 = 0, g0 = 0, M = 0;
+    if (G::FLAT) {
+        m0 = (int)bid * G::NPIXF;
+        M = a.s.N * G::OP * G::OQ;
+        g0 = m0 / G::OQ;
+        n = g0 / G::OP;
+    } else {
+        const int tq = bid % a.tilesQ;  bid /= a.tilesQ;
+        const int tp = bid % a.tilesP;
+        n = bid / a.tilesP;
+        p0 = tp * G::TP;
+        q0 = tq * G::TQ;
+    }
     const int ih0 = p0 * G::ST - a.s.pad, iw0 = q0 * G::ST - a.s.pad;
 
     // per-lane LDS read offsets (floats): pixel position plus the kk half
@@ -104,39 +136,67 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
 #pragma unroll
     for (int pb = 0; pb < G::PBW; ++pb) {
         const int t = (wp * G::PBW + pb) * 32 + j;
-        const int py = t / G::TQ, px = t - py * G::TQ;
-        const int pix = t < G::NPIX ? py * G::ST * G::LW + px * G::ST : 0;
+        int pix;
+        if (G::FLAT) {
+            int m = m0 + t;
+            m = m < M ? m : M - 1;                       // past the last pixel: any valid position
+            const int g = m / G::OQ, q = m - g * G::OQ;
+            const int sI = g / G::OP - n;                // which of the tile's images
+            pix = ((g - g0) * G::ST + sI * (G::R - G::ST)) * G::LW + q * G::ST;
+        } else {
+            const int py = t / G::TQ, px = t - py * G::TQ;
+            pix = t < G::NPIX ? py * G::ST * G::LW + px * G::ST : 0;
+        }
         bbase[pb] = pix + h * G::HOFF;
     }
 
     // Input staging plan: thread tid owns positions tid + i*NT of the chunk's
-    // [CB][PSP] window array; its byte offset from the chunk's first channel, or an
-    // offset no buffer can reach where the window lies outside the image.
+    // [CB][PSP] window array; its byte offset from the chunk's first channel (of the
+    // tile's first image), or an offset no buffer can reach where the window lies
+    // outside the image.
     unsigned goff[G::ITEMS];
 #pragma unroll
     for (int i = 0; i < G::ITEMS; ++i) {
         const int f = i * G::NT + tid;
         const int cc = f / G::PSP, pos = f - cc * G::PSP;
         const int hh = pos / G::LW, col = pos - hh * G::LW;
-        const int ih = ih0 + hh, iw = iw0 + col;
-        const bool ok = (f < G::CB * G::PSP) & (pos < G::PS) & ((unsigned)ih < (unsigned)H) &
+        int ih, img = 0;
+        if (G::FLAT) {
+            // window row hh belongs to the last image whose first row is not below it
+            int gs = g0, start = 0;
+#pragma unroll
+            for (int u = 1; u < G::NSI; ++u) {
+                const int gu = (n + u) * G::OP, su = (gu - g0) * G::ST + u * (G::R - G::ST);
+                if (hh >= su) { img = u; gs = gu; start = su; }
+            }
+            ih = hh - start + (gs - (n + img) * G::OP) * G::ST - a.s.pad;
+        } else {
+            ih = ih0 + hh;
+        }
+        const int iw = iw0 + col;
+        const bool ok = (f < G::CB * G::PSP) & (pos < G::PS) & (n + img < a.s.N) & ((unsigned)ih < (unsigned)H) &
                         ((unsigned)iw < (unsigned)W);
-        goff[i] = ok ? (unsigned)(((cc * H + ih) * W + iw) * 4) : 0x80000000u;
+        goff[i] = ok ? (unsigned)((((img * C + cc) * H + ih) * W + iw) * 4) : 0x80000000u;
     }
     const float *in_n = a.in + (size_t)n * C * H * W;
     const unsigned chan_bytes = (unsigned)(H * W) * 4u;
 
-    // Stage the input window of channels [c0, c0 + CB) into buf.  The resource ends
-    // at the image's last channel, so channels past C read as zeros.
+    // Stage the input window of channels [c0, c0 + CB) into buf.  Rectangular: the
+    // resource ends at the image's last channel, so channels past C read as zeros.
+    // Flat: the window spans images, so the resource runs on and the loads of channels
+    // past C are given the unreachable offset instead.
     auto stage_b = [&](float *buf, int c0) {
-        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)(in_n + (size_t)c0 * H * W), 0, (int)((unsigned)(C - c0) * chan_bytes), 0x00020000);
+        const unsigned span = G::FLAT ? 0x7fffffffu : (unsigned)(C - c0) * chan_bytes;
+        __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc((void *)(in_n + (size_t)c0 * H * W), 0, (int)span, 0x00020000);
 #pragma unroll
         for (int i = 0; i < G::ITEMS; ++i) {
             const int f0 = i * G::NT + wave * 64;           // first position of this wave's 64
             if (f0 < G::CB * G::PSP) {
                 float *dst = buf + f0 + (f0 >= G::HC * G::PSP ? 32 : 0);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, CONVD_LDS(dst), 4, goff[i], 0, 0, 0);
+                unsigned off = goff[i];
+                if (G::FLAT) off = c0 + f0 / G::PSP < C ? off : 0x80000000u;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, CONVD_LDS(dst), 4, off, 0, 0, 0);
             }
         }
     };
@@ -177,59 +237,96 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[pb][v] = 0.f;
 
-    // The reduction over one staged chunk: STEPS rank-2 updates of the wave's tile.
-    auto compute = [&](const float *buf, const float (&av)[G::NA]) {
+    // Chunk i lives in stage buffer i % 3 and in filter register set i % 3.
+    //
+    // One barrier per chunk, placed in the MIDDLE of the chunk's MFMA stream (step TB):
+    // it publishes chunk i+1 (its LDS-direct loads and filter loads were issued one
+    // whole chunk earlier, right after the previous barrier) and proves that every
+    // wave is done with chunk i-1, whose buffer and register set then take chunk i+2.
+    // Because chunk i+1 is readable half a chunk before it is needed, the operand
+    // fetch of its first step is issued under the last MFMAs of chunk i: the matrix
+    // pipe sees no gap at a chunk boundary.  Within a chunk the B operands of step
+    // t+1 are fetched while step t multiplies.
+    constexpr int TB = G::STEPS / 2;
+    auto step_off = [](int t) {   // LDS offset (floats) of reduction step t of a chunk
+        const int cc = t / G::RS, rs = t - cc * G::RS;
+        return cc * G::PSP + (rs / G::S) * G::LW + rs % G::S;
+    };
+    auto fetch = [&](const float *buf, int t, float (&bv)[G::PBW]) {
 #pragma unroll
-        for (int cc = 0; cc < G::HC; ++cc)
+        for (int pb = 0; pb < G::PBW; ++pb) bv[pb] = buf[bbase[pb] + step_off(t)];
+    };
+    const int nch = (C + G::CB - 1) / G::CB;
+    float bcur[G::PBW];
+    // i3 = i % 3 (compile time): buffers and register sets rotate with the chunk index
+    auto chunk = [&](int i, const float *bufc, const float *bufn, float *bufnn, const float (&ac)[G::NA],
+                     float (&ann)[G::NA]) {
 #pragma unroll
-            for (int r = 0; r < G::R; ++r)
-#pragma unroll
-                for (int s = 0; s < G::S; ++s) {
-                    const int boff = cc * G::PSP + r * G::LW + s;
-                    const float aval = av[(cc * G::R + r) * G::S + s];
-#pragma unroll
-                    for (int pb = 0; pb < G::PBW; ++pb)
-                        acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(aval, buf[bbase[pb] + boff], acc[pb], 0, 0, 0);
+        for (int t = 0; t < G::STEPS; ++t) {
+            if (t == TB) {
+                __syncthreads();
+                if (i + 2 < nch) {
+                    stage_b(bufnn, (i + 2) * G::CB);
+                    load_a(ann, (i + 2) * G::CB);
                 }
+            }
+            float bnext[G::PBW];
+            if (t + 1 < G::STEPS) fetch(bufc, t + 1, bnext);
+            else fetch(bufn, 0, bnext);     // past the last chunk: stale but in-bounds, never used
+#pragma unroll
+            for (int pb = 0; pb < G::PBW; ++pb)
+                acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac[t], bcur[pb], acc[pb], 0, 0, 0);
+#pragma unroll
+            for (int pb = 0; pb < G::PBW; ++pb) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+            }
+#pragma unroll
+            for (int pb = 0; pb < G::PBW; ++pb) bcur[pb] = bnext[pb];
+        }
     };
 
-    // Two stage buffers and two register sets, used alternately: chunk i+1 is in
-    // flight (LDS-direct loads and filter loads) while chunk i is reduced.
-    float *buf0 = lds, *buf1 = lds + G::BUF;
-    float a0[G::NA], a1[G::NA];
-    const int nch = (C + G::CB - 1) / G::CB;
-    stage_b(buf0, 0);
+    float a0[G::NA], a1[G::NA], a2[G::NA];
+    float *b0 = lds, *b1 = lds + G::BUF, *b2 = lds + 2 * G::BUF;
+    stage_b(b0, 0);
     load_a(a0, 0);
+    if (nch > 1) {
+        stage_b(b1, G::CB);
+        load_a(a1, G::CB);
+    }
     __syncthreads();
-    for (int ci = 0;; ci += 2) {
-        if (ci + 1 < nch) {
-            stage_b(buf1, (ci + 1) * G::CB);
-            load_a(a1, (ci + 1) * G::CB);
-        }
-        compute(buf0, a0);
-        __syncthreads();
+    fetch(b0, 0, bcur);
+    for (int ci = 0;; ci += 3) {
+        chunk(ci, b0, b1, b2, a0, a2);
         if (ci + 1 >= nch) break;
-        if (ci + 2 < nch) {
-            stage_b(buf0, (ci + 2) * G::CB);
-            load_a(a0, (ci + 2) * G::CB);
-        }
-        compute(buf1, a1);
-        __syncthreads();
+        chunk(ci + 1, b1, b2, b0, a1, a0);
         if (ci + 2 >= nch) break;
+        chunk(ci + 2, b2, b0, b1, a2, a1);
+        if (ci + 3 >= nch) break;
     }
 
     // ---- epilogue: each output element is written exactly once ----
-    float *out_n = a.out + (size_t)n * K * P * Q;
 #pragma unroll
     for (int pb = 0; pb < G::PBW; ++pb) {
         const int t = (wp * G::PBW + pb) * 32 + j;
-        const int py = t / G::TQ, px = t - py * G::TQ;
-        const int p = p0 + py, q = q0 + px;
-        if (t < G::NPIX && p < P && q < Q) {
+        bool live;
+        size_t o;      // offset of out[n'][0][p][q]
+        if (G::FLAT) {
+            const int m = m0 + t, pq = G::OP * G::OQ;
+            const int ni = m / pq;
+            live = m < M;
+            o = (size_t)ni * K * pq + (m - ni * pq);
+        } else {
+            const int py = t / G::TQ, px = t - py * G::TQ;
+            const int p = p0 + py, q = q0 + px;
+            live = t < G::NPIX && p < P && q < Q;
+            o = (size_t)n * K * P * Q + (size_t)p * Q + q;
+        }
+        if (live) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int k = k0 + wk * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-                if (k < K) out_n[((size_t)k * P + p) * Q + q] = acc[pb][v];
+                if (k < K) a.out[o + (size_t)k * P * Q] = acc[pb][v];
             }
         }
     }
@@ -257,8 +354,8 @@ static size_t lds_dma(const Shape &) { return G::LDS_BYTES; }
 template <class G>
 constexpr Variant make_dma_variant(const char *name)
 {
-    return Variant{name, G::R, G::S, G::ST, G::TP, G::TQ, G::KT, G::NPB, G::CB, G::PAIR, G::NT, G::OCC,
-                   &lds_dma<G>, &launch_dma<G>};
+    return Variant{name, G::R, G::S, G::ST, G::TP, G::FLAT ? 0 : G::TQ, G::KT, G::NPB, G::CB, G::PAIR, G::NT, G::OCC,
+                   G::IMG, G::PADC, &lds_dma<G>, &launch_dma<G>};
 }
 
 }  // namespace convd

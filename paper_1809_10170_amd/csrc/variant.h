@@ -33,6 +33,8 @@ struct Variant {
     int pair;             // which reduction index the two k-lanes of one MFMA span
     int threads;          // workgroup size
     int occupancy;        // workgroups per CU the variant is sized for
+    int img, pad;         // flat tiling only (img > 0): the H = W and the pad the variant is compiled for;
+                          // a workgroup then owns NPB*32 consecutive pixels of all images (TP = TQ = 0)
     size_t (*lds_bytes)(const Shape &);
     hipError_t (*launch)(const KernelArgs &, unsigned grid, hipStream_t stream);
 };

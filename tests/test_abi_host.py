@@ -70,16 +70,22 @@ def _check_cover(info, exhaustive):
     N, K, P, Q = info["N"], info["K"], info["P"], info["Q"]
     TP, TQ, KT = info["TP"], info["TQ"], info["KT"]
     tP, tQ, tK = info["tilesP"], info["tilesQ"], info["ktiles"]
-    assert info["grid"] == tP * tQ * tK * N
-    assert info["NPB"] * 32 >= TP * TQ
-    assert (tP - 1) * TP < P <= tP * TP
-    assert (tQ - 1) * TQ < Q <= tQ * TQ
     assert (tK - 1) * KT < K <= tK * KT
+    if info["flat"]:
+        # flat tiling: tQ tiles of NPB*32 consecutive pixels numbered over all images
+        npix = info["NPB"] * 32
+        assert info["grid"] == tQ * tK and tP == 1
+        assert (tQ - 1) * npix < N * P * Q <= tQ * npix
+    else:
+        assert info["grid"] == tP * tQ * tK * N
+        assert info["NPB"] * 32 >= TP * TQ
+        assert (tP - 1) * TP < P <= tP * TP
+        assert (tQ - 1) * TQ < Q <= tQ * TQ
     assert info["lds_bytes"] <= 160 * 1024
     assert info["threads"] % 64 == 0 and 64 <= info["threads"] <= 1024
     assert info["workspace_bytes"] == 0
     assert 0.0 < info["mfma_efficiency"] <= 1.0
-    if exhaustive:
+    if exhaustive and not info["flat"]:
         # replay the kernel's workgroup -> tile decode and count writers per output
         hits = np.zeros((N, K, P, Q), np.int32)
         for bid in range(info["grid"]):
@@ -123,7 +129,9 @@ def test_every_variant_plans_a_matching_shape():
         m = re.match(r"[fdr](\d+)s(\d+)_", nm)
         R, st = (int(m.group(1)), int(m.group(2))) if m else (4, 3)
         C = 3 if nm.startswith("r") else 6   # the row-pair family takes only a few channels
-        plan = cd.Plan(2, C, 37, 41, 70, R, R, st, R // 2, variant=nm)
+        fl = re.search(r"_flat(\d+)_", nm)     # flat tiling is compiled for one image size
+        H, W = (int(fl.group(1)),) * 2 if fl else (37, 41)
+        plan = cd.Plan(2, C, H, W, 70, R, R, st, R // 2, variant=nm)
         info = plan.info()
         assert info["variant"] == nm
         _check_cover(info, exhaustive=True)

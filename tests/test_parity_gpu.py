@@ -100,6 +100,10 @@ def test_every_variant_on_ragged_shape(oracle, name):
         H, W = 83, 241
     elif name.startswith("r"):
         C = 3   # the row-pair family stages all channels at once and takes only a few
+    fl = re.search(r"_flat(\d+)_", name)   # flat tiling is compiled for one image size; many
+    if fl:                                   # images, so that tiles straddle several of them
+        H = W = int(fl.group(1))
+        N = 9
     pd = R // 2
     rng = np.random.default_rng(300 + R + st)
     x = rng.integers(-4, 5, (N, C, H, W)).astype(np.float32)
