@@ -34,6 +34,8 @@ constexpr int64_t kMaxElems = (int64_t)1 << 31;
 thread_local int t_last_hip_error = 0;
 
 int cdiv(int a, int b) { return (a + b - 1) / b; }
+int64_t cdiv64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+constexpr int convd_generic_tq = 32;   // pixel columns per workgroup of the runtime-shape fallback
 
 int validate(int N, int C, int H, int W, int K, int R, int S, int stride, int pad, Shape *out)
 {
@@ -93,23 +95,50 @@ void fill(conv_direct_plan *p, const Shape &s, const Variant &v)
     p->mfma_efficiency = useful / issued;
 }
 
-// Estimated time, in arbitrary units, of running the plan: workgroups are dealt
-// evenly to the CUs; a CU works through its share with up to `occupancy` of them
-// resident, and its four matrix pipes are busy only as far as resident waves cover
-// them.  Waves that have a pipe to themselves cannot hide their own staging and
-// barriers, which the last factor charges for.
+// Estimated run time of the plan in shader clocks (a model, used only to rank the
+// variants that can run a shape).  It is the analytical counterpart, for this GPU, of
+// the paper's Section 3.1 reasoning about how many independent FMAs keep the pipes
+// busy (Equation 1) within the register file (Equation 2):
+//   * a wave needs `mfma_per_wave` 64-clock MFMAs; a SIMD shared by w resident waves
+//     finishes them in w times that, at an efficiency that is high when a second wave
+//     covers the first one's waits and lower when a wave has the pipe to itself;
+//   * workgroups fill the chip's resident slots round after round; the last, partial
+//     round runs with fewer waves per SIMD;
+//   * every workgroup re-stages its input window: bytes that cross L2 -> LDS, charged
+//     at a bandwidth fitted to measurements.  This is what makes compact tiles (small
+//     halo) and wide channel tiles (fewer re-reads of the input) win ties.
 double cost(const conv_direct_plan &p)
 {
     const Variant &v = *p.v;
-    const double useful = (double)p.s.N * p.s.K * p.s.P * p.s.Q * ((double)p.s.C * p.s.R * p.s.S);
-    const double macs_per_wg = useful / p.mfma_efficiency / p.grid;
-    const int waves_per_wg = v.threads / 64;
-    const int wg_per_cu = cdiv((int)p.grid, kNumCU);
-    const int resident = wg_per_cu < v.occupancy ? wg_per_cu : v.occupancy;
-    const int resident_waves = resident * waves_per_wg;
-    const double pipes = resident_waves < 4 ? resident_waves : 4;
-    double c = wg_per_cu * macs_per_wg / pipes;
-    c *= 1.0 + 0.25 * 4.0 / (resident_waves < 4 ? 4 : resident_waves);
+    const Shape &s = p.s;
+    const int wpw = v.threads / 64;                                // waves per workgroup
+    const double useful = (double)s.N * s.K * s.P * s.Q * ((double)s.C * s.R * s.S);
+    const double mfma_per_wave = useful / p.mfma_efficiency / p.grid / wpw / 2048.0;   // 32*32*2 MACs each
+    auto round_time = [&](int wgs_per_cu) {
+        const int waves_per_simd = cdiv(wgs_per_cu * wpw, 4);      // the busiest SIMD
+        const double eff = waves_per_simd >= 2 ? 0.96 : 0.80;
+        return mfma_per_wave * 64.0 * waves_per_simd / eff;
+    };
+    int occ = v.occupancy;
+    const int lds_fit = (int)(kLdsPerCU / (p.lds_bytes ? p.lds_bytes : 1));
+    if (occ > lds_fit) occ = lds_fit;
+    if (occ < 1) occ = 1;
+    const int64_t slots = (int64_t)kNumCU * occ;
+    const int64_t full = p.grid / slots, rem = p.grid % slots;
+    double c = full * round_time(occ);
+    if (rem) c += round_time((int)cdiv64(rem, kNumCU));
+    // prologue and epilogue of each workgroup, mostly hidden behind its CU neighbours
+    c += 12000.0 * (double)cdiv64(p.grid, slots);
+    // input staging traffic
+    double staged;   // floats one workgroup stages in total
+    if (v.R == 0) {
+        staged = (double)s.C * s.R * (2.0 * ((convd_generic_tq - 1) * s.stride + s.S)) * 2.0;
+    } else if (v.pair == convd::PAIR_R) {
+        staged = (double)s.C * v.window;
+    } else {
+        staged = (double)cdiv(s.C, v.CB) * v.CB * v.window;
+    }
+    c += staged * 4.0 * p.grid / 1024.0;
     if (v.R == 0) c *= 3.0;   // the runtime-shape fallback synchronises far more often
     return c;
 }

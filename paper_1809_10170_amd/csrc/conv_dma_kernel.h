@@ -91,7 +91,11 @@ struct DmaGeom {
 
 #define CONVD_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 
-template <class G>
+// TAILC: C is not a multiple of CB.  The last chunk then reaches past the input
+// channels; its filter values are fetched one by one (never past the tensor) and
+// cleared where the channel does not exist.  TAILC = false needs C % CB == 0 and
+// keeps the steady state free of branches and of per-value work.
+template <class G, bool TAILC>
 __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArgs a)
 {
     extern __shared__ __align__(16) float lds[];
@@ -118,10 +122,12 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
     // lies in output row g0 (rows of all images numbered through) of image n
     int n, p0 = 0, q0 = 0, m0 = 0, g0 = 0, M = 0;
     if (G::FLAT) {
+        // (the divisions run on the vector unit; the results are the same in every lane
+        // and go back to scalar registers, or the buffer resource would not be uniform)
         m0 = (int)bid * G::NPIXF;
         M = a.s.N * G::OP * G::OQ;
-        g0 = m0 / G::OQ;
-        n = g0 / G::OP;
+        g0 = __builtin_amdgcn_readfirstlane(m0 / G::OQ);
+        n = __builtin_amdgcn_readfirstlane(g0 / G::OP);
     } else {
         const int tq = bid % a.tilesQ;  bid /= a.tilesQ;
         const int tp = bid % a.tilesP;
@@ -187,8 +193,14 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
     // past C are given the unreachable offset instead.
     auto stage_b = [&](float *buf, int c0) {
         const unsigned span = G::FLAT ? 0x7fffffffu : (unsigned)(C - c0) * chan_bytes;
-        __amdgpu_buffer_rsrc_t rsrc =
-            __builtin_amdgcn_make_buffer_rsrc((void *)(in_n + (size_t)c0 * H * W), 0, (int)span, 0x00020000);
+        // the base is the same in every lane; saying so keeps the resource in scalar
+        // registers (a resource the compiler takes for divergent is looped over lane by lane)
+        const uintptr_t pa = (uintptr_t)(in_n + (size_t)c0 * H * W);
+        // (readfirstlane returns a signed int: widen through unsigned, or a low half with
+        // its top bit set would smear ones over the high half)
+        const uintptr_t pu = ((uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(pa >> 32)) << 32) |
+                             (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)pa);
+        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)pu, 0, (int)span, 0x00020000);
 #pragma unroll
         for (int i = 0; i < G::ITEMS; ++i) {
             const int f0 = i * G::NT + wave * 64;           // first position of this wave's 64
@@ -206,9 +218,11 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
     int krow = k0 + wk * 32 + j;
     krow = krow < K ? krow : K - 1;
     const float *w_lane = a.w + ((size_t)krow * C + h * G::HC) * G::RS;
+    const long long w_total = (long long)K * C * G::RS;
+    const long long w_lane_idx = ((long long)krow * C + h * G::HC) * G::RS;
     auto load_a = [&](float (&dst)[G::NA], int c0) {
-        const float *p = w_lane + (size_t)c0 * G::RS;
-        if (c0 + G::CB <= C) {
+        if (!TAILC) {
+            const float *p = w_lane + (size_t)c0 * G::RS;
             constexpr int N4 = G::NA / 4, REM = G::NA % 4;
 #pragma unroll
             for (int i = 0; i < N4; ++i) {
@@ -221,14 +235,19 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
             }
             if (REM & 1) dst[G::NA - 1] = p[G::NA - 1];
         } else {
-            // last, partial chunk: channels past C contribute zero weights
+            // one value at a time, the index clamped into the tensor; values of channels
+            // that do not exist are cleared by mask_a when the chunk is used
+            const long long base = w_lane_idx + (long long)c0 * G::RS;
 #pragma unroll
             for (int e = 0; e < G::NA; ++e) {
-                const bool ok = c0 + h * G::HC + e / G::RS < C;
-                const float v = *(ok ? p + e : a.w);
-                dst[e] = ok ? v : 0.f;
+                const long long idx = base + e;
+                dst[e] = a.w[idx < w_total ? idx : w_total - 1];
             }
         }
+    };
+    auto mask_a = [&](float (&dst)[G::NA], const float (&src)[G::NA], int c0) {
+#pragma unroll
+        for (int e = 0; e < G::NA; ++e) dst[e] = (!TAILC || c0 + h * G::HC + e / G::RS < C) ? src[e] : 0.f;
     };
 
     dma_floatx16 acc[G::PBW];
@@ -259,16 +278,19 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
     const int nch = (C + G::CB - 1) / G::CB;
     float bcur[G::PBW];
     // i3 = i % 3 (compile time): buffers and register sets rotate with the chunk index
-    auto chunk = [&](int i, const float *bufc, const float *bufn, float *bufnn, const float (&ac)[G::NA],
+    auto chunk = [&](int i, const float *bufc, const float *bufn, float *bufnn, const float (&acr)[G::NA],
                      float (&ann)[G::NA]) {
+        float ac[G::NA];
+        mask_a(ac, acr, i * G::CB);
 #pragma unroll
         for (int t = 0; t < G::STEPS; ++t) {
             if (t == TB) {
                 __syncthreads();
-                if (i + 2 < nch) {
-                    stage_b(bufnn, (i + 2) * G::CB);
-                    load_a(ann, (i + 2) * G::CB);
-                }
+                // no branch here: past the last chunk the last one is staged again, into a
+                // buffer and a register set that nothing reads any more
+                const int cn = (i + 2 < nch ? i + 2 : nch - 1) * G::CB;
+                stage_b(bufnn, cn);
+                load_a(ann, cn);
             }
             float bnext[G::PBW];
             if (t + 1 < G::STEPS) fetch(bufc, t + 1, bnext);
@@ -290,9 +312,10 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
     float *b0 = lds, *b1 = lds + G::BUF, *b2 = lds + 2 * G::BUF;
     stage_b(b0, 0);
     load_a(a0, 0);
-    if (nch > 1) {
-        stage_b(b1, G::CB);
-        load_a(a1, G::CB);
+    {
+        const int c1 = nch > 1 ? G::CB : 0;
+        stage_b(b1, c1);
+        load_a(a1, c1);
     }
     __syncthreads();
     fetch(b0, 0, bcur);
@@ -335,17 +358,23 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
 // ---------------------------------------------------------------------------
 // Host side: launcher and the table entry of one compiled variant.
 // ---------------------------------------------------------------------------
-template <class G>
-static hipError_t launch_dma(const KernelArgs &a, unsigned grid, hipStream_t stream)
+template <class G, bool TAILC>
+static hipError_t launch_dma_t(const KernelArgs &a, unsigned grid, hipStream_t stream)
 {
     if (G::LDS_BYTES > 64 * 1024) {
         // workgroups above the 64 KB default need the limit raised (no allocation involved)
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_dma_kernel<G>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_dma_kernel<G, TAILC>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((conv_dma_kernel<G>), dim3(grid), dim3(G::NT), G::LDS_BYTES, stream, a);
+    hipLaunchKernelGGL((conv_dma_kernel<G, TAILC>), dim3(grid), dim3(G::NT), G::LDS_BYTES, stream, a);
     return hipGetLastError();
+}
+
+template <class G>
+static hipError_t launch_dma(const KernelArgs &a, unsigned grid, hipStream_t stream)
+{
+    return a.s.C % G::CB == 0 ? launch_dma_t<G, false>(a, grid, stream) : launch_dma_t<G, true>(a, grid, stream);
 }
 
 template <class G>
@@ -355,7 +384,7 @@ template <class G>
 constexpr Variant make_dma_variant(const char *name)
 {
     return Variant{name, G::R, G::S, G::ST, G::TP, G::FLAT ? 0 : G::TQ, G::KT, G::NPB, G::CB, G::PAIR, G::NT, G::OCC,
-                   G::IMG, G::PADC, &lds_dma<G>, &launch_dma<G>};
+                   G::PSP, G::IMG, G::PADC, &lds_dma<G>, &launch_dma<G>};
 }
 
 }  // namespace convd

@@ -113,7 +113,7 @@ static hipError_t launch_generic(const KernelArgs &a, unsigned grid, hipStream_t
 }
 
 static const Variant k_generic = {"generic_2x32_k64", 0, 0, 0, GenericGeom::TP, GenericGeom::TQ, GenericGeom::KT,
-                                  2, 2, PAIR_C, GenericGeom::NT, 2, 0, 0, &lds_generic, &launch_generic};
+                                  2, 2, PAIR_C, GenericGeom::NT, 2, 0, 0, 0, &lds_generic, &launch_generic};
 
 // the compiled variants live in their own translation units (conv_variant.hip)
 #ifndef CONVD_VARIANTS_DEF

@@ -233,7 +233,7 @@ template <class G>
 constexpr Variant make_rows_variant(const char *name)
 {
     return Variant{name, G::R, G::S, G::ST, G::TP, G::TQ, G::KT, G::NPB, G::CM, G::PAIR, G::NT, G::OCC,
-                   0, 0, &lds_rows<G>, &launch_rows<G>};
+                   G::PSP, 0, 0, &lds_rows<G>, &launch_rows<G>};
 }
 
 }  // namespace convd

@@ -33,6 +33,7 @@ struct Variant {
     int pair;             // which reduction index the two k-lanes of one MFMA span
     int threads;          // workgroup size
     int occupancy;        // workgroups per CU the variant is sized for
+    int window;           // floats of LDS window staged per input channel (0: runtime-shape fallback)
     int img, pad;         // flat tiling only (img > 0): the H = W and the pad the variant is compiled for;
                           // a workgroup then owns NPB*32 consecutive pixels of all images (TP = TQ = 0)
     size_t (*lds_bytes)(const Shape &);
