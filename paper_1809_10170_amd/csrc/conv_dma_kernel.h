@@ -50,8 +50,9 @@ typedef float dma_f2u __attribute__((ext_vector_type(2), aligned(4)));
 //     touch, the rows of one image after those of the previous one.  No MFMA column
 //     is wasted on tile edges and the grid can be cut to fit the machine.
 template <int R_, int S_, int ST_, int TP_, int TQ_, int PBW_, int WK_, int WP_, int CB_, int OCC_, int IMG_ = 0,
-          int PADC_ = 0>
+          int PADC_ = 0, int PF_ = 1>
 struct DmaGeom {
+    static constexpr int PF = PF_;                       // reduction steps the LDS operand fetch runs ahead
     static constexpr int R = R_, S = S_, ST = ST_;
     static constexpr int PBW = PBW_, WK = WK_, WP = WP_, CB = CB_, OCC = OCC_;
     static constexpr int IMG = IMG_, PADC = PADC_;
@@ -82,9 +83,10 @@ struct DmaGeom {
     static constexpr int ITEMS = (CB * PSP + NT - 1) / NT;   // 64-lane loads per wave and chunk
     static constexpr int NA = HC * RS;                   // filter values per lane and chunk
     static constexpr int STEPS = HC * RS;                // MFMA k-steps per chunk
-    static constexpr size_t LDS_BYTES = sizeof(float) * 3 * (size_t)BUF;   // three stage buffers
+    static constexpr size_t LDS_BYTES = sizeof(float) * (3 * (size_t)BUF + 16);   // three stage buffers, arrival counter
     static_assert(CB % 2 == 0, "channel pairing needs an even chunk");
     static_assert(!FLAT || R >= ST, "flat tiling stacks image windows R - ST rows apart");
+    static_assert(PF >= 1 && 2 * PF < STEPS, "operand fetches for the next chunk must follow the meeting point");
     static_assert(NPB * 32 >= NPIX, "pixel blocks must cover the tile");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
 };
@@ -258,15 +260,34 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
 
     // Chunk i lives in stage buffer i % 3 and in filter register set i % 3.
     //
-    // One barrier per chunk, placed in the MIDDLE of the chunk's MFMA stream (step TB):
-    // it publishes chunk i+1 (its LDS-direct loads and filter loads were issued one
-    // whole chunk earlier, right after the previous barrier) and proves that every
-    // wave is done with chunk i-1, whose buffer and register set then take chunk i+2.
-    // Because chunk i+1 is readable half a chunk before it is needed, the operand
-    // fetch of its first step is issued under the last MFMAs of chunk i: the matrix
-    // pipe sees no gap at a chunk boundary.  Within a chunk the B operands of step
-    // t+1 are fetched while step t multiplies.
-    constexpr int TB = G::STEPS / 2;
+    // The waves of a workgroup meet once per chunk, and the meeting is split in two so
+    // that nobody stands still (a wave that has a matrix pipe to itself cannot hide a
+    // barrier behind another wave):
+    //   * at step TX of chunk i a wave ARRIVES: its own loads of chunk i+1 (LDS-direct
+    //     input loads and filter loads, issued during chunk i-1) have landed and it has
+    //     left chunk i-1 behind; it adds one to a counter in LDS and carries on;
+    //   * at step TY > TX it checks that all waves have arrived, which by then they
+    //     have unless one is a third of a chunk late.  Chunk i+1 is then readable and
+    //     the buffer and register set of chunk i-1 are free: the loads of chunk i+2 are
+    //     issued, and the operand fetch of chunk i+1's first steps follows under the
+    //     last MFMAs of chunk i, so the matrix pipe sees no gap at a chunk boundary.
+    // Within a chunk the B operands of step t+PF are fetched while step t multiplies.
+    constexpr int TY = G::STEPS - G::PF - 1 > G::STEPS / 2 ? G::STEPS - G::PF - 1 : G::STEPS / 2;
+    constexpr int TX = TY * 3 / 5;
+    static_assert(TX < TY && TY + G::PF <= G::STEPS, "arrive, check, then fetch the next chunk");
+    constexpr int NW = G::NT / 64;
+    unsigned *meet = reinterpret_cast<unsigned *>(lds + 3 * G::BUF);   // arrivals so far, all chunks
+    auto arrive = [&]() {
+        // release: everything this wave has issued, the LDS-direct loads included, is complete
+        if (lane == 0) __hip_atomic_fetch_add(meet, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+    auto all_arrived = [&](unsigned target) {
+        // bounded: a wave that never saw the count would go on (to wrong results) rather than hang
+        for (int spin = 0; spin < (1 << 22); ++spin) {
+            if (__hip_atomic_load(meet, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= target) break;
+            __builtin_amdgcn_s_sleep(1);
+        }
+    };
     auto step_off = [](int t) {   // LDS offset (floats) of reduction step t of a chunk
         const int cc = t / G::RS, rs = t - cc * G::RS;
         return cc * G::PSP + (rs / G::S) * G::LW + rs % G::S;
@@ -276,40 +297,45 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
         for (int pb = 0; pb < G::PBW; ++pb) bv[pb] = buf[bbase[pb] + step_off(t)];
     };
     const int nch = (C + G::CB - 1) / G::CB;
-    float bcur[G::PBW];
-    // i3 = i % 3 (compile time): buffers and register sets rotate with the chunk index
+    float bq[G::PF][G::PBW];   // B operands of the next PF steps, oldest first
     auto chunk = [&](int i, const float *bufc, const float *bufn, float *bufnn, const float (&acr)[G::NA],
                      float (&ann)[G::NA]) {
         float ac[G::NA];
         mask_a(ac, acr, i * G::CB);
 #pragma unroll
         for (int t = 0; t < G::STEPS; ++t) {
-            if (t == TB) {
-                __syncthreads();
-                // no branch here: past the last chunk the last one is staged again, into a
-                // buffer and a register set that nothing reads any more
+            if (t == TX) arrive();
+            if (t == TY) {
+                all_arrived((unsigned)NW * (unsigned)(i + 1));
+                // past the last chunk the last one is staged again, into a buffer and a
+                // register set that nothing reads any more (no special case)
                 const int cn = (i + 2 < nch ? i + 2 : nch - 1) * G::CB;
                 stage_b(bufnn, cn);
                 load_a(ann, cn);
             }
-            float bnext[G::PBW];
-            if (t + 1 < G::STEPS) fetch(bufc, t + 1, bnext);
-            else fetch(bufn, 0, bnext);     // past the last chunk: stale but in-bounds, never used
+            float bnew[G::PBW];
+            if (t + G::PF < G::STEPS) fetch(bufc, t + G::PF, bnew);
+            else fetch(bufn, t + G::PF - G::STEPS, bnew);   // past the last chunk: stale but in-bounds, never used
 #pragma unroll
             for (int pb = 0; pb < G::PBW; ++pb)
-                acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac[t], bcur[pb], acc[pb], 0, 0, 0);
+                acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac[t], bq[0][pb], acc[pb], 0, 0, 0);
 #pragma unroll
             for (int pb = 0; pb < G::PBW; ++pb) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
             }
 #pragma unroll
-            for (int pb = 0; pb < G::PBW; ++pb) bcur[pb] = bnext[pb];
+            for (int pb = 0; pb < G::PBW; ++pb) {
+#pragma unroll
+                for (int d = 0; d + 1 < G::PF; ++d) bq[d][pb] = bq[d + 1][pb];
+                bq[G::PF - 1][pb] = bnew[pb];
+            }
         }
     };
 
     float a0[G::NA], a1[G::NA], a2[G::NA];
     float *b0 = lds, *b1 = lds + G::BUF, *b2 = lds + 2 * G::BUF;
+    if (tid == 0) *meet = 0u;
     stage_b(b0, 0);
     load_a(a0, 0);
     {
@@ -318,7 +344,8 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
         load_a(a1, c1);
     }
     __syncthreads();
-    fetch(b0, 0, bcur);
+#pragma unroll
+    for (int d = 0; d < G::PF; ++d) fetch(b0, d, bq[d]);
     for (int ci = 0;; ci += 3) {
         chunk(ci, b0, b1, b2, a0, a2);
         if (ci + 1 >= nch) break;
