@@ -33,27 +33,68 @@ def suite(name, workloads):
     return [workloads.BY_NAME[name]]
 
 
-def cpu_baseline(layers, budget_s=12.0):
-    """The oracle, as it stands, on whole images of the workload's first layers until
-    about budget_s seconds of CPU work are spent."""
-    import numpy as np
+def cpu_baseline(layers, budget_s=15.0):
+    """The oracle, as it stands, on whole images of the workload: layer after layer, one
+    more image (full output) of each per pass, until about budget_s seconds of CPU work
+    are spent."""
     import oracle
     from paper_1809_10170_amd import workloads
     oracle.build()
-    flops, secs, parts = 0, 0.0, []
-    # take the heaviest layer of the workload: one image at a time
-    l = max(layers, key=lambda t: t.flops)
-    x, w = workloads.make_inputs(l, N=min(l.N, 4))
+    flops, secs, done = 0, 0.0, {}
+    inputs = {}
     n_img = 0
-    while secs < budget_s and n_img < x.shape[0]:
-        t0 = time.perf_counter()
-        oracle.conv_forward(x[n_img:n_img + 1], w, l.stride, l.pad)
-        secs += time.perf_counter() - t0
-        flops += l.flops // l.N
+    while secs < budget_s:
+        progressed = False
+        for l in layers:
+            if n_img >= l.N or secs >= budget_s:
+                continue
+            if l.name not in inputs:
+                inputs[l.name] = workloads.make_inputs(l, N=min(l.N, 8))
+            x, w = inputs[l.name]
+            if n_img >= x.shape[0]:
+                continue
+            t0 = time.perf_counter()
+            oracle.conv_forward(x[n_img:n_img + 1], w, l.stride, l.pad)
+            secs += time.perf_counter() - t0
+            flops += l.flops // l.N
+            done[l.name] = n_img + 1
+            progressed = True
         n_img += 1
-    parts.append(f"{n_img} image(s) of {l.name}, full output")
+        if not progressed:
+            break
+    sample = ", ".join(f"{v}x {k}" for k, v in done.items())
     return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(),
-            "kind": "oracle", "sample": "; ".join(parts), "seconds": round(secs, 2)}
+            "kind": "oracle", "sample": f"whole images, full output: {sample}", "seconds": round(secs, 2)}
+
+
+def measured_traffic(layer_name, variant):
+    """HBM bytes per launch of a layer's kernel from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE and WRITE_SIZE scaled by the copy-kernel calibration stated there), or
+    None if the summary has no row for this layer and kernel variant."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+    try:
+        with open(path) as f:
+            for ln in f:
+                cells = [c.strip() for c in ln.split("|")]
+                if len(cells) > 6 and cells[1] == layer_name and cells[2] == variant:
+                    return int((2.0 * float(cells[4]) + 1.0 * float(cells[5])) * 1024)
+    except OSError:
+        pass
+    return None
+
+
+def copy_probe(nbytes=1 << 30, reps=5):
+    """A plain device-to-device copy of known size: under `rocprofv3 --pmc FETCH_SIZE`
+    (or WRITE_SIZE) its counter reading calibrates the same counter read for the
+    convolution kernels."""
+    import torch
+    x = torch.empty(nbytes // 4, device="cuda", dtype=torch.float32).normal_()
+    y = torch.empty_like(x)
+    torch.cuda.synchronize()
+    for _ in range(reps):
+        y.copy_(x)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_probe_bytes_read": nbytes, "copy_probe_bytes_written": nbytes, "reps": reps}))
 
 
 def main():
@@ -65,7 +106,11 @@ def main():
     ap.add_argument("--variant", default=None, help="force a kernel variant (single-layer workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--check", action="store_true", help="also verify sampled outputs against the oracle")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run only a 1 GiB device copy (calibration of the HBM traffic counters)")
     args = ap.parse_args()
+    if args.copy_probe:
+        return copy_probe()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only; --gpus must be 1 "
                  "(the path shards over batch with no exchange step, see DESIGN.md)")
@@ -133,7 +178,8 @@ def main():
     roofline = {"bound": "mfma", "kernel": f"{kern}<{dom['variant']}>", "layer": dom["layer"],
                 "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, 4),
-                "launch_ms": dom["ms_avg"], "traffic": None}
+                "launch_ms": dom["ms_avg"], "traffic": measured_traffic(dom["layer"], dom["variant"]),
+                "algorithmic_bytes": workloads.BY_NAME[dom["layer"]].algorithmic_bytes}
 
     if args.check:
         import oracle
