@@ -249,7 +249,7 @@ int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
     return std::snprintf(buf, n,
                          "variant=%s N=%d C=%d H=%d W=%d K=%d R=%d S=%d stride=%d pad=%d P=%d Q=%d "
                          "TP=%d TQ=%d KT=%d NPB=%d CB=%d pair=%s tilesP=%d tilesQ=%d ktiles=%d grid=%u "
-                         "threads=%d lds_bytes=%zu occupancy=%d flat=%d mfma_efficiency=%.4f workspace_bytes=0",
+                         "threads=%d lds_bytes=%zu occupancy=%d flat=%d mfma_efficiency=%.6g workspace_bytes=0",
                          v.name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, v.TP, v.TQ,
                          v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : "r", plan->tilesP,
                          plan->tilesQ, plan->ktiles, plan->grid, v.threads, plan->lds_bytes, v.occupancy,
