@@ -58,10 +58,20 @@ bool applicable(const Variant &v, const Shape &s)
     if (v.R != 0 && (v.R != s.R || v.S != s.S || v.stride != s.stride)) return false;
     if (v.pair == convd::PAIR_R && s.C > v.CB) return false;   // stages all channels at once
     if (v.img != 0 && (s.H != v.img || s.W != v.img || s.pad != v.pad)) return false;   // flat tiling
+    if (v.pointwise && s.pad != 0) return false;
     if (v.lds_bytes(s) > kLdsPerCU) return false;
+    if (v.R != 0) {
+        // the compiled kernels address the input with 31-bit byte offsets from the first
+        // channel they stage: one chunk of channels (flat tiling: of up to 4 images, whole)
+        const int64_t plane = (int64_t)s.H * s.W * 4;
+        const int64_t reach = v.img != 0 ? 4 * (int64_t)s.C * plane
+                              : (v.pair == convd::PAIR_R || v.pointwise) ? (int64_t)s.C * plane : (int64_t)v.CB * plane;
+        if (reach >= ((int64_t)1 << 31)) return false;
+    }
     const int64_t grid = v.img != 0
                              ? (int64_t)cdiv(s.K, v.KT) * ((((int64_t)s.N * s.P * s.Q) + v.NPB * 32 - 1) / (v.NPB * 32))
-                             : (int64_t)cdiv(s.K, v.KT) * cdiv(s.P, v.TP) * cdiv(s.Q, v.TQ) * s.N;
+                         : v.pointwise ? (int64_t)cdiv(s.K, v.KT) * cdiv64((int64_t)s.P * s.Q, v.TQ) * s.N
+                                       : (int64_t)cdiv(s.K, v.KT) * cdiv(s.P, v.TP) * cdiv(s.Q, v.TQ) * s.N;
     return grid > 0 && grid < kMaxElems;
 }
 
@@ -75,6 +85,11 @@ void fill(conv_direct_plan *p, const Shape &s, const Variant &v)
         p->tilesP = 1;
         p->tilesQ = (int)((((int64_t)s.N * s.P * s.Q) + v.NPB * 32 - 1) / (v.NPB * 32));
         p->grid = (unsigned)((int64_t)p->ktiles * p->tilesQ);
+    } else if (v.pointwise) {
+        // every image is one row of P*Q pixels, cut into tilesQ tiles of TQ
+        p->tilesP = 1;
+        p->tilesQ = (int)cdiv64((int64_t)s.P * s.Q, v.TQ);
+        p->grid = (unsigned)((int64_t)p->ktiles * p->tilesQ * s.N);
     } else {
         p->tilesP = cdiv(s.P, v.TP);
         p->tilesQ = cdiv(s.Q, v.TQ);
@@ -85,6 +100,8 @@ void fill(conv_direct_plan *p, const Shape &s, const Variant &v)
     double red;
     if (v.R == 0) {
         red = 2.0 * cdiv(s.C, 2) * s.R * s.S;
+    } else if (v.pointwise) {
+        red = 2.0 * cdiv(s.C, 2);
     } else if (v.pair == convd::PAIR_C) {
         red = (double)cdiv(s.C, v.CB) * v.CB * s.R * s.S;
     } else {
@@ -138,7 +155,7 @@ double cost(const conv_direct_plan &p)
     } else {
         staged = (double)cdiv(s.C, v.CB) * v.CB * v.window;
     }
-    c += staged * 4.0 * p.grid / 1024.0;
+    c += staged * 4.0 * p.grid / 4096.0;   // bytes / (16 B per clock and CU)
     if (v.R == 0) c *= 3.0;   // the runtime-shape fallback synchronises far more often
     return c;
 }
@@ -249,11 +266,11 @@ int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
     return std::snprintf(buf, n,
                          "variant=%s N=%d C=%d H=%d W=%d K=%d R=%d S=%d stride=%d pad=%d P=%d Q=%d "
                          "TP=%d TQ=%d KT=%d NPB=%d CB=%d pair=%s tilesP=%d tilesQ=%d ktiles=%d grid=%u "
-                         "threads=%d lds_bytes=%zu occupancy=%d flat=%d mfma_efficiency=%.6g workspace_bytes=0",
+                         "threads=%d lds_bytes=%zu occupancy=%d flat=%d pointwise=%d mfma_efficiency=%.6g workspace_bytes=0",
                          v.name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, v.TP, v.TQ,
                          v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : "r", plan->tilesP,
                          plan->tilesQ, plan->ktiles, plan->grid, v.threads, plan->lds_bytes, v.occupancy,
-                         v.img != 0 ? 1 : 0, plan->mfma_efficiency);
+                         v.img != 0 ? 1 : 0, v.pointwise, plan->mfma_efficiency);
 }
 
 const char *conv_direct_strerror(int code)

@@ -1,0 +1,210 @@
+// Direct-convolution forward kernel for gfx950 (MI355X), pointwise family: 1x1 filter,
+// stride 1, no padding.  The paper notes that such layers need no change of algorithm,
+// only loops that match the layout (Section 4.3); here the convolution degenerates to
+//   out[n][k][m] = sum over c of w[k][c] * in[n][c][m],   m = p*W + q,
+// a dense contraction with no halo, so nothing is gained by staging the input in LDS:
+// every wave reads its B operands (32 consecutive pixels of one channel per k-lane
+// half: one 128-byte line) straight from global memory into registers, D reduction
+// steps ahead of the MFMAs that use them, and its filter values as consecutive floats
+// of w[k][.].  There is no LDS, no barrier and no workspace; the waves of a workgroup
+// only share a pixel tile so that their identical input reads meet in the L1 cache.
+//
+// Same MFMA mapping as the other kernels (rows = output channels, columns = pixels).
+// The two k-lanes of v_mfma_f32_32x32x2_f32 take channels s and s + CH, CH = ceil(C/2),
+// so that a lane's filter values for consecutive steps are consecutive in memory.
+#pragma once
+#include "conv_dma_kernel.h"
+
+namespace convd {
+
+template <int KBW_, int PBW_, int WK_, int WP_, int D_, int OCC_>
+struct PwGeom {
+    static constexpr int R = 1, S = 1, ST = 1;
+    static constexpr int KBW = KBW_, PBW = PBW_, WK = WK_, WP = WP_, D = D_, OCC = OCC_;
+    static constexpr int PAIR = PAIR_C;
+    static constexpr int CB = 2 * D;                     // reported: channels in flight per wave
+    static constexpr int NT = 64 * WK * WP;
+    static constexpr int WPE = (OCC * WK * WP + 3) / 4;
+    static constexpr int KT = 32 * KBW * WK;
+    static constexpr int NPB = PBW * WP;
+    static constexpr int TP = 1, TQ = 32 * NPB;          // a tile is TQ consecutive pixels of one image
+    static_assert(D % 4 == 0, "filter values are fetched four steps at a time");
+};
+
+template <class G>
+__global__ void __launch_bounds__(G::NT, G::WPE) conv_pw_kernel(const KernelArgs a)
+{
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    __builtin_assume(wave >= 0 && wave < G::NT / 64);
+    const int wk = wave % G::WK, wp = wave / G::WK;
+    const int h = lane >> 5, j = lane & 31;
+
+    const int C = a.s.C, K = a.s.K;
+    const int HW = a.s.H * a.s.W;             // = P*Q
+    const int CH = (C + 1) / 2;               // reduction steps
+
+    unsigned bid = blockIdx.x;
+    {
+        const unsigned g8 = gridDim.x & ~7u;
+        if (bid < g8) bid = (bid & 7u) * (g8 >> 3) + (bid >> 3);
+    }
+    const int kt = bid % a.ktiles;  bid /= a.ktiles;
+    const int tm = bid % a.tilesQ;
+    const int n = bid / a.tilesQ;
+    const int k0 = kt * G::KT, m0 = tm * G::TQ + wp * G::PBW * 32;
+
+    // B: lane (j, h) reads in[n][s + h*CH][m0 + 32*pb + j]; pixels past the image are
+    // clamped (read, computed, not stored).  Buffer loads keep the addressing to one
+    // 32-bit register per pixel block: byte offset of the lane's pixel in channel h*CH,
+    // plus a scalar offset for the step.
+    unsigned boff[G::PBW];
+#pragma unroll
+    for (int pb = 0; pb < G::PBW; ++pb) {
+        int m = m0 + pb * 32 + j;
+        m = m < HW ? m : HW - 1;
+        boff[pb] = (unsigned)(h * CH * HW + m) * 4u;
+    }
+    const unsigned plane = (unsigned)HW * 4u;
+    __amdgpu_buffer_rsrc_t rsrc;
+    {
+        const uintptr_t pa = (uintptr_t)(a.in + (size_t)n * C * HW);
+        const uintptr_t pu = ((uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(pa >> 32)) << 32) |
+                             (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)pa);
+        rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)pu, 0, (int)((unsigned)C * plane), 0x00020000);
+    }
+    auto load_b_full = [&](float (&bv)[G::PBW], int s) {  // a step that exists in both halves
+        const int soff = __builtin_amdgcn_readfirstlane(s) * (int)plane;
+#pragma unroll
+        for (int pb = 0; pb < G::PBW; ++pb)
+            bv[pb] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)boff[pb], soff, 0));
+    };
+    // the last step of the second half does not exist when C is odd: its filter value
+    // is zero and its B operand is read from the first half instead
+    auto load_b = [&](float (&bv)[G::PBW], int s) {       // any step
+        const bool ok = s + h * CH < C;
+        const int soff = __builtin_amdgcn_readfirstlane(s) * (int)plane;
+#pragma unroll
+        for (int pb = 0; pb < G::PBW; ++pb) {
+            const unsigned off = ok ? boff[pb] : boff[pb] - (unsigned)(h * CH) * plane;
+            bv[pb] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)off, soff, 0));
+        }
+    };
+
+    // A: lane (j, h) of k-block kb reads w[k][h*CH + s], consecutive in s
+    const float *w_lane[G::KBW];
+#pragma unroll
+    for (int kb = 0; kb < G::KBW; ++kb) {
+        int krow = k0 + (wk * G::KBW + kb) * 32 + j;
+        krow = krow < K ? krow : K - 1;
+        w_lane[kb] = a.w + (size_t)krow * C + h * CH;
+    }
+    auto load_a4 = [&](float (&av)[G::KBW][4], int s) {   // steps s .. s+3, all inside the lane's run
+#pragma unroll
+        for (int kb = 0; kb < G::KBW; ++kb) {
+            const dma_f4u v = *reinterpret_cast<const dma_f4u *>(w_lane[kb] + s);
+            av[kb][0] = v[0]; av[kb][1] = v[1]; av[kb][2] = v[2]; av[kb][3] = v[3];
+        }
+    };
+
+    dma_floatx16 acc[G::KBW][G::PBW];
+#pragma unroll
+    for (int kb = 0; kb < G::KBW; ++kb)
+#pragma unroll
+        for (int pb = 0; pb < G::PBW; ++pb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[kb][pb][v] = 0.f;
+
+    auto mfma_step = [&](const float (&bv)[G::PBW], float av, int kb) {
+#pragma unroll
+        for (int pb = 0; pb < G::PBW; ++pb)
+            acc[kb][pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[pb], acc[kb][pb], 0, 0, 0);
+    };
+
+    // Main loop: whole groups of D steps whose filter runs lie inside both halves (the
+    // second half is one step shorter when C is odd).  B operands are D steps ahead.
+    const int nfull = C / 2 / G::D * G::D;    // steps covered by full groups (all valid for both halves)
+    float bq[G::D][G::PBW];
+    float aq[2][G::D / 4][G::KBW][4];         // filter values of this group and of the next
+    if (nfull > 0) {
+        // filter loads first, as in the loop: the loop's waits are counted in load order and
+        // must find the same order on entry as on every later pass
+#pragma unroll
+        for (int u = 0; u < G::D / 4; ++u) load_a4(aq[0][u], 4 * u);
+        __builtin_amdgcn_sched_barrier(0);   // the scheduler may not reorder these loads
+#pragma unroll
+        for (int d = 0; d < G::D; ++d) {
+            load_b_full(bq[d], d);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    auto group = [&](int s0, float (&ac)[G::D / 4][G::KBW][4], float (&an)[G::D / 4][G::KBW][4]) {
+        const int sn = s0 + G::D < nfull ? s0 + G::D : s0;     // next group (clamped: reloads this one)
+#pragma unroll
+        for (int u = 0; u < G::D / 4; ++u) load_a4(an[u], sn + 4 * u);
+#pragma unroll
+        for (int d = 0; d < G::D; ++d) {
+#pragma unroll
+            for (int kb = 0; kb < G::KBW; ++kb) mfma_step(bq[d], ac[d / 4][kb][d % 4], kb);
+            load_b_full(bq[d], sn + d);
+            // keep the reloads of this step's registers right behind the MFMAs that read them
+#pragma unroll
+            for (int pb = 0; pb < G::PBW; ++pb) {
+                __builtin_amdgcn_sched_group_barrier(0x008, G::KBW, 0);   // KBW MFMAs
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);        // one load
+            }
+        }
+    };
+    for (int s0 = 0; s0 < nfull; s0 += 2 * G::D) {
+        group(s0, aq[0], aq[1]);
+        if (s0 + G::D >= nfull) break;
+        group(s0 + G::D, aq[1], aq[0]);
+    }
+    // Remaining steps, one at a time (fewer than D + 1 of them)
+    for (int s = nfull; s < CH; ++s) {
+        float bv[G::PBW];
+        load_b(bv, s);
+        const bool ok = s + h * CH < C;
+#pragma unroll
+        for (int kb = 0; kb < G::KBW; ++kb) {
+            const float av = ok ? w_lane[kb][s] : 0.f;
+            mfma_step(bv, av, kb);
+        }
+    }
+
+    // ---- epilogue: each output element is written exactly once ----
+    float *out_n = a.out + (size_t)n * K * HW;
+#pragma unroll
+    for (int pb = 0; pb < G::PBW; ++pb) {
+        const int m = m0 + pb * 32 + j;
+        if (m < HW) {
+#pragma unroll
+            for (int kb = 0; kb < G::KBW; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int k = k0 + (wk * G::KBW + kb) * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (k < K) out_n[(size_t)k * HW + m] = acc[kb][pb][v];
+                }
+        }
+    }
+}
+
+template <class G>
+static hipError_t launch_pw(const KernelArgs &a, unsigned grid, hipStream_t stream)
+{
+    hipLaunchKernelGGL((conv_pw_kernel<G>), dim3(grid), dim3(G::NT), 0, stream, a);
+    return hipGetLastError();
+}
+
+template <class G>
+static size_t lds_pw(const Shape &) { return 0; }
+
+template <class G>
+constexpr Variant make_pw_variant(const char *name)
+{
+    // "window": the TQ pixels of a channel that a workgroup reads (once, through L1)
+    return Variant{name, 1, 1, 1, G::TP, G::TQ, G::KT, G::NPB, G::CB, G::PAIR, G::NT, G::OCC,
+                   G::TQ, 0, 0, &lds_pw<G>, &launch_pw<G>, 1};
+}
+
+}  // namespace convd

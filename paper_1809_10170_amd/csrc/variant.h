@@ -38,6 +38,8 @@ struct Variant {
                           // a workgroup then owns NPB*32 consecutive pixels of all images (TP = TQ = 0)
     size_t (*lds_bytes)(const Shape &);
     hipError_t (*launch)(const KernelArgs &, unsigned grid, hipStream_t stream);
+    int pointwise;        // 1: needs pad 0 (and R = S = stride = 1); a tile is TQ consecutive pixels of
+                          // one image taken as a single row of H*W pixels
 };
 
 // The compiled variants (host table of pointers; lives beside the fallback kernel).

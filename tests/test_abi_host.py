@@ -76,6 +76,11 @@ def _check_cover(info, exhaustive):
         npix = info["NPB"] * 32
         assert info["grid"] == tQ * tK and tP == 1
         assert (tQ - 1) * npix < N * P * Q <= tQ * npix
+    elif info["pointwise"]:
+        # every image is one row of P*Q pixels, cut into tQ tiles of TQ
+        assert info["grid"] == tQ * tK * N and tP == 1 and TP == 1
+        assert info["NPB"] * 32 == TQ
+        assert (tQ - 1) * TQ < P * Q <= tQ * TQ
     else:
         assert info["grid"] == tP * tQ * tK * N
         assert info["NPB"] * 32 >= TP * TQ
@@ -85,7 +90,7 @@ def _check_cover(info, exhaustive):
     assert info["threads"] % 64 == 0 and 64 <= info["threads"] <= 1024
     assert info["workspace_bytes"] == 0
     assert 0.0 < info["mfma_efficiency"] <= 1.0
-    if exhaustive and not info["flat"]:
+    if exhaustive and not info["flat"] and not info["pointwise"]:
         # replay the kernel's workgroup -> tile decode and count writers per output
         hits = np.zeros((N, K, P, Q), np.int32)
         for bid in range(info["grid"]):
@@ -126,7 +131,7 @@ def test_every_variant_plans_a_matching_shape():
     names = cd.variant_names()
     assert len(names) == len(set(names)) and any(n.startswith("generic") for n in names)
     for nm in names:
-        m = re.match(r"[fdr](\d+)s(\d+)_", nm)
+        m = re.match(r"[fdrp](\d+)s(\d+)_", nm)
         R, st = (int(m.group(1)), int(m.group(2))) if m else (4, 3)
         C = 3 if nm.startswith("r") else 6   # the row-pair family takes only a few channels
         fl = re.search(r"_flat(\d+)_", nm)     # flat tiling is compiled for one image size
@@ -148,3 +153,14 @@ def test_no_kernel_uses_private_scratch():
         assert int(r["ScratchSize [bytes/lane]"]) == 0, r
         assert r["Dynamic Stack"] == "False", r
         assert int(r["VGPRs Spill"]) == 0, r
+
+
+def test_huge_image_planes_fall_back_to_the_runtime_shape_kernel():
+    """The compiled kernels reach the input with 31-bit byte offsets per channel chunk; an
+    image whose chunk does not fit is planned onto the fallback (64-bit indexing)."""
+    plan = cd.Plan(1, 4, 16384, 16384, 1, 3, 3, 1, 1)     # 4 x 1 GiB channel planes
+    assert plan.info()["variant"].startswith("generic")
+    plan.destroy()
+    plan = cd.Plan(1, 4, 4096, 4096, 1, 3, 3, 1, 1)       # 64 MiB planes: compiled variant
+    assert not plan.info()["variant"].startswith("generic")
+    plan.destroy()

@@ -83,7 +83,7 @@ def test_small_shapes_integer_inputs_bit_exact(oracle, shape):
 
 
 def _variant_shape(name):
-    m = re.match(r"[fdr](\d+)s(\d+)_", name)
+    m = re.match(r"[fdrp](\d+)s(\d+)_", name)
     R, st = (int(m.group(1)), int(m.group(2))) if m else (4, 3)
     return R, st
 
