@@ -39,11 +39,12 @@ struct RowGeom {
     static constexpr int LWQ = (LW + ST - 1) / ST;       // columns per phase = LDS row pitch
     static constexpr int PH = LH * LWQ;                  // floats of one phase plane
     static constexpr int PS = ST * PH;                   // floats of one channel's window
-    static constexpr int PSP = (PS + 63) / 64 * 64;      // LDS stride between channels
+    static constexpr int PSP = PS;                       // LDS stride between channels (no gaps: the window
+                                                         // array [CM][ST][LH][LWQ] is a plain mixed-radix count)
     static constexpr int HOFF = R2 * LWQ;                // LDS offset of the second k-lane half
     static constexpr int NA = RG * S;                    // filter values per lane and sub-chunk
     static constexpr int ITEMS = (CM * PSP + NT - 1) / NT;
-    static constexpr size_t LDS_BYTES = sizeof(float) * (size_t)CM * PSP;
+    static constexpr size_t LDS_BYTES = sizeof(float) * (size_t)ITEMS * NT;   // whole 64-lane loads
     static_assert(R2 % RG == 0 && NSUB % 2 == 0, "row groups must tile R2 an even number of times");
     static_assert(NPB * 32 >= NPIX, "pixel blocks must cover the tile");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
@@ -75,26 +76,39 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
     const int ih0 = p0 * G::ST - a.s.pad, iw0 = q0 * G::ST - a.s.pad;
 
     // ---- stage the whole window (all channels) once ----
+    // Thread tid owns positions tid + i*NT of the [CM][ST][LH][LWQ] array.  The position
+    // is kept as its four digits and stepped by NT with carries: no division per load.
     {
         const float *in_n = a.in + (size_t)n * C * H * W;
-        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)in_n, 0, (int)((unsigned)(C * H * W) * 4u), 0x00020000);
-#pragma unroll 4
+        const uintptr_t pa = (uintptr_t)in_n;
+        const uintptr_t pu = ((uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(pa >> 32)) << 32) |
+                             (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)pa);
+        __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc((void *)pu, 0, (int)((unsigned)(C * H * W) * 4u), 0x00020000);
+        constexpr int DQ = G::NT % G::LWQ, D1 = G::NT / G::LWQ;          // NT in mixed radix:
+        constexpr int DH = D1 % G::LH, D2 = D1 / G::LH;                  // NT = ((DC*ST + DP)*LH + DH)*LWQ + DQ
+        constexpr int DP = D2 % G::ST, DC = D2 / G::ST;
+        int cq = tid % G::LWQ, t1 = tid / G::LWQ;
+        int hh = t1 % G::LH, t2 = t1 / G::LH;
+        int ph = t2 % G::ST, cc = t2 / G::ST;
+#pragma unroll 2
         for (int i = 0; i < G::ITEMS; ++i) {
-            const int f0 = i * G::NT + wave * 64;
-            if (f0 < G::CM * G::PSP) {
-                const int f = f0 + lane;
-                const int cc = f / G::PSP, pos = f - cc * G::PSP;
-                const int ph = pos / G::PH, rem = pos - ph * G::PH;
-                const int hh = rem / G::LWQ, cq = rem - hh * G::LWQ;
-                const int ih = ih0 + hh, iw = iw0 + cq * G::ST + ph;
-                // rows past the filter (odd R) meet zero weights; they are stored as zeros
-                // too, so that no value outside the true window can reach an output
-                const bool ok = (pos < G::PS) & (hh < G::LHV) & (cc < C) & ((unsigned)ih < (unsigned)H) &
-                                ((unsigned)iw < (unsigned)W);
-                const unsigned off = ok ? (unsigned)(((cc * H + ih) * W + iw) * 4) : 0x80000000u;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, CONVD_LDS(lds + f0), 4, off, 0, 0, 0);
-            }
+            const int ih = ih0 + hh, iw = iw0 + cq * G::ST + ph;
+            // rows past the filter (odd R) meet zero weights; they are stored as zeros
+            // too, so that no value outside the true window can reach an output
+            const bool ok = (hh < G::LHV) & (cc < C) & ((unsigned)ih < (unsigned)H) & ((unsigned)iw < (unsigned)W);
+            const unsigned off = ok ? (unsigned)(((cc * H + ih) * W + iw) * 4) : 0x80000000u;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, CONVD_LDS(lds + i * G::NT + wave * 64), 4, off, 0, 0, 0);
+            cq += DQ;
+            int carry = cq >= G::LWQ;
+            cq -= carry ? G::LWQ : 0;
+            hh += DH + carry;
+            carry = hh >= G::LH;
+            hh -= carry ? G::LH : 0;
+            ph += DP + carry;
+            carry = ph >= G::ST;
+            ph -= carry ? G::ST : 0;
+            cc += DC + carry;             // cc >= CM past the end of the array: stored as zeros
         }
     }
 
