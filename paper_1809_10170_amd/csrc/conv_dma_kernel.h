@@ -93,6 +93,33 @@ struct DmaGeom {
 
 #define CONVD_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 
+// A pointer that is the same in every lane, moved to scalar registers.
+// (readfirstlane returns a signed int: widen through unsigned, or a low half with its
+// top bit set would smear ones over the high half)
+__device__ __forceinline__ void *uniform_ptr(const void *p)
+{
+    const uintptr_t pa = (uintptr_t)p;
+    return (void *)(((uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(pa >> 32)) << 32) |
+                    (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)pa));
+}
+
+// Epilogue stores of one 32 x 32 accumulator block whose 32 output channels all exist:
+// buffer stores with the channel row as a scalar offset and one precomputed 32-bit
+// register per lane (byte offset of out[.][4h][p][q] from the resource base, or an
+// offset past the resource for lanes without a pixel, which the hardware drops).  No
+// vector ALU work per store: a wave in its epilogue shares the SIMD with waves that
+// issue MFMAs back to back and gets very few vector issue slots.
+__device__ __forceinline__ void store_block(__amdgpu_buffer_rsrc_t rsrc, unsigned voff, int kfirst, unsigned plane,
+                                            const dma_floatx16 &acc)
+{
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int soff = (kfirst + 8 * (v >> 2) + (v & 3)) * (int)plane;
+        const float f = acc[v];   // (a plain float: bit_cast of a vector-element expression is not one)
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, f), rsrc, (int)voff, soff, 0);
+    }
+}
+
 // TAILC: C is not a multiple of CB.  The last chunk then reaches past the input
 // channels; its filter values are fetched one by one (never past the tensor) and
 // cleared where the channel does not exist.  TAILC = false needs C % CB == 0 and
@@ -197,12 +224,8 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
         const unsigned span = G::FLAT ? 0x7fffffffu : (unsigned)(C - c0) * chan_bytes;
         // the base is the same in every lane; saying so keeps the resource in scalar
         // registers (a resource the compiler takes for divergent is looped over lane by lane)
-        const uintptr_t pa = (uintptr_t)(in_n + (size_t)c0 * H * W);
-        // (readfirstlane returns a signed int: widen through unsigned, or a low half with
-        // its top bit set would smear ones over the high half)
-        const uintptr_t pu = ((uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(pa >> 32)) << 32) |
-                             (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)pa);
-        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)pu, 0, (int)span, 0x00020000);
+        __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(in_n + (size_t)c0 * H * W), 0, (int)span, 0x00020000);
 #pragma unroll
         for (int i = 0; i < G::ITEMS; ++i) {
             const int f0 = i * G::NT + wave * 64;           // first position of this wave's 64
@@ -356,27 +379,38 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
     }
 
     // ---- epilogue: each output element is written exactly once ----
+    // Fast path (uniform test): the wave's 32 channels exist and every byte offset from
+    // the first image of the tile fits 31 bits; otherwise plain guarded stores.
+    const int kw = k0 + wk * 32;
+    const bool fast = (kw + 32 <= K) & ((long long)K * P * Q * 4 * G::NSI < (1ll << 31));
+    __amdgpu_buffer_rsrc_t orsrc =
+        __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(a.out + (size_t)n * K * P * Q), 0, 0x7fffffff, 0x00020000);
+    const unsigned oplane = (unsigned)(P * Q) * 4u;
 #pragma unroll
     for (int pb = 0; pb < G::PBW; ++pb) {
         const int t = (wp * G::PBW + pb) * 32 + j;
         bool live;
-        size_t o;      // offset of out[n'][0][p][q]
+        size_t o;      // offset of out[n'][0][p][q] from out[n][0][0][0]
         if (G::FLAT) {
             const int m = m0 + t, pq = G::OP * G::OQ;
             const int ni = m / pq;
             live = m < M;
-            o = (size_t)ni * K * pq + (m - ni * pq);
+            o = (size_t)(ni - n) * K * pq + (m - ni * pq);
         } else {
             const int py = t / G::TQ, px = t - py * G::TQ;
             const int p = p0 + py, q = q0 + px;
             live = t < G::NPIX && p < P && q < Q;
-            o = (size_t)n * K * P * Q + (size_t)p * Q + q;
+            o = (size_t)p * Q + q;
         }
-        if (live) {
+        if (fast) {
+            const unsigned voff = live ? (unsigned)o * 4u + (unsigned)(4 * h) * oplane : 0x80000000u;
+            store_block(orsrc, voff, kw, oplane, acc[pb]);
+        } else if (live) {
+            float *out_o = a.out + (size_t)n * K * P * Q + o;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int k = k0 + wk * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-                if (k < K) a.out[o + (size_t)k * P * Q] = acc[pb][v];
+                const int k = kw + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (k < K) out_o[(size_t)k * P * Q] = acc[pb][v];
             }
         }
     }

@@ -66,13 +66,8 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_pw_kernel(const KernelArgs
         boff[pb] = (unsigned)(h * CH * HW + m) * 4u;
     }
     const unsigned plane = (unsigned)HW * 4u;
-    __amdgpu_buffer_rsrc_t rsrc;
-    {
-        const uintptr_t pa = (uintptr_t)(a.in + (size_t)n * C * HW);
-        const uintptr_t pu = ((uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(pa >> 32)) << 32) |
-                             (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)pa);
-        rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)pu, 0, (int)((unsigned)C * plane), 0x00020000);
-    }
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(a.in + (size_t)n * C * HW), 0,
+                                                                    (int)((unsigned)C * plane), 0x00020000);
     auto load_b_full = [&](float (&bv)[G::PBW], int s) {  // a step that exists in both halves
         const int soff = __builtin_amdgcn_readfirstlane(s) * (int)plane;
 #pragma unroll
@@ -173,18 +168,27 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_pw_kernel(const KernelArgs
     }
 
     // ---- epilogue: each output element is written exactly once ----
+    // (fast path: see store_block)
     float *out_n = a.out + (size_t)n * K * HW;
+    __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(out_n), 0, 0x7fffffff, 0x00020000);
+    const bool fits = (long long)K * HW * 4 < (1ll << 31);
 #pragma unroll
     for (int pb = 0; pb < G::PBW; ++pb) {
         const int m = m0 + pb * 32 + j;
-        if (m < HW) {
+        const bool live = m < HW;
 #pragma unroll
-            for (int kb = 0; kb < G::KBW; ++kb)
+        for (int kb = 0; kb < G::KBW; ++kb) {
+            const int kw = k0 + (wk * G::KBW + kb) * 32;
+            if (fits & (kw + 32 <= K)) {
+                const unsigned voff = live ? (unsigned)m * 4u + (unsigned)(4 * h) * plane : 0x80000000u;
+                store_block(orsrc, voff, kw, plane, acc[kb][pb]);
+            } else if (live) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int k = k0 + (wk * G::KBW + kb) * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                    const int k = kw + 8 * (v >> 2) + 4 * h + (v & 3);
                     if (k < K) out_n[(size_t)k * HW + m] = acc[kb][pb][v];
                 }
+            }
         }
     }
 }

@@ -79,12 +79,8 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
     // Thread tid owns positions tid + i*NT of the [CM][ST][LH][LWQ] array.  The position
     // is kept as its four digits and stepped by NT with carries: no division per load.
     {
-        const float *in_n = a.in + (size_t)n * C * H * W;
-        const uintptr_t pa = (uintptr_t)in_n;
-        const uintptr_t pu = ((uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(pa >> 32)) << 32) |
-                             (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)pa);
-        __amdgpu_buffer_rsrc_t rsrc =
-            __builtin_amdgcn_make_buffer_rsrc((void *)pu, 0, (int)((unsigned)(C * H * W) * 4u), 0x00020000);
+        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            uniform_ptr(a.in + (size_t)n * C * H * W), 0, (int)((unsigned)(C * H * W) * 4u), 0x00020000);
         constexpr int DQ = G::NT % G::LWQ, D1 = G::NT / G::LWQ;          // NT in mixed radix:
         constexpr int DH = D1 % G::LH, D2 = D1 / G::LH;                  // NT = ((DC*ST + DP)*LH + DH)*LWQ + DQ
         constexpr int DP = D2 % G::ST, DC = D2 / G::ST;
@@ -209,20 +205,30 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
     }
 
     // ---- epilogue: each output element is written exactly once ----
+    // (fast path: see store_block)
     float *out_n = a.out + (size_t)n * K * P * Q;
+    __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(out_n), 0, 0x7fffffff, 0x00020000);
+    const unsigned oplane = (unsigned)(P * Q) * 4u;
+    const bool fits = (long long)K * P * Q * 4 < (1ll << 31);
 #pragma unroll
     for (int pb = 0; pb < G::PBW; ++pb) {
         const int t = (wp * G::PBW + pb) * 32 + j;
         const int py = t / G::TQ, px = t - py * G::TQ;
         const int p = p0 + py, q = q0 + px;
-        if (t < G::NPIX && p < P && q < Q) {
+        const bool live = t < G::NPIX && p < P && q < Q;
 #pragma unroll
-            for (int kb = 0; kb < G::KBW; ++kb)
+        for (int kb = 0; kb < G::KBW; ++kb) {
+            const int kw = k0 + (wk * G::KBW + kb) * 32;
+            if (fits & (kw + 32 <= K)) {
+                const unsigned voff = live ? (unsigned)(p * Q + q) * 4u + (unsigned)(4 * h) * oplane : 0x80000000u;
+                store_block(orsrc, voff, kw, oplane, acc[kb][pb]);
+            } else if (live) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int k = k0 + (wk * G::KBW + kb) * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                    const int k = kw + 8 * (v >> 2) + 4 * h + (v & 3);
                     if (k < K) out_n[((size_t)k * P + p) * Q + q] = acc[kb][pb][v];
                 }
+            }
         }
     }
 }
