@@ -11,7 +11,8 @@
 //     LDS once (it is small when C is small), so the main loop has no barrier at
 //     all; the filter streams through registers, RG rows per lane at a time.
 //
-// For stride > 1 the window is stored split by column phase, [phase][row][col/stride],
+// For stride > 1 the window is stored split by column phase, [phase][row][col/stride]
+// (rows padded to whole 64-lane loads),
 // so that the 32 pixels of an MFMA column block read consecutive LDS words for every
 // tap (stride-ST words would collide on the LDS banks).  The split costs nothing:
 // LDS-direct loads take an arbitrary global address per lane.
@@ -36,15 +37,18 @@ struct RowGeom {
     static constexpr int LHV = (TP - 1) * ST + R;        // window rows that hold image data
     static constexpr int LH = (TP - 1) * ST + 2 * R2;    // window rows addressed (odd R: one zero row more)
     static constexpr int LW = (TQ - 1) * ST + S;         // window columns
-    static constexpr int LWQ = (LW + ST - 1) / ST;       // columns per phase = LDS row pitch
-    static constexpr int PH = LH * LWQ;                  // floats of one phase plane
+    static constexpr int LWQ = (LW + ST - 1) / ST;       // columns per phase
+    static constexpr int NSEGR = (LWQ + 63) / 64;        // 64-lane loads per window row
+    static constexpr int LWP = NSEGR * 64;               // LDS row pitch: whole loads, so that a row's last
+                                                         // load cannot spill into the next row
+    static constexpr int PH = LH * LWP;                  // floats of one phase plane
     static constexpr int PS = ST * PH;                   // floats of one channel's window
-    static constexpr int PSP = PS;                       // LDS stride between channels (no gaps: the window
-                                                         // array [CM][ST][LH][LWQ] is a plain mixed-radix count)
-    static constexpr int HOFF = R2 * LWQ;                // LDS offset of the second k-lane half
+    static constexpr int PSP = PS;                       // LDS stride between channels
+    static constexpr int HOFF = R2 * LWP;                // LDS offset of the second k-lane half
     static constexpr int NA = RG * S;                    // filter values per lane and sub-chunk
-    static constexpr int ITEMS = (CM * PSP + NT - 1) / NT;
-    static constexpr size_t LDS_BYTES = sizeof(float) * (size_t)ITEMS * NT;   // whole 64-lane loads
+    static constexpr int NW = NT / 64;
+    static constexpr int ROWS_IT = (CM * LH + NW - 1) / NW;   // window rows per wave, phase and row segment
+    static constexpr size_t LDS_BYTES = sizeof(float) * (size_t)CM * PSP;
     static_assert(R2 % RG == 0 && NSUB % 2 == 0, "row groups must tile R2 an even number of times");
     static_assert(NPB * 32 >= NPIX, "pixel blocks must cover the tile");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
@@ -76,35 +80,44 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
     const int ih0 = p0 * G::ST - a.s.pad, iw0 = q0 * G::ST - a.s.pad;
 
     // ---- stage the whole window (all channels) once ----
-    // Thread tid owns positions tid + i*NT of the [CM][ST][LH][LWQ] array.  The position
-    // is kept as its four digits and stepped by NT with carries: no division per load.
+    // One LDS-direct load brings 64 columns of one window row (channel, phase, row).
+    // Which row is a scalar matter: its byte offset goes into the instruction's scalar
+    // offset, rows outside the image take an all-lanes-unreachable vector offset.  The
+    // vector offsets (column part; unreachable outside the image) are computed once per
+    // phase and segment.  So the loop below costs no vector ALU work per load, which
+    // matters: the wave shares its SIMD with waves issuing MFMAs back to back and gets
+    // very few vector issue slots.
     {
         __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             uniform_ptr(a.in + (size_t)n * C * H * W), 0, (int)((unsigned)(C * H * W) * 4u), 0x00020000);
-        constexpr int DQ = G::NT % G::LWQ, D1 = G::NT / G::LWQ;          // NT in mixed radix:
-        constexpr int DH = D1 % G::LH, D2 = D1 / G::LH;                  // NT = ((DC*ST + DP)*LH + DH)*LWQ + DQ
-        constexpr int DP = D2 % G::ST, DC = D2 / G::ST;
-        int cq = tid % G::LWQ, t1 = tid / G::LWQ;
-        int hh = t1 % G::LH, t2 = t1 / G::LH;
-        int ph = t2 % G::ST, cc = t2 / G::ST;
-#pragma unroll 2
-        for (int i = 0; i < G::ITEMS; ++i) {
-            const int ih = ih0 + hh, iw = iw0 + cq * G::ST + ph;
+        unsigned voffc[G::ST][G::NSEGR];
+#pragma unroll
+        for (int ph = 0; ph < G::ST; ++ph)
+#pragma unroll
+            for (int sg = 0; sg < G::NSEGR; ++sg) {
+                const int cq = sg * 64 + lane, iw = iw0 + cq * G::ST + ph;
+                voffc[ph][sg] = ((cq < G::LWQ) & ((unsigned)iw < (unsigned)W)) ? (unsigned)iw * 4u : 0x80000000u;
+            }
+        const unsigned voob = 0x80000000u;
+#pragma unroll 1
+        for (int i = 0; i < G::ROWS_IT; ++i) {
+            const int row = i * G::NW + wave;            // (channel, window row), scalar
+            const int cc = row / G::LH, hh = row - cc * G::LH;
+            const int ih = ih0 + hh;
             // rows past the filter (odd R) meet zero weights; they are stored as zeros
             // too, so that no value outside the true window can reach an output
-            const bool ok = (hh < G::LHV) & (cc < C) & ((unsigned)ih < (unsigned)H) & ((unsigned)iw < (unsigned)W);
-            const unsigned off = ok ? (unsigned)(((cc * H + ih) * W + iw) * 4) : 0x80000000u;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, CONVD_LDS(lds + i * G::NT + wave * 64), 4, off, 0, 0, 0);
-            cq += DQ;
-            int carry = cq >= G::LWQ;
-            cq -= carry ? G::LWQ : 0;
-            hh += DH + carry;
-            carry = hh >= G::LH;
-            hh -= carry ? G::LH : 0;
-            ph += DP + carry;
-            carry = ph >= G::ST;
-            ph -= carry ? G::ST : 0;
-            cc += DC + carry;             // cc >= CM past the end of the array: stored as zeros
+            const bool ok = (cc < C) & (hh < G::LHV) & ((unsigned)ih < (unsigned)H);
+            const int soff = ok ? ((cc * H + ih) * W) * 4 : 0;
+            if (cc < G::CM) {
+#pragma unroll
+                for (int ph = 0; ph < G::ST; ++ph)
+#pragma unroll
+                    for (int sg = 0; sg < G::NSEGR; ++sg) {
+                        float *dst = lds + ((cc * G::ST + ph) * G::LH + hh) * G::LWP + sg * 64;
+                        if (ok) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, CONVD_LDS(dst), 4, voffc[ph][sg], soff, 0, 0);
+                        else __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, CONVD_LDS(dst), 4, voob, 0, 0, 0);
+                    }
+            }
         }
     }
 
@@ -114,7 +127,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
     for (int pb = 0; pb < G::PBW; ++pb) {
         const int t = (wp * G::PBW + pb) * 32 + j;
         const int py = t / G::TQ, px = t - py * G::TQ;
-        const int pix = t < G::NPIX ? py * G::ST * G::LWQ + px : 0;
+        const int pix = t < G::NPIX ? py * G::ST * G::LWP + px : 0;
         bbase[pb] = pix + h * G::HOFF;
     }
 
@@ -173,7 +186,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
         for (int i = 0; i < G::RG; ++i)
 #pragma unroll
             for (int s = 0; s < G::S; ++s) {
-                const int boff = (s % G::ST) * G::PH + (g * G::RG + i) * G::LWQ + s / G::ST;
+                const int boff = (s % G::ST) * G::PH + (g * G::RG + i) * G::LWP + s / G::ST;
                 float bv[G::PBW];
 #pragma unroll
                 for (int pb = 0; pb < G::PBW; ++pb) bv[pb] = chan[bbase[pb] + boff];
