@@ -74,14 +74,14 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_pw_kernel(const KernelArgs
         for (int pb = 0; pb < G::PBW; ++pb)
             bv[pb] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)boff[pb], soff, 0));
     };
-    // the last step of the second half does not exist when C is odd: its filter value
-    // is zero and its B operand is read from the first half instead
+    // the last step of the second half does not exist when C is odd: both its filter
+    // value and its B operand are zero (the load is sent past the resource's end)
     auto load_b = [&](float (&bv)[G::PBW], int s) {       // any step
         const bool ok = s + h * CH < C;
         const int soff = __builtin_amdgcn_readfirstlane(s) * (int)plane;
 #pragma unroll
         for (int pb = 0; pb < G::PBW; ++pb) {
-            const unsigned off = ok ? boff[pb] : boff[pb] - (unsigned)(h * CH) * plane;
+            const unsigned off = ok ? boff[pb] : 0x80000000u;
             bv[pb] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)off, soff, 0));
         }
     };

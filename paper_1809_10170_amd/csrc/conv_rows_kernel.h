@@ -5,8 +5,9 @@
 // with two differences that keep the MFMA reduction depth useful when C is tiny:
 //
 //   * the two k-lanes of v_mfma_f32_32x32x2_f32 take filter rows r and r + R2
-//     (R2 = ceil(R/2)) of one input channel; for odd R the row past the filter has
-//     zero weights.  The reduction runs over (channel, row pair, filter column);
+//     (R2 = ceil(R/2)) of one input channel; for odd R the first half's last row has no
+//     partner: the second half multiplies a zero weight there.  The reduction runs
+//     over (channel, row pair, filter column);
 //   * the input window of ALL channels of the workgroup's pixel tile is staged into
 //     LDS once (it is small when C is small), so the main loop has no barrier at
 //     all; the filter streams through registers, RG rows per lane at a time.
@@ -34,8 +35,7 @@ struct RowGeom {
     static constexpr int NPIX = TP * TQ;
     static constexpr int R2 = (R + 1) / 2;               // filter rows per k-lane half
     static constexpr int NSUB = R2 / RG;                 // register sub-chunks per channel
-    static constexpr int LHV = (TP - 1) * ST + R;        // window rows that hold image data
-    static constexpr int LH = (TP - 1) * ST + 2 * R2;    // window rows addressed (odd R: one zero row more)
+    static constexpr int LH = (TP - 1) * ST + R;         // window rows
     static constexpr int LW = (TQ - 1) * ST + S;         // window columns
     static constexpr int LWQ = (LW + ST - 1) / ST;       // columns per phase
     static constexpr int NSEGR = (LWQ + 63) / 64;        // 64-lane loads per window row
@@ -104,9 +104,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
             const int row = i * G::NW + wave;            // (channel, window row), scalar
             const int cc = row / G::LH, hh = row - cc * G::LH;
             const int ih = ih0 + hh;
-            // rows past the filter (odd R) meet zero weights; they are stored as zeros
-            // too, so that no value outside the true window can reach an output
-            const bool ok = (cc < C) & (hh < G::LHV) & ((unsigned)ih < (unsigned)H);
+            const bool ok = (cc < C) & ((unsigned)ih < (unsigned)H);
             const int soff = ok ? ((cc * H + ih) * W) * 4 : 0;
             if (cc < G::CM) {
 #pragma unroll
@@ -121,14 +119,19 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
         }
     }
 
-    // per-lane LDS read offsets (floats): pixel position (phase 0) plus the k-lane half
-    int bbase[G::PBW];
+    // per-lane LDS read offsets (floats): pixel position (phase 0) plus the k-lane half.
+    // For odd R the second half has no partner for the first half's last row: there its
+    // weight is zero and it reads the SAME window position as the first half (bsame), a
+    // position inside the output's own window, so that the zero never meets a value
+    // (an Inf, say) that the true sum does not contain.
+    int bbase[G::PBW], bsame[G::PBW];
 #pragma unroll
     for (int pb = 0; pb < G::PBW; ++pb) {
         const int t = (wp * G::PBW + pb) * 32 + j;
         const int py = t / G::TQ, px = t - py * G::TQ;
         const int pix = t < G::NPIX ? py * G::ST * G::LWP + px : 0;
         bbase[pb] = pix + h * G::HOFF;
+        bsame[pb] = pix;
     }
 
     // Filter values of this lane for sub-chunk (c, g): rows g*RG + h*R2 .. + RG of
@@ -187,9 +190,10 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
 #pragma unroll
             for (int s = 0; s < G::S; ++s) {
                 const int boff = (s % G::ST) * G::PH + (g * G::RG + i) * G::LWP + s / G::ST;
+                const bool both = g * G::RG + i + G::R2 < G::R;   // the second half has this row too
                 float bv[G::PBW];
 #pragma unroll
-                for (int pb = 0; pb < G::PBW; ++pb) bv[pb] = chan[bbase[pb] + boff];
+                for (int pb = 0; pb < G::PBW; ++pb) bv[pb] = chan[(both ? bbase[pb] : bsame[pb]) + boff];
 #pragma unroll
                 for (int kb = 0; kb < G::KBW; ++kb)
 #pragma unroll

@@ -204,3 +204,41 @@ def test_unaligned_by_four_bytes_pointers(oracle):
     got = ob[1:].reshape(N, K, P, Q).cpu().numpy()
     _assert_close(got, oracle.conv_forward(x, w, st, pd), oracle.tolerance(C, R, S), "offset pointers")
     assert torch.isnan(ob[0]).item()   # the float before the output was not touched
+
+
+@pytest.mark.parametrize("shape", [
+    # N, C, H, W, K, R, S, stride, pad: odd C (pointwise and channel-pair tails), ragged K, odd filters
+    (2, 5, 20, 24, 40, 1, 1, 1, 0),
+    (2, 7, 30, 33, 70, 3, 3, 1, 1),
+    (3, 6, 13, 13, 130, 3, 3, 1, 1),
+    (1, 3, 60, 230, 64, 7, 7, 2, 3),
+    (1, 3, 99, 227, 96, 11, 11, 4, 0),
+    (1, 9, 31, 31, 33, 5, 5, 1, 2),
+    (2, 12, 57, 55, 130, 3, 3, 2, 1),
+    (2, 5, 9, 7, 33, 2, 4, 3, 2),
+])
+def test_non_finite_inputs_stay_local(oracle, shape):
+    """An Inf in the input and a NaN in the weights may only reach the outputs whose sum
+    really contains them: padding lanes, channel tails and zero-weight filter rows
+    multiply zeros with zeros, never with stale or neighbouring data."""
+    N, C, H, W, K, R, S, st, pd = shape
+    rng = np.random.default_rng(900 + sum(shape))
+    x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    w = rng.uniform(-1, 1, (K, C, R, S)).astype(np.float32)
+    x[N - 1, C - 1, H // 2, W // 2] = np.inf
+    w[K - 1, C - 1, R - 1, S - 1] = np.nan
+    got, info = _run(x, w, st, pd)
+    # Which outputs may see the poisoned values: every output whose window holds the Inf
+    # (an indicator tensor pushed through the oracle), and the whole output channel of the
+    # NaN weight (at the image border that tap meets zero padding, and NaN * 0 is NaN for
+    # an implementation that multiplies the padding instead of skipping it: both are right).
+    xi = np.zeros_like(x); xi[N - 1, C - 1, H // 2, W // 2] = 1
+    touched = oracle.conv_forward(xi, np.ones_like(w), st, pd) != 0
+    touched[:, K - 1] = True
+    clean = ~touched
+    assert np.isfinite(got[clean]).all(), f"{shape} via {info['variant']}: non-finite value leaked"
+    xc = x.copy(); xc[N - 1, C - 1, H // 2, W // 2] = 0
+    wc = w.copy(); wc[K - 1, C - 1, R - 1, S - 1] = 0
+    want = oracle.conv_forward(xc, wc, st, pd)
+    err = np.abs(got.astype(np.float64) - want)[clean].max()
+    assert err <= oracle.tolerance(C, R, S), f"{shape} via {info['variant']}: {err}"
