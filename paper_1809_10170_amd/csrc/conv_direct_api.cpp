@@ -155,7 +155,12 @@ double cost(const conv_direct_plan &p)
     } else {
         staged = (double)cdiv(s.C, v.CB) * v.CB * v.window;
     }
-    c += staged * 4.0 * p.grid / 4096.0;   // bytes / (16 B per clock and CU)
+    c += staged * 4.0 * p.grid / 16384.0;   // bytes / (64 B per clock and CU, all CUs at once)
+    // filter traffic: every wave fetches the whole filter slice of its 32-channel blocks,
+    // however few pixels it owns (what makes very small pixel tiles expensive)
+    if (v.R != 0) {
+        c += (double)p.grid * wpw * 32.0 * s.C * s.R * s.S * 4.0 / 16384.0;
+    }
     if (v.R == 0) c *= 3.0;   // the runtime-shape fallback synchronises far more often
     return c;
 }

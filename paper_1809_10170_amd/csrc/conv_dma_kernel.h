@@ -50,9 +50,16 @@ typedef float dma_f2u __attribute__((ext_vector_type(2), aligned(4)));
 //     touch, the rows of one image after those of the previous one.  No MFMA column
 //     is wasted on tile edges and the grid can be cut to fit the machine.
 template <int R_, int S_, int ST_, int TP_, int TQ_, int PBW_, int WK_, int WP_, int CB_, int OCC_, int IMG_ = 0,
-          int PADC_ = 0, int PF_ = 1>
+          int PADC_ = 0, int PF_ = 1, int SC_ = 1>
 struct DmaGeom {
     static constexpr int PF = PF_;                       // reduction steps the LDS operand fetch runs ahead
+    // Split reduction: SC groups of WK*WP waves share one output tile; group sc reduces
+    // the chunks sc, sc+SC, ... with stage buffers and a meeting counter of its own (the
+    // groups run as independent pipelines), and the partial tiles are summed through LDS
+    // at the end.  This is the paper's input-channel blocking (Section 3.1.2) spread over
+    // waves: it multiplies the parallelism of layers that have few outputs (single
+    // images, 13x13 / 14x14 maps) without any workspace.
+    static constexpr int SC = SC_;
     static constexpr int R = R_, S = S_, ST = ST_;
     static constexpr int PBW = PBW_, WK = WK_, WP = WP_, CB = CB_, OCC = OCC_;
     static constexpr int IMG = IMG_, PADC = PADC_;
@@ -64,8 +71,10 @@ struct DmaGeom {
     static constexpr int NSI = FLAT ? (NRMAX + OP - 2) / OP + 1 : 1;           // flat: images a tile can touch
     static constexpr int TP = FLAT ? 0 : TP_, TQ = FLAT ? OQ : TQ_;
     static constexpr int PAIR = PAIR_C;
-    static constexpr int NT = 64 * WK * WP;              // threads per workgroup
-    static constexpr int WPE = (OCC * WK * WP + 3) / 4;  // waves per SIMD the register budget must allow
+    static constexpr int NWG = WK * WP;                  // waves per split group
+    static constexpr int NTG = 64 * NWG;                 // threads per split group
+    static constexpr int NT = NTG * SC;                  // threads per workgroup
+    static constexpr int WPE = (OCC * NWG * SC + 3) / 4; // waves per SIMD the register budget must allow
     static constexpr int KT = 32 * WK;                   // output channels per workgroup
     static constexpr int NPB = PBW * WP;                 // 32-pixel blocks per workgroup
     static constexpr int NPIX = FLAT ? NPIXF : TP * TQ;  // real pixels in the tile
@@ -80,10 +89,12 @@ struct DmaGeom {
     static constexpr int HC = CB / 2;                    // channels per kk half
     static constexpr int HOFF = HC * PSP + 32;           // LDS offset of the second half (other banks)
     static constexpr int BUF = CB * PSP + 32;            // floats per stage buffer
-    static constexpr int ITEMS = (CB * PSP + NT - 1) / NT;   // 64-lane loads per wave and chunk
+    static constexpr int ITEMS = (CB * PSP + NTG - 1) / NTG; // 64-lane loads per wave and chunk
     static constexpr int NA = HC * RS;                   // filter values per lane and chunk
     static constexpr int STEPS = HC * RS;                // MFMA k-steps per chunk
-    static constexpr size_t LDS_BYTES = sizeof(float) * (3 * (size_t)BUF + 16);   // three stage buffers, arrival counter
+    static constexpr int GRP = 3 * BUF + 16;             // floats per split group: three stage buffers, arrival counter
+    static constexpr int RED = (SC - 1) * NWG * PBW * 1024;   // floats of the final sum's exchange
+    static constexpr size_t LDS_BYTES = sizeof(float) * (size_t)(SC * GRP > RED ? SC * GRP : RED);
     static_assert(CB % 2 == 0, "channel pairing needs an even chunk");
     static_assert(!FLAT || R >= ST, "flat tiling stacks image windows R - ST rows apart");
     static_assert(PF >= 1 && 2 * PF < STEPS, "operand fetches for the next chunk must follow the meeting point");
@@ -129,11 +140,15 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
 {
     extern __shared__ __align__(16) float lds[];
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    __builtin_assume(wave >= 0 && wave < G::NT / 64);
+    const int lane = threadIdx.x & 63;
+    const int wave_wg = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    __builtin_assume(wave_wg >= 0 && wave_wg < G::NT / 64);
+    const int sc = wave_wg / G::NWG;                 // split group of this wave
+    const int wave = wave_wg - sc * G::NWG;          // wave, thread within the group
+    const int tid = wave * 64 + lane;
     const int wk = wave % G::WK, wp = wave / G::WK;
     const int h = lane >> 5, j = lane & 31;
+    const int goffs = sc * G::GRP;                   // LDS offset (floats) of this group's stage buffers and counter
 
     const int C = a.s.C, H = a.s.H, W = a.s.W, K = a.s.K, P = a.s.P, Q = a.s.Q;
 
@@ -182,17 +197,18 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
             const int py = t / G::TQ, px = t - py * G::TQ;
             pix = t < G::NPIX ? py * G::ST * G::LW + px * G::ST : 0;
         }
-        bbase[pb] = pix + h * G::HOFF;
+        bbase[pb] = pix + h * G::HOFF + goffs;   // (group offset folded in: buffers are then addressed
+                                                 // as constant offsets from lds, as without splitting)
     }
 
-    // Input staging plan: thread tid owns positions tid + i*NT of the chunk's
+    // Input staging plan: thread tid owns positions tid + i*NTG of the chunk's
     // [CB][PSP] window array; its byte offset from the chunk's first channel (of the
     // tile's first image), or an offset no buffer can reach where the window lies
     // outside the image.
     unsigned goff[G::ITEMS];
 #pragma unroll
     for (int i = 0; i < G::ITEMS; ++i) {
-        const int f = i * G::NT + tid;
+        const int f = i * G::NTG + tid;
         const int cc = f / G::PSP, pos = f - cc * G::PSP;
         const int hh = pos / G::LW, col = pos - hh * G::LW;
         int ih, img = 0;
@@ -228,9 +244,9 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
             __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(in_n + (size_t)c0 * H * W), 0, (int)span, 0x00020000);
 #pragma unroll
         for (int i = 0; i < G::ITEMS; ++i) {
-            const int f0 = i * G::NT + wave * 64;           // first position of this wave's 64
+            const int f0 = i * G::NTG + wave * 64;          // first position of this wave's 64
             if (f0 < G::CB * G::PSP) {
-                float *dst = buf + f0 + (f0 >= G::HC * G::PSP ? 32 : 0);
+                float *dst = buf + goffs + f0 + (f0 >= G::HC * G::PSP ? 32 : 0);
                 unsigned off = goff[i];
                 if (G::FLAT) off = c0 + f0 / G::PSP < C ? off : 0x80000000u;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, CONVD_LDS(dst), 4, off, 0, 0, 0);
@@ -298,8 +314,8 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
     constexpr int TY = G::STEPS - G::PF - 1 > G::STEPS / 2 ? G::STEPS - G::PF - 1 : G::STEPS / 2;
     constexpr int TX = TY * 3 / 5;
     static_assert(TX < TY && TY + G::PF <= G::STEPS, "arrive, check, then fetch the next chunk");
-    constexpr int NW = G::NT / 64;
-    unsigned *meet = reinterpret_cast<unsigned *>(lds + 3 * G::BUF);   // arrivals so far, all chunks
+    constexpr int NW = G::NWG;
+    unsigned *meet = reinterpret_cast<unsigned *>(lds + goffs + 3 * G::BUF);  // arrivals so far, all chunks
     auto arrive = [&]() {
         // release: everything this wave has issued, the LDS-direct loads included, is complete
         if (lane == 0) __hip_atomic_fetch_add(meet, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -319,12 +335,19 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
 #pragma unroll
         for (int pb = 0; pb < G::PBW; ++pb) bv[pb] = buf[bbase[pb] + step_off(t)];
     };
-    const int nch = (C + G::CB - 1) / G::CB;
+    const int nch = (C + G::CB - 1) / G::CB;            // chunks in all
+    const int nchl = nch > sc ? (nch - sc + G::SC - 1) / G::SC : 0;   // chunks of this split group
+    // first channel of the group's local chunk i (past its last chunk: the layer's last
+    // chunk again, staged into buffers nothing reads)
+    auto chan0 = [&](int i) {
+        const int g = i * G::SC + sc;
+        return (g < nch ? g : nch - 1) * G::CB;
+    };
     float bq[G::PF][G::PBW];   // B operands of the next PF steps, oldest first
     auto chunk = [&](int i, const float *bufc, const float *bufn, float *bufnn, const float (&acr)[G::NA],
                      float (&ann)[G::NA]) {
         float ac[G::NA];
-        mask_a(ac, acr, i * G::CB);
+        mask_a(ac, acr, chan0(i));
 #pragma unroll
         for (int t = 0; t < G::STEPS; ++t) {
             if (t == TX) arrive();
@@ -332,7 +355,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
                 all_arrived((unsigned)NW * (unsigned)(i + 1));
                 // past the last chunk the last one is staged again, into a buffer and a
                 // register set that nothing reads any more (no special case)
-                const int cn = (i + 2 < nch ? i + 2 : nch - 1) * G::CB;
+                const int cn = chan0(i + 2);
                 stage_b(bufnn, cn);
                 load_a(ann, cn);
             }
@@ -357,25 +380,45 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
     };
 
     float a0[G::NA], a1[G::NA], a2[G::NA];
-    float *b0 = lds, *b1 = lds + G::BUF, *b2 = lds + 2 * G::BUF;
+    float *b0 = lds, *b1 = lds + G::BUF, *b2 = lds + 2 * G::BUF;   // (+ goffs, added where they are used)
     if (tid == 0) *meet = 0u;
-    stage_b(b0, 0);
-    load_a(a0, 0);
-    {
-        const int c1 = nch > 1 ? G::CB : 0;
-        stage_b(b1, c1);
-        load_a(a1, c1);
-    }
+    stage_b(b0, chan0(0));
+    load_a(a0, chan0(0));
+    stage_b(b1, chan0(1));
+    load_a(a1, chan0(1));
     __syncthreads();
 #pragma unroll
     for (int d = 0; d < G::PF; ++d) fetch(b0, d, bq[d]);
-    for (int ci = 0;; ci += 3) {
+    for (int ci = 0; ci < nchl; ci += 3) {
         chunk(ci, b0, b1, b2, a0, a2);
-        if (ci + 1 >= nch) break;
-        chunk(ci + 1, b1, b2, b0, a1, a0);
-        if (ci + 2 >= nch) break;
-        chunk(ci + 2, b2, b0, b1, a2, a1);
-        if (ci + 3 >= nch) break;
+        if (ci + 1 < nchl) chunk(ci + 1, b1, b2, b0, a1, a0);
+        if (ci + 2 < nchl) chunk(ci + 2, b2, b0, b1, a2, a1);
+    }
+
+    if (G::SC > 1) {
+        // Sum the split groups' partial tiles into group 0: groups 1.. write theirs to LDS
+        // (the stage buffers are free once every wave is here), group 0 adds them up.
+        __syncthreads();
+        float *red = lds;
+        if (sc > 0) {
+            float *mine = red + ((sc - 1) * G::NWG + wave) * G::PBW * 1024;
+#pragma unroll
+            for (int pb = 0; pb < G::PBW; ++pb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mine[(pb * 16 + v) * 64 + lane] = acc[pb][v];
+        }
+        __syncthreads();
+        if (sc > 0) return;
+#pragma unroll
+        for (int g = 1; g < G::SC; ++g) {
+            const float *theirs = red + ((g - 1) * G::NWG + wave) * G::PBW * 1024;
+#pragma unroll
+            for (int pb = 0; pb < G::PBW; ++pb) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[pb][v] += theirs[(pb * 16 + v) * 64 + lane];
+                __builtin_amdgcn_sched_barrier(0);   // one block at a time: 16 loads in flight, not 16*PBW
+            }
+        }
     }
 
     // ---- epilogue: each output element is written exactly once ----
