@@ -50,7 +50,7 @@ typedef float dma_f2u __attribute__((ext_vector_type(2), aligned(4)));
 //     touch, the rows of one image after those of the previous one.  No MFMA column
 //     is wasted on tile edges and the grid can be cut to fit the machine.
 template <int R_, int S_, int ST_, int TP_, int TQ_, int PBW_, int WK_, int WP_, int CB_, int OCC_, int IMG_ = 0,
-          int PADC_ = 0, int PF_ = 1, int SC_ = 1>
+          int PADC_ = 0, int PF_ = 1, int SC_ = 1, int PBW2_ = 0>
 struct DmaGeom {
     static constexpr int PF = PF_;                       // reduction steps the LDS operand fetch runs ahead
     // Split reduction: SC groups of WK*WP waves share one output tile; group sc reduces
@@ -60,13 +60,19 @@ struct DmaGeom {
     // waves: it multiplies the parallelism of layers that have few outputs (single
     // images, 13x13 / 14x14 maps) without any workspace.
     static constexpr int SC = SC_;
+    // Unequal waves (flat tilings, WP = 2): the waves of the second pixel group own PBW2
+    // blocks instead of PBW.  A SIMD then runs one wave of each kind, PBW + PBW2 blocks in
+    // all, which lets the work per SIMD be an odd number of blocks (13 = 7 + 6 where two
+    // equal waves could only offer 12 or 14).
+    static constexpr int PBW2 = PBW2_;
     static constexpr int R = R_, S = S_, ST = ST_;
     static constexpr int PBW = PBW_, WK = WK_, WP = WP_, CB = CB_, OCC = OCC_;
     static constexpr int IMG = IMG_, PADC = PADC_;
     static constexpr bool FLAT = IMG_ > 0;
     static constexpr int OQ = FLAT ? (IMG + 2 * PADC - S) / ST + 1 : 0;       // flat: output width
     static constexpr int OP = FLAT ? (IMG + 2 * PADC - R) / ST + 1 : 0;       // flat: output height
-    static constexpr int NPIXF = 32 * PBW * WP;                                // flat: pixels per workgroup
+    static constexpr int NPB = PBW2_ ? PBW_ + PBW2_ : PBW_ * WP_;              // 32-pixel blocks per workgroup
+    static constexpr int NPIXF = 32 * NPB;                                     // flat: pixels per workgroup
     static constexpr int NRMAX = FLAT ? (NPIXF + OQ - 2) / OQ + 1 : 0;         // flat: output rows a tile can touch
     static constexpr int NSI = FLAT ? (NRMAX + OP - 2) / OP + 1 : 1;           // flat: images a tile can touch
     static constexpr int TP = FLAT ? 0 : TP_, TQ = FLAT ? OQ : TQ_;
@@ -76,7 +82,6 @@ struct DmaGeom {
     static constexpr int NT = NTG * SC;                  // threads per workgroup
     static constexpr int WPE = (OCC * NWG * SC + 3) / 4; // waves per SIMD the register budget must allow
     static constexpr int KT = 32 * WK;                   // output channels per workgroup
-    static constexpr int NPB = PBW * WP;                 // 32-pixel blocks per workgroup
     static constexpr int NPIX = FLAT ? NPIXF : TP * TQ;  // real pixels in the tile
     static constexpr int RS = R * S;
     // halo window rows; flat: consecutive output rows of one image share input rows as
@@ -96,11 +101,15 @@ struct DmaGeom {
     static constexpr int RED = (SC - 1) * NWG * PBW * 1024;   // floats of the final sum's exchange
     static constexpr size_t LDS_BYTES = sizeof(float) * (size_t)(SC * GRP > RED ? SC * GRP : RED);
     static_assert(CB % 2 == 0, "channel pairing needs an even chunk");
+    static_assert(PBW2 == 0 || (FLAT && WP == 2 && SC == 1 && PBW2 < PBW), "unequal waves: flat tiling, two pixel groups");
     static_assert(!FLAT || R >= ST, "flat tiling stacks image windows R - ST rows apart");
     static_assert(PF >= 1 && 2 * PF < STEPS, "operand fetches for the next chunk must follow the meeting point");
     static_assert(NPB * 32 >= NPIX, "pixel blocks must cover the tile");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
 };
+
+template <int V>
+struct IntTag { static constexpr int value = V; };
 
 #define CONVD_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 
@@ -180,26 +189,6 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
         q0 = tq * G::TQ;
     }
     const int ih0 = p0 * G::ST - a.s.pad, iw0 = q0 * G::ST - a.s.pad;
-
-    // per-lane LDS read offsets (floats): pixel position plus the kk half
-    int bbase[G::PBW];
-#pragma unroll
-    for (int pb = 0; pb < G::PBW; ++pb) {
-        const int t = (wp * G::PBW + pb) * 32 + j;
-        int pix;
-        if (G::FLAT) {
-            int m = m0 + t;
-            m = m < M ? m : M - 1;                       // past the last pixel: any valid position
-            const int g = m / G::OQ, q = m - g * G::OQ;
-            const int sI = g / G::OP - n;                // which of the tile's images
-            pix = ((g - g0) * G::ST + sI * (G::R - G::ST)) * G::LW + q * G::ST;
-        } else {
-            const int py = t / G::TQ, px = t - py * G::TQ;
-            pix = t < G::NPIX ? py * G::ST * G::LW + px * G::ST : 0;
-        }
-        bbase[pb] = pix + h * G::HOFF + goffs;   // (group offset folded in: buffers are then addressed
-                                                 // as constant offsets from lds, as without splitting)
-    }
 
     // Input staging plan: thread tid owns positions tid + i*NTG of the chunk's
     // [CB][PSP] window array; its byte offset from the chunk's first channel (of the
@@ -291,172 +280,200 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
         for (int e = 0; e < G::NA; ++e) dst[e] = (!TAILC || c0 + h * G::HC + e / G::RS < C) ? src[e] : 0.f;
     };
 
-    dma_floatx16 acc[G::PBW];
-#pragma unroll
-    for (int pb = 0; pb < G::PBW; ++pb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[pb][v] = 0.f;
-
-    // Chunk i lives in stage buffer i % 3 and in filter register set i % 3.
-    //
-    // The waves of a workgroup meet once per chunk, and the meeting is split in two so
-    // that nobody stands still (a wave that has a matrix pipe to itself cannot hide a
-    // barrier behind another wave):
-    //   * at step TX of chunk i a wave ARRIVES: its own loads of chunk i+1 (LDS-direct
-    //     input loads and filter loads, issued during chunk i-1) have landed and it has
-    //     left chunk i-1 behind; it adds one to a counter in LDS and carries on;
-    //   * at step TY > TX it checks that all waves have arrived, which by then they
-    //     have unless one is a third of a chunk late.  Chunk i+1 is then readable and
-    //     the buffer and register set of chunk i-1 are free: the loads of chunk i+2 are
-    //     issued, and the operand fetch of chunk i+1's first steps follows under the
-    //     last MFMAs of chunk i, so the matrix pipe sees no gap at a chunk boundary.
-    // Within a chunk the B operands of step t+PF are fetched while step t multiplies.
-    constexpr int TY = G::STEPS - G::PF - 1 > G::STEPS / 2 ? G::STEPS - G::PF - 1 : G::STEPS / 2;
-    constexpr int TX = TY * 3 / 5;
-    static_assert(TX < TY && TY + G::PF <= G::STEPS, "arrive, check, then fetch the next chunk");
-    constexpr int NW = G::NWG;
-    unsigned *meet = reinterpret_cast<unsigned *>(lds + goffs + 3 * G::BUF);  // arrivals so far, all chunks
-    auto arrive = [&]() {
-        // release: everything this wave has issued, the LDS-direct loads included, is complete
-        if (lane == 0) __hip_atomic_fetch_add(meet, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-    };
-    auto all_arrived = [&](unsigned target) {
-        // bounded: a wave that never saw the count would go on (to wrong results) rather than hang
-        for (int spin = 0; spin < (1 << 22); ++spin) {
-            if (__hip_atomic_load(meet, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= target) break;
-            __builtin_amdgcn_s_sleep(1);
+    // Everything below depends on how many pixel blocks the wave owns: PBW, or PBW2 for
+    // the second pixel group of a variant with unequal waves (same protocol, same number
+    // of chunks and meetings, fewer MFMAs per step).
+    auto body = [&](auto pbw_tag) __attribute__((always_inline)) {
+        constexpr int PBW = decltype(pbw_tag)::value;
+        // per-lane LDS read offsets (floats): pixel position plus the kk half
+        int bbase[PBW];
+    #pragma unroll
+        for (int pb = 0; pb < PBW; ++pb) {
+            const int t = (wp * G::PBW + pb) * 32 + j;   // (the first pixel group always owns G::PBW blocks)
+            int pix;
+            if constexpr (G::FLAT) {
+                int m = m0 + t;
+                m = m < M ? m : M - 1;                       // past the last pixel: any valid position
+                const int g = m / G::OQ, q = m - g * G::OQ;
+                const int sI = g / G::OP - n;                // which of the tile's images
+                pix = ((g - g0) * G::ST + sI * (G::R - G::ST)) * G::LW + q * G::ST;
+            } else {
+                const int py = t / G::TQ, px = t - py * G::TQ;
+                pix = t < G::NPIX ? py * G::ST * G::LW + px * G::ST : 0;
+            }
+            bbase[pb] = pix + h * G::HOFF + goffs;   // (group offset folded in: buffers are then addressed
+                                                     // as constant offsets from lds, as without splitting)
         }
-    };
-    auto step_off = [](int t) {   // LDS offset (floats) of reduction step t of a chunk
-        const int cc = t / G::RS, rs = t - cc * G::RS;
-        return cc * G::PSP + (rs / G::S) * G::LW + rs % G::S;
-    };
-    auto fetch = [&](const float *buf, int t, float (&bv)[G::PBW]) {
-#pragma unroll
-        for (int pb = 0; pb < G::PBW; ++pb) bv[pb] = buf[bbase[pb] + step_off(t)];
-    };
-    const int nch = (C + G::CB - 1) / G::CB;            // chunks in all
-    const int nchl = nch > sc ? (nch - sc + G::SC - 1) / G::SC : 0;   // chunks of this split group
-    // first channel of the group's local chunk i (past its last chunk: the layer's last
-    // chunk again, staged into buffers nothing reads)
-    auto chan0 = [&](int i) {
-        const int g = i * G::SC + sc;
-        return (g < nch ? g : nch - 1) * G::CB;
-    };
-    float bq[G::PF][G::PBW];   // B operands of the next PF steps, oldest first
-    auto chunk = [&](int i, const float *bufc, const float *bufn, float *bufnn, const float (&acr)[G::NA],
-                     float (&ann)[G::NA]) {
-        float ac[G::NA];
-        mask_a(ac, acr, chan0(i));
-#pragma unroll
-        for (int t = 0; t < G::STEPS; ++t) {
-            if (t == TX) arrive();
-            if (t == TY) {
-                all_arrived((unsigned)NW * (unsigned)(i + 1));
-                // past the last chunk the last one is staged again, into a buffer and a
-                // register set that nothing reads any more (no special case)
-                const int cn = chan0(i + 2);
-                stage_b(bufnn, cn);
-                load_a(ann, cn);
-            }
-            float bnew[G::PBW];
-            if (t + G::PF < G::STEPS) fetch(bufc, t + G::PF, bnew);
-            else fetch(bufn, t + G::PF - G::STEPS, bnew);   // past the last chunk: stale but in-bounds, never used
-#pragma unroll
-            for (int pb = 0; pb < G::PBW; ++pb)
-                acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac[t], bq[0][pb], acc[pb], 0, 0, 0);
-#pragma unroll
-            for (int pb = 0; pb < G::PBW; ++pb) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-            }
-#pragma unroll
-            for (int pb = 0; pb < G::PBW; ++pb) {
-#pragma unroll
-                for (int d = 0; d + 1 < G::PF; ++d) bq[d][pb] = bq[d + 1][pb];
-                bq[G::PF - 1][pb] = bnew[pb];
-            }
-        }
-    };
 
-    float a0[G::NA], a1[G::NA], a2[G::NA];
-    float *b0 = lds, *b1 = lds + G::BUF, *b2 = lds + 2 * G::BUF;   // (+ goffs, added where they are used)
-    if (tid == 0) *meet = 0u;
-    stage_b(b0, chan0(0));
-    load_a(a0, chan0(0));
-    stage_b(b1, chan0(1));
-    load_a(a1, chan0(1));
-    __syncthreads();
-#pragma unroll
-    for (int d = 0; d < G::PF; ++d) fetch(b0, d, bq[d]);
-    for (int ci = 0; ci < nchl; ci += 3) {
-        chunk(ci, b0, b1, b2, a0, a2);
-        if (ci + 1 < nchl) chunk(ci + 1, b1, b2, b0, a1, a0);
-        if (ci + 2 < nchl) chunk(ci + 2, b2, b0, b1, a2, a1);
-    }
+        dma_floatx16 acc[PBW];
+    #pragma unroll
+        for (int pb = 0; pb < PBW; ++pb)
+    #pragma unroll
+            for (int v = 0; v < 16; ++v) acc[pb][v] = 0.f;
 
-    if (G::SC > 1) {
-        // Sum the split groups' partial tiles into group 0: groups 1.. write theirs to LDS
-        // (the stage buffers are free once every wave is here), group 0 adds them up.
+        // Chunk i lives in stage buffer i % 3 and in filter register set i % 3.
+        //
+        // The waves of a workgroup meet once per chunk, and the meeting is split in two so
+        // that nobody stands still (a wave that has a matrix pipe to itself cannot hide a
+        // barrier behind another wave):
+        //   * at step TX of chunk i a wave ARRIVES: its own loads of chunk i+1 (LDS-direct
+        //     input loads and filter loads, issued during chunk i-1) have landed and it has
+        //     left chunk i-1 behind; it adds one to a counter in LDS and carries on;
+        //   * at step TY > TX it checks that all waves have arrived, which by then they
+        //     have unless one is a third of a chunk late.  Chunk i+1 is then readable and
+        //     the buffer and register set of chunk i-1 are free: the loads of chunk i+2 are
+        //     issued, and the operand fetch of chunk i+1's first steps follows under the
+        //     last MFMAs of chunk i, so the matrix pipe sees no gap at a chunk boundary.
+        // Within a chunk the B operands of step t+PF are fetched while step t multiplies.
+        constexpr int TY = G::STEPS - G::PF - 1 > G::STEPS / 2 ? G::STEPS - G::PF - 1 : G::STEPS / 2;
+        constexpr int TX = TY * 3 / 5;
+        static_assert(TX < TY && TY + G::PF <= G::STEPS, "arrive, check, then fetch the next chunk");
+        constexpr int NW = G::NWG;
+        unsigned *meet = reinterpret_cast<unsigned *>(lds + goffs + 3 * G::BUF);  // arrivals so far, all chunks
+        auto arrive = [&]() {
+            // release: everything this wave has issued, the LDS-direct loads included, is complete
+            if (lane == 0) __hip_atomic_fetch_add(meet, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        };
+        auto all_arrived = [&](unsigned target) {
+            // bounded: a wave that never saw the count would go on (to wrong results) rather than hang
+            for (int spin = 0; spin < (1 << 22); ++spin) {
+                if (__hip_atomic_load(meet, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= target) break;
+                __builtin_amdgcn_s_sleep(1);
+            }
+        };
+        auto step_off = [](int t) {   // LDS offset (floats) of reduction step t of a chunk
+            const int cc = t / G::RS, rs = t - cc * G::RS;
+            return cc * G::PSP + (rs / G::S) * G::LW + rs % G::S;
+        };
+        auto fetch = [&](const float *buf, int t, float (&bv)[PBW]) {
+    #pragma unroll
+            for (int pb = 0; pb < PBW; ++pb) bv[pb] = buf[bbase[pb] + step_off(t)];
+        };
+        const int nch = (C + G::CB - 1) / G::CB;            // chunks in all
+        const int nchl = nch > sc ? (nch - sc + G::SC - 1) / G::SC : 0;   // chunks of this split group
+        // first channel of the group's local chunk i (past its last chunk: the layer's last
+        // chunk again, staged into buffers nothing reads)
+        auto chan0 = [&](int i) {
+            const int g = i * G::SC + sc;
+            return (g < nch ? g : nch - 1) * G::CB;
+        };
+        float bq[G::PF][PBW];   // B operands of the next PF steps, oldest first
+        auto chunk = [&](int i, const float *bufc, const float *bufn, float *bufnn, const float (&acr)[G::NA],
+                         float (&ann)[G::NA]) {
+            float ac[G::NA];
+            mask_a(ac, acr, chan0(i));
+    #pragma unroll
+            for (int t = 0; t < G::STEPS; ++t) {
+                if (t == TX) arrive();
+                if (t == TY) {
+                    all_arrived((unsigned)NW * (unsigned)(i + 1));
+                    // past the last chunk the last one is staged again, into a buffer and a
+                    // register set that nothing reads any more (no special case)
+                    const int cn = chan0(i + 2);
+                    stage_b(bufnn, cn);
+                    load_a(ann, cn);
+                }
+                float bnew[PBW];
+                if (t + G::PF < G::STEPS) fetch(bufc, t + G::PF, bnew);
+                else fetch(bufn, t + G::PF - G::STEPS, bnew);   // past the last chunk: stale but in-bounds, never used
+    #pragma unroll
+                for (int pb = 0; pb < PBW; ++pb)
+                    acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac[t], bq[0][pb], acc[pb], 0, 0, 0);
+    #pragma unroll
+                for (int pb = 0; pb < PBW; ++pb) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                }
+    #pragma unroll
+                for (int pb = 0; pb < PBW; ++pb) {
+    #pragma unroll
+                    for (int d = 0; d + 1 < G::PF; ++d) bq[d][pb] = bq[d + 1][pb];
+                    bq[G::PF - 1][pb] = bnew[pb];
+                }
+            }
+        };
+
+        float a0[G::NA], a1[G::NA], a2[G::NA];
+        float *b0 = lds, *b1 = lds + G::BUF, *b2 = lds + 2 * G::BUF;   // (+ goffs, added where they are used)
+        if (tid == 0) *meet = 0u;
+        stage_b(b0, chan0(0));
+        load_a(a0, chan0(0));
+        stage_b(b1, chan0(1));
+        load_a(a1, chan0(1));
         __syncthreads();
-        float *red = lds;
-        if (sc > 0) {
-            float *mine = red + ((sc - 1) * G::NWG + wave) * G::PBW * 1024;
-#pragma unroll
-            for (int pb = 0; pb < G::PBW; ++pb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) mine[(pb * 16 + v) * 64 + lane] = acc[pb][v];
+    #pragma unroll
+        for (int d = 0; d < G::PF; ++d) fetch(b0, d, bq[d]);
+        for (int ci = 0; ci < nchl; ci += 3) {
+            chunk(ci, b0, b1, b2, a0, a2);
+            if (ci + 1 < nchl) chunk(ci + 1, b1, b2, b0, a1, a0);
+            if (ci + 2 < nchl) chunk(ci + 2, b2, b0, b1, a2, a1);
         }
-        __syncthreads();
-        if (sc > 0) return;
-#pragma unroll
-        for (int g = 1; g < G::SC; ++g) {
-            const float *theirs = red + ((g - 1) * G::NWG + wave) * G::PBW * 1024;
-#pragma unroll
-            for (int pb = 0; pb < G::PBW; ++pb) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[pb][v] += theirs[(pb * 16 + v) * 64 + lane];
-                __builtin_amdgcn_sched_barrier(0);   // one block at a time: 16 loads in flight, not 16*PBW
-            }
-        }
-    }
 
-    // ---- epilogue: each output element is written exactly once ----
-    // Fast path (uniform test): the wave's 32 channels exist and every byte offset from
-    // the first image of the tile fits 31 bits; otherwise plain guarded stores.
-    const int kw = k0 + wk * 32;
-    const bool fast = (kw + 32 <= K) & ((long long)K * P * Q * 4 * G::NSI < (1ll << 31));
-    __amdgpu_buffer_rsrc_t orsrc =
-        __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(a.out + (size_t)n * K * P * Q), 0, 0x7fffffff, 0x00020000);
-    const unsigned oplane = (unsigned)(P * Q) * 4u;
-#pragma unroll
-    for (int pb = 0; pb < G::PBW; ++pb) {
-        const int t = (wp * G::PBW + pb) * 32 + j;
-        bool live;
-        size_t o;      // offset of out[n'][0][p][q] from out[n][0][0][0]
-        if (G::FLAT) {
-            const int m = m0 + t, pq = G::OP * G::OQ;
-            const int ni = m / pq;
-            live = m < M;
-            o = (size_t)(ni - n) * K * pq + (m - ni * pq);
-        } else {
-            const int py = t / G::TQ, px = t - py * G::TQ;
-            const int p = p0 + py, q = q0 + px;
-            live = t < G::NPIX && p < P && q < Q;
-            o = (size_t)p * Q + q;
-        }
-        if (fast) {
-            const unsigned voff = live ? (unsigned)o * 4u + (unsigned)(4 * h) * oplane : 0x80000000u;
-            store_block(orsrc, voff, kw, oplane, acc[pb]);
-        } else if (live) {
-            float *out_o = a.out + (size_t)n * K * P * Q + o;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int k = kw + 8 * (v >> 2) + 4 * h + (v & 3);
-                if (k < K) out_o[(size_t)k * P * Q] = acc[pb][v];
+        if (G::SC > 1) {
+            // Sum the split groups' partial tiles into group 0: groups 1.. write theirs to LDS
+            // (the stage buffers are free once every wave is here), group 0 adds them up.
+            __syncthreads();
+            float *red = lds;
+            if (sc > 0) {
+                float *mine = red + ((sc - 1) * G::NWG + wave) * PBW * 1024;
+    #pragma unroll
+                for (int pb = 0; pb < PBW; ++pb)
+    #pragma unroll
+                    for (int v = 0; v < 16; ++v) mine[(pb * 16 + v) * 64 + lane] = acc[pb][v];
+            }
+            __syncthreads();
+            if (sc > 0) return;
+    #pragma unroll
+            for (int g = 1; g < G::SC; ++g) {
+                const float *theirs = red + ((g - 1) * G::NWG + wave) * PBW * 1024;
+    #pragma unroll
+                for (int pb = 0; pb < PBW; ++pb) {
+    #pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[pb][v] += theirs[(pb * 16 + v) * 64 + lane];
+                    __builtin_amdgcn_sched_barrier(0);   // one block at a time: 16 loads in flight, not 16*PBW
+                }
             }
         }
-    }
+
+        // ---- epilogue: each output element is written exactly once ----
+        // Fast path (uniform test): the wave's 32 channels exist and every byte offset from
+        // the first image of the tile fits 31 bits; otherwise plain guarded stores.
+        const int kw = k0 + wk * 32;
+        const bool fast = (kw + 32 <= K) & ((long long)K * P * Q * 4 * G::NSI < (1ll << 31));
+        __amdgpu_buffer_rsrc_t orsrc =
+            __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(a.out + (size_t)n * K * P * Q), 0, 0x7fffffff, 0x00020000);
+        const unsigned oplane = (unsigned)(P * Q) * 4u;
+    #pragma unroll
+        for (int pb = 0; pb < PBW; ++pb) {
+            const int t = (wp * G::PBW + pb) * 32 + j;   // (the first pixel group always owns G::PBW blocks)
+            bool live;
+            size_t o;      // offset of out[n'][0][p][q] from out[n][0][0][0]
+            if constexpr (G::FLAT) {
+                const int m = m0 + t, pq = G::OP * G::OQ;
+                const int ni = m / pq;
+                live = m < M;
+                o = (size_t)(ni - n) * K * pq + (m - ni * pq);
+            } else {
+                const int py = t / G::TQ, px = t - py * G::TQ;
+                const int p = p0 + py, q = q0 + px;
+                live = t < G::NPIX && p < P && q < Q;
+                o = (size_t)p * Q + q;
+            }
+            if (fast) {
+                const unsigned voff = live ? (unsigned)o * 4u + (unsigned)(4 * h) * oplane : 0x80000000u;
+                store_block(orsrc, voff, kw, oplane, acc[pb]);
+            } else if (live) {
+                float *out_o = a.out + (size_t)n * K * P * Q + o;
+    #pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int k = kw + 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (k < K) out_o[(size_t)k * P * Q] = acc[pb][v];
+                }
+            }
+        }
+    };
+    if (G::PBW2 > 0 && wp == 1) body(IntTag<(G::PBW2 > 0 ? G::PBW2 : G::PBW)>{});
+    else body(IntTag<G::PBW>{});
 }
 
 // ---------------------------------------------------------------------------
