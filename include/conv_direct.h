@@ -97,6 +97,58 @@ int conv_direct_create_with_variant(conv_direct_plan **plan, const char *variant
                                     int stride, int pad);
 const char *conv_direct_variant_name(int index);
 
+/* ------------------------------------------------------------------------
+ * Convolution-friendly layouts (paper: Section 4).
+ *
+ * Activations (Section 4.1): channels in blocks of CONV_DIRECT_ACT_BLOCK = 4; a tensor is
+ * a sequence of blocks, each an H x W row-major matrix of pencils of 4 channels:
+ *     blocked[n][c / 4][h][w][c % 4]            ceil(C/4) * 4 * N*H*W floats
+ * Input and output share this layout, so a layer's output is the next layer's input
+ * with no reshape.  Weights (Section 4.2), fastest to slowest: output channel in its
+ * block of CONV_DIRECT_W_KBLOCK = 32, input channel in its block of 4, filter column,
+ * filter row, input-channel block, output-channel block:
+ *     blocked[k / 32][c / 4][r][s][c % 4][k % 32]   ceil(K/32)*32 * ceil(C/4)*4 * R*S floats
+ * Positions that complete a last block must hold zeros (the re-arrangers below and the
+ * convolution's blocked output write them as zeros).  The paper leaves the block sizes to
+ * the implementation; 4 and 32 are what the fp32 MFMA operand shapes of this GPU want.
+ * The buffers are the caller's, of the sizes above: still no workspace.
+ * ------------------------------------------------------------------------ */
+#define CONV_DIRECT_LAYOUT_PLAIN   0
+#define CONV_DIRECT_LAYOUT_BLOCKED 1
+#define CONV_DIRECT_ACT_BLOCK 4
+#define CONV_DIRECT_W_KBLOCK  32
+
+/*
+ * Like conv_direct_create, with the layouts of the tensors stated.  in_layout covers
+ * `in` and `w` together (blocked input goes with blocked weights; a plain input, as the
+ * paper keeps for the first layer of a network, goes with plain KCRS weights); out_layout
+ * covers `out`.  (PLAIN, PLAIN) is conv_direct_create.  conv_direct_run then expects
+ * buffers of those layouts.  CONV_DIRECT_EINVAL for an unknown layout value,
+ * CONV_DIRECT_EUNSUPPORTED if no compiled variant serves the shape in these layouts.
+ */
+int conv_direct_create_layout(conv_direct_plan **plan,
+                              int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                              int in_layout, int out_layout);
+
+/* conv_direct_create_layout with the kernel variant forced (testing / tuning aid; variant = NULL asks the planner). */
+int conv_direct_create_ex(conv_direct_plan **plan, const char *variant,
+                          int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                          int in_layout, int out_layout);
+
+/* Number of floats of a blocked activation tensor / blocked weight tensor (0 if a dimension is <= 0). */
+size_t conv_direct_blocked_act_elems(int N, int C, int H, int W);
+size_t conv_direct_blocked_w_elems(int K, int C, int R, int S);
+
+/*
+ * Re-arrangers, enqueued on `stream` (hipStream_t; NULL = default), asynchronous, device
+ * pointers, source and destination distinct caller buffers of the plain / blocked sizes,
+ * 4-byte aligned (16 for a blocked activation destination).  pack_w is the one-time
+ * re-arrangement of a trained network's weights (Section 4.3).
+ */
+int conv_direct_pack_act(const float *plain, float *blocked, int N, int C, int H, int W, void *stream);
+int conv_direct_unpack_act(const float *blocked, float *plain, int N, int C, int H, int W, void *stream);
+int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, int S, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -14,6 +14,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("CONV_DIRECT_LIB") or os.path.join(_HERE, "libconv_direct.so")
 
 OK, EINVAL, EUNSUPPORTED, EALIGN, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5
+PLAIN, BLOCKED = 0, 1          # CONV_DIRECT_LAYOUT_*
+ACT_BLOCK, W_KBLOCK = 4, 32    # CONV_DIRECT_ACT_BLOCK, CONV_DIRECT_W_KBLOCK
 
 _lib = None
 
@@ -55,6 +57,17 @@ def lib():
         l.conv_direct_strerror.restype = cp
         l.conv_direct_last_hip_error.argtypes = []
         l.conv_direct_last_hip_error.restype = i
+        l.conv_direct_create_layout.argtypes = [pp] + [i] * 11
+        l.conv_direct_create_layout.restype = i
+        l.conv_direct_create_ex.argtypes = [pp, cp] + [i] * 11
+        l.conv_direct_create_ex.restype = i
+        l.conv_direct_blocked_act_elems.argtypes = [i] * 4
+        l.conv_direct_blocked_act_elems.restype = ctypes.c_size_t
+        l.conv_direct_blocked_w_elems.argtypes = [i] * 4
+        l.conv_direct_blocked_w_elems.restype = ctypes.c_size_t
+        for nm in ("conv_direct_pack_act", "conv_direct_unpack_act", "conv_direct_pack_w"):
+            getattr(l, nm).argtypes = [vp, vp] + [i] * 4 + [vp]
+            getattr(l, nm).restype = i
         _lib = l
     return _lib
 
@@ -76,10 +89,15 @@ def variant_names():
 class Plan:
     """conv_direct_create / run / destroy around one opaque plan pointer."""
 
-    def __init__(self, N, C, H, W, K, R, S, stride, pad, variant: str | None = None):
+    def __init__(self, N, C, H, W, K, R, S, stride, pad, variant: str | None = None,
+                 in_layout: int = PLAIN, out_layout: int = PLAIN):
         self._p = ctypes.c_void_p()
         dims = [int(v) for v in (N, C, H, W, K, R, S, stride, pad)]
-        if variant is None:
+        self.in_layout, self.out_layout = int(in_layout), int(out_layout)
+        if self.in_layout != PLAIN or self.out_layout != PLAIN:
+            rc = lib().conv_direct_create_ex(ctypes.byref(self._p), variant.encode() if variant else None, *dims,
+                                             self.in_layout, self.out_layout)
+        elif variant is None:
             rc = lib().conv_direct_create(ctypes.byref(self._p), *dims)
         else:
             rc = lib().conv_direct_create_with_variant(ctypes.byref(self._p), variant.encode(), *dims)
@@ -126,7 +144,11 @@ class Plan:
         import torch
         N, C, H, W, K, R, S, _, _ = self.dims
         P, Q = self.output_dims()
-        for t, shape, nm in ((x, (N, C, H, W), "in"), (w, (K, C, R, S), "w"), (out, (N, K, P, Q), "out")):
+        cb, kb = ACT_BLOCK, W_KBLOCK
+        xs, ws = ((N, C, H, W), (K, C, R, S)) if self.in_layout == PLAIN else \
+                 ((N, -(-C // cb), H, W, cb), (-(-K // kb), -(-C // cb), R, S, cb, kb))
+        os_ = (N, K, P, Q) if self.out_layout == PLAIN else (N, -(-K // cb), P, Q, cb)
+        for t, shape, nm in ((x, xs, "in"), (w, ws, "w"), (out, os_, "out")):
             if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == shape):
                 raise ValueError(f"{nm}: need a contiguous fp32 device tensor of shape {shape}")
         if stream is None:
@@ -156,3 +178,40 @@ def conv_forward(x, w, stride: int = 1, pad: int = 0, variant: str | None = None
     plan.run(x, w, out)
     plan.destroy()
     return out
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    return stream
+
+
+def _rearrange(fn, what, src, dst, dims, stream):
+    rc = fn(src.data_ptr(), dst.data_ptr(), *[int(d) for d in dims], _stream(stream))
+    if rc != OK:
+        raise ConvDirectError(rc, what)
+    return dst
+
+
+def blocked_act_elems(N, C, H, W) -> int:
+    return int(lib().conv_direct_blocked_act_elems(N, C, H, W))
+
+
+def blocked_w_elems(K, C, R, S) -> int:
+    return int(lib().conv_direct_blocked_w_elems(K, C, R, S))
+
+
+def pack_act(plain, blocked, stream=None):
+    """plain [N][C][H][W] -> blocked [N][ceil(C/4)][H][W][4] (device tensors, both the caller's)."""
+    return _rearrange(lib().conv_direct_pack_act, "conv_direct_pack_act", plain, blocked, plain.shape, stream)
+
+
+def unpack_act(blocked, plain, stream=None):
+    """blocked [N][ceil(C/4)][H][W][4] -> plain [N][C][H][W]."""
+    return _rearrange(lib().conv_direct_unpack_act, "conv_direct_unpack_act", blocked, plain, plain.shape, stream)
+
+
+def pack_w(plain, blocked, stream=None):
+    """plain [K][C][R][S] -> blocked [ceil(K/32)][ceil(C/4)][R][S][4][32]."""
+    return _rearrange(lib().conv_direct_pack_w, "conv_direct_pack_w", plain, blocked, plain.shape, stream)

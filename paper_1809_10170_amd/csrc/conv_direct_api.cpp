@@ -12,6 +12,7 @@
 #include <new>
 
 #include "../../include/conv_direct.h"
+#include "layout.h"
 #include "variant.h"
 
 using convd::Shape;
@@ -24,6 +25,7 @@ struct conv_direct_plan {
     unsigned grid;
     size_t lds_bytes;
     double mfma_efficiency;   // useful / issued multiply-accumulates
+    int in_blocked, out_blocked;   // layouts of in + w, and of out (paper, Section 4)
 };
 
 namespace {
@@ -53,8 +55,10 @@ int validate(int N, int C, int H, int W, int K, int R, int S, int stride, int pa
 }
 
 // Can variant v run shape s at all?
-bool applicable(const Variant &v, const Shape &s)
+bool applicable(const Variant &v, const Shape &s, int in_blocked, int out_blocked)
 {
+    if ((v.in_blocked != 0) != (in_blocked != 0)) return false;
+    if (v.R == 0 && (in_blocked || out_blocked)) return false;   // the runtime-shape fallback knows plain tensors only
     if (v.R != 0 && (v.R != s.R || v.S != s.S || v.stride != s.stride)) return false;
     if (v.pair == convd::PAIR_R && s.C > v.CB) return false;   // stages all channels at once
     if (v.img != 0 && (s.H != v.img || s.W != v.img || s.pad != v.pad)) return false;   // flat tiling
@@ -166,7 +170,7 @@ double cost(const conv_direct_plan &p)
 }
 
 int make_plan(conv_direct_plan **plan, const char *forced, int N, int C, int H, int W, int K, int R,
-              int S, int stride, int pad)
+              int S, int stride, int pad, int in_blocked = 0, int out_blocked = 0)
 {
     if (!plan) return CONV_DIRECT_EINVAL;
     *plan = nullptr;
@@ -182,9 +186,11 @@ int make_plan(conv_direct_plan **plan, const char *forced, int N, int C, int H, 
     for (int i = 0; i < count; ++i) {
         const Variant &v = *table[i];
         if (forced && std::strcmp(forced, v.name) != 0) continue;
-        if (!applicable(v, s)) continue;
+        if (!applicable(v, s, in_blocked, out_blocked)) continue;
         conv_direct_plan cand;
         fill(&cand, s, v);
+        cand.in_blocked = in_blocked;
+        cand.out_blocked = out_blocked;
         const double c = cost(cand);
         if (!have || c < best_cost) {
             best = cand;
@@ -239,6 +245,7 @@ int conv_direct_run(const conv_direct_plan *plan, const float *in, const float *
     a.tilesP = plan->tilesP;
     a.tilesQ = plan->tilesQ;
     a.ktiles = plan->ktiles;
+    a.out_blocked = plan->out_blocked;
     const hipError_t e = plan->v->launch(a, plan->grid, (hipStream_t)stream);
     if (e != hipSuccess) {
         t_last_hip_error = (int)e;
@@ -271,11 +278,13 @@ int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
     return std::snprintf(buf, n,
                          "variant=%s N=%d C=%d H=%d W=%d K=%d R=%d S=%d stride=%d pad=%d P=%d Q=%d "
                          "TP=%d TQ=%d KT=%d NPB=%d CB=%d pair=%s tilesP=%d tilesQ=%d ktiles=%d grid=%u "
-                         "threads=%d lds_bytes=%zu occupancy=%d flat=%d pointwise=%d mfma_efficiency=%.6g workspace_bytes=0",
+                         "threads=%d lds_bytes=%zu occupancy=%d flat=%d pointwise=%d mfma_efficiency=%.6g in_layout=%s "
+                         "out_layout=%s workspace_bytes=0",
                          v.name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, v.TP, v.TQ,
                          v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : "r", plan->tilesP,
                          plan->tilesQ, plan->ktiles, plan->grid, v.threads, plan->lds_bytes, v.occupancy,
-                         v.img != 0 ? 1 : 0, v.pointwise, plan->mfma_efficiency);
+                         v.img != 0 ? 1 : 0, v.pointwise, plan->mfma_efficiency, plan->in_blocked ? "blocked" : "plain",
+                         plan->out_blocked ? "blocked" : "plain");
 }
 
 const char *conv_direct_strerror(int code)
@@ -292,5 +301,74 @@ const char *conv_direct_strerror(int code)
 }
 
 int conv_direct_last_hip_error(void) { return t_last_hip_error; }
+
+int conv_direct_create_ex(conv_direct_plan **plan, const char *variant, int N, int C, int H, int W, int K, int R,
+                          int S, int stride, int pad, int in_layout, int out_layout)
+{
+    if ((in_layout != CONV_DIRECT_LAYOUT_PLAIN && in_layout != CONV_DIRECT_LAYOUT_BLOCKED) ||
+        (out_layout != CONV_DIRECT_LAYOUT_PLAIN && out_layout != CONV_DIRECT_LAYOUT_BLOCKED)) {
+        if (plan) *plan = nullptr;
+        return CONV_DIRECT_EINVAL;
+    }
+    return make_plan(plan, variant, N, C, H, W, K, R, S, stride, pad, in_layout, out_layout);
+}
+
+int conv_direct_create_layout(conv_direct_plan **plan, int N, int C, int H, int W, int K, int R, int S, int stride,
+                              int pad, int in_layout, int out_layout)
+{
+    if ((in_layout != CONV_DIRECT_LAYOUT_PLAIN && in_layout != CONV_DIRECT_LAYOUT_BLOCKED) ||
+        (out_layout != CONV_DIRECT_LAYOUT_PLAIN && out_layout != CONV_DIRECT_LAYOUT_BLOCKED)) {
+        if (plan) *plan = nullptr;
+        return CONV_DIRECT_EINVAL;
+    }
+    return make_plan(plan, nullptr, N, C, H, W, K, R, S, stride, pad, in_layout, out_layout);
+}
+
+size_t conv_direct_blocked_act_elems(int N, int C, int H, int W)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return 0;
+    return (size_t)N * (size_t)((C + 3) / 4) * 4 * (size_t)H * (size_t)W;
+}
+
+size_t conv_direct_blocked_w_elems(int K, int C, int R, int S)
+{
+    if (K <= 0 || C <= 0 || R <= 0 || S <= 0) return 0;
+    return (size_t)((K + 31) / 32) * 32 * (size_t)((C + 3) / 4) * 4 * (size_t)R * (size_t)S;
+}
+
+static int rearrange_check(const void *src, const void *dst, unsigned dst_align, int64_t a, int64_t b, int64_t c, int64_t d)
+{
+    if (!src || !dst || a <= 0 || b <= 0 || c <= 0 || d <= 0) return CONV_DIRECT_EINVAL;
+    if (((uintptr_t)src & 3u) || ((uintptr_t)dst & (dst_align - 1))) return CONV_DIRECT_EALIGN;
+    return CONV_DIRECT_OK;
+}
+
+static int launched(hipError_t e)
+{
+    if (e == hipSuccess) return CONV_DIRECT_OK;
+    t_last_hip_error = (int)e;
+    return CONV_DIRECT_EHIP;
+}
+
+int conv_direct_pack_act(const float *plain, float *blocked, int N, int C, int H, int W, void *stream)
+{
+    const int rc = rearrange_check(plain, blocked, 16, N, C, H, W);
+    if (rc != CONV_DIRECT_OK) return rc;
+    return launched(convd::launch_pack_act(plain, blocked, N, C, H, W, (hipStream_t)stream));
+}
+
+int conv_direct_unpack_act(const float *blocked, float *plain, int N, int C, int H, int W, void *stream)
+{
+    const int rc = rearrange_check(blocked, plain, 4, N, C, H, W);
+    if (rc != CONV_DIRECT_OK) return rc;
+    return launched(convd::launch_unpack_act(blocked, plain, N, C, H, W, (hipStream_t)stream));
+}
+
+int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, int S, void *stream)
+{
+    const int rc = rearrange_check(plain, blocked, 4, K, C, R, S);
+    if (rc != CONV_DIRECT_OK) return rc;
+    return launched(convd::launch_pack_w(plain, blocked, K, C, R, S, (hipStream_t)stream));
+}
 
 }  // extern "C"

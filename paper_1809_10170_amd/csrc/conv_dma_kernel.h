@@ -50,8 +50,17 @@ typedef float dma_f2u __attribute__((ext_vector_type(2), aligned(4)));
 //     touch, the rows of one image after those of the previous one.  No MFMA column
 //     is wasted on tile edges and the grid can be cut to fit the machine.
 template <int R_, int S_, int ST_, int TP_, int TQ_, int PBW_, int WK_, int WP_, int CB_, int OCC_, int IMG_ = 0,
-          int PADC_ = 0, int PF_ = 1, int SC_ = 1, int PBW2_ = 0>
+          int PADC_ = 0, int PF_ = 1, int SC_ = 1, int PBW2_ = 0, int BLK_ = 0>
 struct DmaGeom {
+    // BLK = 1: input and weights in the paper's blocked layouts (Section 4) with pencils of
+    // 4 input channels and weight blocks of 4 input x 32 output channels:
+    //   in [N][C/4][H][W][4]      w [K/32][C/4][R][S][4][32]
+    // A chunk is then one channel block, its window in LDS a [LH][LW][4] array staged by the
+    // same LDS-direct loads (16 window columns per load instead of 64 of one channel); lane
+    // (j, h) reads channels 2h, 2h+1 of its pixel's pencil, 8 adjacent bytes, so the 64
+    // lanes of an operand fetch cover 1 KB without a gap or a bank conflict; the filter
+    // values of a step are 32 consecutive floats per k-lane half (one 128-byte line).
+    static constexpr int BLK = BLK_;
     static constexpr int PF = PF_;                       // reduction steps the LDS operand fetch runs ahead
     // Split reduction: SC groups of WK*WP waves share one output tile; group sc reduces
     // the chunks sc, sc+SC, ... with stage buffers and a meeting counter of its own (the
@@ -92,15 +101,18 @@ struct DmaGeom {
     static constexpr int NSEG = (PS + 63) / 64;          // 64-lane loads per channel
     static constexpr int PSP = NSEG * 64;                // LDS stride between channels
     static constexpr int HC = CB / 2;                    // channels per kk half
-    static constexpr int HOFF = HC * PSP + 32;           // LDS offset of the second half (other banks)
-    static constexpr int BUF = CB * PSP + 32;            // floats per stage buffer
-    static constexpr int ITEMS = (CB * PSP + NTG - 1) / NTG; // 64-lane loads per wave and chunk
+    static constexpr int PXF = BLK ? 4 : 1;              // LDS floats from one window position to the next
+    static constexpr int CHF = BLK ? (4 * PS + 63) / 64 * 64 : CB * PSP;   // floats of one chunk's window array
+    static constexpr int HOFF = BLK ? 2 : HC * PSP + 32; // LDS offset of the second kk half (plain: other banks)
+    static constexpr int BUF = CHF + 32;                 // floats per stage buffer
+    static constexpr int ITEMS = (CHF + NTG - 1) / NTG;  // 64-lane loads per wave and chunk
     static constexpr int NA = HC * RS;                   // filter values per lane and chunk
     static constexpr int STEPS = HC * RS;                // MFMA k-steps per chunk
     static constexpr int GRP = 3 * BUF + 16;             // floats per split group: three stage buffers, arrival counter
     static constexpr int RED = (SC - 1) * NWG * PBW * 1024;   // floats of the final sum's exchange
     static constexpr size_t LDS_BYTES = sizeof(float) * (size_t)(SC * GRP > RED ? SC * GRP : RED);
     static_assert(CB % 2 == 0, "channel pairing needs an even chunk");
+    static_assert(!BLK || CB == 4, "blocked layout: a chunk is one block of 4 channels");
     static_assert(PBW2 == 0 || (FLAT && WP == 2 && SC == 1 && PBW2 < PBW), "unequal waves: flat tiling, two pixel groups");
     static_assert(!FLAT || R >= ST, "flat tiling stacks image windows R - ST rows apart");
     static_assert(PF >= 1 && 2 * PF < STEPS, "operand fetches for the next chunk must follow the meeting point");
@@ -140,6 +152,69 @@ __device__ __forceinline__ void store_block(__amdgpu_buffer_rsrc_t rsrc, unsigne
     }
 }
 
+// The same for an output in the blocked activation layout out[N][K/4][P][Q][4]: the four
+// accumulator registers 4g .. 4g+3 of a lane are channels 8g + 4h .. + 3 of its pixel, one
+// whole pencil, stored with one 16-byte store; voff is the byte offset of the lane's pencil
+// in channel block h, the block pair 2g a scalar offset.  A wave's store covers 512
+// contiguous bytes per k-lane half.
+typedef float dma_f4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_block_pencils(__amdgpu_buffer_rsrc_t rsrc, unsigned voff, int kfirst,
+                                                    unsigned plane16, const dma_floatx16 &acc)
+{
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int soff = (kfirst / 4 + 2 * g) * (int)plane16;
+        const float f0 = acc[4 * g], f1 = acc[4 * g + 1], f2 = acc[4 * g + 2], f3 = acc[4 * g + 3];
+        typedef unsigned u4 __attribute__((ext_vector_type(4)));
+        const u4 d = {__builtin_bit_cast(unsigned, f0), __builtin_bit_cast(unsigned, f1),
+                      __builtin_bit_cast(unsigned, f2), __builtin_bit_cast(unsigned, f3)};
+        __builtin_amdgcn_raw_buffer_store_b128(d, rsrc, (int)voff, soff, 0);
+    }
+}
+
+// Epilogue of one 32 x 32 accumulator block, shared by all kernel families: channels
+// kw .. kw+31 of the lane's pixel, which is pixel `pix` of the image `ni` images after the
+// one that `orsrc` and `out_n` start at.  The output is plain [N][K][P][Q] or blocked
+// [N][K/4][P][Q][4] (the layout a following layer's blocked input has; channels that
+// complete the last pencil are written as zeros).  Fast path (uniform test by the caller:
+// the 32 channels exist and every byte offset fits 31 bits): buffer stores without vector
+// ALU work; otherwise plain guarded stores.  Each output element is written exactly once.
+__device__ __forceinline__ void write_block(bool blocked, bool fast, __amdgpu_buffer_rsrc_t orsrc, float *out_n, int K,
+                                            int PQ, int kw, int h, bool live, int ni, int pix, const dma_floatx16 &acc)
+{
+    const unsigned oplane = (unsigned)PQ * 4u;
+    if (blocked) {
+        const int KO = (K + 3) / 4 * 4;
+        const size_t o = (size_t)ni * KO * PQ + (size_t)pix * 4;   // the pixel's pencil of channel block 0
+        if (fast) {
+            const unsigned voff = live ? (unsigned)o * 4u + (unsigned)h * 4u * oplane : 0x80000000u;
+            store_block_pencils(orsrc, voff, kw, 4u * oplane, acc);
+        } else if (live) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int k = kw + 8 * g + 4 * h;
+                if (k < KO) {
+                    float *d = out_n + o + (size_t)(k / 4) * PQ * 4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) d[e] = k + e < K ? acc[4 * g + e] : 0.f;
+                }
+            }
+        }
+    } else {
+        const size_t o = (size_t)ni * K * PQ + pix;                 // out[n'][0][p][q] from out[n][0][0][0]
+        if (fast) {
+            const unsigned voff = live ? (unsigned)o * 4u + (unsigned)(4 * h) * oplane : 0x80000000u;
+            store_block(orsrc, voff, kw, oplane, acc);
+        } else if (live) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int k = kw + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (k < K) out_n[o + (size_t)k * PQ] = acc[v];
+            }
+        }
+    }
+}
+
 // TAILC: C is not a multiple of CB.  The last chunk then reaches past the input
 // channels; its filter values are fetched one by one (never past the tensor) and
 // cleared where the channel does not exist.  TAILC = false needs C % CB == 0 and
@@ -160,6 +235,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
     const int goffs = sc * G::GRP;                   // LDS offset (floats) of this group's stage buffers and counter
 
     const int C = a.s.C, H = a.s.H, W = a.s.W, K = a.s.K, P = a.s.P, Q = a.s.Q;
+    const int CI = G::BLK ? (C + 3) / 4 * 4 : C;     // channels an image occupies in memory (blocked: whole pencils)
 
     // Workgroup -> tile.  Consecutive workgroup ids are dealt round-robin to the 8
     // XCDs, each with its own L2; the ids are first regrouped so that one XCD works
@@ -198,7 +274,10 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
 #pragma unroll
     for (int i = 0; i < G::ITEMS; ++i) {
         const int f = i * G::NTG + tid;
-        const int cc = f / G::PSP, pos = f - cc * G::PSP;
+        // plain: [CB][PSP] floats, position pos of channel cc; blocked: [PS][4] floats
+        const int cc = G::BLK ? 0 : f / G::PSP;
+        const int pos = G::BLK ? f / 4 : f - cc * G::PSP;
+        const int ci = G::BLK ? f % 4 : 0;
         const int hh = pos / G::LW, col = pos - hh * G::LW;
         int ih, img = 0;
         if (G::FLAT) {
@@ -214,11 +293,13 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
             ih = ih0 + hh;
         }
         const int iw = iw0 + col;
-        const bool ok = (f < G::CB * G::PSP) & (pos < G::PS) & (n + img < a.s.N) & ((unsigned)ih < (unsigned)H) &
+        const bool ok = (f < G::CHF) & (pos < G::PS) & (n + img < a.s.N) & ((unsigned)ih < (unsigned)H) &
                         ((unsigned)iw < (unsigned)W);
-        goff[i] = ok ? (unsigned)((((img * C + cc) * H + ih) * W + iw) * 4) : 0x80000000u;
+        const unsigned off = G::BLK ? (unsigned)((((img * (CI / 4)) * H + ih) * W + iw) * 16 + ci * 4)
+                                    : (unsigned)((((img * C + cc) * H + ih) * W + iw) * 4);
+        goff[i] = ok ? off : 0x80000000u;
     }
-    const float *in_n = a.in + (size_t)n * C * H * W;
+    const float *in_n = a.in + (size_t)n * CI * H * W;
     const unsigned chan_bytes = (unsigned)(H * W) * 4u;
 
     // Stage the input window of channels [c0, c0 + CB) into buf.  Rectangular: the
@@ -226,7 +307,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
     // Flat: the window spans images, so the resource runs on and the loads of channels
     // past C are given the unreachable offset instead.
     auto stage_b = [&](float *buf, int c0) {
-        const unsigned span = G::FLAT ? 0x7fffffffu : (unsigned)(C - c0) * chan_bytes;
+        const unsigned span = G::FLAT ? 0x7fffffffu : (unsigned)(CI - c0) * chan_bytes;
         // the base is the same in every lane; saying so keeps the resource in scalar
         // registers (a resource the compiler takes for divergent is looped over lane by lane)
         __amdgpu_buffer_rsrc_t rsrc =
@@ -234,10 +315,10 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
 #pragma unroll
         for (int i = 0; i < G::ITEMS; ++i) {
             const int f0 = i * G::NTG + wave * 64;          // first position of this wave's 64
-            if (f0 < G::CB * G::PSP) {
-                float *dst = buf + goffs + f0 + (f0 >= G::HC * G::PSP ? 32 : 0);
+            if (f0 < G::CHF) {
+                float *dst = buf + goffs + f0 + (!G::BLK && f0 >= G::HC * G::PSP ? 32 : 0);
                 unsigned off = goff[i];
-                if (G::FLAT) off = c0 + f0 / G::PSP < C ? off : 0x80000000u;
+                if (G::FLAT && !G::BLK) off = c0 + f0 / G::PSP < C ? off : 0x80000000u;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, CONVD_LDS(dst), 4, off, 0, 0, 0);
             }
         }
@@ -250,8 +331,22 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
     const float *w_lane = a.w + ((size_t)krow * C + h * G::HC) * G::RS;
     const long long w_total = (long long)K * C * G::RS;
     const long long w_lane_idx = ((long long)krow * C + h * G::HC) * G::RS;
+    // blocked weights: the 32 output channels of the wave are one block row kb; lane (j, h)
+    // reads, for tap rs and channel cc of its half, float ((rs*4 + 2h + cc)*32 + j) of the
+    // [R][S][4][32] block of (kb, c0/4): a per-lane constant plus a compile-time offset
+    const unsigned wb_lane = (unsigned)((2 * h * 32 + j) * 4);
+    // (a wave whose 32 channels all lie past K reads the last block that exists; its results are discarded)
+    const int kblk = (k0 + wk * 32) / 32 < (K + 31) / 32 ? (k0 + wk * 32) / 32 : (K + 31) / 32 - 1;
+    const float *wb_row = a.w + (size_t)kblk * (CI / 4) * (G::RS * 128);
     auto load_a = [&](float (&dst)[G::NA], int c0) {
-        if (!TAILC) {
+        if constexpr (G::BLK != 0) {
+            __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(
+                uniform_ptr(wb_row + (size_t)(c0 / 4) * (G::RS * 128)), 0, G::RS * 128 * 4, 0x00020000);
+#pragma unroll
+            for (int e = 0; e < G::NA; ++e)   // e = rs*2 + cc, the order the steps use them in
+                dst[e] = __builtin_bit_cast(
+                    float, __builtin_amdgcn_raw_buffer_load_b32(wr, (int)wb_lane, ((e / 2) * 128 + (e % 2) * 32) * 4, 0));
+        } else if (!TAILC) {
             const float *p = w_lane + (size_t)c0 * G::RS;
             constexpr int N4 = G::NA / 4, REM = G::NA % 4;
 #pragma unroll
@@ -301,7 +396,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
                 const int py = t / G::TQ, px = t - py * G::TQ;
                 pix = t < G::NPIX ? py * G::ST * G::LW + px * G::ST : 0;
             }
-            bbase[pb] = pix + h * G::HOFF + goffs;   // (group offset folded in: buffers are then addressed
+            bbase[pb] = pix * G::PXF + h * G::HOFF + goffs;   // (group offset folded in: buffers are then addressed
                                                      // as constant offsets from lds, as without splitting)
         }
 
@@ -342,6 +437,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
             }
         };
         auto step_off = [](int t) {   // LDS offset (floats) of reduction step t of a chunk
+            if (G::BLK) return ((t / 2 / G::S) * G::LW + (t / 2) % G::S) * 4 + t % 2;   // tap t/2, channel t%2 of the half
             const int cc = t / G::RS, rs = t - cc * G::RS;
             return cc * G::PSP + (rs / G::S) * G::LW + rs % G::S;
         };
@@ -435,41 +531,30 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
             }
         }
 
-        // ---- epilogue: each output element is written exactly once ----
-        // Fast path (uniform test): the wave's 32 channels exist and every byte offset from
-        // the first image of the tile fits 31 bits; otherwise plain guarded stores.
+        // ---- epilogue (see write_block) ----
         const int kw = k0 + wk * 32;
-        const bool fast = (kw + 32 <= K) & ((long long)K * P * Q * 4 * G::NSI < (1ll << 31));
-        __amdgpu_buffer_rsrc_t orsrc =
-            __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(a.out + (size_t)n * K * P * Q), 0, 0x7fffffff, 0x00020000);
-        const unsigned oplane = (unsigned)(P * Q) * 4u;
-    #pragma unroll
+        const int KO = a.out_blocked ? (K + 3) / 4 * 4 : K;      // channels an output image occupies
+        const bool fast = (kw + 32 <= K) & ((long long)KO * P * Q * 4 * G::NSI < (1ll << 31));
+        float *out_n = a.out + (size_t)n * KO * P * Q;
+        __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(out_n), 0, 0x7fffffff, 0x00020000);
+#pragma unroll
         for (int pb = 0; pb < PBW; ++pb) {
             const int t = (wp * G::PBW + pb) * 32 + j;   // (the first pixel group always owns G::PBW blocks)
             bool live;
-            size_t o;      // offset of out[n'][0][p][q] from out[n][0][0][0]
+            int ni = 0, pix;      // image of the pixel relative to n, pixel index inside its image
             if constexpr (G::FLAT) {
                 const int m = m0 + t, pq = G::OP * G::OQ;
-                const int ni = m / pq;
+                const int nm = m / pq;
                 live = m < M;
-                o = (size_t)(ni - n) * K * pq + (m - ni * pq);
+                ni = nm - n;
+                pix = m - nm * pq;
             } else {
                 const int py = t / G::TQ, px = t - py * G::TQ;
                 const int p = p0 + py, q = q0 + px;
                 live = t < G::NPIX && p < P && q < Q;
-                o = (size_t)p * Q + q;
+                pix = p * Q + q;
             }
-            if (fast) {
-                const unsigned voff = live ? (unsigned)o * 4u + (unsigned)(4 * h) * oplane : 0x80000000u;
-                store_block(orsrc, voff, kw, oplane, acc[pb]);
-            } else if (live) {
-                float *out_o = a.out + (size_t)n * K * P * Q + o;
-    #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int k = kw + 8 * (v >> 2) + 4 * h + (v & 3);
-                    if (k < K) out_o[(size_t)k * P * Q] = acc[pb][v];
-                }
-            }
+            write_block(a.out_blocked != 0, fast, orsrc, out_n, K, P * Q, kw, h, live, ni, pix, acc[pb]);
         }
     };
     if (G::PBW2 > 0 && wp == 1) body(IntTag<(G::PBW2 > 0 ? G::PBW2 : G::PBW)>{});
@@ -495,7 +580,11 @@ static hipError_t launch_dma_t(const KernelArgs &a, unsigned grid, hipStream_t s
 template <class G>
 static hipError_t launch_dma(const KernelArgs &a, unsigned grid, hipStream_t stream)
 {
-    return a.s.C % G::CB == 0 ? launch_dma_t<G, false>(a, grid, stream) : launch_dma_t<G, true>(a, grid, stream);
+    if constexpr (G::BLK != 0) {
+        return launch_dma_t<G, false>(a, grid, stream);   // blocked layouts hold whole pencils: no ragged chunk
+    } else {
+        return a.s.C % G::CB == 0 ? launch_dma_t<G, false>(a, grid, stream) : launch_dma_t<G, true>(a, grid, stream);
+    }
 }
 
 template <class G>
@@ -505,7 +594,7 @@ template <class G>
 constexpr Variant make_dma_variant(const char *name)
 {
     return Variant{name, G::R, G::S, G::ST, G::TP, G::FLAT ? 0 : G::TQ, G::KT, G::NPB, G::CB, G::PAIR, G::NT, G::OCC,
-                   G::PSP, G::IMG, G::PADC, &lds_dma<G>, &launch_dma<G>};
+                   G::CHF / G::CB, G::IMG, G::PADC, &lds_dma<G>, &launch_dma<G>, 0, G::BLK};
 }
 
 }  // namespace convd

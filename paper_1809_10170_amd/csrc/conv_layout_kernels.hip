@@ -1,0 +1,92 @@
+// Re-arrangers between the plain tensors and the paper's blocked layouts (Section 4):
+//   activations  plain[n][c][h][w]      <->  blocked[n][c/4][h][w][c%4]
+//   weights      plain[k][c][r][s]       ->  blocked[k/32][c/4][r][s][c%4][k%32]
+// Positions that complete the last block are written as zeros.  The paper counts the
+// weight re-arrangement as a one-time cost for a trained network and keeps the first
+// layer's input plain (Section 4.3); the activation re-arrangers exist for callers that
+// enter or leave a chain of blocked layers.  Source and destination are both the
+// caller's buffers: nothing is allocated here.
+#include <hip/hip_runtime.h>
+
+#include "layout.h"
+
+namespace convd {
+
+// one thread per destination pencil (4 floats, one 16-byte store)
+__global__ void __launch_bounds__(256) pack_act_kernel(const float *__restrict__ src, float *__restrict__ dst, int C,
+                                                       long long HW, long long pencils)
+{
+    const int CB4 = (C + 3) / 4;
+    for (long long t = blockIdx.x * 256ll + threadIdx.x; t < pencils; t += gridDim.x * 256ll) {
+        const long long pix = t % HW, nb = t / HW;
+        const int blk = (int)(nb % CB4);
+        const long long n = nb / CB4;
+        float4 v;
+        float *e = &v.x;
+#pragma unroll
+        for (int ci = 0; ci < 4; ++ci) {
+            const int c = blk * 4 + ci;
+            e[ci] = c < C ? src[(n * C + c) * HW + pix] : 0.f;
+        }
+        *reinterpret_cast<float4 *>(dst + t * 4) = v;
+    }
+}
+
+// one thread per destination element
+__global__ void __launch_bounds__(256) unpack_act_kernel(const float *__restrict__ src, float *__restrict__ dst, int C,
+                                                         long long HW, long long elems)
+{
+    const int CB4 = (C + 3) / 4;
+    for (long long t = blockIdx.x * 256ll + threadIdx.x; t < elems; t += gridDim.x * 256ll) {
+        const long long pix = t % HW, nc = t / HW;
+        const int c = (int)(nc % C);
+        const long long n = nc / C;
+        dst[t] = src[((n * CB4 + c / 4) * HW + pix) * 4 + c % 4];
+    }
+}
+
+// one thread per destination element; consecutive threads write consecutive k % 32
+__global__ void __launch_bounds__(256) pack_w_kernel(const float *__restrict__ src, float *__restrict__ dst, int K, int C,
+                                                     int RS, long long elems)
+{
+    const int CB4 = (C + 3) / 4;
+    for (long long t = blockIdx.x * 256ll + threadIdx.x; t < elems; t += gridDim.x * 256ll) {
+        const int ki = (int)(t % 32);
+        const int ci = (int)(t / 32 % 4);
+        const long long u = t / 128;
+        const int rs = (int)(u % RS);
+        const int cblk = (int)(u / RS % CB4);
+        const int kblk = (int)(u / RS / CB4);
+        const int k = kblk * 32 + ki, c = cblk * 4 + ci;
+        dst[t] = (k < K && c < C) ? src[((long long)k * C + c) * RS + rs] : 0.f;
+    }
+}
+
+static unsigned blocks_for(long long items)
+{
+    const long long b = (items + 255) / 256;
+    return (unsigned)(b < 1 ? 1 : b > 65536 ? 65536 : b);
+}
+
+hipError_t launch_pack_act(const float *plain, float *blocked, int N, int C, int H, int W, hipStream_t stream)
+{
+    const long long HW = (long long)H * W, pencils = (long long)N * ((C + 3) / 4) * HW;
+    hipLaunchKernelGGL(pack_act_kernel, dim3(blocks_for(pencils)), dim3(256), 0, stream, plain, blocked, C, HW, pencils);
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack_act(const float *blocked, float *plain, int N, int C, int H, int W, hipStream_t stream)
+{
+    const long long HW = (long long)H * W, elems = (long long)N * C * HW;
+    hipLaunchKernelGGL(unpack_act_kernel, dim3(blocks_for(elems)), dim3(256), 0, stream, blocked, plain, C, HW, elems);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_w(const float *plain, float *blocked, int K, int C, int R, int S, hipStream_t stream)
+{
+    const long long elems = (long long)((K + 31) / 32) * ((C + 3) / 4) * R * S * 128;
+    hipLaunchKernelGGL(pack_w_kernel, dim3(blocks_for(elems)), dim3(256), 0, stream, plain, blocked, K, C, R * S, elems);
+    return hipGetLastError();
+}
+
+}  // namespace convd

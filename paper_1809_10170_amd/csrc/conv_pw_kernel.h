@@ -167,11 +167,11 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_pw_kernel(const KernelArgs
         }
     }
 
-    // ---- epilogue: each output element is written exactly once ----
-    // (fast path: see store_block)
-    float *out_n = a.out + (size_t)n * K * HW;
+    // ---- epilogue (see write_block) ----
+    const int KO = a.out_blocked ? (K + 3) / 4 * 4 : K;
+    float *out_n = a.out + (size_t)n * KO * HW;
     __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(out_n), 0, 0x7fffffff, 0x00020000);
-    const bool fits = (long long)K * HW * 4 < (1ll << 31);
+    const bool fits = (long long)KO * HW * 4 < (1ll << 31);
 #pragma unroll
     for (int pb = 0; pb < G::PBW; ++pb) {
         const int m = m0 + pb * 32 + j;
@@ -179,16 +179,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_pw_kernel(const KernelArgs
 #pragma unroll
         for (int kb = 0; kb < G::KBW; ++kb) {
             const int kw = k0 + (wk * G::KBW + kb) * 32;
-            if (fits & (kw + 32 <= K)) {
-                const unsigned voff = live ? (unsigned)m * 4u + (unsigned)(4 * h) * plane : 0x80000000u;
-                store_block(orsrc, voff, kw, plane, acc[kb][pb]);
-            } else if (live) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int k = kw + 8 * (v >> 2) + 4 * h + (v & 3);
-                    if (k < K) out_n[(size_t)k * HW + m] = acc[kb][pb][v];
-                }
-            }
+            write_block(a.out_blocked != 0, fits & (kw + 32 <= K), orsrc, out_n, K, HW, kw, h, live, 0, m, acc[kb][pb]);
         }
     }
 }

@@ -221,12 +221,11 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
         }
     }
 
-    // ---- epilogue: each output element is written exactly once ----
-    // (fast path: see store_block)
-    float *out_n = a.out + (size_t)n * K * P * Q;
+    // ---- epilogue (see write_block) ----
+    const int KO = a.out_blocked ? (K + 3) / 4 * 4 : K;
+    float *out_n = a.out + (size_t)n * KO * P * Q;
     __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(out_n), 0, 0x7fffffff, 0x00020000);
-    const unsigned oplane = (unsigned)(P * Q) * 4u;
-    const bool fits = (long long)K * P * Q * 4 < (1ll << 31);
+    const bool fits = (long long)KO * P * Q * 4 < (1ll << 31);
 #pragma unroll
     for (int pb = 0; pb < G::PBW; ++pb) {
         const int t = (wp * G::PBW + pb) * 32 + j;
@@ -236,16 +235,8 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
 #pragma unroll
         for (int kb = 0; kb < G::KBW; ++kb) {
             const int kw = k0 + (wk * G::KBW + kb) * 32;
-            if (fits & (kw + 32 <= K)) {
-                const unsigned voff = live ? (unsigned)(p * Q + q) * 4u + (unsigned)(4 * h) * oplane : 0x80000000u;
-                store_block(orsrc, voff, kw, oplane, acc[kb][pb]);
-            } else if (live) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int k = kw + 8 * (v >> 2) + 4 * h + (v & 3);
-                    if (k < K) out_n[((size_t)k * P + p) * Q + q] = acc[kb][pb][v];
-                }
-            }
+            write_block(a.out_blocked != 0, fits & (kw + 32 <= K), orsrc, out_n, K, P * Q, kw, h, live, 0, p * Q + q,
+                        acc[kb][pb]);
         }
     }
 }
@@ -270,7 +261,7 @@ template <class G>
 constexpr Variant make_rows_variant(const char *name)
 {
     return Variant{name, G::R, G::S, G::ST, G::TP, G::TQ, G::KT, G::NPB, G::CM, G::PAIR, G::NT, G::OCC,
-                   G::PSP, 0, 0, &lds_rows<G>, &launch_rows<G>};
+                   G::PSP, 0, 0, &lds_rows<G>, &launch_rows<G>, 0, 0};
 }
 
 }  // namespace convd

@@ -1,0 +1,9 @@
+// Launchers of the layout re-arrangers (conv_layout_kernels.hip), called by the C ABI.
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+namespace convd {
+hipError_t launch_pack_act(const float *plain, float *blocked, int N, int C, int H, int W, hipStream_t stream);
+hipError_t launch_unpack_act(const float *blocked, float *plain, int N, int C, int H, int W, hipStream_t stream);
+hipError_t launch_pack_w(const float *plain, float *blocked, int K, int C, int R, int S, hipStream_t stream);
+}  // namespace convd

@@ -17,6 +17,7 @@ struct KernelArgs {
     float *out;
     Shape s;
     int tilesP, tilesQ, ktiles;   // grid = ktiles * tilesQ * tilesP * N workgroups
+    int out_blocked;              // 0: out[N][K][P][Q]; 1: out[N][ceil(K/4)][P][Q][4] (paper, Section 4.1)
 };
 
 // which reduction index the two k-lanes of one MFMA span: two input channels, or
@@ -40,6 +41,8 @@ struct Variant {
     hipError_t (*launch)(const KernelArgs &, unsigned grid, hipStream_t stream);
     int pointwise;        // 1: needs pad 0 (and R = S = stride = 1); a tile is TQ consecutive pixels of
                           // one image taken as a single row of H*W pixels
+    int in_blocked;       // 1: input and weights in the blocked layouts (paper, Section 4): in [N][C/4][H][W][4],
+                          // w [K/32][C/4][R][S][4][32]
 };
 
 // The compiled variants (host table of pointers; lives beside the fallback kernel).

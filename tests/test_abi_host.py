@@ -131,14 +131,21 @@ def test_every_variant_plans_a_matching_shape():
     names = cd.variant_names()
     assert len(names) == len(set(names)) and any(n.startswith("generic") for n in names)
     for nm in names:
-        m = re.match(r"[fdrp](\d+)s(\d+)_", nm)
+        m = re.match(r"[fdrpb](\d+)s(\d+)_", nm)
         R, st = (int(m.group(1)), int(m.group(2))) if m else (4, 3)
         C = 3 if nm.startswith("r") else 6   # the row-pair family takes only a few channels
         fl = re.search(r"_flat(\d+)_", nm)     # flat tiling is compiled for one image size
         H, W = (int(fl.group(1)),) * 2 if fl else (37, 41)
-        plan = cd.Plan(2, C, H, W, 70, R, R, st, R // 2, variant=nm)
+        blocked = nm.startswith("b")               # variants for the blocked input / weight layouts
+        plan = cd.Plan(2, C, H, W, 70, R, R, st, R // 2, variant=nm,
+                       in_layout=cd.BLOCKED if blocked else cd.PLAIN, out_layout=cd.BLOCKED if blocked else cd.PLAIN)
         info = plan.info()
         assert info["variant"] == nm
+        assert info["in_layout"] == info["out_layout"] == ("blocked" if blocked else "plain")
+        if not blocked:   # a variant serves one input layout only
+            with pytest.raises(cd.ConvDirectError) as e:
+                cd.Plan(2, C, H, W, 70, R, R, st, R // 2, variant=nm, in_layout=cd.BLOCKED)
+            assert e.value.code == cd.EUNSUPPORTED
         _check_cover(info, exhaustive=True)
         plan.destroy()
 
