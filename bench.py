@@ -99,6 +99,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="suite_batched")
     ap.add_argument("--variant", default=None, help="force a kernel variant (single-layer workloads)")
+    ap.add_argument("--layout", default="plain", choices=["plain", "blocked"],
+                    help="blocked: the paper's Section 4 layouts (activations [N][C/4][H][W][4], weights "
+                         "[K/32][C/4][R][S][4][32]); first layers (C < 4) keep a plain input and write a blocked "
+                         "output; the 1x1 layers, which have no blocked variant, are left out")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--check", action="store_true", help="also verify sampled outputs against the oracle")
     ap.add_argument("--copy-probe", action="store_true",
@@ -118,14 +122,27 @@ def main():
         sys.exit("bench.py: no GPU visible")
     cd.lib()   # fail loudly if the HIP library is missing
     layers = suite(args.workload, workloads)
+    blocked = args.layout == "blocked"
+    if blocked:
+        layers = [l for l in layers if not (l.R == 1 and l.S == 1)]
     dev = torch.device("cuda:0")
 
     items = []
     for l in layers:
         x, w = workloads.make_inputs(l)
         xd, wd = torch.from_numpy(x).to(dev), torch.from_numpy(w).to(dev)
-        plan = cd.Plan(*l.dims(), variant=args.variant)
-        out = torch.empty((l.N, l.K, l.P, l.Q), device=dev, dtype=torch.float32)
+        li = cd.BLOCKED if blocked and l.C >= 4 else cd.PLAIN
+        lo = cd.BLOCKED if blocked else cd.PLAIN
+        plan = cd.Plan(*l.dims(), variant=args.variant, in_layout=li, out_layout=lo)
+        if li == cd.BLOCKED:   # re-arranged once, outside the timed region (the weights: a one-time cost; the
+            xb = torch.empty((l.N, -(-l.C // 4), l.H, l.W, 4), device=dev)       # input: a previous layer's output)
+            wb = torch.empty((-(-l.K // 32), -(-l.C // 4), l.R, l.S, 4, 32), device=dev)
+            cd.pack_act(xd, xb)
+            cd.pack_w(wd, wb)
+            torch.cuda.synchronize()
+            xd, wd = xb, wb
+        oshape = (l.N, -(-l.K // 4), l.P, l.Q, 4) if lo == cd.BLOCKED else (l.N, l.K, l.P, l.Q)
+        out = torch.empty(oshape, device=dev, dtype=torch.float32)
         items.append((l, plan, xd, wd, out))
         del x, w
     torch.cuda.synchronize()
@@ -180,7 +197,11 @@ def main():
         import oracle
         for l, plan, xd, wd, out in items:
             pts = workloads.sample_points(l, 4000)
-            want = oracle.conv_forward_points(xd.cpu().numpy(), wd.cpu().numpy(), pts, l.stride, l.pad)
+            x, w = workloads.make_inputs(l)
+            want = oracle.conv_forward_points(x, w, pts, l.stride, l.pad)
+            if plan.out_layout == cd.BLOCKED:
+                out = cd.unpack_act(out, torch.empty((l.N, l.K, l.P, l.Q), device=dev))
+                torch.cuda.synchronize()
             got = out.cpu().numpy()[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]]
             err = float(abs(got - want).max())
             assert err <= oracle.tolerance(l.C, l.R, l.S), (l.name, err)
@@ -190,7 +211,7 @@ def main():
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "layers": [l.name for l in layers],
+        "config": {"workload": args.workload, "layout": args.layout, "layers": [l.name for l in layers],
                    "frac_fp32_mfma_peak": round(value / PEAK_FP32_MFMA_TFLOPS, 4),
                    "workspace_bytes": 0},
         "roofline": roofline,
