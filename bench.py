@@ -102,7 +102,7 @@ def main():
     ap.add_argument("--layout", default="plain", choices=["plain", "blocked"],
                     help="blocked: the paper's Section 4 layouts (activations [N][C/4][H][W][4], weights "
                          "[K/32][C/4][R][S][4][32]); first layers (C < 4) keep a plain input and write a blocked "
-                         "output; the 1x1 layers, which have no blocked variant, are left out")
+                         "output")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--check", action="store_true", help="also verify sampled outputs against the oracle")
     ap.add_argument("--copy-probe", action="store_true",
@@ -123,8 +123,6 @@ def main():
     cd.lib()   # fail loudly if the HIP library is missing
     layers = suite(args.workload, workloads)
     blocked = args.layout == "blocked"
-    if blocked:
-        layers = [l for l in layers if not (l.R == 1 and l.S == 1)]
     dev = torch.device("cuda:0")
 
     items = []

@@ -17,8 +17,15 @@
 
 namespace convd {
 
-template <int KBW_, int PBW_, int WK_, int WP_, int D_, int OCC_>
+//
+// BLK = 1: input and weights in the blocked layouts (paper, Section 4): in [N][C/4][H*W][4],
+// w [K/32][C/4][4][32].  The reduction then runs block by block, two steps per block: in
+// step (cb, cc) the k-lanes take channels 4cb + cc and 4cb + 2 + cc, so that a lane's B
+// operands of both steps are 8 adjacent bytes of its pixel's pencil (one load, 512 contiguous
+// bytes per half-wave) and a step's filter values are 32 consecutive floats per k-lane half.
+template <int KBW_, int PBW_, int WK_, int WP_, int D_, int OCC_, int BLK_ = 0>
 struct PwGeom {
+    static constexpr int BLK = BLK_;
     static constexpr int R = 1, S = 1, ST = 1;
     static constexpr int KBW = KBW_, PBW = PBW_, WK = WK_, WP = WP_, D = D_, OCC = OCC_;
     static constexpr int PAIR = PAIR_C;
@@ -116,55 +123,153 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_pw_kernel(const KernelArgs
             acc[kb][pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[pb], acc[kb][pb], 0, 0, 0);
     };
 
-    // Main loop: whole groups of D steps whose filter runs lie inside both halves (the
-    // second half is one step shorter when C is odd).  B operands are D steps ahead.
-    const int nfull = C / 2 / G::D * G::D;    // steps covered by full groups (all valid for both halves)
-    float bq[G::D][G::PBW];
-    float aq[2][G::D / 4][G::KBW][4];         // filter values of this group and of the next
-    if (nfull > 0) {
-        // filter loads first, as in the loop: the loop's waits are counted in load order and
-        // must find the same order on entry as on every later pass
+    if constexpr (G::BLK != 0) {
+        // ---- blocked layouts ----
+        const int C4 = (C + 3) / 4;
+        const int nsteps = 2 * C4;                       // all of them exist: pad channels hold zeros
+        const int nfullb = nsteps / G::D * G::D;
+        unsigned boffb[G::PBW];                          // byte offset of the lane's two channels in block 0
 #pragma unroll
-        for (int u = 0; u < G::D / 4; ++u) load_a4(aq[0][u], 4 * u);
-        __builtin_amdgcn_sched_barrier(0);   // the scheduler may not reorder these loads
-#pragma unroll
-        for (int d = 0; d < G::D; ++d) {
-            load_b_full(bq[d], d);
-            __builtin_amdgcn_sched_barrier(0);
+        for (int pb = 0; pb < G::PBW; ++pb) {
+            int m = m0 + pb * 32 + j;
+            m = m < HW ? m : HW - 1;
+            boffb[pb] = (unsigned)(m * 4 + 2 * h) * 4u;
         }
-    }
-    auto group = [&](int s0, float (&ac)[G::D / 4][G::KBW][4], float (&an)[G::D / 4][G::KBW][4]) {
-        const int sn = s0 + G::D < nfull ? s0 + G::D : s0;     // next group (clamped: reloads this one)
-#pragma unroll
-        for (int u = 0; u < G::D / 4; ++u) load_a4(an[u], sn + 4 * u);
-#pragma unroll
-        for (int d = 0; d < G::D; ++d) {
-#pragma unroll
-            for (int kb = 0; kb < G::KBW; ++kb) mfma_step(bq[d], ac[d / 4][kb][d % 4], kb);
-            load_b_full(bq[d], sn + d);
-            // keep the reloads of this step's registers right behind the MFMAs that read them
+        const unsigned bplane = (unsigned)HW * 16u;      // bytes of one channel block of one image
+        __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(a.in + (size_t)n * C4 * 4 * HW), 0,
+                                                                      (int)((unsigned)C4 * bplane), 0x00020000);
+        typedef unsigned pw_u2 __attribute__((ext_vector_type(2)));
+        // B operands of the two steps of block cb
+        auto load_b2 = [&](float (&b0)[G::PBW], float (&b1)[G::PBW], int cb) {
+            const int soff = __builtin_amdgcn_readfirstlane(cb) * (int)bplane;
 #pragma unroll
             for (int pb = 0; pb < G::PBW; ++pb) {
-                __builtin_amdgcn_sched_group_barrier(0x008, G::KBW, 0);   // KBW MFMAs
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);        // one load
+                const pw_u2 v = __builtin_amdgcn_raw_buffer_load_b64(rb, (int)boffb[pb], soff, 0);
+                const unsigned u0 = v[0], u1 = v[1];   // (plain scalars: bit_cast of a vector-element expression is not one)
+                b0[pb] = __builtin_bit_cast(float, u0);
+                b1[pb] = __builtin_bit_cast(float, u1);
             }
-        }
-    };
-    for (int s0 = 0; s0 < nfull; s0 += 2 * G::D) {
-        group(s0, aq[0], aq[1]);
-        if (s0 + G::D >= nfull) break;
-        group(s0 + G::D, aq[1], aq[0]);
-    }
-    // Remaining steps, one at a time (fewer than D + 1 of them)
-    for (int s = nfull; s < CH; ++s) {
-        float bv[G::PBW];
-        load_b(bv, s);
-        const bool ok = s + h * CH < C;
+        };
+        // filter values: block row of the wave's k-block kb (clamped: rows past K are computed and
+        // discarded), lane part (2h*32 + j) floats, step part (cb*128 + cc*32) floats
+        __amdgpu_buffer_rsrc_t ra[G::KBW];
 #pragma unroll
         for (int kb = 0; kb < G::KBW; ++kb) {
-            const float av = ok ? w_lane[kb][s] : 0.f;
-            mfma_step(bv, av, kb);
+            int kblk = (k0 + (wk * G::KBW + kb) * 32) / 32;
+            kblk = kblk < (K + 31) / 32 ? kblk : (K + 31) / 32 - 1;
+            ra[kb] = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(a.w + (size_t)kblk * C4 * 128), 0, C4 * 128 * 4,
+                                                       0x00020000);
         }
+        const int aoff = (2 * h * 32 + j) * 4;
+        auto load_a4b = [&](float (&av)[G::KBW][4], int s) {   // steps s .. s+3 = blocks s/2, s/2 + 1
+            const int soff = __builtin_amdgcn_readfirstlane(s / 2) * 512;
+#pragma unroll
+            for (int kb = 0; kb < G::KBW; ++kb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    av[kb][e] = __builtin_bit_cast(
+                        float, __builtin_amdgcn_raw_buffer_load_b32(ra[kb], aoff, soff + ((e / 2) * 128 + (e % 2) * 32) * 4, 0));
+        };
+        float bq[G::D][G::PBW];
+        float aq[2][G::D / 4][G::KBW][4];
+        if (nfullb > 0) {
+#pragma unroll
+            for (int u = 0; u < G::D / 4; ++u) load_a4b(aq[0][u], 4 * u);
+            __builtin_amdgcn_sched_barrier(0);   // keep the load order the loop's counted waits assume
+#pragma unroll
+            for (int d = 0; d < G::D; d += 2) {
+                load_b2(bq[d], bq[d + 1], d / 2);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        auto group = [&](int s0, float (&ac)[G::D / 4][G::KBW][4], float (&an)[G::D / 4][G::KBW][4]) {
+            const int sn = s0 + G::D < nfullb ? s0 + G::D : s0;     // next group (clamped: reloads this one)
+#pragma unroll
+            for (int u = 0; u < G::D / 4; ++u) load_a4b(an[u], sn + 4 * u);
+#pragma unroll
+            for (int d = 0; d < G::D; d += 2) {
+#pragma unroll
+                for (int kb = 0; kb < G::KBW; ++kb) mfma_step(bq[d], ac[d / 4][kb][d % 4], kb);
+#pragma unroll
+                for (int kb = 0; kb < G::KBW; ++kb) mfma_step(bq[d + 1], ac[d / 4][kb][d % 4 + 1], kb);
+                load_b2(bq[d], bq[d + 1], (sn + d) / 2);
+#pragma unroll
+                for (int pb = 0; pb < G::PBW; ++pb) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2 * G::KBW, 0);   // the MFMAs of two steps
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);            // one load
+                }
+            }
+        };
+        for (int s0 = 0; s0 < nfullb; s0 += 2 * G::D) {
+            group(s0, aq[0], aq[1]);
+            if (s0 + G::D >= nfullb) break;
+            group(s0 + G::D, aq[1], aq[0]);
+        }
+        // remaining blocks, one at a time (fewer than D/2 of them)
+        for (int s = nfullb; s < nsteps; s += 2) {
+            float b0[G::PBW], b1[G::PBW];
+            load_b2(b0, b1, s / 2);
+            const int soff = __builtin_amdgcn_readfirstlane(s / 2) * 512;
+#pragma unroll
+            for (int kb = 0; kb < G::KBW; ++kb) {
+                const float a0 = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ra[kb], aoff, soff, 0));
+                const float a1 = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ra[kb], aoff, soff + 128, 0));
+                mfma_step(b0, a0, kb);
+                mfma_step(b1, a1, kb);
+            }
+        }
+    } else {
+        // Main loop: whole groups of D steps whose filter runs lie inside both halves (the
+        // second half is one step shorter when C is odd).  B operands are D steps ahead.
+        const int nfull = C / 2 / G::D * G::D;    // steps covered by full groups (all valid for both halves)
+        float bq[G::D][G::PBW];
+        float aq[2][G::D / 4][G::KBW][4];         // filter values of this group and of the next
+        if (nfull > 0) {
+            // filter loads first, as in the loop: the loop's waits are counted in load order and
+            // must find the same order on entry as on every later pass
+    #pragma unroll
+            for (int u = 0; u < G::D / 4; ++u) load_a4(aq[0][u], 4 * u);
+            __builtin_amdgcn_sched_barrier(0);   // the scheduler may not reorder these loads
+    #pragma unroll
+            for (int d = 0; d < G::D; ++d) {
+                load_b_full(bq[d], d);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        auto group = [&](int s0, float (&ac)[G::D / 4][G::KBW][4], float (&an)[G::D / 4][G::KBW][4]) {
+            const int sn = s0 + G::D < nfull ? s0 + G::D : s0;     // next group (clamped: reloads this one)
+    #pragma unroll
+            for (int u = 0; u < G::D / 4; ++u) load_a4(an[u], sn + 4 * u);
+    #pragma unroll
+            for (int d = 0; d < G::D; ++d) {
+    #pragma unroll
+                for (int kb = 0; kb < G::KBW; ++kb) mfma_step(bq[d], ac[d / 4][kb][d % 4], kb);
+                load_b_full(bq[d], sn + d);
+                // keep the reloads of this step's registers right behind the MFMAs that read them
+    #pragma unroll
+                for (int pb = 0; pb < G::PBW; ++pb) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, G::KBW, 0);   // KBW MFMAs
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);        // one load
+                }
+            }
+        };
+        for (int s0 = 0; s0 < nfull; s0 += 2 * G::D) {
+            group(s0, aq[0], aq[1]);
+            if (s0 + G::D >= nfull) break;
+            group(s0 + G::D, aq[1], aq[0]);
+        }
+        // Remaining steps, one at a time (fewer than D + 1 of them)
+        for (int s = nfull; s < CH; ++s) {
+            float bv[G::PBW];
+            load_b(bv, s);
+            const bool ok = s + h * CH < C;
+    #pragma unroll
+            for (int kb = 0; kb < G::KBW; ++kb) {
+                const float av = ok ? w_lane[kb][s] : 0.f;
+                mfma_step(bv, av, kb);
+            }
+        }
+
     }
 
     // ---- epilogue (see write_block) ----
@@ -199,7 +304,7 @@ constexpr Variant make_pw_variant(const char *name)
 {
     // "window": the TQ pixels of a channel that a workgroup reads (once, through L1)
     return Variant{name, 1, 1, 1, G::TP, G::TQ, G::KT, G::NPB, G::CB, G::PAIR, G::NT, G::OCC,
-                   G::TQ, 0, 0, &lds_pw<G>, &launch_pw<G>, 1};
+                   G::TQ, 0, 0, &lds_pw<G>, &launch_pw<G>, 1, G::BLK};
 }
 
 }  // namespace convd
