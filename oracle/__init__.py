@@ -5,6 +5,7 @@ cpu_baseline leg.  The product package never imports this.
 """
 from .conv_ref import (  # noqa: F401
     build,
+    conv_dgrad,
     conv_forward,
     conv_forward_points,
     conv_forward_reordered,

@@ -169,6 +169,47 @@ int conv_ref_forward_reordered(const float *in, const float *w, double *out,
     return 0;
 }
 
+/*
+ * Data gradient of the layer (the "backward process to update the image" that the
+ * paper's closing section names as a direction; not an algorithm of the paper): the
+ * adjoint of the forward map in its input argument, i.e. every product of the
+ * definition above, scattered back to the input element it read:
+ *
+ *   dx[n][c][h][w] = sum over k, r, s of  dy[n][k][p][q] * w[k][c][r][s]
+ *        for the (p, q) with p*stride + r - pad == h and q*stride + s - pad == w,
+ *        0 <= p < P, 0 <= q < Q  (no such p or q: the term is absent).
+ *
+ * Written as a gather: for each dx element the loops k, r, s in that order, fp64
+ * accumulation.  Pinned by the adjoint identity <dy, forward(x, w)> == <dgrad(dy, w), x>
+ * (exact on integers), delta filters, and the stride-1 identity with a forward pass
+ * over the flipped, transposed filter.
+ */
+int conv_ref_dgrad(const float *dy, const float *w, double *dx,
+                   int N, int C, int H, int W, int K, int R, int S, int stride, int pad)
+{
+    int P, Q;
+    if (check_dims(N, C, H, W, K, R, S, stride, pad, &P, &Q)) return -1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c)
+            for (int h = 0; h < H; ++h)
+                for (int x = 0; x < W; ++x) {
+                    double acc = 0.0;
+                    for (int k = 0; k < K; ++k)
+                        for (int r = 0; r < R; ++r)
+                            for (int s = 0; s < S; ++s) {
+                                const int ph = h + pad - r, qw = x + pad - s;
+                                if (ph < 0 || qw < 0 || ph % stride || qw % stride) continue;
+                                const int p = ph / stride, q = qw / stride;
+                                if (p >= P || q >= Q) continue;
+                                acc += (double)dy[(((size_t)n * K + k) * P + p) * Q + q] *
+                                       (double)w[(((size_t)k * C + c) * R + r) * S + s];
+                            }
+                    dx[(((size_t)n * C + c) * H + h) * W + x] = acc;
+                }
+    return 0;
+}
+
 /* Number of threads conv_ref_forward will use (1 when built without OpenMP). */
 #ifdef _OPENMP
 #include <omp.h>

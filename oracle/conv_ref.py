@@ -49,6 +49,8 @@ def _load():
         lib.conv_ref_forward_reordered.restype = i
         lib.conv_ref_forward_points.argtypes = [fp, fp, ip, dp, ctypes.c_size_t] + dims
         lib.conv_ref_forward_points.restype = i
+        lib.conv_ref_dgrad.argtypes = [fp, fp, dp] + dims
+        lib.conv_ref_dgrad.restype = i
         lib.conv_ref_threads.argtypes = []
         lib.conv_ref_threads.restype = i
         _lib = lib
@@ -122,3 +124,22 @@ def conv_forward_points(x, w, idx, stride: int = 1, pad: int = 0) -> np.ndarray:
     if rc != 0:
         raise ValueError(f"oracle rejected the request (rc={rc})")
     return out
+
+
+def conv_dgrad(dy, w, H: int, W: int, stride: int = 1, pad: int = 0) -> np.ndarray:
+    """Data gradient dx[n,c,h,w] in float64 for fp32 dy [N,K,P,Q] and w [K,C,R,S] of the
+    layer whose input is H x W (the adjoint of conv_forward in its input)."""
+    dy = np.ascontiguousarray(dy, dtype=np.float32)
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    if dy.ndim != 4 or w.ndim != 4 or dy.shape[1] != w.shape[0]:
+        raise ValueError("expected dy [N,K,P,Q] and w [K,C,R,S] with equal K")
+    N, K, P, Q = dy.shape
+    _, C, R, S = w.shape
+    if (P, Q) != (out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)):
+        raise ValueError("dy does not have the layer's output size")
+    dx = np.empty((N, C, H, W), dtype=np.float64)
+    rc = _load().conv_ref_dgrad(_as(dy, ctypes.c_float), _as(w, ctypes.c_float), _as(dx, ctypes.c_double),
+                                N, C, H, W, K, R, S, stride, pad)
+    if rc != 0:
+        raise ValueError(f"oracle rejected the dimensions (rc={rc})")
+    return dx
