@@ -99,6 +99,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="suite_batched")
     ap.add_argument("--variant", default=None, help="force a kernel variant (single-layer workloads)")
+    ap.add_argument("--direction", default="forward", choices=["forward", "dgrad"],
+                    help="dgrad: the data gradient of the suite's stride-1 layers (filter transform + convolution "
+                         "of dy per step); plain layouts")
     ap.add_argument("--layout", default="plain", choices=["plain", "blocked"],
                     help="blocked: the paper's Section 4 layouts (activations [N][C/4][H][W][4], weights "
                          "[K/32][C/4][R][S][4][32]); first layers (C < 4) keep a plain input and write a blocked "
@@ -123,12 +126,27 @@ def main():
     cd.lib()   # fail loudly if the HIP library is missing
     layers = suite(args.workload, workloads)
     blocked = args.layout == "blocked"
+    dgrad = args.direction == "dgrad"
+    if dgrad:
+        if blocked:
+            sys.exit("bench.py: --direction dgrad runs in plain layouts")
+        layers = [l for l in layers if l.stride == 1 and l.R == l.S and l.pad <= l.R - 1]
     dev = torch.device("cuda:0")
 
     items = []
     for l in layers:
         x, w = workloads.make_inputs(l)
         xd, wd = torch.from_numpy(x).to(dev), torch.from_numpy(w).to(dev)
+        if dgrad:
+            # dy stands in for the next layer's gradient: U[-1,1], seeded
+            g = torch.Generator(device="cpu").manual_seed(4242 + l.K)
+            dy = (torch.rand((l.N, l.K, l.P, l.Q), generator=g) * 2 - 1).to(dev)
+            plan = cd.Plan.dgrad(*l.dims())
+            wt = torch.empty((l.C, l.K, l.R, l.S), device=dev)
+            dx = torch.empty((l.N, l.C, l.H, l.W), device=dev)
+            items.append((l, plan, dy, wt, dx, wd))
+            del x, w
+            continue
         li = cd.BLOCKED if blocked and l.C >= 4 else cd.PLAIN
         lo = cd.BLOCKED if blocked else cd.PLAIN
         plan = cd.Plan(*l.dims(), variant=args.variant, in_layout=li, out_layout=lo)
@@ -141,15 +159,22 @@ def main():
             xd, wd = xb, wb
         oshape = (l.N, -(-l.K // 4), l.P, l.Q, 4) if lo == cd.BLOCKED else (l.N, l.K, l.P, l.Q)
         out = torch.empty(oshape, device=dev, dtype=torch.float32)
-        items.append((l, plan, xd, wd, out))
+        items.append((l, plan, xd, wd, out, None))
         del x, w
     torch.cuda.synchronize()
     alloc_before = torch.cuda.memory_allocated()
 
     stream = torch.cuda.current_stream()
+
+    def launch(item):
+        l, plan, xd, wd, out, w_plain = item
+        if w_plain is not None:   # dgrad: the filter transform belongs to the step (weights change every update)
+            cd.dgrad_filter(w_plain, wd, stream.cuda_stream)
+        plan.run(xd, wd, out, stream.cuda_stream)
+
     for _ in range(args.warmup):
-        for l, plan, xd, wd, out in items:
-            plan.run(xd, wd, out, stream.cuda_stream)
+        for item in items:
+            launch(item)
     torch.cuda.synchronize()
 
     # per-layer events inside the timed region, on the stream the kernels run on
@@ -158,16 +183,16 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
-        for i, (l, plan, xd, wd, out) in enumerate(items):
+        for i, item in enumerate(items):
             ev[s][i][0].record(stream)
-            plan.run(xd, wd, out, stream.cuda_stream)
+            launch(item)
             ev[s][i][1].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     assert torch.cuda.memory_allocated() == alloc_before, "device memory was allocated during the timed region"
 
     per_layer = []
-    for i, (l, plan, xd, wd, out) in enumerate(items):
+    for i, (l, plan, xd, wd, out, _) in enumerate(items):
         ms = sorted(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(args.steps))
         avg = sum(ms) / len(ms)
         info = plan.info()
@@ -193,7 +218,18 @@ def main():
 
     if args.check:
         import oracle
-        for l, plan, xd, wd, out in items:
+        for l, plan, xd, wd, out, w_plain in items:
+            if w_plain is not None:
+                # sampled dx elements through the flipped-filter identity (pinned on the CPU against the adjoint definition)
+                import numpy as np
+                rng = np.random.default_rng(5)
+                pts = np.stack([rng.integers(0, d, 4000) for d in (l.N, l.C, l.H, l.W)], axis=1).astype(np.int32)
+                wt = np.ascontiguousarray(w_plain.cpu().numpy()[:, :, ::-1, ::-1].transpose(1, 0, 2, 3))
+                want = oracle.conv_forward_points(xd.cpu().numpy(), wt, pts, 1, l.R - 1 - l.pad)
+                got = out.cpu().numpy()[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]]
+                err = float(abs(got - want).max())
+                assert err <= oracle.tolerance(l.K, l.R, l.S), (l.name, err)
+                continue
             pts = workloads.sample_points(l, 4000)
             x, w = workloads.make_inputs(l)
             want = oracle.conv_forward_points(x, w, pts, l.stride, l.pad)
@@ -205,11 +241,12 @@ def main():
             assert err <= oracle.tolerance(l.C, l.R, l.S), (l.name, err)
 
     rec = {
-        "metric": "conv fwd TFLOP/s (2*N*K*C*R*S*P*Q/t), fp32, zero workspace",
+        "metric": ("conv dgrad TFLOP/s (2*N*K*C*R*S*P*Q/t), fp32, zero workspace" if dgrad else
+                   "conv fwd TFLOP/s (2*N*K*C*R*S*P*Q/t), fp32, zero workspace"),
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "layout": args.layout, "layers": [l.name for l in layers],
+        "config": {"workload": args.workload, "direction": args.direction, "layout": args.layout, "layers": [l.name for l in layers],
                    "frac_fp32_mfma_peak": round(value / PEAK_FP32_MFMA_TFLOPS, 4),
                    "workspace_bytes": 0},
         "roofline": roofline,

@@ -149,6 +149,30 @@ int conv_direct_pack_act(const float *plain, float *blocked, int N, int C, int H
 int conv_direct_unpack_act(const float *blocked, float *plain, int N, int C, int H, int W, void *stream);
 int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, int S, void *stream);
 
+/* ------------------------------------------------------------------------
+ * Data gradient (the backward pass "to update the image" that the paper's closing
+ * section names as a direction), stride 1, plain layouts:
+ *
+ *   dx[n][c][h][w] = sum over k, r, s of dy[n][k][h + pad - r][w + pad - s] * w[k][c][r][s]
+ *
+ * (terms whose dy index falls outside [0,P) x [0,Q) are absent).  For stride 1 this is
+ * itself a forward convolution, of dy [N][K][P][Q] with the filter
+ *   wt[c][k][r][s] = w[k][c][R-1-r][S-1-s]      (C*K*R*S floats, [C][K][R][S])
+ * and padding R-1-pad, and runs on the same zero-workspace kernels:
+ *
+ *   conv_direct_create_dgrad(&plan, N, C, H, W, K, R, S, stride, pad);   // dims of the FORWARD layer
+ *   conv_direct_dgrad_filter(w, wt, K, C, R, S, stream);                 // wt: a caller buffer, once per weight update
+ *   conv_direct_run(plan, dy, wt, dx, stream);                           // dx [N][C][H][W], every element written
+ *
+ * create_dgrad returns CONV_DIRECT_EUNSUPPORTED for stride != 1, R != S or pad > R-1
+ * (a strided layer's data gradient needs a dilated dy, which this library does not
+ * build); conv_direct_output_dims of the plan gives (H, W).  The weight gradient is not
+ * part of this library.
+ * ------------------------------------------------------------------------ */
+int conv_direct_create_dgrad(conv_direct_plan **plan,
+                             int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+int conv_direct_dgrad_filter(const float *w, float *wt, int K, int C, int R, int S, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

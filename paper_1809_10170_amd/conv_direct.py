@@ -65,7 +65,9 @@ def lib():
         l.conv_direct_blocked_act_elems.restype = ctypes.c_size_t
         l.conv_direct_blocked_w_elems.argtypes = [i] * 4
         l.conv_direct_blocked_w_elems.restype = ctypes.c_size_t
-        for nm in ("conv_direct_pack_act", "conv_direct_unpack_act", "conv_direct_pack_w"):
+        l.conv_direct_create_dgrad.argtypes = [pp] + [i] * 9
+        l.conv_direct_create_dgrad.restype = i
+        for nm in ("conv_direct_pack_act", "conv_direct_unpack_act", "conv_direct_pack_w", "conv_direct_dgrad_filter"):
             getattr(l, nm).argtypes = [vp, vp] + [i] * 4 + [vp]
             getattr(l, nm).restype = i
         _lib = l
@@ -105,6 +107,21 @@ class Plan:
             self._p = ctypes.c_void_p()
             raise ConvDirectError(rc, "conv_direct_create")
         self.dims = tuple(dims)
+
+    @classmethod
+    def dgrad(cls, N, C, H, W, K, R, S, stride, pad):
+        """Plan of the data gradient of the forward layer (N, C, H, W, K, R, S, stride, pad):
+        run(dy [N,K,P,Q], wt [C,K,R,S] from dgrad_filter, dx [N,C,H,W])."""
+        self = cls.__new__(cls)
+        self._p = ctypes.c_void_p()
+        self.in_layout = self.out_layout = PLAIN
+        rc = lib().conv_direct_create_dgrad(ctypes.byref(self._p), *[int(v) for v in (N, C, H, W, K, R, S, stride, pad)])
+        if rc != OK:
+            self._p = ctypes.c_void_p()
+            raise ConvDirectError(rc, "conv_direct_create_dgrad")
+        P, Q = H + 2 * pad - R + 1, W + 2 * pad - S + 1
+        self.dims = (int(N), int(K), P, Q, int(C), int(R), int(S), 1, R - 1 - pad)   # the forward problem it runs
+        return self
 
     def output_dims(self):
         P, Q = ctypes.c_int(), ctypes.c_int()
@@ -215,3 +232,8 @@ def unpack_act(blocked, plain, stream=None):
 def pack_w(plain, blocked, stream=None):
     """plain [K][C][R][S] -> blocked [ceil(K/32)][ceil(C/4)][R][S][4][32]."""
     return _rearrange(lib().conv_direct_pack_w, "conv_direct_pack_w", plain, blocked, plain.shape, stream)
+
+
+def dgrad_filter(w, wt, stream=None):
+    """w [K][C][R][S] -> wt [C][K][R][S] with wt[c][k][r][s] = w[k][c][R-1-r][S-1-s] (device tensors)."""
+    return _rearrange(lib().conv_direct_dgrad_filter, "conv_direct_dgrad_filter", w, wt, w.shape, stream)

@@ -324,6 +324,18 @@ int conv_direct_create_layout(conv_direct_plan **plan, int N, int C, int H, int 
     return make_plan(plan, nullptr, N, C, H, W, K, R, S, stride, pad, in_layout, out_layout);
 }
 
+int conv_direct_create_dgrad(conv_direct_plan **plan, int N, int C, int H, int W, int K, int R, int S, int stride,
+                             int pad)
+{
+    if (plan) *plan = nullptr;
+    Shape fwd;
+    const int rc = validate(N, C, H, W, K, R, S, stride, pad, &fwd);
+    if (rc != CONV_DIRECT_OK) return rc;
+    if (stride != 1 || R != S || pad > R - 1) return CONV_DIRECT_EUNSUPPORTED;
+    // the forward problem that computes dx: input dy [N][K][P][Q], C output channels
+    return make_plan(plan, nullptr, N, K, fwd.P, fwd.Q, C, R, S, 1, R - 1 - pad);
+}
+
 size_t conv_direct_blocked_act_elems(int N, int C, int H, int W)
 {
     if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return 0;
@@ -362,6 +374,13 @@ int conv_direct_unpack_act(const float *blocked, float *plain, int N, int C, int
     const int rc = rearrange_check(blocked, plain, 4, N, C, H, W);
     if (rc != CONV_DIRECT_OK) return rc;
     return launched(convd::launch_unpack_act(blocked, plain, N, C, H, W, (hipStream_t)stream));
+}
+
+int conv_direct_dgrad_filter(const float *w, float *wt, int K, int C, int R, int S, void *stream)
+{
+    const int rc = rearrange_check(w, wt, 4, K, C, R, S);
+    if (rc != CONV_DIRECT_OK) return rc;
+    return launched(convd::launch_dgrad_filter(w, wt, K, C, R, S, (hipStream_t)stream));
 }
 
 int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, int S, void *stream)

@@ -62,6 +62,21 @@ __global__ void __launch_bounds__(256) pack_w_kernel(const float *__restrict__ s
     }
 }
 
+// Filter of the data gradient for stride 1 (see conv_direct_create_dgrad):
+//   wt[c][k][r][s] = w[k][c][R-1-r][S-1-s]
+// one thread per destination element
+__global__ void __launch_bounds__(256) dgrad_filter_kernel(const float *__restrict__ src, float *__restrict__ dst, int K,
+                                                           int C, int R, int S, long long elems)
+{
+    for (long long t = blockIdx.x * 256ll + threadIdx.x; t < elems; t += gridDim.x * 256ll) {
+        const int s = (int)(t % S);
+        const int r = (int)(t / S % R);
+        const int k = (int)(t / ((long long)R * S) % K);
+        const int c = (int)(t / ((long long)R * S * K));
+        dst[t] = src[(((long long)k * C + c) * R + (R - 1 - r)) * S + (S - 1 - s)];
+    }
+}
+
 static unsigned blocks_for(long long items)
 {
     const long long b = (items + 255) / 256;
@@ -86,6 +101,13 @@ hipError_t launch_pack_w(const float *plain, float *blocked, int K, int C, int R
 {
     const long long elems = (long long)((K + 31) / 32) * ((C + 3) / 4) * R * S * 128;
     hipLaunchKernelGGL(pack_w_kernel, dim3(blocks_for(elems)), dim3(256), 0, stream, plain, blocked, K, C, R * S, elems);
+    return hipGetLastError();
+}
+
+hipError_t launch_dgrad_filter(const float *w, float *wt, int K, int C, int R, int S, hipStream_t stream)
+{
+    const long long elems = (long long)K * C * R * S;
+    hipLaunchKernelGGL(dgrad_filter_kernel, dim3(blocks_for(elems)), dim3(256), 0, stream, w, wt, K, C, R, S, elems);
     return hipGetLastError();
 }
 

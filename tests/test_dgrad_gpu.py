@@ -1,0 +1,89 @@
+"""GPU parity of the data gradient (stride 1) against the oracle's adjoint definition."""
+import numpy as np
+import pytest
+import torch
+
+from paper_1809_10170_amd import conv_direct as cd
+from paper_1809_10170_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+def _dgrad(dy, w, H, W, pad):
+    N, K, P, Q = dy.shape
+    _, C, R, S = w.shape
+    plan = cd.Plan.dgrad(N, C, H, W, K, R, S, 1, pad)
+    assert plan.output_dims() == (H, W) and plan.workspace_bytes() == 0
+    wd = torch.from_numpy(w).cuda()
+    wt = torch.full((C, K, R, S), float("nan"), device="cuda")
+    cd.dgrad_filter(wd, wt)
+    dx = torch.full((N, C, H, W), float("nan"), device="cuda")
+    plan.run(torch.from_numpy(dy).cuda(), wt, dx)
+    torch.cuda.synchronize()
+    info = plan.info()
+    plan.destroy()
+    return dx.cpu().numpy(), wt.cpu().numpy(), info
+
+
+SMALL = [
+    # N, C, H, W, K, R, S, pad
+    (2, 7, 30, 61, 70, 3, 3, 1),
+    (2, 3, 33, 47, 35, 3, 3, 0),
+    (1, 9, 40, 40, 33, 5, 5, 2),
+    (2, 37, 19, 23, 65, 1, 1, 0),
+    (3, 16, 13, 13, 130, 3, 3, 1),
+    (1, 5, 20, 22, 6, 4, 4, 3),
+    (1, 4, 12, 12, 8, 3, 3, 2),
+]
+
+
+@pytest.mark.parametrize("shape", SMALL)
+def test_small_shapes_integer_inputs_bit_exact(oracle, shape):
+    N, C, H, W, K, R, S, pd = shape
+    rng = np.random.default_rng(500 + sum(shape))
+    w = rng.integers(-4, 5, (K, C, R, S)).astype(np.float32)
+    P, Q = oracle.out_dim(H, R, 1, pd), oracle.out_dim(W, S, 1, pd)
+    dy = rng.integers(-4, 5, (N, K, P, Q)).astype(np.float32)
+    assert K * R * S * 16 < 2 ** 24
+    got, wt, info = _dgrad(dy, w, H, W, pd)
+    assert np.array_equal(wt, w[:, :, ::-1, ::-1].transpose(1, 0, 2, 3)), "dgrad_filter"
+    assert np.array_equal(got.astype(np.float64), oracle.conv_dgrad(dy, w, H, W, 1, pd)), info["variant"]
+
+
+@pytest.mark.parametrize("shape", SMALL)
+def test_small_shapes_random_inputs(oracle, shape):
+    N, C, H, W, K, R, S, pd = shape
+    rng = np.random.default_rng(600 + sum(shape))
+    w = rng.uniform(-1, 1, (K, C, R, S)).astype(np.float32)
+    P, Q = oracle.out_dim(H, R, 1, pd), oracle.out_dim(W, S, 1, pd)
+    dy = rng.uniform(-1, 1, (N, K, P, Q)).astype(np.float32)
+    got, _, info = _dgrad(dy, w, H, W, pd)
+    err = np.abs(got.astype(np.float64) - oracle.conv_dgrad(dy, w, H, W, 1, pd)).max()
+    assert err <= oracle.tolerance(K, R, S), (info["variant"], err)   # the reduction runs over K*R*S
+
+
+def test_unsupported_cases_are_refused():
+    for args in ((2, 8, 20, 20, 8, 3, 3, 2, 1),     # stride 2
+                 (2, 8, 20, 20, 8, 3, 5, 1, 1),     # R != S
+                 (2, 8, 20, 20, 8, 3, 3, 1, 3)):    # pad > R-1
+        with pytest.raises(cd.ConvDirectError) as e:
+            cd.Plan.dgrad(*args)
+        assert e.value.code == cd.EUNSUPPORTED
+
+
+@pytest.mark.parametrize("name", ["alex_conv3_n64", "vgg_c256_56_k256_n32", "pw_c256_56_k64_n64"])
+def test_benchmark_layers_full_size_sampled(oracle, name):
+    """Full-size layers: sampled dx elements against the oracle.  The sample is computed through the
+    flipped-filter identity (pinned on the CPU against the adjoint definition), which lets the oracle
+    evaluate single elements."""
+    l = workloads.BY_NAME[name]
+    _, w = workloads.make_inputs(l)
+    rng = np.random.default_rng(11)
+    dy = rng.uniform(-1, 1, (l.N, l.K, l.P, l.Q)).astype(np.float32)
+    got, _, info = _dgrad(dy, w, l.H, l.W, l.pad)
+    assert not np.isnan(got).any()
+    pts = np.stack([rng.integers(0, d, 4000) for d in (l.N, l.C, l.H, l.W)], axis=1).astype(np.int32)
+    wt = np.ascontiguousarray(w[:, :, ::-1, ::-1].transpose(1, 0, 2, 3))
+    want = oracle.conv_forward_points(dy, wt, pts, 1, l.R - 1 - l.pad)
+    err = np.abs(got[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.float64) - want).max()
+    assert err <= oracle.tolerance(l.K, l.R, l.S), (info["variant"], err)
