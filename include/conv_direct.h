@@ -64,6 +64,22 @@ int conv_direct_create(conv_direct_plan **plan,
 int conv_direct_run(const conv_direct_plan *plan,
                     const float *in, const float *w, float *out, void *stream);
 
+/*
+ * conv_direct_run with the point-wise layers that usually follow a convolution folded
+ * into the store of the result (paper, Section 4.3: skip and activation layers are
+ * point-wise operations that need no change of the algorithm):
+ *   out = relu?( conv(in, w) + bias[k] + residual )
+ *   bias     : device pointer, K floats, or NULL
+ *   residual : device pointer, a tensor of out's layout and size (it may not overlap out), or NULL
+ *   relu     : nonzero applies max(., 0) last
+ * All NULL / 0 is conv_direct_run.  Still one kernel launch and no workspace.
+ * CONV_DIRECT_EUNSUPPORTED if the plan runs on the runtime-shape fallback kernel (shapes no
+ * compiled variant serves), which has no fused tail.
+ */
+int conv_direct_run_fused(const conv_direct_plan *plan,
+                          const float *in, const float *w, const float *bias, const float *residual,
+                          int relu, float *out, void *stream);
+
 /* Free the host plan.  conv_direct_destroy(NULL) is a no-op that returns OK. */
 int conv_direct_destroy(conv_direct_plan *plan);
 

@@ -13,3 +13,4 @@ from .conv_ref import (  # noqa: F401
     threads,
     tolerance,
 )
+from .tail_ref import apply_tail, conv_forward_fused  # noqa: F401,E402

@@ -45,6 +45,8 @@ def lib():
         l.conv_direct_variant_name.restype = cp
         l.conv_direct_run.argtypes = [vp, vp, vp, vp, vp]
         l.conv_direct_run.restype = i
+        l.conv_direct_run_fused.argtypes = [vp, vp, vp, vp, vp, i, vp, vp]
+        l.conv_direct_run_fused.restype = i
         l.conv_direct_destroy.argtypes = [vp]
         l.conv_direct_destroy.restype = i
         l.conv_direct_output_dims.argtypes = [vp, ctypes.POINTER(i), ctypes.POINTER(i)]
@@ -156,8 +158,9 @@ class Plan:
         if rc != OK:
             raise ConvDirectError(rc, "conv_direct_run")
 
-    def run(self, x, w, out, stream: int | None = None) -> None:
-        """Device tensors (contiguous fp32); asynchronous on torch's current stream by default."""
+    def run(self, x, w, out, stream: int | None = None, bias=None, residual=None, relu: bool = False) -> None:
+        """Device tensors (contiguous fp32); asynchronous on torch's current stream by default.
+        bias [K], residual (out's shape and layout) and relu fold the point-wise tail into the store."""
         import torch
         N, C, H, W, K, R, S, _, _ = self.dims
         P, Q = self.output_dims()
@@ -170,7 +173,16 @@ class Plan:
                 raise ValueError(f"{nm}: need a contiguous fp32 device tensor of shape {shape}")
         if stream is None:
             stream = torch.cuda.current_stream().cuda_stream
-        self.run_ptr(x.data_ptr(), w.data_ptr(), out.data_ptr(), stream)
+        if bias is None and residual is None and not relu:
+            return self.run_ptr(x.data_ptr(), w.data_ptr(), out.data_ptr(), stream)
+        for t, shape, nm in ((bias, (K,), "bias"), (residual, os_, "residual")):
+            if t is not None and not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == shape):
+                raise ValueError(f"{nm}: need a contiguous fp32 device tensor of shape {shape}")
+        rc = lib().conv_direct_run_fused(self._p, x.data_ptr(), w.data_ptr(), bias.data_ptr() if bias is not None else None,
+                                         residual.data_ptr() if residual is not None else None, 1 if relu else 0,
+                                         out.data_ptr(), stream)
+        if rc != OK:
+            raise ConvDirectError(rc, "conv_direct_run_fused")
 
     def destroy(self) -> None:
         if self._p:

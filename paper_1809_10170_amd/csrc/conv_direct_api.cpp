@@ -235,8 +235,17 @@ const char *conv_direct_variant_name(int index)
 int conv_direct_run(const conv_direct_plan *plan, const float *in, const float *w, float *out,
                     void *stream)
 {
+    return conv_direct_run_fused(plan, in, w, nullptr, nullptr, 0, out, stream);
+}
+
+int conv_direct_run_fused(const conv_direct_plan *plan, const float *in, const float *w, const float *bias,
+                          const float *residual, int relu, float *out, void *stream)
+{
     if (!plan || !in || !w || !out) return CONV_DIRECT_EINVAL;
-    if (((uintptr_t)in | (uintptr_t)w | (uintptr_t)out) & 3u) return CONV_DIRECT_EALIGN;
+    if (((uintptr_t)in | (uintptr_t)w | (uintptr_t)out | (uintptr_t)bias | (uintptr_t)residual) & 3u)
+        return CONV_DIRECT_EALIGN;
+    const bool tail = bias || residual || relu;
+    if (tail && plan->v->R == 0) return CONV_DIRECT_EUNSUPPORTED;   // the runtime-shape fallback has no fused tail
     convd::KernelArgs a;
     a.in = in;
     a.w = w;
@@ -246,6 +255,9 @@ int conv_direct_run(const conv_direct_plan *plan, const float *in, const float *
     a.tilesQ = plan->tilesQ;
     a.ktiles = plan->ktiles;
     a.out_blocked = plan->out_blocked;
+    a.bias = bias;
+    a.residual = residual;
+    a.relu = relu ? 1 : 0;
     const hipError_t e = plan->v->launch(a, plan->grid, (hipStream_t)stream);
     if (e != hipSuccess) {
         t_last_hip_error = (int)e;

@@ -179,8 +179,20 @@ __device__ __forceinline__ void store_block_pencils(__amdgpu_buffer_rsrc_t rsrc,
 // complete the last pencil are written as zeros).  Fast path (uniform test by the caller:
 // the 32 channels exist and every byte offset fits 31 bits): buffer stores without vector
 // ALU work; otherwise plain guarded stores.  Each output element is written exactly once.
-__device__ __forceinline__ void write_block(bool blocked, bool fast, __amdgpu_buffer_rsrc_t orsrc, float *out_n, int K,
-                                            int PQ, int kw, int h, bool live, int ni, int pix, const dma_floatx16 &acc)
+//
+// Point-wise layers that follow a convolution (bias, skip connection, activation) fold
+// into this store (paper, Section 4.3: they "should not require any significant change"):
+// with a tail, every value becomes relu?(acc + bias[k] + residual[where it is stored])
+// before it is written.  Without one (the uniform test below) nothing changes.
+struct Tail {
+    const float *bias;     // K floats or NULL
+    const float *res_n;    // the residual tensor at the position out_n has in out, or NULL
+    int relu;
+};
+
+__device__ __forceinline__ void store_tile_block(bool blocked, bool fast, __amdgpu_buffer_rsrc_t orsrc, float *out_n,
+                                                 int K, int PQ, int kw, int h, bool live, int ni, int pix,
+                                                 const dma_floatx16 &acc)
 {
     const unsigned oplane = (unsigned)PQ * 4u;
     if (blocked) {
@@ -215,11 +227,78 @@ __device__ __forceinline__ void write_block(bool blocked, bool fast, __amdgpu_bu
     }
 }
 
+// FUSED is a compile-time switch: kernels are instantiated with and without the tail, so
+// that the plain convolution's epilogue carries none of its registers or instructions.
+template <bool FUSED>
+__device__ __forceinline__ void write_block(bool blocked, bool fast, __amdgpu_buffer_rsrc_t orsrc, float *out_n, int K,
+                                            int PQ, int kw, int h, bool live, int ni, int pix, const dma_floatx16 &acc,
+                                            const Tail &tail)
+{
+    if constexpr (!FUSED) {
+        store_tile_block(blocked, fast, orsrc, out_n, K, PQ, kw, h, live, ni, pix, acc);
+        return;
+    }
+    const int KO = blocked ? (K + 3) / 4 * 4 : K;
+    dma_floatx16 val;
+    if (fast) {
+        // the wave's 32 channels exist and offsets fit 31 bits: bias and residual come in by buffer
+        // loads addressed like the stores (scalar channel offsets, one per-lane register, lanes
+        // without a pixel read past the resource and get zeros), no address arithmetic per value
+        const unsigned oplane = (unsigned)PQ * 4u;
+        __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(tail.bias), 0, tail.bias ? K * 4 : 0, 0x00020000);
+        __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(tail.res_n), 0, tail.res_n ? 0x7fffffff : 0, 0x00020000);
+        // (an absent bias or residual is a resource of size 0: its loads return zeros)
+        const size_t o = blocked ? (size_t)ni * KO * PQ + (size_t)pix * 4 : (size_t)ni * K * PQ + pix;
+        const unsigned voff = !live ? 0x80000000u
+                              : blocked ? (unsigned)o * 4u + (unsigned)h * 4u * oplane : (unsigned)o * 4u + (unsigned)(4 * h) * oplane;
+        typedef unsigned tail_u4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {     // four values at a time keeps the loads in flight, and their registers, few
+            float rv[4];
+            if (blocked) {
+                const tail_u4 d = __builtin_amdgcn_raw_buffer_load_b128(rr, (int)voff, (kw / 4 + 2 * g) * (int)(4u * oplane), 0);
+                const unsigned d0 = d[0], d1 = d[1], d2 = d[2], d3 = d[3];
+                rv[0] = __builtin_bit_cast(float, d0); rv[1] = __builtin_bit_cast(float, d1);
+                rv[2] = __builtin_bit_cast(float, d2); rv[3] = __builtin_bit_cast(float, d3);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    rv[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rr, (int)voff, (kw + 8 * g + e) * (int)oplane, 0));
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float bvv = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, 16 * h, (kw + 8 * g + e) * 4, 0));
+                float x = acc[4 * g + e] + bvv + rv[e];
+                if (tail.relu) x = x > 0.f ? x : 0.f;
+                val[4 * g + e] = x;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int k = kw + 8 * (v >> 2) + 4 * h + (v & 3);
+            float x = acc[v];
+            if (k < K) {
+                if (tail.bias) x += tail.bias[k];
+                if (tail.res_n && live) {
+                    const size_t idx = blocked ? (size_t)ni * KO * PQ + ((size_t)(k / 4) * PQ + pix) * 4 + (k & 3)
+                                               : (size_t)ni * K * PQ + (size_t)k * PQ + pix;
+                    x += tail.res_n[idx];
+                }
+                if (tail.relu) x = x > 0.f ? x : 0.f;
+            }
+            val[v] = x;
+        }
+    }
+    store_tile_block(blocked, fast, orsrc, out_n, K, PQ, kw, h, live, ni, pix, val);
+}
+
 // TAILC: C is not a multiple of CB.  The last chunk then reaches past the input
 // channels; its filter values are fetched one by one (never past the tensor) and
 // cleared where the channel does not exist.  TAILC = false needs C % CB == 0 and
 // keeps the steady state free of branches and of per-value work.
-template <class G, bool TAILC>
+template <class G, bool TAILC, bool FUSED>
 __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArgs a)
 {
     extern __shared__ __align__(16) float lds[];
@@ -537,6 +616,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
         const bool fast = (kw + 32 <= K) & ((long long)KO * P * Q * 4 * G::NSI < (1ll << 31));
         float *out_n = a.out + (size_t)n * KO * P * Q;
         __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(out_n), 0, 0x7fffffff, 0x00020000);
+        const Tail tail{a.bias, a.residual ? a.residual + (size_t)n * KO * P * Q : nullptr, a.relu};
 #pragma unroll
         for (int pb = 0; pb < PBW; ++pb) {
             const int t = (wp * G::PBW + pb) * 32 + j;   // (the first pixel group always owns G::PBW blocks)
@@ -554,7 +634,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
                 live = t < G::NPIX && p < P && q < Q;
                 pix = p * Q + q;
             }
-            write_block(a.out_blocked != 0, fast, orsrc, out_n, K, P * Q, kw, h, live, ni, pix, acc[pb]);
+            write_block<FUSED>(a.out_blocked != 0, fast, orsrc, out_n, K, P * Q, kw, h, live, ni, pix, acc[pb], tail);
         }
     };
     if (G::PBW2 > 0 && wp == 1) body(IntTag<(G::PBW2 > 0 ? G::PBW2 : G::PBW)>{});
@@ -564,17 +644,25 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
 // ---------------------------------------------------------------------------
 // Host side: launcher and the table entry of one compiled variant.
 // ---------------------------------------------------------------------------
-template <class G, bool TAILC>
-static hipError_t launch_dma_t(const KernelArgs &a, unsigned grid, hipStream_t stream)
+inline bool has_tail(const KernelArgs &a) { return a.bias != nullptr || a.residual != nullptr || a.relu != 0; }
+
+template <class G, bool TAILC, bool FUSED>
+static hipError_t launch_dma_tf(const KernelArgs &a, unsigned grid, hipStream_t stream)
 {
     if (G::LDS_BYTES > 64 * 1024) {
         // workgroups above the 64 KB default need the limit raised (no allocation involved)
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_dma_kernel<G, TAILC>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_dma_kernel<G, TAILC, FUSED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((conv_dma_kernel<G, TAILC>), dim3(grid), dim3(G::NT), G::LDS_BYTES, stream, a);
+    hipLaunchKernelGGL((conv_dma_kernel<G, TAILC, FUSED>), dim3(grid), dim3(G::NT), G::LDS_BYTES, stream, a);
     return hipGetLastError();
+}
+
+template <class G, bool TAILC>
+static hipError_t launch_dma_t(const KernelArgs &a, unsigned grid, hipStream_t stream)
+{
+    return has_tail(a) ? launch_dma_tf<G, TAILC, true>(a, grid, stream) : launch_dma_tf<G, TAILC, false>(a, grid, stream);
 }
 
 template <class G>

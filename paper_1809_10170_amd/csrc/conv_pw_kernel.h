@@ -38,7 +38,7 @@ struct PwGeom {
     static_assert(D % 4 == 0, "filter values are fetched four steps at a time");
 };
 
-template <class G>
+template <class G, bool FUSED>
 __global__ void __launch_bounds__(G::NT, G::WPE) conv_pw_kernel(const KernelArgs a)
 {
     const int tid = threadIdx.x, lane = tid & 63;
@@ -277,6 +277,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_pw_kernel(const KernelArgs
     float *out_n = a.out + (size_t)n * KO * HW;
     __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(out_n), 0, 0x7fffffff, 0x00020000);
     const bool fits = (long long)KO * HW * 4 < (1ll << 31);
+    const Tail tail{a.bias, a.residual ? a.residual + (size_t)n * KO * HW : nullptr, a.relu};
 #pragma unroll
     for (int pb = 0; pb < G::PBW; ++pb) {
         const int m = m0 + pb * 32 + j;
@@ -284,7 +285,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_pw_kernel(const KernelArgs
 #pragma unroll
         for (int kb = 0; kb < G::KBW; ++kb) {
             const int kw = k0 + (wk * G::KBW + kb) * 32;
-            write_block(a.out_blocked != 0, fits & (kw + 32 <= K), orsrc, out_n, K, HW, kw, h, live, 0, m, acc[kb][pb]);
+            write_block<FUSED>(a.out_blocked != 0, fits & (kw + 32 <= K), orsrc, out_n, K, HW, kw, h, live, 0, m, acc[kb][pb], tail);
         }
     }
 }
@@ -292,7 +293,8 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_pw_kernel(const KernelArgs
 template <class G>
 static hipError_t launch_pw(const KernelArgs &a, unsigned grid, hipStream_t stream)
 {
-    hipLaunchKernelGGL((conv_pw_kernel<G>), dim3(grid), dim3(G::NT), 0, stream, a);
+    if (has_tail(a)) hipLaunchKernelGGL((conv_pw_kernel<G, true>), dim3(grid), dim3(G::NT), 0, stream, a);
+    else hipLaunchKernelGGL((conv_pw_kernel<G, false>), dim3(grid), dim3(G::NT), 0, stream, a);
     return hipGetLastError();
 }
 

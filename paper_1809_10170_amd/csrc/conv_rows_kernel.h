@@ -54,7 +54,7 @@ struct RowGeom {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
 };
 
-template <class G>
+template <class G, bool FUSED>
 __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelArgs a)
 {
     extern __shared__ __align__(16) float lds[];
@@ -226,6 +226,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
     float *out_n = a.out + (size_t)n * KO * P * Q;
     __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(out_n), 0, 0x7fffffff, 0x00020000);
     const bool fits = (long long)KO * P * Q * 4 < (1ll << 31);
+    const Tail tail{a.bias, a.residual ? a.residual + (size_t)n * KO * P * Q : nullptr, a.relu};
 #pragma unroll
     for (int pb = 0; pb < G::PBW; ++pb) {
         const int t = (wp * G::PBW + pb) * 32 + j;
@@ -235,23 +236,29 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
 #pragma unroll
         for (int kb = 0; kb < G::KBW; ++kb) {
             const int kw = k0 + (wk * G::KBW + kb) * 32;
-            write_block(a.out_blocked != 0, fits & (kw + 32 <= K), orsrc, out_n, K, P * Q, kw, h, live, 0, p * Q + q,
-                        acc[kb][pb]);
+            write_block<FUSED>(a.out_blocked != 0, fits & (kw + 32 <= K), orsrc, out_n, K, P * Q, kw, h, live, 0, p * Q + q,
+                        acc[kb][pb], tail);
         }
     }
+}
+
+template <class G, bool FUSED>
+static hipError_t launch_rows_f(const KernelArgs &a, unsigned grid, hipStream_t stream)
+{
+    if (G::LDS_BYTES > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_rows_kernel<G, FUSED>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((conv_rows_kernel<G, FUSED>), dim3(grid), dim3(G::NT), G::LDS_BYTES, stream, a);
+    return hipGetLastError();
 }
 
 template <class G>
 static hipError_t launch_rows(const KernelArgs &a, unsigned grid, hipStream_t stream)
 {
     if (a.s.C > G::CM) return hipErrorInvalidValue;   // the planner never asks for this
-    if (G::LDS_BYTES > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_rows_kernel<G>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES);
-        if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL((conv_rows_kernel<G>), dim3(grid), dim3(G::NT), G::LDS_BYTES, stream, a);
-    return hipGetLastError();
+    return has_tail(a) ? launch_rows_f<G, true>(a, grid, stream) : launch_rows_f<G, false>(a, grid, stream);
 }
 
 template <class G>

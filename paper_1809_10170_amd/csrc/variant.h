@@ -18,6 +18,10 @@ struct KernelArgs {
     Shape s;
     int tilesP, tilesQ, ktiles;   // grid = ktiles * tilesQ * tilesP * N workgroups
     int out_blocked;              // 0: out[N][K][P][Q]; 1: out[N][ceil(K/4)][P][Q][4] (paper, Section 4.1)
+    // fused point-wise tail (all optional): out = relu?(conv + bias[k] + residual[same position as out])
+    const float *bias;            // K floats, or NULL
+    const float *residual;        // a tensor of out's layout and size, or NULL
+    int relu;
 };
 
 // which reduction index the two k-lanes of one MFMA span: two input channels, or
