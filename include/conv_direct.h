@@ -189,6 +189,31 @@ int conv_direct_create_dgrad(conv_direct_plan **plan,
                              int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 int conv_direct_dgrad_filter(const float *w, float *wt, int K, int C, int R, int S, void *stream);
 
+/* ------------------------------------------------------------------------
+ * Measured choice of the blocking (the paper's closing section proposes auto-tuning
+ * the loops' blocking parameters to close the remaining gap to peak).
+ *
+ * conv_direct_create_tuned runs every compiled variant that can serve the shape, `reps`
+ * times each (after one untimed run), on the caller's own buffers and stream, times
+ * them with HIP events and returns a plan for the fastest.  It synchronises the stream,
+ * overwrites `out`, allocates no device memory, and records the winner in a per-process
+ * table that conv_direct_create / _create_layout consult first from then on (exact match
+ * of all dimensions and layouts).  conv_direct_tuning_save / _load write and read that
+ * table as text, one line per shape:
+ *     N C H W K R S stride pad in_layout out_layout variant
+ * A loaded entry that names an unknown variant, or one that cannot run its shape, is
+ * ignored (the analytical planner decides).  conv_direct_tuning_clear empties the table.
+ * The functions that touch the table are not thread-safe against each other.
+ * ------------------------------------------------------------------------ */
+int conv_direct_create_tuned(conv_direct_plan **plan,
+                             int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                             int in_layout, int out_layout,
+                             const float *in, const float *w, float *out, void *stream, int reps);
+int conv_direct_tuning_save(const char *path);   /* CONV_DIRECT_EINVAL if the file cannot be written */
+int conv_direct_tuning_load(const char *path);   /* CONV_DIRECT_EINVAL if the file cannot be read or a line is malformed */
+int conv_direct_tuning_clear(void);
+int conv_direct_tuning_size(void);               /* number of entries */
+
 #ifdef __cplusplus
 }
 #endif

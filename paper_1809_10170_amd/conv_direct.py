@@ -67,6 +67,14 @@ def lib():
         l.conv_direct_blocked_act_elems.restype = ctypes.c_size_t
         l.conv_direct_blocked_w_elems.argtypes = [i] * 4
         l.conv_direct_blocked_w_elems.restype = ctypes.c_size_t
+        l.conv_direct_create_tuned.argtypes = [pp] + [i] * 11 + [vp, vp, vp, vp, i]
+        l.conv_direct_create_tuned.restype = i
+        for nm in ("conv_direct_tuning_save", "conv_direct_tuning_load"):
+            getattr(l, nm).argtypes = [cp]
+            getattr(l, nm).restype = i
+        for nm in ("conv_direct_tuning_clear", "conv_direct_tuning_size"):
+            getattr(l, nm).argtypes = []
+            getattr(l, nm).restype = i
         l.conv_direct_create_dgrad.argtypes = [pp] + [i] * 9
         l.conv_direct_create_dgrad.restype = i
         for nm in ("conv_direct_pack_act", "conv_direct_unpack_act", "conv_direct_pack_w", "conv_direct_dgrad_filter"):
@@ -109,6 +117,23 @@ class Plan:
             self._p = ctypes.c_void_p()
             raise ConvDirectError(rc, "conv_direct_create")
         self.dims = tuple(dims)
+
+    @classmethod
+    def tuned(cls, x, w, out, N, C, H, W, K, R, S, stride, pad, in_layout: int = PLAIN, out_layout: int = PLAIN,
+              reps: int = 5, stream: int | None = None):
+        """Time every variant that serves the shape on the given device tensors (out is overwritten, the
+        stream synchronised) and return a plan for the fastest; the choice is remembered for later plans."""
+        self = cls.__new__(cls)
+        self._p = ctypes.c_void_p()
+        self.in_layout, self.out_layout = int(in_layout), int(out_layout)
+        dims = [int(v) for v in (N, C, H, W, K, R, S, stride, pad)]
+        rc = lib().conv_direct_create_tuned(ctypes.byref(self._p), *dims, self.in_layout, self.out_layout,
+                                            x.data_ptr(), w.data_ptr(), out.data_ptr(), _stream(stream), int(reps))
+        if rc != OK:
+            self._p = ctypes.c_void_p()
+            raise ConvDirectError(rc, "conv_direct_create_tuned")
+        self.dims = tuple(dims)
+        return self
 
     @classmethod
     def dgrad(cls, N, C, H, W, K, R, S, stride, pad):
@@ -249,3 +274,23 @@ def pack_w(plain, blocked, stream=None):
 def dgrad_filter(w, wt, stream=None):
     """w [K][C][R][S] -> wt [C][K][R][S] with wt[c][k][r][s] = w[k][c][R-1-r][S-1-s] (device tensors)."""
     return _rearrange(lib().conv_direct_dgrad_filter, "conv_direct_dgrad_filter", w, wt, w.shape, stream)
+
+
+def tuning_save(path: str) -> None:
+    rc = lib().conv_direct_tuning_save(os.fsencode(path))
+    if rc != OK:
+        raise ConvDirectError(rc, "conv_direct_tuning_save")
+
+
+def tuning_load(path: str) -> None:
+    rc = lib().conv_direct_tuning_load(os.fsencode(path))
+    if rc != OK:
+        raise ConvDirectError(rc, "conv_direct_tuning_load")
+
+
+def tuning_clear() -> None:
+    lib().conv_direct_tuning_clear()
+
+
+def tuning_size() -> int:
+    return int(lib().conv_direct_tuning_size())

@@ -10,6 +10,8 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <string>
+#include <vector>
 
 #include "../../include/conv_direct.h"
 #include "layout.h"
@@ -169,6 +171,33 @@ double cost(const conv_direct_plan &p)
     return c;
 }
 
+// Measured choices (conv_direct_create_tuned, conv_direct_tuning_load): shape and layouts -> variant name.
+struct TunedEntry {
+    int key[11];   // N C H W K R S stride pad in_layout out_layout
+    std::string variant;
+};
+std::vector<TunedEntry> g_tuned;
+
+const TunedEntry *tuned_lookup(const int (&key)[11])
+{
+    for (const TunedEntry &e : g_tuned)
+        if (std::memcmp(e.key, key, sizeof key) == 0) return &e;
+    return nullptr;
+}
+
+void tuned_store(const int (&key)[11], const char *variant)
+{
+    for (TunedEntry &e : g_tuned)
+        if (std::memcmp(e.key, key, sizeof key) == 0) {
+            e.variant = variant;
+            return;
+        }
+    TunedEntry e;
+    std::memcpy(e.key, key, sizeof key);
+    e.variant = variant;
+    g_tuned.push_back(e);
+}
+
 int make_plan(conv_direct_plan **plan, const char *forced, int N, int C, int H, int W, int K, int R,
               int S, int stride, int pad, int in_blocked = 0, int out_blocked = 0)
 {
@@ -177,6 +206,15 @@ int make_plan(conv_direct_plan **plan, const char *forced, int N, int C, int H, 
     Shape s;
     const int rc = validate(N, C, H, W, K, R, S, stride, pad, &s);
     if (rc != CONV_DIRECT_OK) return rc;
+    if (!forced) {
+        // a measured choice for exactly this problem wins over the model, if it still names a variant that can run it
+        const int key[11] = {N, C, H, W, K, R, S, stride, pad, in_blocked, out_blocked};
+        if (const TunedEntry *e = tuned_lookup(key)) {
+            const std::string name = e->variant;   // (a copy: the recursion below does not touch the table, but be safe)
+            if (make_plan(plan, name.c_str(), N, C, H, W, K, R, S, stride, pad, in_blocked, out_blocked) == CONV_DIRECT_OK)
+                return CONV_DIRECT_OK;
+        }
+    }
 
     conv_direct_plan best;
     bool have = false;
@@ -335,6 +373,104 @@ int conv_direct_create_layout(conv_direct_plan **plan, int N, int C, int H, int 
     }
     return make_plan(plan, nullptr, N, C, H, W, K, R, S, stride, pad, in_layout, out_layout);
 }
+
+int conv_direct_create_tuned(conv_direct_plan **plan, int N, int C, int H, int W, int K, int R, int S, int stride,
+                             int pad, int in_layout, int out_layout, const float *in, const float *w, float *out,
+                             void *stream, int reps)
+{
+    if (plan) *plan = nullptr;
+    if (!plan || !in || !w || !out || reps < 1) return CONV_DIRECT_EINVAL;
+    if ((in_layout != CONV_DIRECT_LAYOUT_PLAIN && in_layout != CONV_DIRECT_LAYOUT_BLOCKED) ||
+        (out_layout != CONV_DIRECT_LAYOUT_PLAIN && out_layout != CONV_DIRECT_LAYOUT_BLOCKED))
+        return CONV_DIRECT_EINVAL;
+    if (((uintptr_t)in | (uintptr_t)w | (uintptr_t)out) & 3u) return CONV_DIRECT_EALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+        if (e0) (void)hipEventDestroy(e0);
+        t_last_hip_error = (int)hipGetLastError();
+        return CONV_DIRECT_EHIP;
+    }
+    int count = 0, rc = CONV_DIRECT_EUNSUPPORTED;
+    const Variant *const *table = convd::variant_table(&count);
+    std::string best;
+    float best_ms = 0.f;
+    for (int i = 0; i < count; ++i) {
+        conv_direct_plan *cand = nullptr;
+        if (make_plan(&cand, table[i]->name, N, C, H, W, K, R, S, stride, pad, in_layout, out_layout) != CONV_DIRECT_OK)
+            continue;
+        int r = conv_direct_run(cand, in, w, out, stream);   // untimed: code object load, caches
+        if (r == CONV_DIRECT_OK && hipEventRecord(e0, st) != hipSuccess) r = CONV_DIRECT_EHIP;
+        for (int k = 0; k < reps && r == CONV_DIRECT_OK; ++k) r = conv_direct_run(cand, in, w, out, stream);
+        float ms = 0.f;
+        if (r == CONV_DIRECT_OK && (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                                    hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
+            r = CONV_DIRECT_EHIP;
+        delete cand;
+        if (r != CONV_DIRECT_OK) {
+            rc = r;
+            best.clear();
+            break;
+        }
+        if (best.empty() || ms < best_ms) {
+            best = table[i]->name;
+            best_ms = ms;
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (best.empty()) return rc;
+    const int key[11] = {N, C, H, W, K, R, S, stride, pad, in_layout, out_layout};
+    tuned_store(key, best.c_str());
+    return make_plan(plan, best.c_str(), N, C, H, W, K, R, S, stride, pad, in_layout, out_layout);
+}
+
+int conv_direct_tuning_save(const char *path)
+{
+    if (!path) return CONV_DIRECT_EINVAL;
+    FILE *f = std::fopen(path, "w");
+    if (!f) return CONV_DIRECT_EINVAL;
+    for (const TunedEntry &e : g_tuned) {
+        for (int v : e.key) std::fprintf(f, "%d ", v);
+        std::fprintf(f, "%s\n", e.variant.c_str());
+    }
+    return std::fclose(f) == 0 ? CONV_DIRECT_OK : CONV_DIRECT_EINVAL;
+}
+
+int conv_direct_tuning_load(const char *path)
+{
+    if (!path) return CONV_DIRECT_EINVAL;
+    FILE *f = std::fopen(path, "r");
+    if (!f) return CONV_DIRECT_EINVAL;
+    std::vector<TunedEntry> got;
+    char line[512];
+    int rc = CONV_DIRECT_OK;
+    while (std::fgets(line, sizeof line, f)) {
+        if (line[0] == '#' || line[0] == '\n') continue;
+        TunedEntry e;
+        char name[128];
+        int *k = e.key;
+        if (std::sscanf(line, "%d %d %d %d %d %d %d %d %d %d %d %127s", k, k + 1, k + 2, k + 3, k + 4, k + 5, k + 6, k + 7,
+                        k + 8, k + 9, k + 10, name) != 12) {
+            rc = CONV_DIRECT_EINVAL;
+            break;
+        }
+        e.variant = name;
+        got.push_back(e);
+    }
+    std::fclose(f);
+    if (rc != CONV_DIRECT_OK) return rc;   // nothing taken from a malformed file
+    for (const TunedEntry &e : got) tuned_store(e.key, e.variant.c_str());
+    return CONV_DIRECT_OK;
+}
+
+int conv_direct_tuning_clear(void)
+{
+    g_tuned.clear();
+    return CONV_DIRECT_OK;
+}
+
+int conv_direct_tuning_size(void) { return (int)g_tuned.size(); }
 
 int conv_direct_create_dgrad(conv_direct_plan **plan, int N, int C, int H, int W, int K, int R, int S, int stride,
                              int pad)

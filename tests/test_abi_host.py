@@ -171,3 +171,37 @@ def test_huge_image_planes_fall_back_to_the_runtime_shape_kernel():
     plan = cd.Plan(1, 4, 4096, 4096, 1, 3, 3, 1, 1)       # 64 MiB planes: compiled variant
     assert not plan.info()["variant"].startswith("generic")
     plan.destroy()
+
+
+def test_tuning_table_round_trip_and_override(tmp_path):
+    """The measured-choice table: loaded entries win over the model for exactly their problem,
+    unknown or unusable entries fall back to it, malformed files change nothing."""
+    cd.tuning_clear()
+    shape = (2, 16, 30, 30, 64, 3, 3, 1, 1)
+    default = cd.Plan(*shape).info()["variant"]
+    other = next(n for n in ("d3s1_8x28_k128", "d3s1_14x14_k128", "d3s1_4x56_k128") if n != default)
+    good = tmp_path / "tuned.txt"
+    good.write_text("# measured choices\n"
+                    + " ".join(map(str, shape)) + f" 0 0 {other}\n"
+                    + "2 16 31 31 64 3 3 1 1 0 0 no_such_variant\n"
+                    + "2 16 32 32 64 3 3 1 1 0 0 r11s4_4x55_k96\n")
+    cd.tuning_load(str(good))
+    assert cd.tuning_size() == 3
+    assert cd.Plan(*shape).info()["variant"] == other
+    assert cd.Plan(3, *shape[1:]).info()["variant"] == cd.Plan(3, *shape[1:], variant=None).info()["variant"]
+    for hw in (31, 32):   # unknown variant / a variant that cannot run the shape: the model decides
+        p = cd.Plan(2, 16, hw, hw, 64, 3, 3, 1, 1)
+        assert p.info()["variant"] not in ("no_such_variant", "r11s4_4x55_k96")
+    out = tmp_path / "saved.txt"
+    cd.tuning_save(str(out))
+    assert sorted(l.split() for l in out.read_text().splitlines()) == \
+        sorted(l.split() for l in good.read_text().splitlines() if not l.startswith("#"))
+    bad = tmp_path / "bad.txt"
+    bad.write_text("1 2 3 4 5 6 7 8 9 0 0 d3s1_8x28_k128\n1 2 3 oops\n")
+    with pytest.raises(cd.ConvDirectError) as e:
+        cd.tuning_load(str(bad))
+    assert e.value.code == cd.EINVAL and cd.tuning_size() == 3
+    with pytest.raises(cd.ConvDirectError):
+        cd.tuning_load(str(tmp_path / "missing.txt"))
+    cd.tuning_clear()
+    assert cd.tuning_size() == 0 and cd.Plan(*shape).info()["variant"] == default
