@@ -28,6 +28,8 @@ PEAK_HBM_GBPS = 8000.0
 def suite(name, workloads):
     if name == "suite_batched":
         return [l for l in workloads.ALL_LAYERS if l.N >= 32]
+    if name == "suite_inception":   # GoogLeNet-shaped layers; a suite of its own, not the headline metric
+        return list(workloads.INCEPTION)
     if name == "suite_all":
         return list(workloads.ALL_LAYERS)
     return [workloads.BY_NAME[name]]

@@ -28,6 +28,7 @@ struct conv_direct_plan {
     size_t lds_bytes;
     double mfma_efficiency;   // useful / issued multiply-accumulates
     int in_blocked, out_blocked;   // layouts of in + w, and of out (paper, Section 4)
+    int pw_flat;                   // pointwise kernels: tiles run over the pixels of all images
 };
 
 namespace {
@@ -56,6 +57,19 @@ int validate(int N, int C, int H, int W, int K, int R, int S, int stride, int pa
     return CONV_DIRECT_OK;
 }
 
+// Pointwise kernels cut every image into tiles of TQ pixels; when the image is not a
+// multiple of the tile (7x7, 14x14, 28x28 maps against tiles of 224 or 448) the pixels of all
+// images are numbered through instead and a tile takes TQ consecutive ones.  A tile then
+// reaches over TQ/HW + 2 images at most, all addressed from the first with 31-bit offsets.
+bool pointwise_flat(const Variant &v, const Shape &s)
+{
+    if (v.pointwise != 2) return false;
+    const int64_t hw = (int64_t)s.H * s.W;
+    const int64_t images = v.TQ / hw + 2;
+    const int64_t chans = s.C > s.K ? s.C : s.K;
+    return images * (chans + 3) * hw * 4 < ((int64_t)1 << 31);
+}
+
 // Can variant v run shape s at all?
 bool applicable(const Variant &v, const Shape &s, int in_blocked, int out_blocked)
 {
@@ -65,6 +79,7 @@ bool applicable(const Variant &v, const Shape &s, int in_blocked, int out_blocke
     if (v.pair == convd::PAIR_R && s.C > v.CB) return false;   // stages all channels at once
     if (v.img != 0 && (s.H != v.img || s.W != v.img || s.pad != v.pad)) return false;   // flat tiling
     if (v.pointwise && s.pad != 0) return false;
+    if (v.pointwise == 2 && (!pointwise_flat(v, s) || ((int64_t)s.H * s.W) % v.TQ == 0)) return false;
     if (v.lds_bytes(s) > kLdsPerCU) return false;
     if (v.R != 0) {
         // the compiled kernels address the input with 31-bit byte offsets from the first
@@ -76,6 +91,7 @@ bool applicable(const Variant &v, const Shape &s, int in_blocked, int out_blocke
     }
     const int64_t grid = v.img != 0
                              ? (int64_t)cdiv(s.K, v.KT) * ((((int64_t)s.N * s.P * s.Q) + v.NPB * 32 - 1) / (v.NPB * 32))
+                         : pointwise_flat(v, s) ? (int64_t)cdiv(s.K, v.KT) * cdiv64((int64_t)s.N * s.P * s.Q, v.TQ)
                          : v.pointwise ? (int64_t)cdiv(s.K, v.KT) * cdiv64((int64_t)s.P * s.Q, v.TQ) * s.N
                                        : (int64_t)cdiv(s.K, v.KT) * cdiv(s.P, v.TP) * cdiv(s.Q, v.TQ) * s.N;
     return grid > 0 && grid < kMaxElems;
@@ -86,7 +102,12 @@ void fill(conv_direct_plan *p, const Shape &s, const Variant &v)
     p->s = s;
     p->v = &v;
     p->ktiles = cdiv(s.K, v.KT);
-    if (v.img != 0) {
+    p->pw_flat = pointwise_flat(v, s) ? 1 : 0;
+    if (p->pw_flat) {
+        p->tilesP = 1;
+        p->tilesQ = (int)cdiv64((int64_t)s.N * s.P * s.Q, v.TQ);
+        p->grid = (unsigned)((int64_t)p->ktiles * p->tilesQ);
+    } else if (v.img != 0) {
         // flat tiling: tilesQ pixel tiles of NPB*32 consecutive pixels over all images
         p->tilesP = 1;
         p->tilesQ = (int)((((int64_t)s.N * s.P * s.Q) + v.NPB * 32 - 1) / (v.NPB * 32));
@@ -333,7 +354,7 @@ int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
                          v.name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, v.TP, v.TQ,
                          v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : "r", plan->tilesP,
                          plan->tilesQ, plan->ktiles, plan->grid, v.threads, plan->lds_bytes, v.occupancy,
-                         v.img != 0 ? 1 : 0, v.pointwise, plan->mfma_efficiency, plan->in_blocked ? "blocked" : "plain",
+                         (v.img != 0 || plan->pw_flat) ? 1 : 0, v.pointwise, plan->mfma_efficiency, plan->in_blocked ? "blocked" : "plain",
                          plan->out_blocked ? "blocked" : "plain");
 }
 

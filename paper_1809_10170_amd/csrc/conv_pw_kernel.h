@@ -23,9 +23,13 @@ namespace convd {
 // step (cb, cc) the k-lanes take channels 4cb + cc and 4cb + 2 + cc, so that a lane's B
 // operands of both steps are 8 adjacent bytes of its pixel's pencil (one load, 512 contiguous
 // bytes per half-wave) and a step's filter values are 32 consecutive floats per k-lane half.
-template <int KBW_, int PBW_, int WK_, int WP_, int D_, int OCC_, int BLK_ = 0>
+//
+// FLAT = 1: for images smaller than a tile (7x7, 14x14, 28x28 maps) the pixels of all images
+// are numbered through, m = n*H*W + p*W + q, and a tile is TQ consecutive ones.
+template <int KBW_, int PBW_, int WK_, int WP_, int D_, int OCC_, int BLK_ = 0, int FLAT_ = 0>
 struct PwGeom {
     static constexpr int BLK = BLK_;
+    static constexpr bool FLAT = FLAT_ != 0;
     static constexpr int R = 1, S = 1, ST = 1;
     static constexpr int KBW = KBW_, PBW = PBW_, WK = WK_, WP = WP_, D = D_, OCC = OCC_;
     static constexpr int PAIR = PAIR_C;
@@ -57,9 +61,24 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_pw_kernel(const KernelArgs
         if (bid < g8) bid = (bid & 7u) * (g8 >> 3) + (bid >> 3);
     }
     const int kt = bid % a.ktiles;  bid /= a.ktiles;
-    const int tm = bid % a.tilesQ;
-    const int n = bid / a.tilesQ;
-    const int k0 = kt * G::KT, m0 = tm * G::TQ + wp * G::PBW * 32;
+    // per-image tiling: image n, tile tm of its H*W pixels.  Flat tiling (images smaller than
+    // a tile): tile bid of the N*H*W pixels of all images; n is then the image the tile starts in
+    const int tm = G::FLAT ? (int)bid : (int)(bid % a.tilesQ);
+    const int n = G::FLAT ? __builtin_amdgcn_readfirstlane((int)(((long long)tm * G::TQ) / HW)) : (int)(bid / a.tilesQ);
+    const int k0 = kt * G::KT, m0 = tm * G::TQ + wp * G::PBW * 32;   // m0: in the image, or in all images (flat)
+    const int M = G::FLAT ? a.s.N * HW : HW;                       // pixels m0 + .. may reach
+    // pixel m (past the end: the last one; read, computed, not stored) -> image relative to n, pixel in the image
+    auto locate = [&](int m, int &ni, int &ml) {
+        m = m < M ? m : M - 1;
+        if (G::FLAT) {
+            const int nl = m / HW;
+            ni = nl - n;
+            ml = m - nl * HW;
+        } else {
+            ni = 0;
+            ml = m;
+        }
+    };
 
     // B: lane (j, h) reads in[n][s + h*CH][m0 + 32*pb + j]; pixels past the image are
     // clamped (read, computed, not stored).  Buffer loads keep the addressing to one
@@ -68,13 +87,14 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_pw_kernel(const KernelArgs
     unsigned boff[G::PBW];
 #pragma unroll
     for (int pb = 0; pb < G::PBW; ++pb) {
-        int m = m0 + pb * 32 + j;
-        m = m < HW ? m : HW - 1;
-        boff[pb] = (unsigned)(h * CH * HW + m) * 4u;
+        int ni, ml;
+        locate(m0 + pb * 32 + j, ni, ml);
+        boff[pb] = (unsigned)((ni * C + h * CH) * HW + ml) * 4u;
     }
     const unsigned plane = (unsigned)HW * 4u;
-    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(a.in + (size_t)n * C * HW), 0,
-                                                                    (int)((unsigned)C * plane), 0x00020000);
+    // (flat: the tile's pixels lie in several images, the resource runs on past image n)
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        uniform_ptr(a.in + (size_t)n * C * HW), 0, G::FLAT ? 0x7fffffff : (int)((unsigned)C * plane), 0x00020000);
     auto load_b_full = [&](float (&bv)[G::PBW], int s) {  // a step that exists in both halves
         const int soff = __builtin_amdgcn_readfirstlane(s) * (int)plane;
 #pragma unroll
@@ -131,13 +151,13 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_pw_kernel(const KernelArgs
         unsigned boffb[G::PBW];                          // byte offset of the lane's two channels in block 0
 #pragma unroll
         for (int pb = 0; pb < G::PBW; ++pb) {
-            int m = m0 + pb * 32 + j;
-            m = m < HW ? m : HW - 1;
-            boffb[pb] = (unsigned)(m * 4 + 2 * h) * 4u;
+            int ni, ml;
+            locate(m0 + pb * 32 + j, ni, ml);
+            boffb[pb] = (unsigned)((ni * C4 * HW + ml) * 4 + 2 * h) * 4u;
         }
         const unsigned bplane = (unsigned)HW * 16u;      // bytes of one channel block of one image
-        __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(a.in + (size_t)n * C4 * 4 * HW), 0,
-                                                                      (int)((unsigned)C4 * bplane), 0x00020000);
+        __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
+            uniform_ptr(a.in + (size_t)n * C4 * 4 * HW), 0, G::FLAT ? 0x7fffffff : (int)((unsigned)C4 * bplane), 0x00020000);
         typedef unsigned pw_u2 __attribute__((ext_vector_type(2)));
         // B operands of the two steps of block cb
         auto load_b2 = [&](float (&b0)[G::PBW], float (&b1)[G::PBW], int cb) {
@@ -276,16 +296,18 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_pw_kernel(const KernelArgs
     const int KO = a.out_blocked ? (K + 3) / 4 * 4 : K;
     float *out_n = a.out + (size_t)n * KO * HW;
     __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(out_n), 0, 0x7fffffff, 0x00020000);
-    const bool fits = (long long)KO * HW * 4 < (1ll << 31);
+    const bool fits = (long long)KO * HW * 4 * (G::FLAT ? G::TQ / HW + 2 : 1) < (1ll << 31);
     const Tail tail{a.bias, a.residual ? a.residual + (size_t)n * KO * HW : nullptr, a.relu};
 #pragma unroll
     for (int pb = 0; pb < G::PBW; ++pb) {
         const int m = m0 + pb * 32 + j;
-        const bool live = m < HW;
+        const bool live = m < M;
+        int ni, ml;
+        locate(m, ni, ml);
 #pragma unroll
         for (int kb = 0; kb < G::KBW; ++kb) {
             const int kw = k0 + (wk * G::KBW + kb) * 32;
-            write_block<FUSED>(a.out_blocked != 0, fits & (kw + 32 <= K), orsrc, out_n, K, HW, kw, h, live, 0, m, acc[kb][pb], tail);
+            write_block<FUSED>(a.out_blocked != 0, fits & (kw + 32 <= K), orsrc, out_n, K, HW, kw, h, live, ni, ml, acc[kb][pb], tail);
         }
     }
 }
@@ -306,7 +328,7 @@ constexpr Variant make_pw_variant(const char *name)
 {
     // "window": the TQ pixels of a channel that a workgroup reads (once, through L1)
     return Variant{name, 1, 1, 1, G::TP, G::TQ, G::KT, G::NPB, G::CB, G::PAIR, G::NT, G::OCC,
-                   G::TQ, 0, 0, &lds_pw<G>, &launch_pw<G>, 1, G::BLK};
+                   G::TQ, 0, 0, &lds_pw<G>, &launch_pw<G>, G::FLAT ? 2 : 1, G::BLK};
 }
 
 }  // namespace convd

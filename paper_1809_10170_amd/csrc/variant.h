@@ -44,7 +44,8 @@ struct Variant {
     size_t (*lds_bytes)(const Shape &);
     hipError_t (*launch)(const KernelArgs &, unsigned grid, hipStream_t stream);
     int pointwise;        // 1: needs pad 0 (and R = S = stride = 1); a tile is TQ consecutive pixels of
-                          // one image taken as a single row of H*W pixels
+                          // one image taken as a single row of H*W pixels.  2: the same over the pixels of
+                          // ALL images numbered through (for images that are not a multiple of the tile)
     int in_blocked;       // 1: input and weights in the blocked layouts (paper, Section 4): in [N][C/4][H][W][4],
                           // w [K/32][C/4][R][S][4][32]
 };

@@ -102,8 +102,27 @@ MIX = [
     _mk(5, 3, "s2_c3_224_k64_7x7_n64", 64, 3, 224, 64, 7, 2, 3),
 ]
 
+# Group 6: GoogLeNet-shaped layers (the paper's third network; its layer list is not in the
+# paper's text): the three branch kinds of an inception module -- 1x1 reductions, 3x3 and
+# 5x5 convolutions behind them -- at the three spatial sizes such modules run at, with
+# channel counts of that kind (many of them not multiples of 32 or 128), and the 3x3 layer
+# of the stem.  A suite of its own: not part of the headline metric.
+_INCEPTION = [
+    ("inc_56_3x3_c64_k192", 64, 56, 192, 3, 1),
+    ("inc_28_1x1_c192_k64", 192, 28, 64, 1, 0),
+    ("inc_28_3x3_c96_k128", 96, 28, 128, 3, 1),
+    ("inc_28_5x5_c16_k32", 16, 28, 32, 5, 2),
+    ("inc_14_1x1_c480_k192", 480, 14, 192, 1, 0),
+    ("inc_14_3x3_c112_k224", 112, 14, 224, 3, 1),
+    ("inc_14_5x5_c24_k64", 24, 14, 64, 5, 2),
+    ("inc_7_1x1_c832_k256", 832, 7, 256, 1, 0),
+    ("inc_7_3x3_c160_k320", 160, 7, 320, 3, 1),
+    ("inc_7_5x5_c32_k128", 32, 7, 128, 5, 2),
+]
+INCEPTION = [_mk(6, i, f"{nm}_n64", 64, C, HW, K, RS, 1, pd) for i, (nm, C, HW, K, RS, pd) in enumerate(_INCEPTION)]
+
 ALL_LAYERS = [TOY] + ALEX_CONV1 + ALEX_REST + VGG + MIX
-BY_NAME = {l.name: l for l in ALL_LAYERS}
+BY_NAME = {l.name: l for l in ALL_LAYERS + INCEPTION}
 
 # The layer the headline number is quoted on (largest flop count among the batched
 # layers whose shape the main 3x3 kernel serves).

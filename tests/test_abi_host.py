@@ -102,7 +102,7 @@ def _check_cover(info, exhaustive):
         assert hits.min() == 1 and hits.max() == 1
 
 
-@pytest.mark.parametrize("layer", workloads.ALL_LAYERS, ids=lambda l: l.name)
+@pytest.mark.parametrize("layer", workloads.ALL_LAYERS + workloads.INCEPTION, ids=lambda l: l.name)
 def test_plan_for_every_benchmark_layer(layer):
     plan = cd.Plan(*layer.dims())
     assert plan.output_dims() == (layer.P, layer.Q)

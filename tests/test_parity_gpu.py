@@ -126,7 +126,7 @@ def test_toy_config_full(oracle):
     _assert_close(got, oracle.conv_forward(x, w, l.stride, l.pad), oracle.tolerance(l.C, l.R, l.S), l.name)
 
 
-@pytest.mark.parametrize("layer", [l for l in workloads.ALL_LAYERS if l is not workloads.TOY],
+@pytest.mark.parametrize("layer", [l for l in workloads.ALL_LAYERS if l is not workloads.TOY] + workloads.INCEPTION,
                          ids=lambda l: l.name)
 def test_benchmark_layers_full_size(oracle, layer):
     """Full-size layers in the launch configuration the benchmark times: the first and
