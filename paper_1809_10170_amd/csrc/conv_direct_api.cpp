@@ -172,7 +172,8 @@ double cost(const conv_direct_plan &p)
     double c = full * round_time(occ);
     if (rem) c += round_time((int)cdiv64(rem, kNumCU));
     // prologue and epilogue of each workgroup, mostly hidden behind its CU neighbours
-    c += 12000.0 * (double)cdiv64(p.grid, slots);
+    // (per round every resident workgroup of a CU pays it: small workgroups, many per CU, pay more)
+    c += 12000.0 * (occ > 2 ? occ / 2.0 : 1.0) * (double)cdiv64(p.grid, slots);
     // input staging traffic
     double staged;   // floats one workgroup stages in total
     if (v.R == 0) {
