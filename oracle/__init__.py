@@ -9,6 +9,7 @@ from .conv_ref import (  # noqa: F401
     conv_forward,
     conv_forward_points,
     conv_forward_reordered,
+    conv_wgrad,
     out_dim,
     threads,
     tolerance,

@@ -210,6 +210,43 @@ int conv_ref_dgrad(const float *dy, const float *w, double *dx,
     return 0;
 }
 
+/*
+ * Weight gradient of the layer (the "backward process to update the ... kernel" of the
+ * paper's closing section; not an algorithm of the paper): the adjoint of the forward map
+ * in its filter argument, i.e. every product of the definition, collected per filter
+ * element:
+ *
+ *   dw[k][c][r][s] = sum over n, p, q of
+ *        dy[n][k][p][q] * x[n][c][p*stride + r - pad][q*stride + s - pad]
+ *
+ * (taps outside the image absent).  Loops n, p, q in that order per dw element, fp64
+ * accumulation.  Pinned by <dy, forward(x, w)> == <wgrad(x, dy), w> (exact on
+ * integers), single-element filters, and float64 autograd.
+ */
+int conv_ref_wgrad(const float *x, const float *dy, double *dw,
+                   int N, int C, int H, int W, int K, int R, int S, int stride, int pad)
+{
+    int P, Q;
+    if (check_dims(N, C, H, W, K, R, S, stride, pad, &P, &Q)) return -1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int k = 0; k < K; ++k)
+        for (int c = 0; c < C; ++c)
+            for (int r = 0; r < R; ++r)
+                for (int s = 0; s < S; ++s) {
+                    double acc = 0.0;
+                    for (int n = 0; n < N; ++n)
+                        for (int p = 0; p < P; ++p)
+                            for (int q = 0; q < Q; ++q) {
+                                const int ih = p * stride + r - pad, iw = q * stride + s - pad;
+                                if (ih < 0 || ih >= H || iw < 0 || iw >= W) continue;
+                                acc += (double)dy[(((size_t)n * K + k) * P + p) * Q + q] *
+                                       (double)x[(((size_t)n * C + c) * H + ih) * W + iw];
+                            }
+                    dw[(((size_t)k * C + c) * R + r) * S + s] = acc;
+                }
+    return 0;
+}
+
 /* Number of threads conv_ref_forward will use (1 when built without OpenMP). */
 #ifdef _OPENMP
 #include <omp.h>

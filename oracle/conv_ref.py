@@ -49,6 +49,8 @@ def _load():
         lib.conv_ref_forward_reordered.restype = i
         lib.conv_ref_forward_points.argtypes = [fp, fp, ip, dp, ctypes.c_size_t] + dims
         lib.conv_ref_forward_points.restype = i
+        lib.conv_ref_wgrad.argtypes = [fp, fp, dp] + dims
+        lib.conv_ref_wgrad.restype = i
         lib.conv_ref_dgrad.argtypes = [fp, fp, dp] + dims
         lib.conv_ref_dgrad.restype = i
         lib.conv_ref_threads.argtypes = []
@@ -143,3 +145,22 @@ def conv_dgrad(dy, w, H: int, W: int, stride: int = 1, pad: int = 0) -> np.ndarr
     if rc != 0:
         raise ValueError(f"oracle rejected the dimensions (rc={rc})")
     return dx
+
+
+def conv_wgrad(x, dy, R: int, S: int, stride: int = 1, pad: int = 0) -> np.ndarray:
+    """Weight gradient dw[k,c,r,s] in float64 for fp32 x [N,C,H,W] and dy [N,K,P,Q] of the
+    layer with an R x S filter (the adjoint of conv_forward in its filter)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    dy = np.ascontiguousarray(dy, dtype=np.float32)
+    if x.ndim != 4 or dy.ndim != 4 or x.shape[0] != dy.shape[0]:
+        raise ValueError("expected x [N,C,H,W] and dy [N,K,P,Q] with equal N")
+    N, C, H, W = x.shape
+    _, K, P, Q = dy.shape
+    if (P, Q) != (out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)):
+        raise ValueError("dy does not have the layer's output size")
+    dw = np.empty((K, C, R, S), dtype=np.float64)
+    rc = _load().conv_ref_wgrad(_as(x, ctypes.c_float), _as(dy, ctypes.c_float), _as(dw, ctypes.c_double),
+                                N, C, H, W, K, R, S, stride, pad)
+    if rc != 0:
+        raise ValueError(f"oracle rejected the dimensions (rc={rc})")
+    return dw
