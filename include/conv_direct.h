@@ -182,12 +182,29 @@ int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, 
  *
  * create_dgrad returns CONV_DIRECT_EUNSUPPORTED for stride != 1, R != S or pad > R-1
  * (a strided layer's data gradient needs a dilated dy, which this library does not
- * build); conv_direct_output_dims of the plan gives (H, W).  The weight gradient is not
- * part of this library.
+ * build); conv_direct_output_dims of the plan gives (H, W).
+ *
+ * Weight gradient (the backward pass "to update ... the kernel"), plain layouts, any
+ * stride, filter widths S in {1, 3, 5, 7, 11} with the strides the forward variants serve:
+ *
+ *   dw[k][c][r][s] = sum over n, p, q of dy[n][k][p][q] * x[n][c][p*stride + r - pad][q*stride + s - pad]
+ *
+ *   conv_direct_create_wgrad(&plan, N, C, H, W, K, R, S, stride, pad);   // dims of the FORWARD layer
+ *   conv_direct_run_wgrad(plan, x, dy, dw, stream);                      // dw [K][C][R][S], every element written
+ *
+ * Two launches (a fill that clears dw, then the reduction, whose workgroups add their
+ * partial sums into dw with fp32 atomics): no workspace, but the order of the additions
+ * is not fixed, so the last bits of dw can differ between runs.  A wgrad plan can only be
+ * passed to conv_direct_run_wgrad, _plan_info, _workspace_bytes and _destroy;
+ * CONV_DIRECT_EUNSUPPORTED if no compiled variant serves the filter width and stride.
  * ------------------------------------------------------------------------ */
 int conv_direct_create_dgrad(conv_direct_plan **plan,
                              int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 int conv_direct_dgrad_filter(const float *w, float *wt, int K, int C, int R, int S, void *stream);
+int conv_direct_create_wgrad(conv_direct_plan **plan,
+                             int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+int conv_direct_run_wgrad(const conv_direct_plan *plan,
+                          const float *x, const float *dy, float *dw, void *stream);
 
 /* ------------------------------------------------------------------------
  * Measured choice of the blocking (the paper's closing section proposes auto-tuning

@@ -61,8 +61,9 @@ def _units(only=None):
             g.writelines(ln for ln in f if (m := re.match(r"\s*X\(\s*(\w+)", ln)) and m.group(1) in only)
         defs = [f'-DCONVD_VARIANTS_DEF="{sub}"']
     units.append(("generic", "conv_generic_kernel.hip", defs, COMMON_DEPS, ",".join(sorted(only or []))))
+    units.append(("wgrad", "conv_wgrad.hip", [], COMMON_DEPS + [os.path.join(CSRC, "wgrad.h"), os.path.join(CSRC, "conv_dma_kernel.h")], ""))
     units.append(("layout", "conv_layout_kernels.hip", [], COMMON_DEPS + [os.path.join(CSRC, "layout.h")], ""))
-    units.append(("api", "conv_direct_api.cpp", [], COMMON_DEPS + [os.path.join(CSRC, "layout.h")], ""))
+    units.append(("api", "conv_direct_api.cpp", [], COMMON_DEPS + [os.path.join(CSRC, "layout.h"), os.path.join(CSRC, "wgrad.h")], ""))
     return units
 
 

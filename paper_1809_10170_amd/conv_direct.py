@@ -75,6 +75,10 @@ def lib():
         for nm in ("conv_direct_tuning_clear", "conv_direct_tuning_size"):
             getattr(l, nm).argtypes = []
             getattr(l, nm).restype = i
+        l.conv_direct_create_wgrad.argtypes = [pp] + [i] * 9
+        l.conv_direct_create_wgrad.restype = i
+        l.conv_direct_run_wgrad.argtypes = [vp, vp, vp, vp, vp]
+        l.conv_direct_run_wgrad.restype = i
         l.conv_direct_create_dgrad.argtypes = [pp] + [i] * 9
         l.conv_direct_create_dgrad.restype = i
         for nm in ("conv_direct_pack_act", "conv_direct_unpack_act", "conv_direct_pack_w", "conv_direct_dgrad_filter"):
@@ -149,6 +153,31 @@ class Plan:
         P, Q = H + 2 * pad - R + 1, W + 2 * pad - S + 1
         self.dims = (int(N), int(K), P, Q, int(C), int(R), int(S), 1, R - 1 - pad)   # the forward problem it runs
         return self
+
+    @classmethod
+    def wgrad(cls, N, C, H, W, K, R, S, stride, pad):
+        """Plan of the weight gradient of the forward layer: run_wgrad(x [N,C,H,W], dy [N,K,P,Q], dw [K,C,R,S])."""
+        self = cls.__new__(cls)
+        self._p = ctypes.c_void_p()
+        self.in_layout = self.out_layout = PLAIN
+        dims = [int(v) for v in (N, C, H, W, K, R, S, stride, pad)]
+        rc = lib().conv_direct_create_wgrad(ctypes.byref(self._p), *dims)
+        if rc != OK:
+            self._p = ctypes.c_void_p()
+            raise ConvDirectError(rc, "conv_direct_create_wgrad")
+        self.dims = tuple(dims)
+        return self
+
+    def run_wgrad(self, x, dy, dw, stream: int | None = None) -> None:
+        import torch
+        N, C, H, W, K, R, S, st, pd = self.dims
+        P, Q = (H + 2 * pd - R) // st + 1, (W + 2 * pd - S) // st + 1
+        for t, shape, nm in ((x, (N, C, H, W), "x"), (dy, (N, K, P, Q), "dy"), (dw, (K, C, R, S), "dw")):
+            if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == shape):
+                raise ValueError(f"{nm}: need a contiguous fp32 device tensor of shape {shape}")
+        rc = lib().conv_direct_run_wgrad(self._p, x.data_ptr(), dy.data_ptr(), dw.data_ptr(), _stream(stream))
+        if rc != OK:
+            raise ConvDirectError(rc, "conv_direct_run_wgrad")
 
     def output_dims(self):
         P, Q = ctypes.c_int(), ctypes.c_int()

@@ -16,6 +16,7 @@
 #include "../../include/conv_direct.h"
 #include "layout.h"
 #include "variant.h"
+#include "wgrad.h"
 
 using convd::Shape;
 using convd::Variant;
@@ -29,6 +30,8 @@ struct conv_direct_plan {
     double mfma_efficiency;   // useful / issued multiply-accumulates
     int in_blocked, out_blocked;   // layouts of in + w, and of out (paper, Section 4)
     int pw_flat;                   // pointwise kernels: tiles run over the pixels of all images
+    const convd::WgradVariant *wv; // weight-gradient plans only (v is then NULL)
+    int wg_cgroups, wg_splits;
 };
 
 namespace {
@@ -37,6 +40,13 @@ constexpr int kNumCU = 256;                   // MI355X
 constexpr size_t kLdsPerCU = 160 * 1024;
 constexpr int64_t kMaxElems = (int64_t)1 << 31;
 thread_local int t_last_hip_error = 0;
+
+int launched(hipError_t e)
+{
+    if (e == hipSuccess) return CONV_DIRECT_OK;
+    t_last_hip_error = (int)e;
+    return CONV_DIRECT_EHIP;
+}
 
 int cdiv(int a, int b) { return (a + b - 1) / b; }
 int64_t cdiv64(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -238,7 +248,7 @@ int make_plan(conv_direct_plan **plan, const char *forced, int N, int C, int H, 
         }
     }
 
-    conv_direct_plan best;
+    conv_direct_plan best{};
     bool have = false;
     double best_cost = 0.0;
     int count = 0;
@@ -247,7 +257,7 @@ int make_plan(conv_direct_plan **plan, const char *forced, int N, int C, int H, 
         const Variant &v = *table[i];
         if (forced && std::strcmp(forced, v.name) != 0) continue;
         if (!applicable(v, s, in_blocked, out_blocked)) continue;
-        conv_direct_plan cand;
+        conv_direct_plan cand{};
         fill(&cand, s, v);
         cand.in_blocked = in_blocked;
         cand.out_blocked = out_blocked;
@@ -301,7 +311,7 @@ int conv_direct_run(const conv_direct_plan *plan, const float *in, const float *
 int conv_direct_run_fused(const conv_direct_plan *plan, const float *in, const float *w, const float *bias,
                           const float *residual, int relu, float *out, void *stream)
 {
-    if (!plan || !in || !w || !out) return CONV_DIRECT_EINVAL;
+    if (!plan || !in || !w || !out || !plan->v) return CONV_DIRECT_EINVAL;
     if (((uintptr_t)in | (uintptr_t)w | (uintptr_t)out | (uintptr_t)bias | (uintptr_t)residual) & 3u)
         return CONV_DIRECT_EALIGN;
     const bool tail = bias || residual || relu;
@@ -334,7 +344,7 @@ int conv_direct_destroy(conv_direct_plan *plan)
 
 int conv_direct_output_dims(const conv_direct_plan *plan, int *P, int *Q)
 {
-    if (!plan || !P || !Q) return CONV_DIRECT_EINVAL;
+    if (!plan || !P || !Q || !plan->v) return CONV_DIRECT_EINVAL;
     *P = plan->s.P;
     *Q = plan->s.Q;
     return CONV_DIRECT_OK;
@@ -345,6 +355,14 @@ size_t conv_direct_workspace_bytes(const conv_direct_plan *) { return 0; }
 int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
 {
     if (!plan || (!buf && n)) return CONV_DIRECT_EINVAL;
+    if (plan->wv) {
+        const Shape &s = plan->s;
+        return std::snprintf(buf, n,
+                             "variant=%s kind=wgrad N=%d C=%d H=%d W=%d K=%d R=%d S=%d stride=%d pad=%d P=%d Q=%d "
+                             "ktiles=%d cgroups=%d splits=%d grid=%u threads=%d workspace_bytes=0",
+                             plan->wv->name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, plan->ktiles,
+                             plan->wg_cgroups, plan->wg_splits, plan->grid, 64 * plan->wv->WK);
+    }
     const Variant &v = *plan->v;
     const Shape &s = plan->s;
     return std::snprintf(buf, n,
@@ -494,6 +512,71 @@ int conv_direct_tuning_clear(void)
 
 int conv_direct_tuning_size(void) { return (int)g_tuned.size(); }
 
+int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W, int K, int R, int S, int stride,
+                             int pad)
+{
+    if (!plan) return CONV_DIRECT_EINVAL;
+    *plan = nullptr;
+    Shape s;
+    const int rc = validate(N, C, H, W, K, R, S, stride, pad, &s);
+    if (rc != CONV_DIRECT_OK) return rc;
+    // offsets inside one image and one chunk's channel range are 32-bit
+    if ((int64_t)K * s.P * s.Q * 4 >= ((int64_t)1 << 31) || (int64_t)C * H * W * 4 >= ((int64_t)1 << 31))
+        return CONV_DIRECT_EUNSUPPORTED;
+    int count = 0;
+    const convd::WgradVariant *table = convd::wgrad_table(&count);
+    const convd::WgradVariant *best = nullptr;
+    double best_score = 0.0;
+    for (int i = 0; i < count; ++i) {
+        const convd::WgradVariant &v = table[i];
+        if (v.S != S || v.stride != stride) continue;
+        // used fraction of the MFMA work: pixels of a row over whole chunks, output and input channels over whole tiles
+        const double score = ((double)s.Q / ((double)cdiv(s.Q, v.PXC) * v.PXC)) *
+                             ((double)K / ((double)cdiv(K, 32 * v.WK) * 32 * v.WK)) *
+                             ((double)C / ((double)cdiv(C, 32 * v.CBW) * 32 * v.CBW)) * (v.WK == 4 ? 1.0 : 0.98);
+        if (!best || score > best_score) {
+            best = &v;
+            best_score = score;
+        }
+    }
+    if (!best) return CONV_DIRECT_EUNSUPPORTED;
+    conv_direct_plan *p = new (std::nothrow) conv_direct_plan();
+    if (!p) return CONV_DIRECT_ENOMEM;
+    p->s = s;
+    p->v = nullptr;
+    p->wv = best;
+    p->ktiles = cdiv(K, 32 * best->WK);
+    p->wg_cgroups = cdiv(C, 32 * best->CBW);
+    const int64_t tiles = (int64_t)p->ktiles * p->wg_cgroups * R;
+    int64_t splits = cdiv64(3 * kNumCU, tiles);     // about three workgroups per CU in all
+    if (splits > N) splits = N;
+    if (splits < 1) splits = 1;
+    p->wg_splits = (int)splits;
+    p->grid = (unsigned)(tiles * splits);
+    *plan = p;
+    return CONV_DIRECT_OK;
+}
+
+int conv_direct_run_wgrad(const conv_direct_plan *plan, const float *x, const float *dy, float *dw, void *stream)
+{
+    if (!plan || !plan->wv || !x || !dy || !dw) return CONV_DIRECT_EINVAL;
+    if (((uintptr_t)x | (uintptr_t)dy | (uintptr_t)dw) & 3u) return CONV_DIRECT_EALIGN;
+    const Shape &s = plan->s;
+    hipError_t e = convd::wgrad_clear(dw, (long long)s.K * s.C * s.R * s.S, (hipStream_t)stream);
+    if (e == hipSuccess) {
+        convd::WgradArgs a;
+        a.x = x;
+        a.dy = dy;
+        a.dw = dw;
+        a.s = s;
+        a.ktiles = plan->ktiles;
+        a.cgroups = plan->wg_cgroups;
+        a.splits = plan->wg_splits;
+        e = plan->wv->launch(a, plan->grid, (hipStream_t)stream);
+    }
+    return launched(e);
+}
+
 int conv_direct_create_dgrad(conv_direct_plan **plan, int N, int C, int H, int W, int K, int R, int S, int stride,
                              int pad)
 {
@@ -525,12 +608,6 @@ static int rearrange_check(const void *src, const void *dst, unsigned dst_align,
     return CONV_DIRECT_OK;
 }
 
-static int launched(hipError_t e)
-{
-    if (e == hipSuccess) return CONV_DIRECT_OK;
-    t_last_hip_error = (int)e;
-    return CONV_DIRECT_EHIP;
-}
 
 int conv_direct_pack_act(const float *plain, float *blocked, int N, int C, int H, int W, void *stream)
 {

@@ -1,0 +1,231 @@
+// Weight gradient of the convolution layer for gfx950 (MI355X), fp32 MFMA, no workspace.
+//
+//   dw[k][c][r][s] = sum over n, p, q of  dy[n][k][p][q] * x[n][c][p*stride + r - pad][q*stride + s - pad]
+//
+// (taps outside the image contribute nothing).  The paper names the backward pass "to
+// update ... the kernel" as a direction (closing section) and gives no algorithm; this is
+// the same direct scheme turned around: a dense contraction whose reduction runs over the
+// output pixels, computed from the plain tensors with the input window of a row of
+// pixels staged in LDS, so that the S taps of a filter row read it at S constant offsets
+// and no lowered copy of x exists.
+//
+// v_mfma_f32_32x32x2_f32 with rows = output channels k (A = dy), columns = input channels
+// c (B = x), the two k-lanes = two neighbouring output pixels.  One wave owns the 32 x 32
+// results of one k-block for CBW channel blocks and the S taps of ONE filter row r:
+// CBW*S accumulator blocks.  A workgroup of WK waves (32*WK output channels) walks over
+// chunks of PXC consecutive pixels of one output row: per chunk it stages dy[32*WK][PXC]
+// and x[32*CBW][(PXC-1)*ST + S] (input row p*ST + r - pad) into LDS with LDS-direct loads
+// (out-of-range pixels read zeros), double-buffered: the loads of chunk i+1 are in flight
+// while chunk i multiplies.
+//
+// The reduction over all N*P*Q pixels is split over `splits` workgroups per result tile
+// (each takes every splits-th image) so that the grid fills the chip; their partial sums
+// meet in dw itself by fp32 atomic adds (dw is cleared by a fill kernel first).  No
+// workspace, but the order of those additions, and with it the last bits, varies.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "conv_dma_kernel.h"   // CONVD_LDS, uniform_ptr, vector types
+#include "wgrad.h"
+
+namespace convd {
+
+template <int S_, int ST_, int CBW_, int WK_, int PXC_>
+struct WgGeom {
+    static constexpr int S = S_, ST = ST_, CBW = CBW_, WK = WK_, PXC = PXC_;
+    static constexpr int NT = 64 * WK;
+    static constexpr int KT = 32 * WK;                    // output channels per workgroup
+    static constexpr int CT = 32 * CBW;                   // input channels per workgroup
+    static constexpr int PA = 66;                         // LDS pitch of a dy row: 64 pixels + 2 (banks 2i + pixel)
+    static constexpr int WX = (PXC - 1) * ST + S;         // input columns a chunk needs
+    static constexpr int NLX = (WX + 63) / 64;            // 64-lane loads per input channel
+    static constexpr int PX = NLX * 64 + 2;               // LDS pitch of an input row (2 mod 64: banks 2c + column)
+    static constexpr int ABUF = KT * PA, XBUF = CT * PX;  // floats
+    static constexpr int BUF = ABUF + XBUF;
+    static constexpr size_t LDS_BYTES = sizeof(float) * 2 * (size_t)BUF;
+    static_assert(PXC == 32 || PXC == 64, "a dy row segment is staged by one 64-lane load");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
+};
+
+template <class G>
+__global__ void __launch_bounds__(G::NT, 1) conv_wgrad_kernel(const WgradArgs a)
+{
+    extern __shared__ __align__(16) float lds[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    __builtin_assume(wave >= 0 && wave < G::WK);
+    const int h = lane >> 5, j = lane & 31;
+    const int N = a.s.N, C = a.s.C, H = a.s.H, W = a.s.W, K = a.s.K, R = a.s.R, P = a.s.P, Q = a.s.Q, pad = a.s.pad;
+
+    // workgroup -> (pixel split, filter row, channel group, k tile); neighbours share dy
+    unsigned bid = blockIdx.x;
+    const int cg = bid % a.cgroups;  bid /= a.cgroups;
+    const int r = bid % R;           bid /= R;
+    const int kt = bid % a.ktiles;
+    const int ps = bid / a.ktiles;
+    const int k0 = kt * G::KT, c0 = cg * G::CT;
+
+    // a chunk: image n, output row p, first column q0
+    int n = ps, p = 0, q0 = 0;
+    auto row_ok = [&](int pp) { return (unsigned)(pp * G::ST + r - pad) < (unsigned)H; };
+    auto settle = [&]() {   // move (n, p) forward to the next output row whose input row exists
+        while (n < N && !row_ok(p)) {
+            if (++p == P) { p = 0; n += a.splits; }
+        }
+    };
+    auto advance = [&]() {
+        q0 += G::PXC;
+        if (q0 >= Q) {
+            q0 = 0;
+            if (++p == P) { p = 0; n += a.splits; }
+            settle();
+        }
+    };
+    settle();
+
+    // Stage the chunk (n, p, q0) into buffer b: dy rows wave, wave+WK, ... and input
+    // channels likewise; lanes past the row's end or outside the image load zeros; rows
+    // of output channels >= K and input channels >= C are skipped (they feed results
+    // that are never written).
+    auto stage = [&](int b, int sn, int sp, int sq0) {
+        float *abuf = lds + b * G::BUF, *xbuf = abuf + G::ABUF;
+        {
+            const unsigned voff = sq0 + lane < Q ? (unsigned)lane * 4u : 0x80000000u;
+            const float *base = a.dy + (((size_t)sn * K + k0) * P + sp) * Q + sq0;
+            __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
+            const int plane = P * Q * 4;
+#pragma unroll
+            for (int i = 0; i < G::KT / G::WK; ++i) {
+                const int row = i * G::WK + wave;
+                if (k0 + row < K)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(abuf + row * G::PA), 4, voff, row * plane, 0, 0);
+            }
+        }
+        {
+            const int ih = sp * G::ST + r - pad;           // exists (the chunk list skips rows without one)
+            const int iw0 = sq0 * G::ST - pad;
+            const float *base = a.x + (((size_t)sn * C + c0) * H + ih) * W;
+            __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
+            const int plane = H * W * 4;
+            unsigned voff[G::NLX];
+#pragma unroll
+            for (int u = 0; u < G::NLX; ++u) {
+                const int col = u * 64 + lane, iw = iw0 + col;
+                voff[u] = (col < G::WX && (unsigned)iw < (unsigned)W) ? (unsigned)iw * 4u : 0x80000000u;
+            }
+#pragma unroll
+            for (int i = 0; i < G::CT / G::WK; ++i) {
+                const int ch = i * G::WK + wave;
+                if (c0 + ch < C) {
+#pragma unroll
+                    for (int u = 0; u < G::NLX; ++u)
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(xbuf + ch * G::PX + u * 64), 4, voff[u],
+                                                                 ch * plane, 0, 0);
+                }
+            }
+        }
+    };
+
+    dma_floatx16 acc[G::CBW][G::S];
+#pragma unroll
+    for (int cb = 0; cb < G::CBW; ++cb)
+#pragma unroll
+        for (int s = 0; s < G::S; ++s)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[cb][s][v] = 0.f;
+
+    const int aoff = (wave * 32 + j) * G::PA + h;            // lane (k = j, pixel parity h)
+    const int xoff = j * G::PX + h * G::ST;                   // lane (c = j, pixel parity h)
+
+    int b = 0;
+    if (n < N) stage(0, n, p, q0);
+    while (n < N) {
+        const int cn = n, cp = p, cq0 = q0;
+        (void)cn; (void)cp; (void)cq0;
+        advance();                                            // (n, p, q0) is now the next chunk
+        __syncthreads();   // chunk b has landed (the barrier's fence waits for the LDS-direct loads) and
+                           // every wave has left the other buffer
+        if (n < N) stage(b ^ 1, n, p, q0);
+        const float *abuf = lds + b * G::BUF, *xbuf = abuf + G::ABUF;
+#pragma unroll
+        for (int t = 0; t < G::PXC / 2; ++t) {
+            const float av = abuf[aoff + 2 * t];
+#pragma unroll
+            for (int cb = 0; cb < G::CBW; ++cb)
+#pragma unroll
+                for (int s = 0; s < G::S; ++s) {
+                    const float bv = xbuf[xoff + cb * 32 * G::PX + 2 * t * G::ST + s];
+                    acc[cb][s] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[cb][s], 0, 0, 0);
+                }
+        }
+        b ^= 1;
+    }
+
+    // partial sums of this pixel split -> dw (cleared before the launch)
+    const int RS = R * G::S;
+#pragma unroll
+    for (int cb = 0; cb < G::CBW; ++cb) {
+        const int c = c0 + cb * 32 + j;
+#pragma unroll
+        for (int s = 0; s < G::S; ++s)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int k = k0 + wave * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (k < K && c < C) unsafeAtomicAdd(a.dw + ((size_t)k * C + c) * RS + r * G::S + s, acc[cb][s][v]);
+            }
+    }
+}
+
+__global__ void __launch_bounds__(256) wgrad_clear_kernel(float *dw, long long elems)
+{
+    for (long long t = blockIdx.x * 256ll + threadIdx.x; t < elems; t += gridDim.x * 256ll) dw[t] = 0.f;
+}
+
+template <class G>
+static hipError_t launch_wg(const WgradArgs &a, unsigned grid, hipStream_t stream)
+{
+    if (G::LDS_BYTES > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_wgrad_kernel<G>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((conv_wgrad_kernel<G>), dim3(grid), dim3(G::NT), G::LDS_BYTES, stream, a);
+    return hipGetLastError();
+}
+
+template <class G>
+constexpr WgradVariant make_wg(const char *name)
+{
+    return WgradVariant{name, G::S, G::ST, G::CBW, G::WK, G::PXC, &launch_wg<G>};
+}
+
+// name: w<S>s<stride>_c<channels per workgroup>_k<output channels per workgroup>_p<pixels per chunk>
+static WgradVariant g_wgrad[] = {
+    make_wg<WgGeom<3, 1, 2, 4, 64>>("w3s1_c64_k128_p64"),
+    make_wg<WgGeom<3, 1, 2, 4, 32>>("w3s1_c64_k128_p32"),
+    make_wg<WgGeom<3, 1, 2, 2, 64>>("w3s1_c64_k64_p64"),
+    make_wg<WgGeom<3, 2, 2, 4, 32>>("w3s2_c64_k128_p32"),
+    make_wg<WgGeom<5, 1, 1, 4, 32>>("w5s1_c32_k128_p32"),
+    make_wg<WgGeom<5, 1, 1, 4, 64>>("w5s1_c32_k128_p64"),
+    make_wg<WgGeom<1, 1, 4, 4, 64>>("w1s1_c128_k128_p64"),
+    make_wg<WgGeom<1, 1, 4, 2, 64>>("w1s1_c128_k64_p64"),
+    make_wg<WgGeom<7, 2, 1, 2, 64>>("w7s2_c32_k64_p64"),
+    make_wg<WgGeom<11, 4, 1, 4, 32>>("w11s4_c32_k128_p32"),
+};
+
+const WgradVariant *wgrad_table(int *count)
+{
+    *count = (int)(sizeof(g_wgrad) / sizeof(g_wgrad[0]));
+    return g_wgrad;
+}
+
+hipError_t wgrad_clear(float *dw, long long elems, hipStream_t stream)
+{
+    long long blocks = (elems + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(wgrad_clear_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, dw, elems);
+    return hipGetLastError();
+}
+
+}  // namespace convd

@@ -1,0 +1,27 @@
+// Host-side description of the weight-gradient kernels (conv_wgrad.hip), read by the C ABI.
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+#include "variant.h"
+
+namespace convd {
+
+struct WgradArgs {
+    const float *x;     // [N][C][H][W]
+    const float *dy;    // [N][K][P][Q]
+    float *dw;          // [K][C][R][S], cleared before the launch, added to atomically
+    Shape s;
+    int ktiles, cgroups, splits;   // grid = splits * ktiles * R * cgroups workgroups
+};
+
+struct WgradVariant {
+    const char *name;
+    int S, stride;      // filter width and stride the variant is compiled for (any R)
+    int CBW, WK, PXC;   // 32-channel input blocks and 32-channel output blocks per workgroup, pixels per chunk
+    hipError_t (*launch)(const WgradArgs &, unsigned grid, hipStream_t stream);
+};
+
+const WgradVariant *wgrad_table(int *count);
+hipError_t wgrad_clear(float *dw, long long elems, hipStream_t stream);
+
+}  // namespace convd

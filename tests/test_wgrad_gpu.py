@@ -1,0 +1,96 @@
+"""GPU parity of the weight gradient against the oracle's adjoint definition."""
+import numpy as np
+import pytest
+import torch
+
+from paper_1809_10170_amd import conv_direct as cd
+from paper_1809_10170_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+def _wgrad(x, dy, R, S, st, pd):
+    N, C, H, W = x.shape
+    K = dy.shape[1]
+    plan = cd.Plan.wgrad(N, C, H, W, K, R, S, st, pd)
+    assert plan.workspace_bytes() == 0
+    dw = torch.full((K, C, R, S), float("nan"), device="cuda")
+    plan.run_wgrad(torch.from_numpy(x).cuda(), torch.from_numpy(dy).cuda(), dw)
+    torch.cuda.synchronize()
+    info = plan.info()
+    plan.destroy()
+    return dw.cpu().numpy(), info
+
+
+SMALL = [
+    # N, C, H, W, K, R, S, stride, pad
+    (2, 7, 30, 61, 70, 3, 3, 1, 1),        # ragged C and K, rows longer than a chunk
+    (5, 40, 13, 13, 130, 3, 3, 1, 1),      # several images per workgroup, three channel groups
+    (2, 3, 33, 47, 35, 3, 3, 1, 0),
+    (1, 9, 40, 40, 33, 5, 5, 1, 2),
+    (2, 37, 19, 23, 65, 1, 1, 1, 0),
+    (2, 12, 57, 55, 130, 3, 3, 2, 1),
+    (2, 3, 75, 230, 64, 7, 7, 2, 3),
+    (2, 3, 99, 227, 96, 11, 11, 4, 0),
+    (1, 4, 12, 12, 8, 3, 3, 1, 2),         # pad larger than usual: whole filter rows without an input row
+    (3, 5, 20, 70, 6, 5, 3, 1, 1),         # R != S
+]
+
+
+@pytest.mark.parametrize("shape", SMALL)
+def test_small_shapes_integer_inputs_bit_exact(oracle, shape):
+    N, C, H, W, K, R, S, st, pd = shape
+    rng = np.random.default_rng(800 + sum(shape))
+    x = rng.integers(-2, 3, (N, C, H, W)).astype(np.float32)
+    P, Q = oracle.out_dim(H, R, st, pd), oracle.out_dim(W, S, st, pd)
+    dy = rng.integers(-2, 3, (N, K, P, Q)).astype(np.float32)
+    assert N * P * Q * 4 < 2 ** 24          # every partial sum exact in fp32, whatever the order
+    got, info = _wgrad(x, dy, R, S, st, pd)
+    assert not np.isnan(got).any()
+    assert np.array_equal(got.astype(np.float64), oracle.conv_wgrad(x, dy, R, S, st, pd)), info["variant"]
+
+
+@pytest.mark.parametrize("shape", SMALL[:6])
+def test_small_shapes_random_inputs(oracle, shape):
+    N, C, H, W, K, R, S, st, pd = shape
+    rng = np.random.default_rng(900 + sum(shape))
+    x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    P, Q = oracle.out_dim(H, R, st, pd), oracle.out_dim(W, S, st, pd)
+    dy = rng.uniform(-1, 1, (N, K, P, Q)).astype(np.float32)
+    got, info = _wgrad(x, dy, R, S, st, pd)
+    # the reduction runs over N*P*Q products of magnitude <= 1: the forward bar with that length
+    tol = 1e-4 * np.sqrt(N * P * Q)
+    err = np.abs(got.astype(np.float64) - oracle.conv_wgrad(x, dy, R, S, st, pd)).max()
+    assert err <= tol, (info["variant"], err)
+
+
+def test_unsupported_filter_width_is_refused():
+    with pytest.raises(cd.ConvDirectError) as e:
+        cd.Plan.wgrad(2, 8, 20, 20, 8, 3, 4, 1, 1)
+    assert e.value.code == cd.EUNSUPPORTED
+
+
+def test_wgrad_plan_is_not_a_forward_plan():
+    plan = cd.Plan.wgrad(2, 8, 20, 20, 8, 3, 3, 1, 1)
+    x = torch.zeros((2, 8, 20, 20), device="cuda")
+    w = torch.zeros((8, 8, 3, 3), device="cuda")
+    out = torch.zeros((2, 8, 20, 20), device="cuda")
+    assert cd.lib().conv_direct_run(plan._p, x.data_ptr(), w.data_ptr(), out.data_ptr(), None) == cd.EINVAL
+    plan.destroy()
+
+
+@pytest.mark.parametrize("name", ["alex_conv3_n64", "vgg_c256_56_k256_n32"])
+def test_benchmark_layers_full_size_sampled(oracle, name):
+    """Full-size layers: a sample of dw's output channels in full against the oracle (its cost is that of
+    the forward pass per output channel)."""
+    l = workloads.BY_NAME[name]
+    x, _ = workloads.make_inputs(l)
+    rng = np.random.default_rng(13)
+    dy = rng.uniform(-1, 1, (l.N, l.K, l.P, l.Q)).astype(np.float32)
+    got, info = _wgrad(x, dy, l.R, l.S, l.stride, l.pad)
+    assert not np.isnan(got).any()
+    ks = sorted({0, l.K - 1, int(rng.integers(0, l.K))})
+    want = oracle.conv_wgrad(x, np.ascontiguousarray(dy[:, ks]), l.R, l.S, l.stride, l.pad)
+    tol = 1e-4 * np.sqrt(l.N * l.P * l.Q)
+    err = np.abs(got[ks].astype(np.float64) - want).max()
+    assert err <= tol, (info["variant"], err)
