@@ -530,10 +530,11 @@ int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W
     for (int i = 0; i < count; ++i) {
         const convd::WgradVariant &v = table[i];
         if (v.S != S || v.stride != stride) continue;
+        if (v.pack && (C * S > 32 * v.pack || C > 32 * v.CBW)) continue;
         // used fraction of the MFMA work: pixels of a row over whole chunks, output and input channels over whole tiles
+        const double cols = v.pack ? (double)C * S / (32.0 * v.pack) : (double)C / ((double)cdiv(C, 32 * v.CBW) * 32 * v.CBW);
         const double score = ((double)s.Q / ((double)cdiv(s.Q, v.PXC) * v.PXC)) *
-                             ((double)K / ((double)cdiv(K, 32 * v.WK) * 32 * v.WK)) *
-                             ((double)C / ((double)cdiv(C, 32 * v.CBW) * 32 * v.CBW)) * (v.WK == 4 ? 1.0 : 0.98);
+                             ((double)K / ((double)cdiv(K, 32 * v.WK) * 32 * v.WK)) * cols * (v.WK == 4 ? 1.0 : 0.98);
         if (!best || score > best_score) {
             best = &v;
             best_score = score;
@@ -549,7 +550,7 @@ int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W
     p->wg_cgroups = cdiv(C, 32 * best->CBW);
     const int64_t tiles = (int64_t)p->ktiles * p->wg_cgroups * R;
     int64_t splits = cdiv64(3 * kNumCU, tiles);     // about three workgroups per CU in all
-    if (splits > N) splits = N;
+    if (splits > (int64_t)N * s.P) splits = (int64_t)N * s.P;   // the unit of a split is one output row of one image
     if (splits < 1) splits = 1;
     p->wg_splits = (int)splits;
     p->grid = (unsigned)(tiles * splits);

@@ -31,9 +31,15 @@
 
 namespace convd {
 
-template <int S_, int ST_, int CBW_, int WK_, int PXC_>
+//
+// PACK > 0 (layers with very few input channels, C*S <= 32*PACK): the MFMA columns are the
+// (input channel, filter column) pairs c*S + s packed into PACK blocks of 32, instead of 32
+// channels per block and one block per filter column; with C = 3 that fills 21 of 32 columns
+// (S = 7) instead of 3.
+template <int S_, int ST_, int CBW_, int WK_, int PXC_, int PACK_ = 0>
 struct WgGeom {
-    static constexpr int S = S_, ST = ST_, CBW = CBW_, WK = WK_, PXC = PXC_;
+    static constexpr int S = S_, ST = ST_, CBW = CBW_, WK = WK_, PXC = PXC_, PACK = PACK_;
+    static constexpr int NBLK = PACK ? PACK : CBW * S;   // accumulator blocks per wave
     static constexpr int NT = 64 * WK;
     static constexpr int KT = 32 * WK;                    // output channels per workgroup
     static constexpr int CT = 32 * CBW;                   // input channels per workgroup
@@ -66,19 +72,23 @@ __global__ void __launch_bounds__(G::NT, 1) conv_wgrad_kernel(const WgradArgs a)
     const int ps = bid / a.ktiles;
     const int k0 = kt * G::KT, c0 = cg * G::CT;
 
-    // a chunk: image n, output row p, first column q0
-    int n = ps, p = 0, q0 = 0;
-    auto row_ok = [&](int pp) { return (unsigned)(pp * G::ST + r - pad) < (unsigned)H; };
-    auto settle = [&]() {   // move (n, p) forward to the next output row whose input row exists
-        while (n < N && !row_ok(p)) {
-            if (++p == P) { p = 0; n += a.splits; }
+    // The reduction runs over output rows u = n*P + p of all images; this workgroup takes rows
+    // ps, ps + splits, ...  A chunk: image n, output row p, first column q0.
+    const int rows_all = N * P;
+    int u = ps, n = 0, p = 0, q0 = 0;
+    auto settle = [&]() {   // move u forward to the next row of this split whose input row exists
+        for (; u < rows_all; u += a.splits) {
+            n = u / P;
+            p = u - n * P;
+            if ((unsigned)(p * G::ST + r - pad) < (unsigned)H) break;
         }
+        if (u >= rows_all) n = N;
     };
     auto advance = [&]() {
         q0 += G::PXC;
         if (q0 >= Q) {
             q0 = 0;
-            if (++p == P) { p = 0; n += a.splits; }
+            u += a.splits;
             settle();
         }
     };
@@ -127,16 +137,25 @@ __global__ void __launch_bounds__(G::NT, 1) conv_wgrad_kernel(const WgradArgs a)
         }
     };
 
-    dma_floatx16 acc[G::CBW][G::S];
+    dma_floatx16 acc[G::NBLK];
 #pragma unroll
-    for (int cb = 0; cb < G::CBW; ++cb)
+    for (int b = 0; b < G::NBLK; ++b)
 #pragma unroll
-        for (int s = 0; s < G::S; ++s)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[cb][s][v] = 0.f;
+        for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
 
     const int aoff = (wave * 32 + j) * G::PA + h;            // lane (k = j, pixel parity h)
-    const int xoff = j * G::PX + h * G::ST;                   // lane (c = j, pixel parity h)
+    // LDS offset of the lane's B operand of block b at pixel pair 0: column j of the block is input
+    // channel cb*32 + j at filter column s (b = cb*S + s), or the packed pair (c, s) = divmod(b*32 + j, S)
+    int xoff[G::NBLK];
+#pragma unroll
+    for (int b = 0; b < G::NBLK; ++b) {
+        if (G::PACK) {
+            const int col = b * 32 + j < C * G::S ? b * 32 + j : 0;   // (columns past C*S: any valid position, discarded)
+            xoff[b] = (col / G::S) * G::PX + col % G::S + h * G::ST;
+        } else {
+            xoff[b] = ((b / G::S) * 32 + j) * G::PX + b % G::S + h * G::ST;
+        }
+    }
 
     int b = 0;
     if (n < N) stage(0, n, p, q0);
@@ -152,12 +171,10 @@ __global__ void __launch_bounds__(G::NT, 1) conv_wgrad_kernel(const WgradArgs a)
         for (int t = 0; t < G::PXC / 2; ++t) {
             const float av = abuf[aoff + 2 * t];
 #pragma unroll
-            for (int cb = 0; cb < G::CBW; ++cb)
-#pragma unroll
-                for (int s = 0; s < G::S; ++s) {
-                    const float bv = xbuf[xoff + cb * 32 * G::PX + 2 * t * G::ST + s];
-                    acc[cb][s] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[cb][s], 0, 0, 0);
-                }
+            for (int b = 0; b < G::NBLK; ++b) {
+                const float bv = xbuf[xoff[b] + 2 * t * G::ST];
+                acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[b], 0, 0, 0);
+            }
         }
         b ^= 1;
     }
@@ -165,15 +182,15 @@ __global__ void __launch_bounds__(G::NT, 1) conv_wgrad_kernel(const WgradArgs a)
     // partial sums of this pixel split -> dw (cleared before the launch)
     const int RS = R * G::S;
 #pragma unroll
-    for (int cb = 0; cb < G::CBW; ++cb) {
-        const int c = c0 + cb * 32 + j;
+    for (int b = 0; b < G::NBLK; ++b) {
+        const int col = b * 32 + j;
+        const int c = G::PACK ? col / G::S : c0 + (b / G::S) * 32 + j;
+        const int s = G::PACK ? col % G::S : b % G::S;
 #pragma unroll
-        for (int s = 0; s < G::S; ++s)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int k = k0 + wave * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-                if (k < K && c < C) unsafeAtomicAdd(a.dw + ((size_t)k * C + c) * RS + r * G::S + s, acc[cb][s][v]);
-            }
+        for (int v = 0; v < 16; ++v) {
+            const int k = k0 + wave * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+            if (k < K && c < C) unsafeAtomicAdd(a.dw + ((size_t)k * C + c) * RS + r * G::S + s, acc[b][v]);
+        }
     }
 }
 
@@ -197,7 +214,7 @@ static hipError_t launch_wg(const WgradArgs &a, unsigned grid, hipStream_t strea
 template <class G>
 constexpr WgradVariant make_wg(const char *name)
 {
-    return WgradVariant{name, G::S, G::ST, G::CBW, G::WK, G::PXC, &launch_wg<G>};
+    return WgradVariant{name, G::S, G::ST, G::CBW, G::WK, G::PXC, G::PACK, &launch_wg<G>};
 }
 
 // name: w<S>s<stride>_c<channels per workgroup>_k<output channels per workgroup>_p<pixels per chunk>
@@ -212,6 +229,10 @@ static WgradVariant g_wgrad[] = {
     make_wg<WgGeom<1, 1, 4, 2, 64>>("w1s1_c128_k64_p64"),
     make_wg<WgGeom<7, 2, 1, 2, 64>>("w7s2_c32_k64_p64"),
     make_wg<WgGeom<11, 4, 1, 4, 32>>("w11s4_c32_k128_p32"),
+    // packed (channel, filter column) columns for layers with very few input channels
+    make_wg<WgGeom<3, 1, 1, 4, 64, 1>>("w3s1_pack1_k128_p64"),
+    make_wg<WgGeom<7, 2, 1, 2, 64, 1>>("w7s2_pack1_k64_p64"),
+    make_wg<WgGeom<11, 4, 1, 4, 32, 2>>("w11s4_pack2_k128_p32"),
 };
 
 const WgradVariant *wgrad_table(int *count)
