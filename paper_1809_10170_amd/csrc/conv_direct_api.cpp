@@ -531,9 +531,11 @@ int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W
         const convd::WgradVariant &v = table[i];
         if (v.S != S || v.stride != stride) continue;
         if (v.pack && (C * S > 32 * v.pack || C > 32 * v.CBW)) continue;
+        if (v.qw && v.qw != s.Q) continue;
         // used fraction of the MFMA work: pixels of a row over whole chunks, output and input channels over whole tiles
         const double cols = v.pack ? (double)C * S / (32.0 * v.pack) : (double)C / ((double)cdiv(C, 32 * v.CBW) * 32 * v.CBW);
-        const double score = ((double)s.Q / ((double)cdiv(s.Q, v.PXC) * v.PXC)) *
+        const double pix = v.qw ? (double)s.P * s.Q / ((double)cdiv(s.P, v.PXC / v.qw) * v.PXC) : (double)s.Q / ((double)cdiv(s.Q, v.PXC) * v.PXC);
+        const double score = pix *
                              ((double)K / ((double)cdiv(K, 32 * v.WK) * 32 * v.WK)) * cols * (v.WK == 4 ? 1.0 : 0.98);
         if (!best || score > best_score) {
             best = &v;
@@ -549,9 +551,24 @@ int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W
     p->ktiles = cdiv(K, 32 * best->WK);
     p->wg_cgroups = cdiv(C, 32 * best->CBW);
     const int64_t tiles = (int64_t)p->ktiles * p->wg_cgroups * R;
-    int64_t splits = cdiv64(3 * kNumCU, tiles);     // about three workgroups per CU in all
-    if (splits > (int64_t)N * s.P) splits = (int64_t)N * s.P;   // the unit of a split is one output row of one image
-    if (splits < 1) splits = 1;
+    // How many workgroups share the pixels of one result tile: more of them fill the chip more
+    // evenly, but every one adds a full set of atomic additions into dw.  One workgroup runs per CU
+    // at a time (its LDS).  Estimated clocks: rounds * (chunks of a workgroup * MFMA clocks of a
+    // chunk + the atomics of its accumulators), the constants fitted to measurements.
+    const int nblk = best->pack ? best->pack : best->CBW * S;
+    const int npx = best->qw ? (best->PXC / best->qw) * best->qw : best->PXC;
+    const int64_t units = best->qw ? (int64_t)N * cdiv(s.P, best->PXC / best->qw) : (int64_t)N * s.P;
+    const int64_t chunks_per_unit = best->qw ? 1 : cdiv(s.Q, best->PXC);
+    const double chunk_clk = (npx / 2.0) * nblk * 64.0 / 0.65, atomics_clk = nblk * 16.0 * 2000.0;
+    int64_t splits = 1;
+    double best_clk = 0.0;
+    for (int64_t sp = 1; sp <= units && sp <= 4096; ++sp) {
+        const double clk = (double)cdiv64(tiles * sp, kNumCU) * ((double)cdiv64(units, sp) * chunks_per_unit * chunk_clk + atomics_clk);
+        if (sp == 1 || clk < best_clk) {
+            best_clk = clk;
+            splits = sp;
+        }
+    }
     p->wg_splits = (int)splits;
     p->grid = (unsigned)(tiles * splits);
     *plan = p;

@@ -36,20 +36,30 @@ namespace convd {
 // (input channel, filter column) pairs c*S + s packed into PACK blocks of 32, instead of 32
 // channels per block and one block per filter column; with C = 3 that fills 21 of 32 columns
 // (S = 7) instead of 3.
-template <int S_, int ST_, int CBW_, int WK_, int PXC_, int PACK_ = 0>
+//
+// QW > 0 (small maps whose output rows are QW pixels wide, QW fixed at compile time): a chunk
+// is RPC = PXC / QW whole output rows instead of a piece of one, so that a 13-pixel row does
+// not leave 19 of 32 pixel slots empty.  The dy pixels of such a chunk are still one
+// contiguous run; the input rows they need sit in LDS one after the other, 32 words apart.
+template <int S_, int ST_, int CBW_, int WK_, int PXC_, int PACK_ = 0, int QW_ = 0>
 struct WgGeom {
-    static constexpr int S = S_, ST = ST_, CBW = CBW_, WK = WK_, PXC = PXC_, PACK = PACK_;
+    static constexpr int S = S_, ST = ST_, CBW = CBW_, WK = WK_, PXC = PXC_, PACK = PACK_, QW = QW_;
     static constexpr int NBLK = PACK ? PACK : CBW * S;   // accumulator blocks per wave
+    static constexpr int RPC = QW ? PXC / QW : 1;        // output rows per chunk
+    static constexpr int NPX = QW ? RPC * QW : PXC;      // pixels per chunk
+    static constexpr int PXR = 32;                       // QW: LDS words from one input row to the next
     static constexpr int NT = 64 * WK;
     static constexpr int KT = 32 * WK;                    // output channels per workgroup
     static constexpr int CT = 32 * CBW;                   // input channels per workgroup
     static constexpr int PA = 66;                         // LDS pitch of a dy row: 64 pixels + 2 (banks 2i + pixel)
-    static constexpr int WX = (PXC - 1) * ST + S;         // input columns a chunk needs
-    static constexpr int NLX = (WX + 63) / 64;            // 64-lane loads per input channel
-    static constexpr int PX = NLX * 64 + 2;               // LDS pitch of an input row (2 mod 64: banks 2c + column)
+    static constexpr int WX = ((QW ? QW : PXC) - 1) * ST + S;   // input columns a chunk needs
+    static constexpr int NLX = (WX + 63) / 64;            // 64-lane loads per input channel (row chunks)
+    static constexpr int PX = QW ? RPC * PXR + 2 : NLX * 64 + 2;   // LDS pitch of an input channel (2 mod 64: banks 2c + column)
+    static_assert(!QW || (WX <= PXR && RPC >= 1 && PACK == 0), "small-map chunks: an input row fits 32 words");
     static constexpr int ABUF = KT * PA, XBUF = CT * PX;  // floats
     static constexpr int BUF = ABUF + XBUF;
-    static constexpr size_t LDS_BYTES = sizeof(float) * 2 * (size_t)BUF;
+    static constexpr size_t LDS_BYTES = sizeof(float) * (2 * (size_t)BUF + 64);   // (+ slack: an odd last pixel pair reads
+                                                                                  // a few words past the last input row)
     static_assert(PXC == 32 || PXC == 64, "a dy row segment is staged by one 64-lane load");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
 };
@@ -74,19 +84,21 @@ __global__ void __launch_bounds__(G::NT, 1) conv_wgrad_kernel(const WgradArgs a)
 
     // The reduction runs over output rows u = n*P + p of all images; this workgroup takes rows
     // ps, ps + splits, ...  A chunk: image n, output row p, first column q0.
-    const int rows_all = N * P;
+    // (small-map chunks: the unit is a group of RPC output rows, p its first row, one chunk per unit)
+    const int PG = G::QW ? (P + G::RPC - 1) / G::RPC : P;   // units per image
+    const int rows_all = N * PG;
     int u = ps, n = 0, p = 0, q0 = 0;
-    auto settle = [&]() {   // move u forward to the next row of this split whose input row exists
+    auto settle = [&]() {   // move u forward to the next unit of this split (row chunks: whose input row exists)
         for (; u < rows_all; u += a.splits) {
-            n = u / P;
-            p = u - n * P;
-            if ((unsigned)(p * G::ST + r - pad) < (unsigned)H) break;
+            n = u / PG;
+            p = (u - n * PG) * G::RPC;
+            if (G::QW || (unsigned)(p * G::ST + r - pad) < (unsigned)H) break;
         }
         if (u >= rows_all) n = N;
     };
     auto advance = [&]() {
         q0 += G::PXC;
-        if (q0 >= Q) {
+        if (G::QW || q0 >= Q) {
             q0 = 0;
             u += a.splits;
             settle();
@@ -101,7 +113,9 @@ __global__ void __launch_bounds__(G::NT, 1) conv_wgrad_kernel(const WgradArgs a)
     auto stage = [&](int b, int sn, int sp, int sq0) {
         float *abuf = lds + b * G::BUF, *xbuf = abuf + G::ABUF;
         {
-            const unsigned voff = sq0 + lane < Q ? (unsigned)lane * 4u : 0x80000000u;
+            // pixels of the chunk that exist: the rest of the row, or whole rows down to the image's last
+            const int npix = G::QW ? (P - sp < G::RPC ? P - sp : G::RPC) * G::QW : Q - sq0;
+            const unsigned voff = lane < npix ? (unsigned)lane * 4u : 0x80000000u;
             const float *base = a.dy + (((size_t)sn * K + k0) * P + sp) * Q + sq0;
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
             const int plane = P * Q * 4;
@@ -112,7 +126,31 @@ __global__ void __launch_bounds__(G::NT, 1) conv_wgrad_kernel(const WgradArgs a)
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(abuf + row * G::PA), 4, voff, row * plane, 0, 0);
             }
         }
-        {
+        if constexpr (G::QW != 0) {
+            // RPC input rows per channel, 32 words apart: only the first 32 lanes take part in a load
+            // (a disabled lane writes nothing), lanes past the row's columns or outside the image load zeros
+            const float *base = a.x + ((size_t)sn * C + c0) * H * W;
+            __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
+            const int plane = H * W * 4;
+            const int iw = lane - pad;
+            const bool colok = lane < G::WX && (unsigned)iw < (unsigned)W;
+            if (lane < G::PXR) {
+#pragma unroll
+                for (int i = 0; i < G::CT / G::WK; ++i) {
+                    const int ch = i * G::WK + wave;
+                    if (c0 + ch < C) {
+#pragma unroll
+                        for (int ri = 0; ri < G::RPC; ++ri) {
+                            const int ih = (sp + ri) * G::ST + r - pad;
+                            const bool rowok = (unsigned)ih < (unsigned)H;
+                            const unsigned voff = (colok && rowok) ? (unsigned)iw * 4u : 0x80000000u;
+                            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(xbuf + ch * G::PX + ri * G::PXR), 4, voff,
+                                                                     ch * plane + (rowok ? ih : 0) * W * 4, 0, 0);
+                        }
+                    }
+                }
+            }
+        } else {
             const int ih = sp * G::ST + r - pad;           // exists (the chunk list skips rows without one)
             const int iw0 = sq0 * G::ST - pad;
             const float *base = a.x + (((size_t)sn * C + c0) * H + ih) * W;
@@ -153,7 +191,7 @@ __global__ void __launch_bounds__(G::NT, 1) conv_wgrad_kernel(const WgradArgs a)
             const int col = b * 32 + j < C * G::S ? b * 32 + j : 0;   // (columns past C*S: any valid position, discarded)
             xoff[b] = (col / G::S) * G::PX + col % G::S + h * G::ST;
         } else {
-            xoff[b] = ((b / G::S) * 32 + j) * G::PX + b % G::S + h * G::ST;
+            xoff[b] = ((b / G::S) * 32 + j) * G::PX + b % G::S + (G::QW ? 0 : h * G::ST);
         }
     }
 
@@ -168,11 +206,20 @@ __global__ void __launch_bounds__(G::NT, 1) conv_wgrad_kernel(const WgradArgs a)
         if (n < N) stage(b ^ 1, n, p, q0);
         const float *abuf = lds + b * G::BUF, *xbuf = abuf + G::ABUF;
 #pragma unroll
-        for (int t = 0; t < G::PXC / 2; ++t) {
+        for (int t = 0; t < (G::NPX + 1) / 2; ++t) {
             const float av = abuf[aoff + 2 * t];
+            // LDS offset of the step's two pixels: along the row, or (small maps) row and column of
+            // pixels 2t and 2t+1 of the chunk, the lane's one picked by its pixel parity
+            int po = 2 * t * G::ST;
+            if (G::QW) {
+                constexpr int QWc = G::QW ? G::QW : 1;
+                const int o0 = (2 * t / QWc) * G::PXR + (2 * t % QWc) * G::ST;
+                const int o1 = ((2 * t + 1) / QWc) * G::PXR + ((2 * t + 1) % QWc) * G::ST;
+                po = h ? o1 : o0;
+            }
 #pragma unroll
             for (int b = 0; b < G::NBLK; ++b) {
-                const float bv = xbuf[xoff[b] + 2 * t * G::ST];
+                const float bv = xbuf[xoff[b] + po];
                 acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[b], 0, 0, 0);
             }
         }
@@ -214,7 +261,7 @@ static hipError_t launch_wg(const WgradArgs &a, unsigned grid, hipStream_t strea
 template <class G>
 constexpr WgradVariant make_wg(const char *name)
 {
-    return WgradVariant{name, G::S, G::ST, G::CBW, G::WK, G::PXC, G::PACK, &launch_wg<G>};
+    return WgradVariant{name, G::S, G::ST, G::CBW, G::WK, G::PXC, G::PACK, G::QW, &launch_wg<G>};
 }
 
 // name: w<S>s<stride>_c<channels per workgroup>_k<output channels per workgroup>_p<pixels per chunk>
@@ -229,6 +276,12 @@ static WgradVariant g_wgrad[] = {
     make_wg<WgGeom<1, 1, 4, 2, 64>>("w1s1_c128_k64_p64"),
     make_wg<WgGeom<7, 2, 1, 2, 64>>("w7s2_c32_k64_p64"),
     make_wg<WgGeom<11, 4, 1, 4, 32>>("w11s4_c32_k128_p32"),
+    // small maps: chunks of whole output rows of a fixed width
+    make_wg<WgGeom<3, 1, 2, 4, 64, 0, 13>>("w3s1_c64_k128_q13"),
+    make_wg<WgGeom<3, 1, 2, 4, 64, 0, 14>>("w3s1_c64_k128_q14"),
+    make_wg<WgGeom<3, 1, 2, 4, 64, 0, 28>>("w3s1_c64_k128_q28"),
+    make_wg<WgGeom<3, 1, 1, 4, 64, 0, 7>>("w3s1_c32_k128_q7"),
+    make_wg<WgGeom<5, 1, 1, 4, 64, 0, 27>>("w5s1_c32_k128_q27"),
     // packed (channel, filter column) columns for layers with very few input channels
     make_wg<WgGeom<3, 1, 1, 4, 64, 1>>("w3s1_pack1_k128_p64"),
     make_wg<WgGeom<7, 2, 1, 2, 64, 1>>("w7s2_pack1_k64_p64"),

@@ -34,6 +34,11 @@ SMALL = [
     (2, 3, 99, 227, 96, 11, 11, 4, 0),
     (1, 4, 12, 12, 8, 3, 3, 1, 2),         # pad larger than usual: whole filter rows without an input row
     (3, 5, 20, 70, 6, 5, 3, 1, 1),         # R != S
+    (3, 20, 14, 14, 40, 3, 3, 1, 1),       # small maps: chunks of whole rows (14, 28, 7, 27 wide; 13 above)
+    (2, 9, 30, 28, 33, 3, 3, 1, 1),
+    (5, 33, 7, 7, 70, 3, 3, 1, 1),
+    (2, 10, 27, 27, 40, 5, 5, 1, 2),
+    (2, 8, 22, 13, 16, 3, 3, 1, 1),        # 22 rows of 13: a ragged last group of rows
 ]
 
 
