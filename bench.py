@@ -101,9 +101,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="suite_batched")
     ap.add_argument("--variant", default=None, help="force a kernel variant (single-layer workloads)")
-    ap.add_argument("--direction", default="forward", choices=["forward", "dgrad"],
+    ap.add_argument("--direction", default="forward", choices=["forward", "dgrad", "wgrad"],
                     help="dgrad: the data gradient of the suite's stride-1 layers (filter transform + convolution "
-                         "of dy per step); plain layouts")
+                         "of dy per step); wgrad: the weight gradient of every layer (clear + reduction per step); "
+                         "plain layouts")
     ap.add_argument("--layout", default="plain", choices=["plain", "blocked"],
                     help="blocked: the paper's Section 4 layouts (activations [N][C/4][H][W][4], weights "
                          "[K/32][C/4][R][S][4][32]); first layers (C < 4) keep a plain input and write a blocked "
@@ -129,9 +130,10 @@ def main():
     layers = suite(args.workload, workloads)
     blocked = args.layout == "blocked"
     dgrad = args.direction == "dgrad"
+    wgrad = args.direction == "wgrad"
+    if (dgrad or wgrad) and blocked:
+        sys.exit("bench.py: the gradients run in plain layouts")
     if dgrad:
-        if blocked:
-            sys.exit("bench.py: --direction dgrad runs in plain layouts")
         layers = [l for l in layers if l.stride == 1 and l.R == l.S and l.pad <= l.R - 1]
     dev = torch.device("cuda:0")
 
@@ -139,6 +141,14 @@ def main():
     for l in layers:
         x, w = workloads.make_inputs(l)
         xd, wd = torch.from_numpy(x).to(dev), torch.from_numpy(w).to(dev)
+        if wgrad:
+            g = torch.Generator(device="cpu").manual_seed(4242 + l.K)
+            dy = (torch.rand((l.N, l.K, l.P, l.Q), generator=g) * 2 - 1).to(dev)
+            plan = cd.Plan.wgrad(*l.dims())
+            dw = torch.empty((l.K, l.C, l.R, l.S), device=dev)
+            items.append((l, plan, xd, dy, dw, "wgrad"))
+            del x, w
+            continue
         if dgrad:
             # dy stands in for the next layer's gradient: U[-1,1], seeded
             g = torch.Generator(device="cpu").manual_seed(4242 + l.K)
@@ -170,6 +180,8 @@ def main():
 
     def launch(item):
         l, plan, xd, wd, out, w_plain = item
+        if isinstance(w_plain, str):   # wgrad: (x, dy) -> dw
+            return plan.run_wgrad(xd, wd, out, stream.cuda_stream)
         if w_plain is not None:   # dgrad: the filter transform belongs to the step (weights change every update)
             cd.dgrad_filter(w_plain, wd, stream.cuda_stream)
         plan.run(xd, wd, out, stream.cuda_stream)
@@ -211,7 +223,7 @@ def main():
     value = total_flops / (ms_per_step * 1e-3) / 1e12
 
     dom = max(per_layer, key=lambda r: r["ms_avg"])
-    kern = "conv_rows_kernel" if dom["variant"].startswith("r") else "conv_dma_kernel"
+    kern = {"r": "conv_rows_kernel", "p": "conv_pw_kernel", "w": "conv_wgrad_kernel"}.get(dom["variant"][0], "conv_dma_kernel")
     roofline = {"bound": "mfma", "kernel": f"{kern}<{dom['variant']}>", "layer": dom["layer"],
                 "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, 4),
@@ -221,6 +233,14 @@ def main():
     if args.check:
         import oracle
         for l, plan, xd, wd, out, w_plain in items:
+            if isinstance(w_plain, str):
+                # three output channels of dw in full (each costs the oracle a forward pass of one channel)
+                import numpy as np
+                ks = sorted({0, l.K - 1, l.K // 2})
+                want = oracle.conv_wgrad(xd.cpu().numpy(), np.ascontiguousarray(wd.cpu().numpy()[:, ks]), l.R, l.S, l.stride, l.pad)
+                err = float(abs(out.cpu().numpy()[ks] - want).max())
+                assert err <= 1e-4 * (l.N * l.P * l.Q) ** 0.5, (l.name, err)
+                continue
             if w_plain is not None:
                 # sampled dx elements through the flipped-filter identity (pinned on the CPU against the adjoint definition)
                 import numpy as np
@@ -243,7 +263,8 @@ def main():
             assert err <= oracle.tolerance(l.C, l.R, l.S), (l.name, err)
 
     rec = {
-        "metric": ("conv dgrad TFLOP/s (2*N*K*C*R*S*P*Q/t), fp32, zero workspace" if dgrad else
+        "metric": ("conv wgrad TFLOP/s (2*N*K*C*R*S*P*Q/t), fp32, zero workspace" if wgrad else
+                   "conv dgrad TFLOP/s (2*N*K*C*R*S*P*Q/t), fp32, zero workspace" if dgrad else
                    "conv fwd TFLOP/s (2*N*K*C*R*S*P*Q/t), fp32, zero workspace"),
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,

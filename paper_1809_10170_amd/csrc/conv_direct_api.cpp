@@ -535,7 +535,8 @@ int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W
         // used fraction of the MFMA work: pixels of a row over whole chunks, output and input channels over whole tiles
         const double cols = v.pack ? (double)C * S / (32.0 * v.pack) : (double)C / ((double)cdiv(C, 32 * v.CBW) * 32 * v.CBW);
         const double pix = v.qw ? (double)s.P * s.Q / ((double)cdiv(s.P, v.PXC / v.qw) * v.PXC) : (double)s.Q / ((double)cdiv(s.Q, v.PXC) * v.PXC);
-        const double score = pix *
+        // (two workgroups per CU keep the matrix pipes busier than one: a wave's waits are covered)
+        const double score = pix * (v.per_cu == 2 ? 1.12 : 1.0) *
                              ((double)K / ((double)cdiv(K, 32 * v.WK) * 32 * v.WK)) * cols * (v.WK == 4 ? 1.0 : 0.98);
         if (!best || score > best_score) {
             best = &v;
@@ -552,18 +553,20 @@ int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W
     p->wg_cgroups = cdiv(C, 32 * best->CBW);
     const int64_t tiles = (int64_t)p->ktiles * p->wg_cgroups * R;
     // How many workgroups share the pixels of one result tile: more of them fill the chip more
-    // evenly, but every one adds a full set of atomic additions into dw.  One workgroup runs per CU
-    // at a time (its LDS).  Estimated clocks: rounds * (chunks of a workgroup * MFMA clocks of a
+    // evenly, but every one adds a full set of atomic additions into dw.  One or two workgroups run
+    // per CU at a time (their LDS).  Estimated clocks: rounds * (chunks of a workgroup * MFMA clocks of a
     // chunk + the atomics of its accumulators), the constants fitted to measurements.
     const int nblk = best->pack ? best->pack : best->CBW * S;
     const int npx = best->qw ? (best->PXC / best->qw) * best->qw : best->PXC;
     const int64_t units = best->qw ? (int64_t)N * cdiv(s.P, best->PXC / best->qw) : (int64_t)N * s.P;
     const int64_t chunks_per_unit = best->qw ? 1 : cdiv(s.Q, best->PXC);
-    const double chunk_clk = (npx / 2.0) * nblk * 64.0 / 0.65, atomics_clk = nblk * 16.0 * 2000.0;
+    const double chunk_clk = (npx / 2.0) * nblk * 64.0 / 0.65 * (best->per_cu == 2 ? 1.6 : 1.0);   // (two share a SIMD)
+    const double atomics_clk = nblk * 16.0 * 2000.0;
+    const int64_t slots = (int64_t)kNumCU * best->per_cu;
     int64_t splits = 1;
     double best_clk = 0.0;
     for (int64_t sp = 1; sp <= units && sp <= 4096; ++sp) {
-        const double clk = (double)cdiv64(tiles * sp, kNumCU) * ((double)cdiv64(units, sp) * chunks_per_unit * chunk_clk + atomics_clk);
+        const double clk = (double)cdiv64(tiles * sp, slots) * ((double)cdiv64(units, sp) * chunks_per_unit * chunk_clk + atomics_clk);
         if (sp == 1 || clk < best_clk) {
             best_clk = clk;
             splits = sp;

@@ -51,7 +51,10 @@ struct WgGeom {
     static constexpr int NT = 64 * WK;
     static constexpr int KT = 32 * WK;                    // output channels per workgroup
     static constexpr int CT = 32 * CBW;                   // input channels per workgroup
-    static constexpr int PA = 66;                         // LDS pitch of a dy row: 64 pixels + 2 (banks 2i + pixel)
+    // LDS pitch of a dy row: the chunk's pixels + 2 (banks 2i + pixel, all different).  A 32-pixel
+    // chunk is staged by the first 32 lanes only, so that two workgroups fit the LDS of a CU.
+    static constexpr int PA = (PXC == 32 && QW_ == 0) ? 34 : 66;
+    static constexpr bool HALF_A = PA == 34;
     static constexpr int WX = ((QW ? QW : PXC) - 1) * ST + S;   // input columns a chunk needs
     static constexpr int NLX = (WX + 63) / 64;            // 64-lane loads per input channel (row chunks)
     static constexpr int PX = QW ? RPC * PXR + 2 : NLX * 64 + 2;   // LDS pitch of an input channel (2 mod 64: banks 2c + column)
@@ -65,7 +68,7 @@ struct WgGeom {
 };
 
 template <class G>
-__global__ void __launch_bounds__(G::NT, 1) conv_wgrad_kernel(const WgradArgs a)
+__global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv_wgrad_kernel(const WgradArgs a)
 {
     extern __shared__ __align__(16) float lds[];
     const int lane = threadIdx.x & 63;
@@ -119,11 +122,13 @@ __global__ void __launch_bounds__(G::NT, 1) conv_wgrad_kernel(const WgradArgs a)
             const float *base = a.dy + (((size_t)sn * K + k0) * P + sp) * Q + sq0;
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
             const int plane = P * Q * 4;
+            if (!G::HALF_A || lane < 32) {   // (a disabled lane writes nothing: rows 34 words apart do not overlap)
 #pragma unroll
-            for (int i = 0; i < G::KT / G::WK; ++i) {
-                const int row = i * G::WK + wave;
-                if (k0 + row < K)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(abuf + row * G::PA), 4, voff, row * plane, 0, 0);
+                for (int i = 0; i < G::KT / G::WK; ++i) {
+                    const int row = i * G::WK + wave;
+                    if (k0 + row < K)
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(abuf + row * G::PA), 4, voff, row * plane, 0, 0);
+                }
             }
         }
         if constexpr (G::QW != 0) {
@@ -261,7 +266,7 @@ static hipError_t launch_wg(const WgradArgs &a, unsigned grid, hipStream_t strea
 template <class G>
 constexpr WgradVariant make_wg(const char *name)
 {
-    return WgradVariant{name, G::S, G::ST, G::CBW, G::WK, G::PXC, G::PACK, G::QW, &launch_wg<G>};
+    return WgradVariant{name, G::S, G::ST, G::CBW, G::WK, G::PXC, G::PACK, G::QW, G::LDS_BYTES <= 80 * 1024 ? 2 : 1, &launch_wg<G>};
 }
 
 // name: w<S>s<stride>_c<channels per workgroup>_k<output channels per workgroup>_p<pixels per chunk>
@@ -269,6 +274,7 @@ static WgradVariant g_wgrad[] = {
     make_wg<WgGeom<3, 1, 2, 4, 64>>("w3s1_c64_k128_p64"),
     make_wg<WgGeom<3, 1, 2, 4, 32>>("w3s1_c64_k128_p32"),
     make_wg<WgGeom<3, 1, 2, 2, 64>>("w3s1_c64_k64_p64"),
+    make_wg<WgGeom<3, 1, 2, 2, 32>>("w3s1_c64_k64_p32"),
     make_wg<WgGeom<3, 2, 2, 4, 32>>("w3s2_c64_k128_p32"),
     make_wg<WgGeom<5, 1, 1, 4, 32>>("w5s1_c32_k128_p32"),
     make_wg<WgGeom<5, 1, 1, 4, 64>>("w5s1_c32_k128_p64"),

@@ -20,6 +20,7 @@ struct WgradVariant {
     int CBW, WK, PXC;   // 32-channel input blocks and 32-channel output blocks per workgroup, pixels per chunk
     int pack;           // > 0: columns are (channel, filter column) pairs in `pack` blocks of 32; needs C*S <= 32*pack
     int qw;             // > 0: chunks of PXC / qw whole output rows; needs Q == qw
+    int per_cu;         // workgroups whose LDS fits one CU together (1 or 2)
     hipError_t (*launch)(const WgradArgs &, unsigned grid, hipStream_t stream);
 };
 
