@@ -78,7 +78,13 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
     const int N = a.s.N, C = a.s.C, H = a.s.H, W = a.s.W, K = a.s.K, R = a.s.R, P = a.s.P, Q = a.s.Q, pad = a.s.pad;
 
     // workgroup -> (pixel split, filter row, channel group, k tile); neighbours share dy
+    // (consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2: regroup
+    // them so that the workgroups that read the same dy rows run on one XCD)
     unsigned bid = blockIdx.x;
+    {
+        const unsigned g8 = gridDim.x & ~7u;
+        if (bid < g8) bid = (bid & 7u) * (g8 >> 3) + (bid >> 3);
+    }
     const int cg = bid % a.cgroups;  bid /= a.cgroups;
     const int r = bid % R;           bid /= R;
     const int kt = bid % a.ktiles;
