@@ -216,22 +216,46 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
                            // every wave has left the other buffer
         if (n < N) stage(b ^ 1, n, p, q0);
         const float *abuf = lds + b * G::BUF, *xbuf = abuf + G::ABUF;
-#pragma unroll
-        for (int t = 0; t < (G::NPX + 1) / 2; ++t) {
-            const float av = abuf[aoff + 2 * t];
+        // operands of step t+1 are fetched from LDS while step t multiplies
+        constexpr int NST = (G::NPX + 1) / 2;
+        auto pix_off = [&](int t) {
             // LDS offset of the step's two pixels: along the row, or (small maps) row and column of
             // pixels 2t and 2t+1 of the chunk, the lane's one picked by its pixel parity
-            int po = 2 * t * G::ST;
             if (G::QW) {
                 constexpr int QWc = G::QW ? G::QW : 1;
                 const int o0 = (2 * t / QWc) * G::PXR + (2 * t % QWc) * G::ST;
                 const int o1 = ((2 * t + 1) / QWc) * G::PXR + ((2 * t + 1) % QWc) * G::ST;
-                po = h ? o1 : o0;
+                return h ? o1 : o0;
+            }
+            return 2 * t * G::ST;
+        };
+        float an = abuf[aoff], bn[G::NBLK];
+        {
+            const int po = pix_off(0);
+#pragma unroll
+            for (int bb = 0; bb < G::NBLK; ++bb) bn[bb] = xbuf[xoff[bb] + po];
+        }
+#pragma unroll
+        for (int t = 0; t < NST; ++t) {
+            const float av = an;
+            float bv[G::NBLK];
+#pragma unroll
+            for (int bb = 0; bb < G::NBLK; ++bb) bv[bb] = bn[bb];
+            if (t + 1 < NST) {
+                an = abuf[aoff + 2 * (t + 1)];
+                const int po = pix_off(t + 1);
+#pragma unroll
+                for (int bb = 0; bb < G::NBLK; ++bb) bn[bb] = xbuf[xoff[bb] + po];
             }
 #pragma unroll
-            for (int b = 0; b < G::NBLK; ++b) {
-                const float bv = xbuf[xoff[b] + po];
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[b], 0, 0, 0);
+            for (int bb = 0; bb < G::NBLK; ++bb)
+                acc[bb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[bb], acc[bb], 0, 0, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);       // the next step's LDS reads between them: dy and one x
+#pragma unroll
+            for (int bb = 1; bb < G::NBLK; ++bb) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
         }
         b ^= 1;
