@@ -118,7 +118,7 @@ def main():
         return copy_probe()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only; --gpus must be 1 "
-                 "(the path shards over batch with no exchange step, see DESIGN.md)")
+                 "(the forward pass shards over the batch with no exchange step; nothing here uses a second GPU)")
 
     import torch
     from paper_1809_10170_amd import conv_direct as cd
