@@ -205,3 +205,45 @@ def test_tuning_table_round_trip_and_override(tmp_path):
         cd.tuning_load(str(tmp_path / "missing.txt"))
     cd.tuning_clear()
     assert cd.tuning_size() == 0 and cd.Plan(*shape).info()["variant"] == default
+
+
+def test_layout_gradient_and_tail_entry_points_check_arguments_before_any_launch():
+    L = cd.lib()
+    import ctypes
+    p = ctypes.c_void_p()
+    dims = (2, 8, 20, 20, 8, 3, 3, 1, 1)
+    # layouts
+    assert L.conv_direct_create_layout(ctypes.byref(p), *dims, 2, 0) == cd.EINVAL and not p
+    assert L.conv_direct_create_layout(ctypes.byref(p), *dims, 0, -1) == cd.EINVAL and not p
+    assert L.conv_direct_create_ex(ctypes.byref(p), b"no_such_variant", *dims, 1, 1) == cd.EUNSUPPORTED and not p
+    assert cd.blocked_act_elems(2, 5, 3, 4) == 2 * 8 * 3 * 4 and cd.blocked_act_elems(0, 5, 3, 4) == 0
+    assert cd.blocked_w_elems(33, 5, 3, 3) == 64 * 8 * 9 and cd.blocked_w_elems(33, 5, 3, -1) == 0
+    for fn in (L.conv_direct_pack_act, L.conv_direct_unpack_act, L.conv_direct_pack_w, L.conv_direct_dgrad_filter):
+        assert fn(None, 4096, 2, 3, 4, 5, None) == cd.EINVAL
+        assert fn(4096, 8192, 2, 0, 4, 5, None) == cd.EINVAL
+        assert fn(4098, 8192, 2, 3, 4, 5, None) == cd.EALIGN
+    assert L.conv_direct_pack_act(4096, 8196, 2, 3, 4, 5, None) == cd.EALIGN      # blocked destination: 16 bytes
+    # gradients
+    assert L.conv_direct_create_dgrad(ctypes.byref(p), 2, 8, 20, 20, 8, 3, 3, 2, 1) == cd.EUNSUPPORTED and not p
+    assert L.conv_direct_create_dgrad(ctypes.byref(p), 2, 8, 20, 20, 8, 3, 3, 0, 1) == cd.EINVAL
+    assert L.conv_direct_create_wgrad(ctypes.byref(p), 2, 8, 20, 20, 8, 3, 4, 1, 1) == cd.EUNSUPPORTED and not p
+    assert L.conv_direct_create_wgrad(ctypes.byref(p), 2, 8, 20, 20, 0, 3, 3, 1, 1) == cd.EINVAL
+    wg = cd.Plan.wgrad(*dims)
+    info = wg.info()
+    assert info["kind"] == "wgrad" and info["workspace_bytes"] == 0 and info["grid"] == info["ktiles"] * info["cgroups"] * 3 * info["splits"]
+    P, Q = ctypes.c_int(), ctypes.c_int()
+    assert L.conv_direct_output_dims(wg._p, ctypes.byref(P), ctypes.byref(Q)) == cd.EINVAL      # not a forward plan
+    assert L.conv_direct_run(wg._p, 4096, 8192, 12288, None) == cd.EINVAL
+    assert L.conv_direct_run_wgrad(wg._p, 4096, 8192, 12290, None) == cd.EALIGN
+    assert L.conv_direct_run_wgrad(wg._p, None, 8192, 12288, None) == cd.EINVAL
+    fwd = cd.Plan(*dims)
+    assert L.conv_direct_run_wgrad(fwd._p, 4096, 8192, 12288, None) == cd.EINVAL                 # not a wgrad plan
+    assert L.conv_direct_run_fused(fwd._p, 4096, 8192, 4098, None, 0, 12288, None) == cd.EALIGN  # misaligned bias
+    dg = cd.Plan.dgrad(*dims)
+    assert dg.output_dims() == (20, 20) and dg.info()["C"] == 8 and dg.info()["pad"] == 1
+    for pl in (wg, fwd, dg):
+        pl.destroy()
+    # measured choice: arguments
+    assert L.conv_direct_create_tuned(ctypes.byref(p), *dims, 0, 0, None, 8192, 12288, None, 3) == cd.EINVAL
+    assert L.conv_direct_create_tuned(ctypes.byref(p), *dims, 0, 0, 4096, 8192, 12288, None, 0) == cd.EINVAL
+    assert L.conv_direct_create_tuned(ctypes.byref(p), *dims, 0, 3, 4096, 8192, 12288, None, 3) == cd.EINVAL
