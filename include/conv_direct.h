@@ -185,7 +185,8 @@ int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, 
  * build); conv_direct_output_dims of the plan gives (H, W).
  *
  * Weight gradient (the backward pass "to update ... the kernel"), plain layouts, any
- * stride, filter widths S in {1, 3, 5, 7, 11} with the strides the forward variants serve:
+ * filter, strides up to 4 (compiled variants for the filter widths and strides of the forward
+ * variants, a slower run-time-shape variant for the rest):
  *
  *   dw[k][c][r][s] = sum over n, p, q of dy[n][k][p][q] * x[n][c][p*stride + r - pad][q*stride + s - pad]
  *
@@ -196,7 +197,7 @@ int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, 
  * partial sums into dw with fp32 atomics): no workspace, but the order of the additions
  * is not fixed, so the last bits of dw can differ between runs.  A wgrad plan can only be
  * passed to conv_direct_run_wgrad, _plan_info, _workspace_bytes and _destroy;
- * CONV_DIRECT_EUNSUPPORTED if no compiled variant serves the filter width and stride.
+ * CONV_DIRECT_EUNSUPPORTED for strides above 4.
  * ------------------------------------------------------------------------ */
 int conv_direct_create_dgrad(conv_direct_plan **plan,
                              int N, int C, int H, int W, int K, int R, int S, int stride, int pad);

@@ -41,10 +41,16 @@ namespace convd {
 // is RPC = PXC / QW whole output rows instead of a piece of one, so that a 13-pixel row does
 // not leave 19 of 32 pixel slots empty.  The dy pixels of such a chunk are still one
 // contiguous run; the input rows they need sit in LDS one after the other, 32 words apart.
+//
+// S = 0: the fallback for any filter width and any stride up to ST (which then only sizes the LDS):
+// the filter column becomes one more grid dimension, a wave owns CBW blocks of one tap, and the
+// stride is read at run time.
 template <int S_, int ST_, int CBW_, int WK_, int PXC_, int PACK_ = 0, int QW_ = 0>
 struct WgGeom {
     static constexpr int S = S_, ST = ST_, CBW = CBW_, WK = WK_, PXC = PXC_, PACK = PACK_, QW = QW_;
-    static constexpr int NBLK = PACK ? PACK : CBW * S;   // accumulator blocks per wave
+    static constexpr bool RT = S_ == 0;
+    static constexpr int SB = RT ? 1 : S_;               // filter columns a wave owns
+    static constexpr int NBLK = PACK ? PACK : CBW * SB;  // accumulator blocks per wave
     static constexpr int RPC = QW ? PXC / QW : 1;        // output rows per chunk
     static constexpr int NPX = QW ? RPC * QW : PXC;      // pixels per chunk
     static constexpr int PXR = 32;                       // QW: LDS words from one input row to the next
@@ -55,7 +61,8 @@ struct WgGeom {
     // chunk is staged by the first 32 lanes only, so that two workgroups fit the LDS of a CU.
     static constexpr int PA = (PXC == 32 && QW_ == 0) ? 34 : 66;
     static constexpr bool HALF_A = PA == 34;
-    static constexpr int WX = ((QW ? QW : PXC) - 1) * ST + S;   // input columns a chunk needs
+    static constexpr int WX = ((QW ? QW : PXC) - 1) * ST + SB;  // input columns a chunk needs (fallback: at most)
+    static_assert(!RT || (PACK == 0 && QW == 0), "the fallback uses plain row chunks");
     static constexpr int NLX = (WX + 63) / 64;            // 64-lane loads per input channel (row chunks)
     static constexpr int PX = QW ? RPC * PXR + 2 : NLX * 64 + 2;   // LDS pitch of an input channel (2 mod 64: banks 2c + column)
     static_assert(!QW || (WX <= PXR && RPC >= 1 && PACK == 0), "small-map chunks: an input row fits 32 words");
@@ -76,6 +83,7 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
     __builtin_assume(wave >= 0 && wave < G::WK);
     const int h = lane >> 5, j = lane & 31;
     const int N = a.s.N, C = a.s.C, H = a.s.H, W = a.s.W, K = a.s.K, R = a.s.R, P = a.s.P, Q = a.s.Q, pad = a.s.pad;
+    const int st = G::RT ? a.s.stride : G::ST;       // (a compile-time constant except in the fallback)
 
     // workgroup -> (pixel split, filter row, channel group, k tile); neighbours share dy
     // (consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2: regroup
@@ -85,6 +93,8 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
         const unsigned g8 = gridDim.x & ~7u;
         if (bid < g8) bid = (bid & 7u) * (g8 >> 3) + (bid >> 3);
     }
+    int s0 = 0;                                      // fallback: the filter column of this workgroup
+    if (G::RT) { s0 = bid % a.s.S;  bid /= a.s.S; }
     const int cg = bid % a.cgroups;  bid /= a.cgroups;
     const int r = bid % R;           bid /= R;
     const int kt = bid % a.ktiles;
@@ -101,7 +111,7 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
         for (; u < rows_all; u += a.splits) {
             n = u / PG;
             p = (u - n * PG) * G::RPC;
-            if (G::QW || (unsigned)(p * G::ST + r - pad) < (unsigned)H) break;
+            if (G::QW || (unsigned)(p * st + r - pad) < (unsigned)H) break;
         }
         if (u >= rows_all) n = N;
     };
@@ -162,8 +172,9 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
                 }
             }
         } else {
-            const int ih = sp * G::ST + r - pad;           // exists (the chunk list skips rows without one)
-            const int iw0 = sq0 * G::ST - pad;
+            const int ih = sp * st + r - pad;              // exists (the chunk list skips rows without one)
+            const int iw0 = sq0 * st - pad + s0;
+            const int wx = (G::PXC - 1) * st + G::SB;      // columns the chunk needs
             const float *base = a.x + (((size_t)sn * C + c0) * H + ih) * W;
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
             const int plane = H * W * 4;
@@ -171,7 +182,7 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
 #pragma unroll
             for (int u = 0; u < G::NLX; ++u) {
                 const int col = u * 64 + lane, iw = iw0 + col;
-                voff[u] = (col < G::WX && (unsigned)iw < (unsigned)W) ? (unsigned)iw * 4u : 0x80000000u;
+                voff[u] = (col < wx && (unsigned)iw < (unsigned)W) ? (unsigned)iw * 4u : 0x80000000u;
             }
 #pragma unroll
             for (int i = 0; i < G::CT / G::WK; ++i) {
@@ -202,7 +213,7 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
             const int col = b * 32 + j < C * G::S ? b * 32 + j : 0;   // (columns past C*S: any valid position, discarded)
             xoff[b] = (col / G::S) * G::PX + col % G::S + h * G::ST;
         } else {
-            xoff[b] = ((b / G::S) * 32 + j) * G::PX + b % G::S + (G::QW ? 0 : h * G::ST);
+            xoff[b] = ((b / G::SB) * 32 + j) * G::PX + b % G::SB + (G::QW ? 0 : h * st);
         }
     }
 
@@ -227,7 +238,7 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
                 const int o1 = ((2 * t + 1) / QWc) * G::PXR + ((2 * t + 1) % QWc) * G::ST;
                 return h ? o1 : o0;
             }
-            return 2 * t * G::ST;
+            return 2 * t * st;
         };
         float an = abuf[aoff], bn[G::NBLK];
         {
@@ -262,16 +273,17 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
     }
 
     // partial sums of this pixel split -> dw (cleared before the launch)
-    const int RS = R * G::S;
+    const int SF = G::RT ? a.s.S : G::S;             // filter width
+    const int RS = R * SF;
 #pragma unroll
     for (int b = 0; b < G::NBLK; ++b) {
         const int col = b * 32 + j;
-        const int c = G::PACK ? col / G::S : c0 + (b / G::S) * 32 + j;
-        const int s = G::PACK ? col % G::S : b % G::S;
+        const int c = G::PACK ? col / G::SB : c0 + (b / G::SB) * 32 + j;
+        const int s = G::PACK ? col % G::SB : G::RT ? s0 : b % G::SB;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int k = k0 + wave * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-            if (k < K && c < C) unsafeAtomicAdd(a.dw + ((size_t)k * C + c) * RS + r * G::S + s, acc[b][v]);
+            if (k < K && c < C) unsafeAtomicAdd(a.dw + ((size_t)k * C + c) * RS + r * SF + s, acc[b][v]);
         }
     }
 }
@@ -312,6 +324,8 @@ static WgradVariant g_wgrad[] = {
     make_wg<WgGeom<1, 1, 4, 2, 64>>("w1s1_c128_k64_p64"),
     make_wg<WgGeom<7, 2, 1, 2, 64>>("w7s2_c32_k64_p64"),
     make_wg<WgGeom<11, 4, 1, 4, 32>>("w11s4_c32_k128_p32"),
+    // any filter width, any stride up to 4
+    make_wg<WgGeom<0, 4, 2, 4, 32>>("w_any_c64_k128_p32"),
     // small maps: chunks of whole output rows of a fixed width
     make_wg<WgGeom<3, 1, 2, 4, 64, 0, 13>>("w3s1_c64_k128_q13"),
     make_wg<WgGeom<3, 1, 2, 4, 64, 0, 14>>("w3s1_c64_k128_q14"),

@@ -226,7 +226,7 @@ def test_layout_gradient_and_tail_entry_points_check_arguments_before_any_launch
     # gradients
     assert L.conv_direct_create_dgrad(ctypes.byref(p), 2, 8, 20, 20, 8, 3, 3, 2, 1) == cd.EUNSUPPORTED and not p
     assert L.conv_direct_create_dgrad(ctypes.byref(p), 2, 8, 20, 20, 8, 3, 3, 0, 1) == cd.EINVAL
-    assert L.conv_direct_create_wgrad(ctypes.byref(p), 2, 8, 20, 20, 8, 3, 4, 1, 1) == cd.EUNSUPPORTED and not p
+    assert L.conv_direct_create_wgrad(ctypes.byref(p), 2, 8, 40, 40, 8, 3, 4, 5, 1) == cd.EUNSUPPORTED and not p
     assert L.conv_direct_create_wgrad(ctypes.byref(p), 2, 8, 20, 20, 0, 3, 3, 1, 1) == cd.EINVAL
     wg = cd.Plan.wgrad(*dims)
     info = wg.info()

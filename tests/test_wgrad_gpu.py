@@ -69,10 +69,22 @@ def test_small_shapes_random_inputs(oracle, shape):
     assert err <= tol, (info["variant"], err)
 
 
-def test_unsupported_filter_width_is_refused():
+def test_unsupported_stride_is_refused():
     with pytest.raises(cd.ConvDirectError) as e:
-        cd.Plan.wgrad(2, 8, 20, 20, 8, 3, 4, 1, 1)
+        cd.Plan.wgrad(2, 8, 40, 40, 8, 3, 3, 5, 1)
     assert e.value.code == cd.EUNSUPPORTED
+
+
+@pytest.mark.parametrize("shape", [(2, 9, 21, 30, 40, 3, 4, 1, 1), (2, 70, 17, 19, 33, 2, 2, 2, 0), (1, 5, 30, 41, 8, 4, 6, 3, 2),
+                                   (2, 6, 33, 37, 9, 3, 3, 4, 1)])
+def test_fallback_for_other_filter_widths_and_strides(oracle, shape):
+    N, C, H, W, K, R, S, st, pd = shape
+    rng = np.random.default_rng(950 + sum(shape))
+    x = rng.integers(-2, 3, (N, C, H, W)).astype(np.float32)
+    dy = rng.integers(-2, 3, (N, K, oracle.out_dim(H, R, st, pd), oracle.out_dim(W, S, st, pd))).astype(np.float32)
+    got, info = _wgrad(x, dy, R, S, st, pd)
+    assert info["variant"].startswith("w_any")
+    assert np.array_equal(got.astype(np.float64), oracle.conv_wgrad(x, dy, R, S, st, pd))
 
 
 def test_wgrad_plan_is_not_a_forward_plan():
