@@ -73,8 +73,6 @@ int conv_direct_run(const conv_direct_plan *plan,
  *   residual : device pointer, a tensor of out's layout and size (it may not overlap out), or NULL
  *   relu     : nonzero applies max(., 0) last
  * All NULL / 0 is conv_direct_run.  Still one kernel launch and no workspace.
- * CONV_DIRECT_EUNSUPPORTED if the plan runs on the runtime-shape fallback kernel (shapes no
- * compiled variant serves), which has no fused tail.
  */
 int conv_direct_run_fused(const conv_direct_plan *plan,
                           const float *in, const float *w, const float *bias, const float *residual,
@@ -139,8 +137,7 @@ const char *conv_direct_variant_name(int index);
  * `in` and `w` together (blocked input goes with blocked weights; a plain input, as the
  * paper keeps for the first layer of a network, goes with plain KCRS weights); out_layout
  * covers `out`.  (PLAIN, PLAIN) is conv_direct_create.  conv_direct_run then expects
- * buffers of those layouts.  CONV_DIRECT_EINVAL for an unknown layout value,
- * CONV_DIRECT_EUNSUPPORTED if no compiled variant serves the shape in these layouts.
+ * buffers of those layouts.  CONV_DIRECT_EINVAL for an unknown layout value.
  */
 int conv_direct_create_layout(conv_direct_plan **plan,
                               int N, int C, int H, int W, int K, int R, int S, int stride, int pad,

@@ -83,8 +83,7 @@ bool pointwise_flat(const Variant &v, const Shape &s)
 // Can variant v run shape s at all?
 bool applicable(const Variant &v, const Shape &s, int in_blocked, int out_blocked)
 {
-    if ((v.in_blocked != 0) != (in_blocked != 0)) return false;
-    if (v.R == 0 && (in_blocked || out_blocked)) return false;   // the runtime-shape fallback knows plain tensors only
+    if (v.R != 0 && (v.in_blocked != 0) != (in_blocked != 0)) return false;   // (the runtime-shape fallback takes either)
     if (v.R != 0 && (v.R != s.R || v.S != s.S || v.stride != s.stride)) return false;
     if (v.pair == convd::PAIR_R && s.C > v.CB) return false;   // stages all channels at once
     if (v.img != 0 && (s.H != v.img || s.W != v.img || s.pad != v.pad)) return false;   // flat tiling
@@ -314,8 +313,7 @@ int conv_direct_run_fused(const conv_direct_plan *plan, const float *in, const f
     if (!plan || !in || !w || !out || !plan->v) return CONV_DIRECT_EINVAL;
     if (((uintptr_t)in | (uintptr_t)w | (uintptr_t)out | (uintptr_t)bias | (uintptr_t)residual) & 3u)
         return CONV_DIRECT_EALIGN;
-    const bool tail = bias || residual || relu;
-    if (tail && plan->v->R == 0) return CONV_DIRECT_EUNSUPPORTED;   // the runtime-shape fallback has no fused tail
+
     convd::KernelArgs a;
     a.in = in;
     a.w = w;
@@ -325,6 +323,7 @@ int conv_direct_run_fused(const conv_direct_plan *plan, const float *in, const f
     a.tilesQ = plan->tilesQ;
     a.ktiles = plan->ktiles;
     a.out_blocked = plan->out_blocked;
+    a.in_blocked = plan->in_blocked;
     a.bias = bias;
     a.residual = residual;
     a.relu = relu ? 1 : 0;

@@ -13,7 +13,9 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // Fallback for any filter size and stride (runtime R, S, stride).  Same operand
 // mapping; one chunk is one pair of input channels at one filter row, so the LDS
 // need is independent of R.  Tile: 2 output rows x 32 columns x 64 channels,
-// four waves each owning one 32x32 accumulator block.
+// four waves each owning one 32x32 accumulator block.  It reads and writes element by
+// element, so either layout of each tensor (plain, or the blocked layouts of the
+// paper's Section 4) and the fused point-wise tail are index arithmetic here.
 // ---------------------------------------------------------------------------
 struct GenericGeom {
     static constexpr int TP = 2, TQ = 32, KT = 64, NT = 256, KP = KT + 1;
@@ -42,7 +44,8 @@ __global__ void __launch_bounds__(GenericGeom::NT) conv_generic_kernel(const Ker
     const int n = bid / a.tilesP;
     const int p0 = tp * G::TP, q0 = tq * G::TQ, k0 = kt * G::KT;
     const int iw0 = q0 * st - a.s.pad;
-    const float *in_n = a.in + (size_t)n * C * H * W;
+    const int C4 = (C + 3) / 4, KO = a.out_blocked ? (K + 3) / 4 * 4 : K;
+    const float *in_n = a.in + (size_t)n * (a.in_blocked ? C4 * 4 : C) * H * W;
 
     const int bbase = (h * G::TP + wp) * LW + j * st;
     const int abase = h * G::KP + wk * 32 + j;
@@ -60,15 +63,19 @@ __global__ void __launch_bounds__(GenericGeom::NT) conv_generic_kernel(const Ker
                 const int ih = (p0 + py) * st + r - a.s.pad, iw = iw0 + ww, c = c0 + cc;
                 float v = 0.f;
                 if (c < C && (unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W)
-                    v = in_n[((size_t)c * H + ih) * W + iw];
+                    v = a.in_blocked ? in_n[((((size_t)(c >> 2)) * H + ih) * W + iw) * 4 + (c & 3)]
+                                     : in_n[((size_t)c * H + ih) * W + iw];
                 ldsB[e] = v;
             }
             for (int e = tid; e < nA; e += G::NT) {
                 const int kk = e / (2 * S), rem = e - kk * (2 * S);
                 const int cc = rem / S, s = rem - cc * S;
                 float v = 0.f;
-                if (k0 + kk < K && c0 + cc < C)
-                    v = a.w[(((size_t)(k0 + kk) * C + c0 + cc) * R + r) * S + s];
+                if (k0 + kk < K && c0 + cc < C) {
+                    const int k = k0 + kk, c = c0 + cc;
+                    v = a.in_blocked ? a.w[(((((size_t)(k >> 5)) * C4 + (c >> 2)) * R + r) * S + s) * 128 + (c & 3) * 32 + (k & 31)]
+                                     : a.w[(((size_t)k * C + c) * R + r) * S + s];
+                }
                 ldsA[(s * 2 + cc) * G::KP + kk] = v;
             }
             __syncthreads();
@@ -83,11 +90,21 @@ __global__ void __launch_bounds__(GenericGeom::NT) conv_generic_kernel(const Ker
 
     const int p = p0 + wp, q = q0 + j;
     if (p < P && q < Q) {
-        float *out_n = a.out + (size_t)n * K * P * Q;
+        const size_t img = (size_t)n * KO * P * Q;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int k = k0 + wk * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-            if (k < K) out_n[((size_t)k * P + p) * Q + q] = acc[v];
+            if (k >= KO) continue;
+            const size_t idx = img + (a.out_blocked ? (((size_t)(k >> 2)) * P * Q + (size_t)p * Q + q) * 4 + (k & 3)
+                                                    : ((size_t)k * P + p) * Q + q);
+            float x = 0.f;                       // (blocked: channels completing the last pencil are zeros)
+            if (k < K) {
+                x = acc[v];
+                if (a.bias) x += a.bias[k];
+                if (a.residual) x += a.residual[idx];
+                if (a.relu) x = x > 0.f ? x : 0.f;
+            }
+            a.out[idx] = x;
         }
     }
 }

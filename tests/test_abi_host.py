@@ -142,7 +142,7 @@ def test_every_variant_plans_a_matching_shape():
         info = plan.info()
         assert info["variant"] == nm
         assert info["in_layout"] == info["out_layout"] == ("blocked" if blocked else "plain")
-        if not blocked:   # a variant serves one input layout only
+        if not blocked and not nm.startswith("generic"):   # a compiled variant serves one input layout only
             with pytest.raises(cd.ConvDirectError) as e:
                 cd.Plan(2, C, H, W, 70, R, R, st, R // 2, variant=nm, in_layout=cd.BLOCKED)
             assert e.value.code == cd.EUNSUPPORTED

@@ -72,14 +72,27 @@ def test_fused_tail_random_inputs_and_plain_run_unchanged(oracle):
     assert np.abs(o2.cpu().numpy() - oracle.conv_forward(x, w, st, pd)).max() <= tol
 
 
-def test_fallback_kernel_refuses_a_tail():
-    plan = cd.Plan(1, 2, 5, 300, 3, 1, 7, 1, 3)       # a shape only the runtime-shape kernel serves
-    assert plan.info()["variant"].startswith("generic")
-    x, w = torch.zeros((1, 2, 5, 300), device="cuda"), torch.zeros((3, 2, 1, 7), device="cuda")
-    out = torch.empty((1, 3, *plan.output_dims()), device="cuda")
-    with pytest.raises(cd.ConvDirectError) as e:
-        plan.run(x, w, out, relu=True)
-    assert e.value.code == cd.EUNSUPPORTED
-    plan.run(x, w, out)
-    torch.cuda.synchronize()
-    plan.destroy()
+def test_fallback_kernel_applies_the_tail_too(oracle):
+    shape = (1, 2, 5, 300, 3, 1, 7, 1, 3)              # a shape only the runtime-shape kernel serves
+    N, C, H, W, K, R, S, st, pd = shape
+    rng = np.random.default_rng(21)
+    x = rng.integers(-4, 5, (N, C, H, W)).astype(np.float32)
+    w = rng.integers(-4, 5, (K, C, R, S)).astype(np.float32)
+    for out_layout in (cd.PLAIN, cd.BLOCKED):
+        plan = cd.Plan(*shape, out_layout=out_layout)
+        assert plan.info()["variant"].startswith("generic")
+        P, Q = plan.output_dims()
+        b = rng.integers(-9, 10, (K,)).astype(np.float32)
+        r = rng.integers(-9, 10, (N, K, P, Q)).astype(np.float32)
+        blocked = out_layout == cd.BLOCKED
+        out = torch.full((N, 1, P, Q, 4) if blocked else (N, K, P, Q), float("nan"), device="cuda")
+        rd = torch.from_numpy(L.pack_activations(r, 4) if blocked else r).cuda()
+        plan.run(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), out, bias=torch.from_numpy(b).cuda(),
+                 residual=rd, relu=True)
+        torch.cuda.synchronize()
+        plan.destroy()
+        got = out.cpu().numpy()
+        if blocked:
+            assert np.all(got[:, -1, :, :, K % 4:] == 0)
+            got = L.unpack_activations(got, K)
+        assert np.array_equal(got.astype(np.float64), oracle.conv_forward_fused(x, w, st, pd, b, r, True))
