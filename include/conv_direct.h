@@ -164,11 +164,12 @@ int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, 
 
 /* ------------------------------------------------------------------------
  * Data gradient (the backward pass "to update the image" that the paper's closing
- * section names as a direction), stride 1, plain layouts:
+ * section names as a direction), plain layouts:
  *
  *   dx[n][c][h][w] = sum over k, r, s of dy[n][k][h + pad - r][w + pad - s] * w[k][c][r][s]
  *
- * (terms whose dy index falls outside [0,P) x [0,Q) are absent).  For stride 1 this is
+ * for stride 1, and in general with dy indices (h + pad - r) / stride, (w + pad - s) / stride
+ * where both divide (terms whose dy index falls outside [0,P) x [0,Q) are absent).  For stride 1 this is
  * itself a forward convolution, of dy [N][K][P][Q] with the filter
  *   wt[c][k][r][s] = w[k][c][R-1-r][S-1-s]      (C*K*R*S floats, [C][K][R][S])
  * and padding R-1-pad, and runs on the same zero-workspace kernels:
@@ -177,9 +178,9 @@ int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, 
  *   conv_direct_dgrad_filter(w, wt, K, C, R, S, stream);                 // wt: a caller buffer, once per weight update
  *   conv_direct_run(plan, dy, wt, dx, stream);                           // dx [N][C][H][W], every element written
  *
- * create_dgrad returns CONV_DIRECT_EUNSUPPORTED for stride != 1, R != S or pad > R-1
- * (a strided layer's data gradient needs a dilated dy, which this library does not
- * build); conv_direct_output_dims of the plan gives (H, W).
+ * Strided layers, filters with R != S and pad > R-1 are served too, by the slow
+ * runtime-shape kernel (dy read as if zeros stood between its elements): same three
+ * calls.  conv_direct_output_dims of the plan gives (H, W).
  *
  * Weight gradient (the backward pass "to update ... the kernel"), plain layouts, any
  * filter, strides up to 4 (compiled variants for the filter widths and strides of the forward

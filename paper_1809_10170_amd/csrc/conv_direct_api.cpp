@@ -30,6 +30,7 @@ struct conv_direct_plan {
     double mfma_efficiency;   // useful / issued multiply-accumulates
     int in_blocked, out_blocked;   // layouts of in + w, and of out (paper, Section 4)
     int pw_flat;                   // pointwise kernels: tiles run over the pixels of all images
+    int dil, pad_h, pad_w;         // data gradients on the runtime-shape kernel (dil >= 1), see variant.h
     const convd::WgradVariant *wv; // weight-gradient plans only (v is then NULL)
     int wg_cgroups, wg_splits;
 };
@@ -324,6 +325,9 @@ int conv_direct_run_fused(const conv_direct_plan *plan, const float *in, const f
     a.ktiles = plan->ktiles;
     a.out_blocked = plan->out_blocked;
     a.in_blocked = plan->in_blocked;
+    a.dil = plan->dil;
+    a.pad_h = plan->pad_h;
+    a.pad_w = plan->pad_w;
     a.bias = bias;
     a.residual = residual;
     a.relu = relu ? 1 : 0;
@@ -604,9 +608,30 @@ int conv_direct_create_dgrad(conv_direct_plan **plan, int N, int C, int H, int W
     Shape fwd;
     const int rc = validate(N, C, H, W, K, R, S, stride, pad, &fwd);
     if (rc != CONV_DIRECT_OK) return rc;
-    if (stride != 1 || R != S || pad > R - 1) return CONV_DIRECT_EUNSUPPORTED;
-    // the forward problem that computes dx: input dy [N][K][P][Q], C output channels
-    return make_plan(plan, nullptr, N, K, fwd.P, fwd.Q, C, R, S, 1, R - 1 - pad);
+    if (stride == 1 && R == S && pad <= R - 1) {
+        // the forward problem that computes dx: input dy [N][K][P][Q], C output channels
+        return make_plan(plan, nullptr, N, K, fwd.P, fwd.Q, C, R, S, 1, R - 1 - pad);
+    }
+    // Otherwise (strided layer, unequal filter sides, pad > R-1): the same forward problem over dy
+    // with zeros between its elements and paddings R-1-pad, S-1-pad (negative: a crop), on the
+    // runtime-shape kernel, whose output size is the layer's input size.
+    int count = 0;
+    const Variant *const *table = convd::variant_table(&count);
+    const Variant *generic = nullptr;
+    for (int i = 0; i < count; ++i)
+        if (table[i]->R == 0) generic = table[i];
+    if (!generic) return CONV_DIRECT_EUNSUPPORTED;
+    if ((int64_t)N * K * fwd.P * fwd.Q >= kMaxElems) return CONV_DIRECT_EUNSUPPORTED;
+    Shape s{N, K, fwd.P, fwd.Q, C, R, S, 1, 0, H, W};   // in = dy, K' = C, P' x Q' = H x W
+    if (generic->lds_bytes(s) > kLdsPerCU) return CONV_DIRECT_EUNSUPPORTED;
+    conv_direct_plan *p = new (std::nothrow) conv_direct_plan();
+    if (!p) return CONV_DIRECT_ENOMEM;
+    fill(p, s, *generic);
+    p->dil = stride;
+    p->pad_h = R - 1 - pad;
+    p->pad_w = S - 1 - pad;
+    *plan = p;
+    return CONV_DIRECT_OK;
 }
 
 size_t conv_direct_blocked_act_elems(int N, int C, int H, int W)

@@ -16,6 +16,11 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // four waves each owning one 32x32 accumulator block.  It reads and writes element by
 // element, so either layout of each tensor (plain, or the blocked layouts of the
 // paper's Section 4) and the fused point-wise tail are index arithmetic here.
+//
+// It also serves the data gradients the fast path does not (strided layers, unequal
+// filter sides, pad > R-1): with a.dil > 1 the "input" is dy read as if zeros stood
+// between its elements (position i exists where i % dil == 0 and is element i / dil), and
+// the paddings of the two dimensions may differ and be negative (a crop).
 // ---------------------------------------------------------------------------
 struct GenericGeom {
     static constexpr int TP = 2, TQ = 32, KT = 64, NT = 256, KP = KT + 1;
@@ -43,7 +48,9 @@ __global__ void __launch_bounds__(GenericGeom::NT) conv_generic_kernel(const Ker
     const int tp = bid % a.tilesP;
     const int n = bid / a.tilesP;
     const int p0 = tp * G::TP, q0 = tq * G::TQ, k0 = kt * G::KT;
-    const int iw0 = q0 * st - a.s.pad;
+    const int dil = a.dil > 1 ? a.dil : 1;
+    const int pad_h = a.dil ? a.pad_h : a.s.pad, pad_w = a.dil ? a.pad_w : a.s.pad;
+    const int iw0 = q0 * st - pad_w;
     const int C4 = (C + 3) / 4, KO = a.out_blocked ? (K + 3) / 4 * 4 : K;
     const float *in_n = a.in + (size_t)n * (a.in_blocked ? C4 * 4 : C) * H * W;
 
@@ -60,9 +67,16 @@ __global__ void __launch_bounds__(GenericGeom::NT) conv_generic_kernel(const Ker
             for (int e = tid; e < nB; e += G::NT) {
                 const int cc = e / (G::TP * LW), rem = e - cc * (G::TP * LW);
                 const int py = rem / LW, ww = rem - py * LW;
-                const int ih = (p0 + py) * st + r - a.s.pad, iw = iw0 + ww, c = c0 + cc;
+                int ih = (p0 + py) * st + r - pad_h, iw = iw0 + ww;
+                const int c = c0 + cc;
+                bool ok = c < C && ih >= 0 && iw >= 0;
+                if (dil > 1) {   // dilated input: only every dil-th position holds an element
+                    ok = ok && ih % dil == 0 && iw % dil == 0;
+                    ih /= dil;
+                    iw /= dil;
+                }
                 float v = 0.f;
-                if (c < C && (unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W)
+                if (ok && ih < H && iw < W)
                     v = a.in_blocked ? in_n[((((size_t)(c >> 2)) * H + ih) * W + iw) * 4 + (c & 3)]
                                      : in_n[((size_t)c * H + ih) * W + iw];
                 ldsB[e] = v;

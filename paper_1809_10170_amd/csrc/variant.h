@@ -17,6 +17,8 @@ struct KernelArgs {
     float *out;
     Shape s;
     int tilesP, tilesQ, ktiles;   // grid = ktiles * tilesQ * tilesP * N workgroups
+    int dil, pad_h, pad_w;        // runtime-shape fallback as a data gradient: dil >= 1 marks the mode (input dilation,
+                                  // separate and possibly negative paddings); dil = 0: an ordinary forward pass
     int in_blocked;               // runtime-shape fallback only (the compiled variants fix it at compile time)
     int out_blocked;              // 0: out[N][K][P][Q]; 1: out[N][ceil(K/4)][P][Q][4] (paper, Section 4.1)
     // fused point-wise tail (all optional): out = relu?(conv + bias[k] + residual[same position as out])

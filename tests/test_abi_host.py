@@ -224,7 +224,9 @@ def test_layout_gradient_and_tail_entry_points_check_arguments_before_any_launch
         assert fn(4098, 8192, 2, 3, 4, 5, None) == cd.EALIGN
     assert L.conv_direct_pack_act(4096, 8196, 2, 3, 4, 5, None) == cd.EALIGN      # blocked destination: 16 bytes
     # gradients
-    assert L.conv_direct_create_dgrad(ctypes.byref(p), 2, 8, 20, 20, 8, 3, 3, 2, 1) == cd.EUNSUPPORTED and not p
+    sd = cd.Plan.dgrad(2, 8, 20, 20, 8, 3, 3, 2, 1)                      # strided: the runtime-shape kernel
+    assert sd.info()["variant"].startswith("generic") and sd.output_dims() == (20, 20)
+    sd.destroy()
     assert L.conv_direct_create_dgrad(ctypes.byref(p), 2, 8, 20, 20, 8, 3, 3, 0, 1) == cd.EINVAL
     assert L.conv_direct_create_wgrad(ctypes.byref(p), 2, 8, 40, 40, 8, 3, 4, 5, 1) == cd.EUNSUPPORTED and not p
     assert L.conv_direct_create_wgrad(ctypes.byref(p), 2, 8, 20, 20, 0, 3, 3, 1, 1) == cd.EINVAL

@@ -62,13 +62,34 @@ def test_small_shapes_random_inputs(oracle, shape):
     assert err <= oracle.tolerance(K, R, S), (info["variant"], err)   # the reduction runs over K*R*S
 
 
-def test_unsupported_cases_are_refused():
-    for args in ((2, 8, 20, 20, 8, 3, 3, 2, 1),     # stride 2
-                 (2, 8, 20, 20, 8, 3, 5, 1, 1),     # R != S
-                 (2, 8, 20, 20, 8, 3, 3, 1, 3)):    # pad > R-1
-        with pytest.raises(cd.ConvDirectError) as e:
-            cd.Plan.dgrad(*args)
-        assert e.value.code == cd.EUNSUPPORTED
+GENERAL = [
+    # N, C, H, W, K, R, S, stride, pad: strided layers, unequal filter sides, pad > R-1
+    (2, 8, 20, 20, 9, 3, 3, 2, 1),
+    (2, 5, 23, 31, 7, 3, 5, 1, 1),
+    (1, 6, 20, 22, 8, 3, 3, 1, 3),
+    (2, 3, 75, 64, 10, 7, 7, 2, 3),
+    (1, 3, 51, 47, 12, 11, 11, 4, 0),
+    (2, 4, 17, 19, 5, 2, 4, 3, 2),
+    (1, 7, 16, 16, 6, 1, 1, 2, 0),
+]
+
+
+@pytest.mark.parametrize("shape", GENERAL)
+def test_general_cases_on_the_runtime_shape_kernel(oracle, shape):
+    N, C, H, W, K, R, S, st, pd = shape
+    rng = np.random.default_rng(650 + sum(shape))
+    w = rng.integers(-4, 5, (K, C, R, S)).astype(np.float32)
+    P, Q = oracle.out_dim(H, R, st, pd), oracle.out_dim(W, S, st, pd)
+    dy = rng.integers(-4, 5, (N, K, P, Q)).astype(np.float32)
+    plan = cd.Plan.dgrad(*shape)
+    assert plan.output_dims() == (H, W) and plan.info()["variant"].startswith("generic")
+    wt = torch.full((C, K, R, S), float("nan"), device="cuda")
+    cd.dgrad_filter(torch.from_numpy(w).cuda(), wt)
+    dx = torch.full((N, C, H, W), float("nan"), device="cuda")
+    assert cd.lib().conv_direct_run(plan._p, torch.from_numpy(dy).cuda().data_ptr(), wt.data_ptr(), dx.data_ptr(), None) == cd.OK
+    torch.cuda.synchronize()
+    plan.destroy()
+    assert np.array_equal(dx.cpu().numpy().astype(np.float64), oracle.conv_dgrad(dy, w, H, W, st, pd))
 
 
 @pytest.mark.parametrize("name", ["alex_conv3_n64", "vgg_c256_56_k256_n32", "pw_c256_56_k64_n64"])
