@@ -57,20 +57,21 @@ struct WgGeom {
     static constexpr int NT = 64 * WK;
     static constexpr int KT = 32 * WK;                    // output channels per workgroup
     static constexpr int CT = 32 * CBW;                   // input channels per workgroup
-    // LDS pitch of a dy row: the chunk's pixels + 2 (banks 2i + pixel, all different).  A 32-pixel
-    // chunk is staged by the first 32 lanes only, so that two workgroups fit the LDS of a CU.
-    static constexpr int PA = (PXC == 32 && QW_ == 0) ? 34 : 66;
-    static constexpr bool HALF_A = PA == 34;
+    // LDS pitch of a dy row: odd, so that the 32 rows one half-wave reads at the same pixel fall into
+    // 32 different banks.  A 32-pixel chunk is staged by the first 32 lanes only, so that two
+    // workgroups fit the LDS of a CU.
+    static constexpr int PA = (PXC == 32 && QW_ == 0) ? 33 : 65;
+    static constexpr bool HALF_A = PA == 33;
     static constexpr int WX = ((QW ? QW : PXC) - 1) * ST + SB;  // input columns a chunk needs (fallback: at most)
     static_assert(!RT || (PACK == 0 && QW == 0), "the fallback uses plain row chunks");
     static constexpr int NLX = (WX + 63) / 64;            // 64-lane loads per input channel (row chunks)
-    static constexpr int PX = QW ? RPC * PXR + 2 : NLX * 64 + 2;   // LDS pitch of an input channel (2 mod 64: banks 2c + column)
+    static constexpr int PX = QW ? RPC * PXR + 1 : NLX * 64 + 1;   // LDS pitch of an input channel (odd: 32 channels, 32 banks)
     static_assert(!QW || (WX <= PXR && RPC >= 1 && PACK == 0), "small-map chunks: an input row fits 32 words");
     static constexpr int ABUF = KT * PA, XBUF = CT * PX;  // floats
     static constexpr int BUF = ABUF + XBUF;
     static constexpr size_t LDS_BYTES = sizeof(float) * (2 * (size_t)BUF + 64);   // (+ slack: an odd last pixel pair reads
                                                                                   // a few words past the last input row)
-    static_assert(PXC == 32 || PXC == 64, "a dy row segment is staged by one 64-lane load");
+    static_assert(PXC <= 64 && PXC % 2 == 0, "a dy row segment is staged by one 64-lane load");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
 };
 
@@ -138,7 +139,7 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
             const float *base = a.dy + (((size_t)sn * K + k0) * P + sp) * Q + sq0;
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
             const int plane = P * Q * 4;
-            if (!G::HALF_A || lane < 32) {   // (a disabled lane writes nothing: rows 34 words apart do not overlap)
+            if (!G::HALF_A || lane < 32) {   // (a disabled lane writes nothing: rows 33 words apart do not overlap)
 #pragma unroll
                 for (int i = 0; i < G::KT / G::WK; ++i) {
                     const int row = i * G::WK + wave;
