@@ -85,6 +85,11 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
     const int h = lane >> 5, j = lane & 31;
     const int N = a.s.N, C = a.s.C, H = a.s.H, W = a.s.W, K = a.s.K, R = a.s.R, P = a.s.P, Q = a.s.Q, pad = a.s.pad;
     const int st = G::RT ? a.s.stride : G::ST;       // (a compile-time constant except in the fallback)
+    // (scalars, not the argument struct, go into the lambdas below: a struct captured by reference
+    // ends up in private memory)
+    const float *const xp = a.x, *const dyp = a.dy;
+    float *const dwp = a.dw;
+    const int splits = a.splits, cgroups = a.cgroups, ktiles = a.ktiles, SFILT = a.s.S;
 
     // workgroup -> (pixel split, filter row, channel group, k tile); neighbours share dy
     // (consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2: regroup
@@ -95,11 +100,11 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
         if (bid < g8) bid = (bid & 7u) * (g8 >> 3) + (bid >> 3);
     }
     int s0 = 0;                                      // fallback: the filter column of this workgroup
-    if (G::RT) { s0 = bid % a.s.S;  bid /= a.s.S; }
-    const int cg = bid % a.cgroups;  bid /= a.cgroups;
+    if (G::RT) { s0 = bid % SFILT;  bid /= SFILT; }
+    const int cg = bid % cgroups;  bid /= cgroups;
     const int r = bid % R;           bid /= R;
-    const int kt = bid % a.ktiles;
-    const int ps = bid / a.ktiles;
+    const int kt = bid % ktiles;
+    const int ps = bid / ktiles;
     const int k0 = kt * G::KT, c0 = cg * G::CT;
 
     // The reduction runs over output rows u = n*P + p of all images; this workgroup takes rows
@@ -108,19 +113,19 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
     const int PG = G::QW ? (P + G::RPC - 1) / G::RPC : P;   // units per image
     const int rows_all = N * PG;
     int u = ps, n = 0, p = 0, q0 = 0;
-    auto settle = [&]() {   // move u forward to the next unit of this split (row chunks: whose input row exists)
-        for (; u < rows_all; u += a.splits) {
+    auto settle = [&]() __attribute__((always_inline)) {   // move u forward to the next unit of this split (row chunks: whose input row exists)
+        for (; u < rows_all; u += splits) {
             n = u / PG;
             p = (u - n * PG) * G::RPC;
             if (G::QW || (unsigned)(p * st + r - pad) < (unsigned)H) break;
         }
         if (u >= rows_all) n = N;
     };
-    auto advance = [&]() {
+    auto advance = [&]() __attribute__((always_inline)) {
         q0 += G::PXC;
         if (G::QW || q0 >= Q) {
             q0 = 0;
-            u += a.splits;
+            u += splits;
             settle();
         }
     };
@@ -130,13 +135,13 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
     // channels likewise; lanes past the row's end or outside the image load zeros; rows
     // of output channels >= K and input channels >= C are skipped (they feed results
     // that are never written).
-    auto stage = [&](int b, int sn, int sp, int sq0) {
+    auto stage = [&](int b, int sn, int sp, int sq0) __attribute__((always_inline)) {
         float *abuf = lds + b * G::BUF, *xbuf = abuf + G::ABUF;
         {
             // pixels of the chunk that exist: the rest of the row, or whole rows down to the image's last
             const int npix = G::QW ? (P - sp < G::RPC ? P - sp : G::RPC) * G::QW : Q - sq0;
             const unsigned voff = lane < npix ? (unsigned)lane * 4u : 0x80000000u;
-            const float *base = a.dy + (((size_t)sn * K + k0) * P + sp) * Q + sq0;
+            const float *base = dyp + (((size_t)sn * K + k0) * P + sp) * Q + sq0;
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
             const int plane = P * Q * 4;
             if (!G::HALF_A || lane < 32) {   // (a disabled lane writes nothing: rows 33 words apart do not overlap)
@@ -151,7 +156,7 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
         if constexpr (G::QW != 0) {
             // RPC input rows per channel, 32 words apart: only the first 32 lanes take part in a load
             // (a disabled lane writes nothing), lanes past the row's columns or outside the image load zeros
-            const float *base = a.x + ((size_t)sn * C + c0) * H * W;
+            const float *base = xp + ((size_t)sn * C + c0) * H * W;
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
             const int plane = H * W * 4;
             const int iw = lane - pad;
@@ -176,7 +181,7 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
             const int ih = sp * st + r - pad;              // exists (the chunk list skips rows without one)
             const int iw0 = sq0 * st - pad + s0;
             const int wx = (G::PXC - 1) * st + G::SB;      // columns the chunk needs
-            const float *base = a.x + (((size_t)sn * C + c0) * H + ih) * W;
+            const float *base = xp + (((size_t)sn * C + c0) * H + ih) * W;
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
             const int plane = H * W * 4;
             unsigned voff[G::NLX];
@@ -204,6 +209,10 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
 
+    // LDS addresses are one register plus an immediate: the buffer's base goes into the per-lane
+    // registers (one set per buffer, the chunk loop is unrolled over the two buffers), the step's
+    // part into the immediate -- no vector ALU work per fetch, which a wave between its own MFMAs
+    // would wait some 20 clocks for each time.
     const int aoff = (wave * 32 + j) * G::PA + h;            // lane (k = j, pixel parity h)
     // LDS offset of the lane's B operand of block b at pixel pair 0: column j of the block is input
     // channel cb*32 + j at filter column s (b = cb*S + s), or the packed pair (c, s) = divmod(b*32 + j, S)
@@ -218,34 +227,38 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
         }
     }
 
-    int b = 0;
-    if (n < N) stage(0, n, p, q0);
-    while (n < N) {
-        const int cn = n, cp = p, cq0 = q0;
-        (void)cn; (void)cp; (void)cq0;
+    int aoffB[2], xoffB[2][G::NBLK];
+#pragma unroll
+    for (int bf = 0; bf < 2; ++bf) {
+        aoffB[bf] = bf * G::BUF + aoff;
+#pragma unroll
+        for (int bb = 0; bb < G::NBLK; ++bb) xoffB[bf][bb] = bf * G::BUF + G::ABUF + xoff[bb];
+    }
+    constexpr int NST = (G::NPX + 1) / 2;
+    auto pix_off = [&](int t) {
+        // LDS offset of the step's two pixels: along the row, or (small maps) row and column of
+        // pixels 2t and 2t+1 of the chunk, the lane's one picked by its pixel parity
+        if (G::QW) {
+            constexpr int QWc = G::QW ? G::QW : 1;
+            const int o0 = (2 * t / QWc) * G::PXR + (2 * t % QWc) * G::ST;
+            const int o1 = ((2 * t + 1) / QWc) * G::PXR + ((2 * t + 1) % QWc) * G::ST;
+            return h ? o1 : o0;
+        }
+        return 2 * t * st;
+    };
+    // one chunk out of buffer bf (a compile-time constant): meet, send the next chunk's loads, multiply
+    auto chunk = [&](auto bft) __attribute__((always_inline)) {
+        constexpr int bf = decltype(bft)::value;
         advance();                                            // (n, p, q0) is now the next chunk
-        __syncthreads();   // chunk b has landed (the barrier's fence waits for the LDS-direct loads) and
+        __syncthreads();   // chunk bf has landed (the barrier's fence waits for the LDS-direct loads) and
                            // every wave has left the other buffer
-        if (n < N) stage(b ^ 1, n, p, q0);
-        const float *abuf = lds + b * G::BUF, *xbuf = abuf + G::ABUF;
+        if (n < N) stage(bf ^ 1, n, p, q0);
         // operands of step t+1 are fetched from LDS while step t multiplies
-        constexpr int NST = (G::NPX + 1) / 2;
-        auto pix_off = [&](int t) {
-            // LDS offset of the step's two pixels: along the row, or (small maps) row and column of
-            // pixels 2t and 2t+1 of the chunk, the lane's one picked by its pixel parity
-            if (G::QW) {
-                constexpr int QWc = G::QW ? G::QW : 1;
-                const int o0 = (2 * t / QWc) * G::PXR + (2 * t % QWc) * G::ST;
-                const int o1 = ((2 * t + 1) / QWc) * G::PXR + ((2 * t + 1) % QWc) * G::ST;
-                return h ? o1 : o0;
-            }
-            return 2 * t * st;
-        };
-        float an = abuf[aoff], bn[G::NBLK];
+        float an = lds[aoffB[bf]], bn[G::NBLK];
         {
             const int po = pix_off(0);
 #pragma unroll
-            for (int bb = 0; bb < G::NBLK; ++bb) bn[bb] = xbuf[xoff[bb] + po];
+            for (int bb = 0; bb < G::NBLK; ++bb) bn[bb] = lds[xoffB[bf][bb] + po];
         }
 #pragma unroll
         for (int t = 0; t < NST; ++t) {
@@ -254,27 +267,25 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
 #pragma unroll
             for (int bb = 0; bb < G::NBLK; ++bb) bv[bb] = bn[bb];
             if (t + 1 < NST) {
-                an = abuf[aoff + 2 * (t + 1)];
+                an = lds[aoffB[bf] + 2 * (t + 1)];
                 const int po = pix_off(t + 1);
 #pragma unroll
-                for (int bb = 0; bb < G::NBLK; ++bb) bn[bb] = xbuf[xoff[bb] + po];
+                for (int bb = 0; bb < G::NBLK; ++bb) bn[bb] = lds[xoffB[bf][bb] + po];
             }
 #pragma unroll
             for (int bb = 0; bb < G::NBLK; ++bb)
                 acc[bb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[bb], acc[bb], 0, 0, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // one MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);       // the next step's LDS reads between them: dy and one x
-#pragma unroll
-            for (int bb = 1; bb < G::NBLK; ++bb) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
         }
-        b ^= 1;
+    };
+    if (n < N) stage(0, n, p, q0);
+    while (n < N) {
+        chunk(IntTag<0>{});
+        if (!(n < N)) break;
+        chunk(IntTag<1>{});
     }
 
     // partial sums of this pixel split -> dw (cleared before the launch)
-    const int SF = G::RT ? a.s.S : G::S;             // filter width
+    const int SF = G::RT ? SFILT : G::S;             // filter width
     const int RS = R * SF;
 #pragma unroll
     for (int b = 0; b < G::NBLK; ++b) {
@@ -284,7 +295,7 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int k = k0 + wave * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-            if (k < K && c < C) unsafeAtomicAdd(a.dw + ((size_t)k * C + c) * RS + r * SF + s, acc[b][v]);
+            if (k < K && c < C) unsafeAtomicAdd(dwp + ((size_t)k * C + c) * RS + r * SF + s, acc[b][v]);
         }
     }
 }
