@@ -22,7 +22,8 @@
 
 namespace convd {
 
-template <int R_, int S_, int ST_, int TP_, int TQ_, int KBW_, int PBW_, int WK_, int WP_, int CM_, int RG_, int OCC_>
+template <int R_, int S_, int ST_, int TP_, int TQ_, int KBW_, int PBW_, int WK_, int WP_, int CM_, int RG_, int OCC_,
+          int NFULL_ = 0>
 struct RowGeom {
     static constexpr int R = R_, S = S_, ST = ST_, TP = TP_, TQ = TQ_;
     static constexpr int KBW = KBW_, PBW = PBW_, WK = WK_, WP = WP_, CM = CM_, RG = RG_, OCC = OCC_;
@@ -31,7 +32,11 @@ struct RowGeom {
     static constexpr int NT = 64 * WK * WP;
     static constexpr int WPE = (OCC * WK * WP + 3) / 4;
     static constexpr int KT = 32 * KBW * WK;            // a wave owns KBW x PBW 32x32 results
-    static constexpr int NPB = PBW * WP;
+    // Unequal waves (NFULL > 0): only the first NFULL pixel groups own PBW blocks, the others
+    // PBW - 1.  Waves are numbered k-group fastest, so with WK odd every SIMD of the CU still
+    // gets its share of both kinds.
+    static constexpr int NFULL = NFULL_;
+    static constexpr int NPB = NFULL_ ? NFULL_ + (PBW_ - 1) * WP_ : PBW_ * WP_;
     static constexpr int NPIX = TP * TQ;
     static constexpr int R2 = (R + 1) / 2;               // filter rows per k-lane half
     static constexpr int NSUB = R2 / RG;                 // register sub-chunks per channel
@@ -51,6 +56,7 @@ struct RowGeom {
     static constexpr size_t LDS_BYTES = sizeof(float) * (size_t)CM * PSP;
     static_assert(R2 % RG == 0 && NSUB % 2 == 0, "row groups must tile R2 an even number of times");
     static_assert(NPB * 32 >= NPIX, "pixel blocks must cover the tile");
+    static_assert(NFULL == 0 || (NFULL < WP && PBW > 1), "unequal waves: some groups of each kind");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
 };
 
@@ -119,127 +125,137 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
         }
     }
 
-    // per-lane LDS read offsets (floats): pixel position (phase 0) plus the k-lane half.
-    // For odd R the second half has no partner for the first half's last row: there its
-    // weight is zero and it reads the SAME window position as the first half (bsame), a
-    // position inside the output's own window, so that the zero never meets a value
-    // (an Inf, say) that the true sum does not contain.
-    int bbase[G::PBW], bsame[G::PBW];
-#pragma unroll
-    for (int pb = 0; pb < G::PBW; ++pb) {
-        const int t = (wp * G::PBW + pb) * 32 + j;
-        const int py = t / G::TQ, px = t - py * G::TQ;
-        const int pix = t < G::NPIX ? py * G::ST * G::LWP + px : 0;
-        bbase[pb] = pix + h * G::HOFF;
-        bsame[pb] = pix;
-    }
+    // Everything below depends on how many pixel blocks the wave owns (see NFULL): the
+    // body is compiled once per count and the wave takes its own.
+    auto body = [&](auto pbw_tag) __attribute__((always_inline)) {
+    constexpr int PBW = decltype(pbw_tag)::value;
+    // first pixel block of the wave
+    const int pb0 = G::NFULL ? wp * (G::PBW - 1) + (wp < G::NFULL ? wp : G::NFULL) : wp * G::PBW;
 
-    // Filter values of this lane for sub-chunk (c, g): rows g*RG + h*R2 .. + RG of
-    // w[k][c], RG*S consecutive floats.  Rows past R (second half, odd R) are zeros and
-    // are not read.
-    const float *w_lane[G::KBW];
-#pragma unroll
-    for (int kb = 0; kb < G::KBW; ++kb) {
-        int krow = k0 + (wk * G::KBW + kb) * 32 + j;
-        krow = krow < K ? krow : K - 1;
-        w_lane[kb] = a.w + (size_t)krow * C * G::R * G::S + h * G::R2 * G::S;
-    }
-    auto load_a = [&](float (&dst)[G::KBW][G::NA], int c, int g) {
-#pragma unroll
+        // per-lane LDS read offsets (floats): pixel position (phase 0) plus the k-lane half.
+        // For odd R the second half has no partner for the first half's last row: there its
+        // weight is zero and it reads the SAME window position as the first half (bsame), a
+        // position inside the output's own window, so that the zero never meets a value
+        // (an Inf, say) that the true sum does not contain.
+        int bbase[PBW], bsame[PBW];
+    #pragma unroll
+        for (int pb = 0; pb < PBW; ++pb) {
+            const int t = (pb0 + pb) * 32 + j;
+            const int py = t / G::TQ, px = t - py * G::TQ;
+            const int pix = t < G::NPIX ? py * G::ST * G::LWP + px : 0;
+            bbase[pb] = pix + h * G::HOFF;
+            bsame[pb] = pix;
+        }
+
+        // Filter values of this lane for sub-chunk (c, g): rows g*RG + h*R2 .. + RG of
+        // w[k][c], RG*S consecutive floats.  Rows past R (second half, odd R) are zeros and
+        // are not read.
+        const float *w_lane[G::KBW];
+    #pragma unroll
         for (int kb = 0; kb < G::KBW; ++kb) {
-        const float *p = w_lane[kb] + ((size_t)c * G::R + g * G::RG) * G::S;
-#pragma unroll
-        for (int i = 0; i < G::RG; ++i) {
-            const float *pr = p + i * G::S;
-            float *d = dst[kb] + i * G::S;
-            // row g*RG + i + h*R2 exists for both halves iff it exists for the second
-            const bool both = g * G::RG + i + G::R2 < G::R;
-            const bool ok = both | (h == 0);
-            const float *q = ok ? pr : a.w;     // lanes without a row read a valid address
-            constexpr int N4 = G::S / 4, REM = G::S % 4;
-#pragma unroll
-            for (int u = 0; u < N4; ++u) {
-                const dma_f4u v = *reinterpret_cast<const dma_f4u *>(q + 4 * u);
-                d[4 * u] = v[0]; d[4 * u + 1] = v[1]; d[4 * u + 2] = v[2]; d[4 * u + 3] = v[3];
+            int krow = k0 + (wk * G::KBW + kb) * 32 + j;
+            krow = krow < K ? krow : K - 1;
+            w_lane[kb] = a.w + (size_t)krow * C * G::R * G::S + h * G::R2 * G::S;
+        }
+        auto load_a = [&](float (&dst)[G::KBW][G::NA], int c, int g) {
+    #pragma unroll
+            for (int kb = 0; kb < G::KBW; ++kb) {
+            const float *p = w_lane[kb] + ((size_t)c * G::R + g * G::RG) * G::S;
+    #pragma unroll
+            for (int i = 0; i < G::RG; ++i) {
+                const float *pr = p + i * G::S;
+                float *d = dst[kb] + i * G::S;
+                // row g*RG + i + h*R2 exists for both halves iff it exists for the second
+                const bool both = g * G::RG + i + G::R2 < G::R;
+                const bool ok = both | (h == 0);
+                const float *q = ok ? pr : a.w;     // lanes without a row read a valid address
+                constexpr int N4 = G::S / 4, REM = G::S % 4;
+    #pragma unroll
+                for (int u = 0; u < N4; ++u) {
+                    const dma_f4u v = *reinterpret_cast<const dma_f4u *>(q + 4 * u);
+                    d[4 * u] = v[0]; d[4 * u + 1] = v[1]; d[4 * u + 2] = v[2]; d[4 * u + 3] = v[3];
+                }
+                if (REM >= 2) {
+                    const dma_f2u v = *reinterpret_cast<const dma_f2u *>(q + 4 * N4);
+                    d[4 * N4] = v[0]; d[4 * N4 + 1] = v[1];
+                }
+                if (REM & 1) d[G::S - 1] = q[G::S - 1];
+                if (!both) {
+    #pragma unroll
+                    for (int u = 0; u < G::S; ++u) d[u] = ok ? d[u] : 0.f;
+                }
             }
-            if (REM >= 2) {
-                const dma_f2u v = *reinterpret_cast<const dma_f2u *>(q + 4 * N4);
-                d[4 * N4] = v[0]; d[4 * N4 + 1] = v[1];
             }
-            if (REM & 1) d[G::S - 1] = q[G::S - 1];
-            if (!both) {
-#pragma unroll
-                for (int u = 0; u < G::S; ++u) d[u] = ok ? d[u] : 0.f;
+        };
+
+        dma_floatx16 acc[G::KBW][PBW];
+    #pragma unroll
+        for (int kb = 0; kb < G::KBW; ++kb)
+    #pragma unroll
+            for (int pb = 0; pb < PBW; ++pb)
+    #pragma unroll
+                for (int v = 0; v < 16; ++v) acc[kb][pb][v] = 0.f;
+
+        // RG*S rank-2 updates: rows g*RG .. of the first half, columns 0 .. S-1
+        auto compute = [&](const float *chan, int g, const float (&av)[G::KBW][G::NA]) {
+    #pragma unroll
+            for (int i = 0; i < G::RG; ++i)
+    #pragma unroll
+                for (int s = 0; s < G::S; ++s) {
+                    const int boff = (s % G::ST) * G::PH + (g * G::RG + i) * G::LWP + s / G::ST;
+                    const bool both = g * G::RG + i + G::R2 < G::R;   // the second half has this row too
+                    float bv[PBW];
+    #pragma unroll
+                    for (int pb = 0; pb < PBW; ++pb) bv[pb] = chan[(both ? bbase[pb] : bsame[pb]) + boff];
+    #pragma unroll
+                    for (int kb = 0; kb < G::KBW; ++kb)
+    #pragma unroll
+                        for (int pb = 0; pb < PBW; ++pb)
+                            acc[kb][pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[kb][i * G::S + s], bv[pb], acc[kb][pb], 0, 0, 0);
+                }
+        };
+
+        float a0[G::KBW][G::NA], a1[G::KBW][G::NA];
+        load_a(a0, 0, 0);
+        __syncthreads();   // the staged window is complete (the compiler waits for the LDS-direct loads)
+        for (int c = 0; c < C; ++c) {
+            const float *chan = lds + c * G::PSP;
+    #pragma unroll
+            for (int g = 0; g < G::NSUB; g += 2) {
+                load_a(a1, c, g + 1);
+                compute(chan, g, a0);
+                {
+                    // next sub-chunk: same channel, or the first of the next channel (clamped at the end)
+                    const bool last = g + 2 == G::NSUB;
+                    const int cn = last ? (c + 1 < C ? c + 1 : c) : c;
+                    load_a(a0, cn, last ? 0 : g + 2);
+                }
+                compute(chan, g + 1, a1);
             }
         }
+
+        // ---- epilogue (see write_block) ----
+        const int KO = a.out_blocked ? (K + 3) / 4 * 4 : K;
+        float *out_n = a.out + (size_t)n * KO * P * Q;
+        __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(out_n), 0, 0x7fffffff, 0x00020000);
+        const bool fits = (long long)KO * P * Q * 4 < (1ll << 31);
+        const Tail tail{a.bias, a.residual ? a.residual + (size_t)n * KO * P * Q : nullptr, a.relu};
+    #pragma unroll
+        for (int pb = 0; pb < PBW; ++pb) {
+            const int t = (pb0 + pb) * 32 + j;
+            const int py = t / G::TQ, px = t - py * G::TQ;
+            const int p = p0 + py, q = q0 + px;
+            const bool live = t < G::NPIX && p < P && q < Q;
+    #pragma unroll
+            for (int kb = 0; kb < G::KBW; ++kb) {
+                const int kw = k0 + (wk * G::KBW + kb) * 32;
+                write_block<FUSED>(a.out_blocked != 0, fits & (kw + 32 <= K), orsrc, out_n, K, P * Q, kw, h, live, 0, p * Q + q,
+                            acc[kb][pb], tail);
+            }
         }
     };
-
-    dma_floatx16 acc[G::KBW][G::PBW];
-#pragma unroll
-    for (int kb = 0; kb < G::KBW; ++kb)
-#pragma unroll
-        for (int pb = 0; pb < G::PBW; ++pb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[kb][pb][v] = 0.f;
-
-    // RG*S rank-2 updates: rows g*RG .. of the first half, columns 0 .. S-1
-    auto compute = [&](const float *chan, int g, const float (&av)[G::KBW][G::NA]) {
-#pragma unroll
-        for (int i = 0; i < G::RG; ++i)
-#pragma unroll
-            for (int s = 0; s < G::S; ++s) {
-                const int boff = (s % G::ST) * G::PH + (g * G::RG + i) * G::LWP + s / G::ST;
-                const bool both = g * G::RG + i + G::R2 < G::R;   // the second half has this row too
-                float bv[G::PBW];
-#pragma unroll
-                for (int pb = 0; pb < G::PBW; ++pb) bv[pb] = chan[(both ? bbase[pb] : bsame[pb]) + boff];
-#pragma unroll
-                for (int kb = 0; kb < G::KBW; ++kb)
-#pragma unroll
-                    for (int pb = 0; pb < G::PBW; ++pb)
-                        acc[kb][pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[kb][i * G::S + s], bv[pb], acc[kb][pb], 0, 0, 0);
-            }
-    };
-
-    float a0[G::KBW][G::NA], a1[G::KBW][G::NA];
-    load_a(a0, 0, 0);
-    __syncthreads();   // the staged window is complete (the compiler waits for the LDS-direct loads)
-    for (int c = 0; c < C; ++c) {
-        const float *chan = lds + c * G::PSP;
-#pragma unroll
-        for (int g = 0; g < G::NSUB; g += 2) {
-            load_a(a1, c, g + 1);
-            compute(chan, g, a0);
-            {
-                // next sub-chunk: same channel, or the first of the next channel (clamped at the end)
-                const bool last = g + 2 == G::NSUB;
-                const int cn = last ? (c + 1 < C ? c + 1 : c) : c;
-                load_a(a0, cn, last ? 0 : g + 2);
-            }
-            compute(chan, g + 1, a1);
-        }
-    }
-
-    // ---- epilogue (see write_block) ----
-    const int KO = a.out_blocked ? (K + 3) / 4 * 4 : K;
-    float *out_n = a.out + (size_t)n * KO * P * Q;
-    __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(out_n), 0, 0x7fffffff, 0x00020000);
-    const bool fits = (long long)KO * P * Q * 4 < (1ll << 31);
-    const Tail tail{a.bias, a.residual ? a.residual + (size_t)n * KO * P * Q : nullptr, a.relu};
-#pragma unroll
-    for (int pb = 0; pb < G::PBW; ++pb) {
-        const int t = (wp * G::PBW + pb) * 32 + j;
-        const int py = t / G::TQ, px = t - py * G::TQ;
-        const int p = p0 + py, q = q0 + px;
-        const bool live = t < G::NPIX && p < P && q < Q;
-#pragma unroll
-        for (int kb = 0; kb < G::KBW; ++kb) {
-            const int kw = k0 + (wk * G::KBW + kb) * 32;
-            write_block<FUSED>(a.out_blocked != 0, fits & (kw + 32 <= K), orsrc, out_n, K, P * Q, kw, h, live, 0, p * Q + q,
-                        acc[kb][pb], tail);
-        }
-    }
+    if (G::NFULL > 0 && wp >= G::NFULL) body(IntTag<(G::NFULL > 0 ? G::PBW - 1 : G::PBW)>{});
+    else body(IntTag<G::PBW>{});
 }
 
 template <class G, bool FUSED>
