@@ -298,6 +298,35 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_pw_kernel(const KernelArgs
     __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(out_n), 0, 0x7fffffff, 0x00020000);
     const bool fits = (long long)KO * HW * 4 * (G::FLAT ? G::TQ / HW + 2 : 1) < (1ll << 31);
     const Tail tail{a.bias, a.residual ? a.residual + (size_t)n * KO * HW : nullptr, a.relu};
+    if (!FUSED && !a.out_blocked && fits && k0 + G::KT <= K) {
+        // Plain output, all channels present: the wave's PBW blocks are consecutive pixels,
+        // so storing channel row by channel row (blocks innermost) sends PBW * 128 contiguous
+        // bytes of one row to memory back to back instead of 128 bytes per row and block.
+        unsigned voff[G::PBW];
+        const unsigned oplane = (unsigned)HW * 4u;
+#pragma unroll
+        for (int pb = 0; pb < G::PBW; ++pb) {
+            const int m = m0 + pb * 32 + j;
+            int ni, ml;
+            locate(m, ni, ml);
+            const size_t o = (size_t)ni * K * HW + ml;
+            voff[pb] = m < M ? (unsigned)o * 4u + (unsigned)(4 * h) * oplane : 0x80000000u;
+        }
+#pragma unroll
+        for (int kb = 0; kb < G::KBW; ++kb) {
+            const int kw = k0 + (wk * G::KBW + kb) * 32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int soff = (kw + 8 * (v >> 2) + (v & 3)) * (int)oplane;
+#pragma unroll
+                for (int pb = 0; pb < G::PBW; ++pb) {
+                    const float f = acc[kb][pb][v];
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, f), orsrc, (int)voff[pb], soff, 0);
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int pb = 0; pb < G::PBW; ++pb) {
         const int m = m0 + pb * 32 + j;
