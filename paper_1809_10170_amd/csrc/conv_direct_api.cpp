@@ -535,12 +535,13 @@ int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W
         if (v.S == 0 ? stride > v.stride : (v.S != S || v.stride != stride)) continue;   // S = 0: the fallback
         if (v.pack && (C * S > 32 * v.pack || C > 32 * v.CBW)) continue;
         if (v.qw && v.qw != s.Q) continue;
+        if (v.allr && (R != S || stride != 1)) continue;
         // used fraction of the MFMA work: pixels of a row over whole chunks, output and input channels over whole tiles
         const double cols = v.pack ? (double)C * S / (32.0 * v.pack) : (double)C / ((double)cdiv(C, 32 * v.CBW) * 32 * v.CBW);
         const double pix = v.qw ? (double)s.P * s.Q / ((double)cdiv(s.P, v.PXC / v.qw) * v.PXC) : (double)s.Q / ((double)cdiv(s.Q, v.PXC) * v.PXC);
         // (two workgroups per CU keep the matrix pipes busier than one: a wave's waits are covered)
         const double score = pix * (v.per_cu == 2 ? 1.12 : 1.0) *
-                             ((double)K / ((double)cdiv(K, 32 * v.WK) * 32 * v.WK)) * cols * (v.WK == 4 ? 1.0 : 0.98) * (v.S == 0 ? 0.5 : 1.0);
+                             ((double)K / ((double)cdiv(K, 32 * v.WK) * 32 * v.WK)) * cols * (v.WK == 4 ? 1.0 : 0.98) * (v.S == 0 ? 0.5 : 1.0) * (v.allr ? 1.25 : 1.0);   // (coalesced atomic additions, dy staged once for all filter rows: measured 1.2 to 1.3)
         if (!best || score > best_score) {
             best = &v;
             best_score = score;
@@ -554,12 +555,12 @@ int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W
     p->wv = best;
     p->ktiles = cdiv(K, 32 * best->WK);
     p->wg_cgroups = cdiv(C, 32 * best->CBW);
-    const int64_t tiles = (int64_t)p->ktiles * p->wg_cgroups * R * (best->S == 0 ? S : 1);   // (fallback: one tap each)
+    const int64_t tiles = (int64_t)p->ktiles * p->wg_cgroups * (best->allr ? 1 : R) * (best->S == 0 ? S : 1);   // (fallback: one tap each)
     // How many workgroups share the pixels of one result tile: more of them fill the chip more
     // evenly, but every one adds a full set of atomic additions into dw.  One or two workgroups run
     // per CU at a time (their LDS).  Estimated clocks: rounds * (chunks of a workgroup * MFMA clocks of a
     // chunk + the atomics of its accumulators), the constants fitted to measurements.
-    const int nblk = best->pack ? best->pack : best->CBW * (best->S == 0 ? 1 : S);
+    const int nblk = best->pack ? best->pack : best->CBW * (best->S == 0 ? 1 : S) * (best->allr ? R : 1);
     const int npx = best->qw ? (best->PXC / best->qw) * best->qw : best->PXC;
     const int64_t units = best->qw ? (int64_t)N * cdiv(s.P, best->PXC / best->qw) : (int64_t)N * s.P;
     const int64_t chunks_per_unit = best->qw ? 1 : cdiv(s.Q, best->PXC);

@@ -45,12 +45,21 @@ namespace convd {
 // S = 0: the fallback for any filter width and any stride up to ST (which then only sizes the LDS):
 // the filter column becomes one more grid dimension, a wave owns CBW blocks of one tap, and the
 // stride is read at run time.
-template <int S_, int ST_, int CBW_, int WK_, int PXC_, int PACK_ = 0, int QW_ = 0>
+//
+// AR = 1 (square filters, stride 1): a wave owns ALL S*S taps of 32*CBW input channels instead of the S
+// taps of one filter row, and the MFMA columns are the flattened (channel, tap) indices c*S*S + r*S + s
+// in blocks of 32.  The filter row is then no grid dimension: a chunk stages the S input rows its output
+// row needs (dy is staged once for all of them), and, above all, the 32 lanes of an accumulator row hold
+// 32 CONSECUTIVE floats of dw[k][.][.][.], so that a wave's atomic additions cover two 128-byte lines
+// instead of some twenty.  In LDS an input row is RP words and a channel S*RP words with RP = S (mod 32):
+// the 32 columns of a block then read 32 different banks.
+template <int S_, int ST_, int CBW_, int WK_, int PXC_, int PACK_ = 0, int QW_ = 0, int AR_ = 0>
 struct WgGeom {
-    static constexpr int S = S_, ST = ST_, CBW = CBW_, WK = WK_, PXC = PXC_, PACK = PACK_, QW = QW_;
+    static constexpr int S = S_, ST = ST_, CBW = CBW_, WK = WK_, PXC = PXC_, PACK = PACK_, QW = QW_, AR = AR_;
     static constexpr bool RT = S_ == 0;
     static constexpr int SB = RT ? 1 : S_;               // filter columns a wave owns
-    static constexpr int NBLK = PACK ? PACK : CBW * SB;  // accumulator blocks per wave
+    static constexpr int NR = AR ? S_ : 1;               // filter rows a wave owns
+    static constexpr int NBLK = PACK ? PACK : CBW * SB * NR;  // accumulator blocks per wave
     static constexpr int RPC = QW ? PXC / QW : 1;        // output rows per chunk
     static constexpr int NPX = QW ? RPC * QW : PXC;      // pixels per chunk
     static constexpr int PXR = 32;                       // QW: LDS words from one input row to the next
@@ -65,7 +74,9 @@ struct WgGeom {
     static constexpr int WX = ((QW ? QW : PXC) - 1) * ST + SB;  // input columns a chunk needs (fallback: at most)
     static_assert(!RT || (PACK == 0 && QW == 0), "the fallback uses plain row chunks");
     static constexpr int NLX = (WX + 63) / 64;            // 64-lane loads per input channel (row chunks)
-    static constexpr int PX = QW ? RPC * PXR + 1 : NLX * 64 + 1;   // LDS pitch of an input channel (odd: 32 channels, 32 banks)
+    static constexpr int RP = WX + ((S_ - WX) % 32 + 32) % 32;     // AR: LDS pitch of an input row, = S (mod 32)
+    static constexpr int PX = AR ? NR * RP : QW ? RPC * PXR + 1 : NLX * 64 + 1;   // LDS pitch of an input channel (odd: 32 channels, 32 banks)
+    static_assert(!AR || (PACK == 0 && QW == 0 && !RT && ST == 1 && (32 * CBW * S_ * S_) % 32 == 0), "all-rows mode: plain row chunks, stride 1");
     static_assert(!QW || (WX <= PXR && RPC >= 1 && PACK == 0), "small-map chunks: an input row fits 32 words");
     static constexpr int ABUF = KT * PA, XBUF = CT * PX;  // floats
     static constexpr int BUF = ABUF + XBUF;
@@ -102,7 +113,8 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
     int s0 = 0;                                      // fallback: the filter column of this workgroup
     if (G::RT) { s0 = bid % SFILT;  bid /= SFILT; }
     const int cg = bid % cgroups;  bid /= cgroups;
-    const int r = bid % R;           bid /= R;
+    int r = 0;                                       // (all-rows mode: no such grid dimension)
+    if (!G::AR) { r = bid % R;  bid /= R; }
     const int kt = bid % ktiles;
     const int ps = bid / ktiles;
     const int k0 = kt * G::KT, c0 = cg * G::CT;
@@ -117,7 +129,7 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
         for (; u < rows_all; u += splits) {
             n = u / PG;
             p = (u - n * PG) * G::RPC;
-            if (G::QW || (unsigned)(p * st + r - pad) < (unsigned)H) break;
+            if (G::QW || G::AR || (unsigned)(p * st + r - pad) < (unsigned)H) break;
         }
         if (u >= rows_all) n = N;
     };
@@ -177,6 +189,36 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
                     }
                 }
             }
+        } else if constexpr (G::AR != 0) {
+            // S input rows per channel, RP words apart; lanes past a row's RP words take no part (a disabled
+            // lane writes nothing), columns or rows outside the image load zeros
+            const int iw0 = sq0 - pad;
+            const float *base = xp + ((size_t)sn * C + c0) * H * W;
+            __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
+            const int plane = H * W * 4;
+            unsigned voff[G::NLX];
+#pragma unroll
+            for (int u = 0; u < G::NLX; ++u) {
+                const int col = u * 64 + lane, iw = iw0 + col;
+                voff[u] = (col < G::WX && (unsigned)iw < (unsigned)W) ? (unsigned)iw * 4u : 0x80000000u;
+            }
+#pragma unroll
+            for (int i = 0; i < G::CT / G::WK; ++i) {
+                const int ch = i * G::WK + wave;
+                if (c0 + ch < C) {
+#pragma unroll
+                    for (int ri = 0; ri < G::NR; ++ri) {
+                        const int ih = sp + ri - pad;
+                        const bool rowok = (unsigned)ih < (unsigned)H;
+#pragma unroll
+                        for (int u = 0; u < G::NLX; ++u)
+                            if (u * 64 + lane < G::RP)
+                                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(xbuf + ch * G::PX + ri * G::RP + u * 64), 4,
+                                                                         rowok ? voff[u] : 0x80000000u,
+                                                                         ch * plane + (rowok ? ih : 0) * W * 4, 0, 0);
+                    }
+                }
+            }
         } else {
             const int ih = sp * st + r - pad;              // exists (the chunk list skips rows without one)
             const int iw0 = sq0 * st - pad + s0;
@@ -222,6 +264,10 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
         if (G::PACK) {
             const int col = b * 32 + j < C * G::S ? b * 32 + j : 0;   // (columns past C*S: any valid position, discarded)
             xoff[b] = (col / G::S) * G::PX + col % G::S + h * G::ST;
+        } else if (G::AR) {
+            constexpr int SS = G::SB * G::NR;                         // taps per channel
+            const int col = b * 32 + j, tap = col % SS;
+            xoff[b] = (col / SS) * G::PX + (tap / G::SB) * G::RP + tap % G::SB + h;
         } else {
             xoff[b] = ((b / G::SB) * 32 + j) * G::PX + b % G::SB + (G::QW ? 0 : h * st);
         }
@@ -246,19 +292,19 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
         }
         return 2 * t * st;
     };
-    // one chunk out of buffer bf (a compile-time constant): meet, send the next chunk's loads, multiply
-    auto chunk = [&](auto bft) __attribute__((always_inline)) {
-        constexpr int bf = decltype(bft)::value;
+    // one chunk out of buffer bf, whose per-lane LDS offsets are aoffc and xoffc: meet, send the next
+    // chunk's loads, multiply
+    auto chunk_body = [&](int bf, int aoffc, const int (&xoffc)[G::NBLK]) __attribute__((always_inline)) {
         advance();                                            // (n, p, q0) is now the next chunk
         __syncthreads();   // chunk bf has landed (the barrier's fence waits for the LDS-direct loads) and
                            // every wave has left the other buffer
         if (n < N) stage(bf ^ 1, n, p, q0);
         // operands of step t+1 are fetched from LDS while step t multiplies
-        float an = lds[aoffB[bf]], bn[G::NBLK];
+        float an = lds[aoffc], bn[G::NBLK];
         {
             const int po = pix_off(0);
 #pragma unroll
-            for (int bb = 0; bb < G::NBLK; ++bb) bn[bb] = lds[xoffB[bf][bb] + po];
+            for (int bb = 0; bb < G::NBLK; ++bb) bn[bb] = lds[xoffc[bb] + po];
         }
 #pragma unroll
         for (int t = 0; t < NST; ++t) {
@@ -267,10 +313,10 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
 #pragma unroll
             for (int bb = 0; bb < G::NBLK; ++bb) bv[bb] = bn[bb];
             if (t + 1 < NST) {
-                an = lds[aoffB[bf] + 2 * (t + 1)];
+                an = lds[aoffc + 2 * (t + 1)];
                 const int po = pix_off(t + 1);
 #pragma unroll
-                for (int bb = 0; bb < G::NBLK; ++bb) bn[bb] = lds[xoffB[bf][bb] + po];
+                for (int bb = 0; bb < G::NBLK; ++bb) bn[bb] = lds[xoffc[bb] + po];
             }
 #pragma unroll
             for (int bb = 0; bb < G::NBLK; ++bb)
@@ -278,15 +324,44 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
         }
     };
     if (n < N) stage(0, n, p, q0);
-    while (n < N) {
-        chunk(IntTag<0>{});
-        if (!(n < N)) break;
-        chunk(IntTag<1>{});
+    if constexpr (G::AR != 0) {
+        // One loop body for both buffers (the buffer's base is added to the per-lane offsets once per
+        // chunk): with nine accumulator blocks a loop unrolled over the two buffers, whose second half
+        // can be left early, costs a second set of accumulator registers.
+        int bf = 0;
+        while (n < N) {
+            int xoffc[G::NBLK];
+#pragma unroll
+            for (int bb = 0; bb < G::NBLK; ++bb) xoffc[bb] = xoff[bb] + bf * G::BUF + G::ABUF;
+            chunk_body(bf, aoff + bf * G::BUF, xoffc);
+            bf ^= 1;
+        }
+    } else {
+        // (the loop is unrolled over the two buffers, whose offsets are then constants of each half)
+        while (n < N) {
+            chunk_body(0, aoffB[0], xoffB[0]);
+            if (!(n < N)) break;
+            chunk_body(1, aoffB[1], xoffB[1]);
+        }
     }
 
     // partial sums of this pixel split -> dw (cleared before the launch)
     const int SF = G::RT ? SFILT : G::S;             // filter width
     const int RS = R * SF;
+    if constexpr (G::AR != 0) {
+        // column b*32 + j is float b*32 + j of the run dw[k][c0 .. c0 + CT)[.][.]
+#pragma unroll
+        for (int b = 0; b < G::NBLK; ++b) {
+            const int col = b * 32 + j;
+            const bool cok = c0 + col / (G::SB * G::NR) < C;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int k = k0 + wave * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (k < K && cok) unsafeAtomicAdd(dwp + ((size_t)k * C + c0) * (G::SB * G::NR) + col, acc[b][v]);
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int b = 0; b < G::NBLK; ++b) {
         const int col = b * 32 + j;
@@ -320,7 +395,7 @@ static hipError_t launch_wg(const WgradArgs &a, unsigned grid, hipStream_t strea
 template <class G>
 constexpr WgradVariant make_wg(const char *name)
 {
-    return WgradVariant{name, G::S, G::ST, G::CBW, G::WK, G::PXC, G::PACK, G::QW, G::LDS_BYTES <= 80 * 1024 ? 2 : 1, &launch_wg<G>};
+    return WgradVariant{name, G::S, G::ST, G::CBW, G::WK, G::PXC, G::PACK, G::QW, G::LDS_BYTES <= 80 * 1024 ? 2 : 1, &launch_wg<G>, G::AR};
 }
 
 // name: w<S>s<stride>_c<channels per workgroup>_k<output channels per workgroup>_p<pixels per chunk>
@@ -336,6 +411,9 @@ static WgradVariant g_wgrad[] = {
     make_wg<WgGeom<1, 1, 4, 2, 64>>("w1s1_c128_k64_p64"),
     make_wg<WgGeom<7, 2, 1, 2, 64>>("w7s2_c32_k64_p64"),
     make_wg<WgGeom<11, 4, 1, 4, 32>>("w11s4_c32_k128_p32"),
+    // all S*S taps per wave, columns = consecutive floats of dw (coalesced atomic additions)
+    make_wg<WgGeom<3, 1, 1, 4, 32, 0, 0, 1>>("w3s1_ar_c32_k128_p32"),
+    make_wg<WgGeom<3, 1, 1, 4, 64, 0, 0, 1>>("w3s1_ar_c32_k128_p64"),
     // any filter width, any stride up to 4
     make_wg<WgGeom<0, 4, 2, 4, 32>>("w_any_c64_k128_p32"),
     // small maps: chunks of whole output rows of a fixed width

@@ -11,7 +11,7 @@ struct WgradArgs {
     const float *dy;    // [N][K][P][Q]
     float *dw;          // [K][C][R][S], cleared before the launch, added to atomically
     Shape s;
-    int ktiles, cgroups, splits;   // grid = splits * ktiles * R * cgroups workgroups
+    int ktiles, cgroups, splits;   // grid = splits * ktiles * R * cgroups workgroups (all-rows variants: without R)
 };
 
 struct WgradVariant {
@@ -22,6 +22,7 @@ struct WgradVariant {
     int qw;             // > 0: chunks of PXC / qw whole output rows; needs Q == qw
     int per_cu;         // workgroups whose LDS fits one CU together (1 or 2)
     hipError_t (*launch)(const WgradArgs &, unsigned grid, hipStream_t stream);
+    int allr;           // 1: a workgroup owns all filter rows (needs R == S, stride 1); the filter row is no grid dimension
 };
 
 const WgradVariant *wgrad_table(int *count);
