@@ -364,7 +364,7 @@ int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
                              "variant=%s kind=wgrad N=%d C=%d H=%d W=%d K=%d R=%d S=%d stride=%d pad=%d P=%d Q=%d "
                              "ktiles=%d cgroups=%d splits=%d grid=%u threads=%d workspace_bytes=0",
                              plan->wv->name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, plan->ktiles,
-                             plan->wg_cgroups, plan->wg_splits, plan->grid, 64 * plan->wv->WK);
+                             plan->wg_cgroups, plan->wg_splits, plan->grid, 64 * plan->wv->WK * plan->wv->WC);
     }
     const Variant &v = *plan->v;
     const Shape &s = plan->s;
@@ -535,13 +535,13 @@ int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W
         if (v.S == 0 ? stride > v.stride : (v.S != S || v.stride != stride)) continue;   // S = 0: the fallback
         if (v.pack && (C * S > 32 * v.pack || C > 32 * v.CBW)) continue;
         if (v.qw && v.qw != s.Q) continue;
-        if (v.allr && (R != S || stride != 1)) continue;
+        if (v.allr && R != S) continue;
         // used fraction of the MFMA work: pixels of a row over whole chunks, output and input channels over whole tiles
-        const double cols = v.pack ? (double)C * S / (32.0 * v.pack) : (double)C / ((double)cdiv(C, 32 * v.CBW) * 32 * v.CBW);
+        const double cols = v.pack ? (double)C * S / (32.0 * v.pack) : (double)C / ((double)cdiv(C, 32 * v.CBW * v.WC) * 32 * v.CBW * v.WC);
         const double pix = v.qw ? (double)s.P * s.Q / ((double)cdiv(s.P, v.PXC / v.qw) * v.PXC) : (double)s.Q / ((double)cdiv(s.Q, v.PXC) * v.PXC);
         // (two workgroups per CU keep the matrix pipes busier than one: a wave's waits are covered)
         const double score = pix * (v.per_cu == 2 ? 1.12 : 1.0) *
-                             ((double)K / ((double)cdiv(K, 32 * v.WK) * 32 * v.WK)) * cols * (v.WK == 4 ? 1.0 : 0.98) * (v.S == 0 ? 0.5 : 1.0) * (v.allr ? 1.25 : 1.0);   // (coalesced atomic additions, dy staged once for all filter rows: measured 1.2 to 1.3)
+                             ((double)K / ((double)cdiv(K, 32 * v.WK) * 32 * v.WK)) * cols * (v.WK * v.WC == 4 ? 1.0 : 0.98) * (v.S == 0 ? 0.5 : 1.0) * (v.allr ? 1.25 : 1.0);   // (coalesced atomic additions, dy staged once for all filter rows: measured 1.2 to 1.3)
         if (!best || score > best_score) {
             best = &v;
             best_score = score;
@@ -554,7 +554,7 @@ int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W
     p->v = nullptr;
     p->wv = best;
     p->ktiles = cdiv(K, 32 * best->WK);
-    p->wg_cgroups = cdiv(C, 32 * best->CBW);
+    p->wg_cgroups = cdiv(C, 32 * best->CBW * best->WC);
     const int64_t tiles = (int64_t)p->ktiles * p->wg_cgroups * (best->allr ? 1 : R) * (best->S == 0 ? S : 1);   // (fallback: one tap each)
     // How many workgroups share the pixels of one result tile: more of them fill the chip more
     // evenly, but every one adds a full set of atomic additions into dw.  One or two workgroups run

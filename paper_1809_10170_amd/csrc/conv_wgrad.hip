@@ -53,19 +53,25 @@ namespace convd {
 // 32 CONSECUTIVE floats of dw[k][.][.][.], so that a wave's atomic additions cover two 128-byte lines
 // instead of some twenty.  In LDS an input row is RP words and a channel S*RP words with RP = S (mod 32):
 // the 32 columns of a block then read 32 different banks.
-template <int S_, int ST_, int CBW_, int WK_, int PXC_, int PACK_ = 0, int QW_ = 0, int AR_ = 0>
+//
+// WC > 1: the waves of a workgroup also spread over WC groups of 32*CBW input channels (wave = k-block +
+// WK * channel group), which all read the same staged dy: a tile of 32*WK output x 32*CBW*WC input
+// channels whose accumulators are shared out over WK*WC waves.
+template <int S_, int ST_, int CBW_, int WK_, int PXC_, int PACK_ = 0, int QW_ = 0, int AR_ = 0, int WC_ = 1>
 struct WgGeom {
-    static constexpr int S = S_, ST = ST_, CBW = CBW_, WK = WK_, PXC = PXC_, PACK = PACK_, QW = QW_, AR = AR_;
+    static constexpr int S = S_, ST = ST_, CBW = CBW_, WK = WK_, PXC = PXC_, PACK = PACK_, QW = QW_, AR = AR_, WC = WC_;
+    static constexpr int NW = WK_ * WC_;                 // waves per workgroup
     static constexpr bool RT = S_ == 0;
     static constexpr int SB = RT ? 1 : S_;               // filter columns a wave owns
     static constexpr int NR = AR ? S_ : 1;               // filter rows a wave owns
     static constexpr int NBLK = PACK ? PACK : CBW * SB * NR;  // accumulator blocks per wave
     static constexpr int RPC = QW ? PXC / QW : 1;        // output rows per chunk
     static constexpr int NPX = QW ? RPC * QW : PXC;      // pixels per chunk
-    static constexpr int PXR = 32;                       // QW: LDS words from one input row to the next
-    static constexpr int NT = 64 * WK;
+    static constexpr int PXR = AR_ ? 32 + S_ : 32;       // QW: LDS words from one input row to the next (all-rows mode: = S mod 32)
+    static constexpr int XROWS = QW ? RPC + NR - 1 : NR; // input rows a chunk stages per channel
+    static constexpr int NT = 64 * NW;
     static constexpr int KT = 32 * WK;                    // output channels per workgroup
-    static constexpr int CT = 32 * CBW;                   // input channels per workgroup
+    static constexpr int CT = 32 * CBW * WC;              // input channels per workgroup
     // LDS pitch of a dy row: odd, so that the 32 rows one half-wave reads at the same pixel fall into
     // 32 different banks.  A 32-pixel chunk is staged by the first 32 lanes only, so that two
     // workgroups fit the LDS of a CU.
@@ -75,8 +81,11 @@ struct WgGeom {
     static_assert(!RT || (PACK == 0 && QW == 0), "the fallback uses plain row chunks");
     static constexpr int NLX = (WX + 63) / 64;            // 64-lane loads per input channel (row chunks)
     static constexpr int RP = WX + ((S_ - WX) % 32 + 32) % 32;     // AR: LDS pitch of an input row, = S (mod 32)
-    static constexpr int PX = AR ? NR * RP : QW ? RPC * PXR + 1 : NLX * 64 + 1;   // LDS pitch of an input channel (odd: 32 channels, 32 banks)
-    static_assert(!AR || (PACK == 0 && QW == 0 && !RT && ST == 1 && (32 * CBW * S_ * S_) % 32 == 0), "all-rows mode: plain row chunks, stride 1");
+    // LDS pitch of an input channel: odd (32 channels, 32 banks); all-rows mode: = S*S (mod 32), like the columns
+    static constexpr int PX = AR ? (QW ? XROWS * PXR + ((NR * S_ - XROWS * PXR) % 32 + 32) % 32 : NR * RP)
+                                 : QW ? RPC * PXR + 1 : NLX * 64 + 1;
+    static_assert(!AR || (PACK == 0 && !RT && (QW == 0 || ST == 1)), "all-rows mode: no packing; small-map chunks at stride 1");
+    static_assert(WC == 1 || (PACK == 0 && 32 % WC == 0), "channel groups of waves: whole dy rows per wave");
     static_assert(!QW || (WX <= PXR && RPC >= 1 && PACK == 0), "small-map chunks: an input row fits 32 words");
     static constexpr int ABUF = KT * PA, XBUF = CT * PX;  // floats
     static constexpr int BUF = ABUF + XBUF;
@@ -92,7 +101,8 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
     extern __shared__ __align__(16) float lds[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    __builtin_assume(wave >= 0 && wave < G::WK);
+    __builtin_assume(wave >= 0 && wave < G::NW);
+    const int wk = wave % G::WK, wc = wave / G::WK;   // k-block and channel group of the wave
     const int h = lane >> 5, j = lane & 31;
     const int N = a.s.N, C = a.s.C, H = a.s.H, W = a.s.W, K = a.s.K, R = a.s.R, P = a.s.P, Q = a.s.Q, pad = a.s.pad;
     const int st = G::RT ? a.s.stride : G::ST;       // (a compile-time constant except in the fallback)
@@ -125,6 +135,8 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
     const int PG = G::QW ? (P + G::RPC - 1) / G::RPC : P;   // units per image
     const int rows_all = N * PG;
     int u = ps, n = 0, p = 0, q0 = 0;
+    // the slack behind the second buffer is read (times a zero of dy) when a chunk has an odd number of pixels
+    if (threadIdx.x < 64) lds[2 * G::BUF + threadIdx.x] = 0.f;
     auto settle = [&]() __attribute__((always_inline)) {   // move u forward to the next unit of this split (row chunks: whose input row exists)
         for (; u < rows_all; u += splits) {
             n = u / PG;
@@ -158,8 +170,8 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
             const int plane = P * Q * 4;
             if (!G::HALF_A || lane < 32) {   // (a disabled lane writes nothing: rows 33 words apart do not overlap)
 #pragma unroll
-                for (int i = 0; i < G::KT / G::WK; ++i) {
-                    const int row = i * G::WK + wave;
+                for (int i = 0; i < G::KT / G::NW; ++i) {
+                    const int row = i * G::NW + wave;
                     if (k0 + row < K)
                         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(abuf + row * G::PA), 4, voff, row * plane, 0, 0);
                 }
@@ -175,11 +187,11 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
             const bool colok = lane < G::WX && (unsigned)iw < (unsigned)W;
             if (lane < G::PXR) {
 #pragma unroll
-                for (int i = 0; i < G::CT / G::WK; ++i) {
-                    const int ch = i * G::WK + wave;
+                for (int i = 0; i < G::CT / G::NW; ++i) {
+                    const int ch = i * G::NW + wave;
                     if (c0 + ch < C) {
 #pragma unroll
-                        for (int ri = 0; ri < G::RPC; ++ri) {
+                        for (int ri = 0; ri < G::XROWS; ++ri) {   // (all-rows mode: the halo rows of all taps too)
                             const int ih = (sp + ri) * G::ST + r - pad;
                             const bool rowok = (unsigned)ih < (unsigned)H;
                             const unsigned voff = (colok && rowok) ? (unsigned)iw * 4u : 0x80000000u;
@@ -192,7 +204,7 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
         } else if constexpr (G::AR != 0) {
             // S input rows per channel, RP words apart; lanes past a row's RP words take no part (a disabled
             // lane writes nothing), columns or rows outside the image load zeros
-            const int iw0 = sq0 - pad;
+            const int iw0 = sq0 * G::ST - pad;
             const float *base = xp + ((size_t)sn * C + c0) * H * W;
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
             const int plane = H * W * 4;
@@ -203,12 +215,12 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
                 voff[u] = (col < G::WX && (unsigned)iw < (unsigned)W) ? (unsigned)iw * 4u : 0x80000000u;
             }
 #pragma unroll
-            for (int i = 0; i < G::CT / G::WK; ++i) {
-                const int ch = i * G::WK + wave;
+            for (int i = 0; i < G::CT / G::NW; ++i) {
+                const int ch = i * G::NW + wave;
                 if (c0 + ch < C) {
 #pragma unroll
                     for (int ri = 0; ri < G::NR; ++ri) {
-                        const int ih = sp + ri - pad;
+                        const int ih = sp * G::ST + ri - pad;
                         const bool rowok = (unsigned)ih < (unsigned)H;
 #pragma unroll
                         for (int u = 0; u < G::NLX; ++u)
@@ -233,8 +245,8 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
                 voff[u] = (col < wx && (unsigned)iw < (unsigned)W) ? (unsigned)iw * 4u : 0x80000000u;
             }
 #pragma unroll
-            for (int i = 0; i < G::CT / G::WK; ++i) {
-                const int ch = i * G::WK + wave;
+            for (int i = 0; i < G::CT / G::NW; ++i) {
+                const int ch = i * G::NW + wave;
                 if (c0 + ch < C) {
 #pragma unroll
                     for (int u = 0; u < G::NLX; ++u)
@@ -255,7 +267,7 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
     // registers (one set per buffer, the chunk loop is unrolled over the two buffers), the step's
     // part into the immediate -- no vector ALU work per fetch, which a wave between its own MFMAs
     // would wait some 20 clocks for each time.
-    const int aoff = (wave * 32 + j) * G::PA + h;            // lane (k = j, pixel parity h)
+    const int aoff = (wk * 32 + j) * G::PA + h;              // lane (k = j, pixel parity h)
     // LDS offset of the lane's B operand of block b at pixel pair 0: column j of the block is input
     // channel cb*32 + j at filter column s (b = cb*S + s), or the packed pair (c, s) = divmod(b*32 + j, S)
     int xoff[G::NBLK];
@@ -267,9 +279,9 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
         } else if (G::AR) {
             constexpr int SS = G::SB * G::NR;                         // taps per channel
             const int col = b * 32 + j, tap = col % SS;
-            xoff[b] = (col / SS) * G::PX + (tap / G::SB) * G::RP + tap % G::SB + h;
+            xoff[b] = (wc * 32 * G::CBW + col / SS) * G::PX + (tap / G::SB) * (G::QW ? G::PXR : G::RP) + tap % G::SB + (G::QW ? 0 : h * G::ST);
         } else {
-            xoff[b] = ((b / G::SB) * 32 + j) * G::PX + b % G::SB + (G::QW ? 0 : h * st);
+            xoff[b] = ((wc * G::CBW + b / G::SB) * 32 + j) * G::PX + b % G::SB + (G::QW ? 0 : h * st);
         }
     }
 
@@ -353,11 +365,11 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
 #pragma unroll
         for (int b = 0; b < G::NBLK; ++b) {
             const int col = b * 32 + j;
-            const bool cok = c0 + col / (G::SB * G::NR) < C;
+            const bool cok = c0 + wc * 32 * G::CBW + col / (G::SB * G::NR) < C;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int k = k0 + wave * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-                if (k < K && cok) unsafeAtomicAdd(dwp + ((size_t)k * C + c0) * (G::SB * G::NR) + col, acc[b][v]);
+                const int k = k0 + wk * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (k < K && cok) unsafeAtomicAdd(dwp + ((size_t)k * C + c0 + wc * 32 * G::CBW) * (G::SB * G::NR) + col, acc[b][v]);
             }
         }
         return;
@@ -365,11 +377,11 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
 #pragma unroll
     for (int b = 0; b < G::NBLK; ++b) {
         const int col = b * 32 + j;
-        const int c = G::PACK ? col / G::SB : c0 + (b / G::SB) * 32 + j;
+        const int c = G::PACK ? col / G::SB : c0 + (wc * G::CBW + b / G::SB) * 32 + j;
         const int s = G::PACK ? col % G::SB : G::RT ? s0 : b % G::SB;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int k = k0 + wave * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+            const int k = k0 + wk * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
             if (k < K && c < C) unsafeAtomicAdd(dwp + ((size_t)k * C + c) * RS + r * SF + s, acc[b][v]);
         }
     }
@@ -395,7 +407,7 @@ static hipError_t launch_wg(const WgradArgs &a, unsigned grid, hipStream_t strea
 template <class G>
 constexpr WgradVariant make_wg(const char *name)
 {
-    return WgradVariant{name, G::S, G::ST, G::CBW, G::WK, G::PXC, G::PACK, G::QW, G::LDS_BYTES <= 80 * 1024 ? 2 : 1, &launch_wg<G>, G::AR};
+    return WgradVariant{name, G::S, G::ST, G::CBW, G::WK, G::PXC, G::PACK, G::QW, G::LDS_BYTES <= 80 * 1024 ? 2 : 1, &launch_wg<G>, G::AR, G::WC};
 }
 
 // name: w<S>s<stride>_c<channels per workgroup>_k<output channels per workgroup>_p<pixels per chunk>
@@ -414,6 +426,12 @@ static WgradVariant g_wgrad[] = {
     // all S*S taps per wave, columns = consecutive floats of dw (coalesced atomic additions)
     make_wg<WgGeom<3, 1, 1, 4, 32, 0, 0, 1>>("w3s1_ar_c32_k128_p32"),
     make_wg<WgGeom<3, 1, 1, 4, 64, 0, 0, 1>>("w3s1_ar_c32_k128_p64"),
+    make_wg<WgGeom<3, 1, 1, 2, 32, 0, 0, 1, 2>>("w3s1_ar_c64_k64_p32"),
+    make_wg<WgGeom<3, 2, 1, 4, 32, 0, 0, 1>>("w3s2_ar_c32_k128_p32"),
+    make_wg<WgGeom<3, 1, 1, 4, 64, 0, 13, 1>>("w3s1_ar_c32_k128_q13"),
+    make_wg<WgGeom<3, 1, 1, 4, 64, 0, 14, 1>>("w3s1_ar_c32_k128_q14"),
+    make_wg<WgGeom<3, 1, 1, 4, 64, 0, 28, 1>>("w3s1_ar_c32_k128_q28"),
+    make_wg<WgGeom<3, 1, 1, 4, 56, 0, 7, 1>>("w3s1_ar_c32_k128_q7"),
     // any filter width, any stride up to 4
     make_wg<WgGeom<0, 4, 2, 4, 32>>("w_any_c64_k128_p32"),
     // small maps: chunks of whole output rows of a fixed width

@@ -23,6 +23,7 @@ struct WgradVariant {
     int per_cu;         // workgroups whose LDS fits one CU together (1 or 2)
     hipError_t (*launch)(const WgradArgs &, unsigned grid, hipStream_t stream);
     int allr;           // 1: a workgroup owns all filter rows (needs R == S, stride 1); the filter row is no grid dimension
+    int WC;             // groups of 32*CBW input channels per workgroup (their waves share the staged dy)
 };
 
 const WgradVariant *wgrad_table(int *count);
