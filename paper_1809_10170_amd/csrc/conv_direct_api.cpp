@@ -533,11 +533,12 @@ int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W
     for (int i = 0; i < count; ++i) {
         const convd::WgradVariant &v = table[i];
         if (v.S == 0 ? stride > v.stride : (v.S != S || v.stride != stride)) continue;   // S = 0: the fallback
-        if (v.pack && (C * S > 32 * v.pack || C > 32 * v.CBW)) continue;
+        if (v.pack && !v.allr && (C * S > 32 * v.pack || C > 32 * v.CBW)) continue;
+        if (v.pack && v.allr && (C * R * S > 32 * v.pack || C > 4)) continue;
         if (v.qw && v.qw != s.Q) continue;
         if (v.allr && R != S) continue;
         // used fraction of the MFMA work: pixels of a row over whole chunks, output and input channels over whole tiles
-        const double cols = v.pack ? (double)C * S / (32.0 * v.pack) : (double)C / ((double)cdiv(C, 32 * v.CBW * v.WC) * 32 * v.CBW * v.WC);
+        const double cols = v.pack ? (double)C * S * (v.allr ? R : 1) / (32.0 * v.pack) : (double)C / ((double)cdiv(C, 32 * v.CBW * v.WC) * 32 * v.CBW * v.WC);
         const double pix = v.qw ? (double)s.P * s.Q / ((double)cdiv(s.P, v.PXC / v.qw) * v.PXC) : (double)s.Q / ((double)cdiv(s.Q, v.PXC) * v.PXC);
         // (two workgroups per CU keep the matrix pipes busier than one: a wave's waits are covered)
         const double score = pix * (v.per_cu == 2 ? 1.12 : 1.0) *

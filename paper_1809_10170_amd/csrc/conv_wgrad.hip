@@ -71,11 +71,12 @@ struct WgGeom {
     static constexpr int XROWS = QW ? RPC + NR - 1 : NR; // input rows a chunk stages per channel
     static constexpr int NT = 64 * NW;
     static constexpr int KT = 32 * WK;                    // output channels per workgroup
-    static constexpr int CT = 32 * CBW * WC;              // input channels per workgroup
+    static constexpr int CT = (PACK && AR) ? 4 : 32 * CBW * WC;   // input channels per workgroup (packed all-rows mode:
+                                                          // the C <= 4 channels of a first layer)
     // LDS pitch of a dy row: odd, so that the 32 rows one half-wave reads at the same pixel fall into
     // 32 different banks.  A 32-pixel chunk is staged by the first 32 lanes only, so that two
     // workgroups fit the LDS of a CU.
-    static constexpr int PA = (PXC == 32 && QW_ == 0) ? 33 : 65;
+    static constexpr int PA = PXC == 32 ? 33 : 65;
     static constexpr bool HALF_A = PA == 33;
     static constexpr int WX = ((QW ? QW : PXC) - 1) * ST + SB;  // input columns a chunk needs (fallback: at most)
     static_assert(!RT || (PACK == 0 && QW == 0), "the fallback uses plain row chunks");
@@ -84,7 +85,7 @@ struct WgGeom {
     // LDS pitch of an input channel: odd (32 channels, 32 banks); all-rows mode: = S*S (mod 32), like the columns
     static constexpr int PX = AR ? (QW ? XROWS * PXR + ((NR * S_ - XROWS * PXR) % 32 + 32) % 32 : NR * RP)
                                  : QW ? RPC * PXR + 1 : NLX * 64 + 1;
-    static_assert(!AR || (PACK == 0 && !RT && (QW == 0 || ST == 1)), "all-rows mode: no packing; small-map chunks at stride 1");
+    static_assert(!AR || (!RT && (QW == 0 || (ST == 1 && PACK == 0))), "all-rows mode: small-map chunks at stride 1, unpacked");
     static_assert(WC == 1 || (PACK == 0 && 32 % WC == 0), "channel groups of waves: whole dy rows per wave");
     static_assert(!QW || (WX <= PXR && RPC >= 1 && PACK == 0), "small-map chunks: an input row fits 32 words");
     static constexpr int ABUF = KT * PA, XBUF = CT * PX;  // floats
@@ -273,12 +274,13 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
     int xoff[G::NBLK];
 #pragma unroll
     for (int b = 0; b < G::NBLK; ++b) {
-        if (G::PACK) {
+        if (G::PACK && !G::AR) {
             const int col = b * 32 + j < C * G::S ? b * 32 + j : 0;   // (columns past C*S: any valid position, discarded)
             xoff[b] = (col / G::S) * G::PX + col % G::S + h * G::ST;
         } else if (G::AR) {
             constexpr int SS = G::SB * G::NR;                         // taps per channel
-            const int col = b * 32 + j, tap = col % SS;
+            // (packed: the columns are all C*S*S (channel, tap) pairs; those past them read any valid position)
+            const int col = (!G::PACK || b * 32 + j < C * SS) ? b * 32 + j : 0, tap = col % SS;
             xoff[b] = (wc * 32 * G::CBW + col / SS) * G::PX + (tap / G::SB) * (G::QW ? G::PXR : G::RP) + tap % G::SB + (G::QW ? 0 : h * G::ST);
         } else {
             xoff[b] = ((wc * G::CBW + b / G::SB) * 32 + j) * G::PX + b % G::SB + (G::QW ? 0 : h * st);
@@ -365,7 +367,7 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
 #pragma unroll
         for (int b = 0; b < G::NBLK; ++b) {
             const int col = b * 32 + j;
-            const bool cok = c0 + wc * 32 * G::CBW + col / (G::SB * G::NR) < C;
+            const bool cok = G::PACK ? col < C * G::SB * G::NR : c0 + wc * 32 * G::CBW + col / (G::SB * G::NR) < C;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int k = k0 + wk * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
@@ -428,10 +430,17 @@ static WgradVariant g_wgrad[] = {
     make_wg<WgGeom<3, 1, 1, 4, 64, 0, 0, 1>>("w3s1_ar_c32_k128_p64"),
     make_wg<WgGeom<3, 1, 1, 2, 32, 0, 0, 1, 2>>("w3s1_ar_c64_k64_p32"),
     make_wg<WgGeom<3, 2, 1, 4, 32, 0, 0, 1>>("w3s2_ar_c32_k128_p32"),
+    // first layers: all (channel, tap) pairs of C <= 4 channels packed into blocks of 32 columns
+    make_wg<WgGeom<7, 2, 1, 2, 64, 5, 0, 1>>("w7s2_arpack5_k64_p64"),
+    make_wg<WgGeom<11, 4, 1, 4, 32, 12, 0, 1>>("w11s4_arpack12_k128_p32"),
+    make_wg<WgGeom<3, 1, 1, 4, 32, 1, 0, 1>>("w3s1_arpack1_k128_p32"),
     make_wg<WgGeom<3, 1, 1, 4, 64, 0, 13, 1>>("w3s1_ar_c32_k128_q13"),
     make_wg<WgGeom<3, 1, 1, 4, 64, 0, 14, 1>>("w3s1_ar_c32_k128_q14"),
     make_wg<WgGeom<3, 1, 1, 4, 64, 0, 28, 1>>("w3s1_ar_c32_k128_q28"),
     make_wg<WgGeom<3, 1, 1, 4, 56, 0, 7, 1>>("w3s1_ar_c32_k128_q7"),
+    make_wg<WgGeom<3, 1, 1, 4, 32, 0, 13, 1>>("w3s1_ar_c32_k128_q13h"),
+    make_wg<WgGeom<3, 1, 1, 4, 32, 0, 14, 1>>("w3s1_ar_c32_k128_q14h"),
+    make_wg<WgGeom<3, 1, 1, 4, 32, 0, 7, 1>>("w3s1_ar_c32_k128_q7h"),
     // any filter width, any stride up to 4
     make_wg<WgGeom<0, 4, 2, 4, 32>>("w_any_c64_k128_p32"),
     // small maps: chunks of whole output rows of a fixed width
