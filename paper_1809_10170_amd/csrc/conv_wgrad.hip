@@ -76,7 +76,7 @@ struct WgGeom {
     // LDS pitch of a dy row: odd, so that the 32 rows one half-wave reads at the same pixel fall into
     // 32 different banks.  A 32-pixel chunk is staged by the first 32 lanes only, so that two
     // workgroups fit the LDS of a CU.
-    static constexpr int PA = PXC == 32 ? 33 : 65;
+    static constexpr int PA = PXC <= 32 ? 33 : 65;
     static constexpr bool HALF_A = PA == 33;
     static constexpr int WX = ((QW ? QW : PXC) - 1) * ST + SB;  // input columns a chunk needs (fallback: at most)
     static_assert(!RT || (PACK == 0 && QW == 0), "the fallback uses plain row chunks");
@@ -429,6 +429,8 @@ static WgradVariant g_wgrad[] = {
     make_wg<WgGeom<3, 1, 1, 4, 32, 0, 0, 1>>("w3s1_ar_c32_k128_p32"),
     make_wg<WgGeom<3, 1, 1, 4, 64, 0, 0, 1>>("w3s1_ar_c32_k128_p64"),
     make_wg<WgGeom<3, 1, 1, 2, 32, 0, 0, 1, 2>>("w3s1_ar_c64_k64_p32"),
+    make_wg<WgGeom<3, 1, 1, 4, 28, 0, 0, 1>>("w3s1_ar_c32_k128_p28"),
+    make_wg<WgGeom<3, 2, 1, 4, 28, 0, 0, 1>>("w3s2_ar_c32_k128_p28"),
     make_wg<WgGeom<3, 2, 1, 4, 32, 0, 0, 1>>("w3s2_ar_c32_k128_p32"),
     // first layers: all (channel, tap) pairs of C <= 4 channels packed into blocks of 32 columns
     make_wg<WgGeom<7, 2, 1, 2, 64, 5, 0, 1>>("w7s2_arpack5_k64_p64"),
