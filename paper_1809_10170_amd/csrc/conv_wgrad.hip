@@ -427,7 +427,6 @@ static WgradVariant g_wgrad[] = {
     make_wg<WgGeom<11, 4, 1, 4, 32>>("w11s4_c32_k128_p32"),
     // all S*S taps per wave, columns = consecutive floats of dw (coalesced atomic additions)
     make_wg<WgGeom<3, 1, 1, 4, 32, 0, 0, 1>>("w3s1_ar_c32_k128_p32"),
-    make_wg<WgGeom<3, 1, 1, 4, 64, 0, 0, 1>>("w3s1_ar_c32_k128_p64"),
     make_wg<WgGeom<3, 1, 1, 2, 32, 0, 0, 1, 2>>("w3s1_ar_c64_k64_p32"),
     make_wg<WgGeom<3, 1, 1, 4, 28, 0, 0, 1>>("w3s1_ar_c32_k128_p28"),
     make_wg<WgGeom<3, 2, 1, 4, 28, 0, 0, 1>>("w3s2_ar_c32_k128_p28"),
@@ -436,9 +435,6 @@ static WgradVariant g_wgrad[] = {
     make_wg<WgGeom<7, 2, 1, 2, 64, 5, 0, 1>>("w7s2_arpack5_k64_p64"),
     make_wg<WgGeom<11, 4, 1, 4, 32, 12, 0, 1>>("w11s4_arpack12_k128_p32"),
     make_wg<WgGeom<3, 1, 1, 4, 32, 1, 0, 1>>("w3s1_arpack1_k128_p32"),
-    make_wg<WgGeom<3, 1, 1, 4, 64, 0, 13, 1>>("w3s1_ar_c32_k128_q13"),
-    make_wg<WgGeom<3, 1, 1, 4, 64, 0, 14, 1>>("w3s1_ar_c32_k128_q14"),
-    make_wg<WgGeom<3, 1, 1, 4, 64, 0, 28, 1>>("w3s1_ar_c32_k128_q28"),
     make_wg<WgGeom<3, 1, 1, 4, 56, 0, 7, 1>>("w3s1_ar_c32_k128_q7"),
     make_wg<WgGeom<3, 1, 1, 4, 32, 0, 13, 1>>("w3s1_ar_c32_k128_q13h"),
     make_wg<WgGeom<3, 1, 1, 4, 32, 0, 14, 1>>("w3s1_ar_c32_k128_q14h"),

@@ -69,6 +69,52 @@ def test_small_shapes_random_inputs(oracle, shape):
     assert err <= tol, (info["variant"], err)
 
 
+@pytest.mark.parametrize("shape,variant", [
+    ((2, 40, 20, 64, 48, 3, 3, 1, 1), "w3s1_ar_c64_k64_p32"),       # waves spread over two channel groups
+    ((2, 20, 9, 56, 70, 3, 3, 1, 1), "w3s1_ar_c32_k128_p28"),       # rows of two 28-pixel chunks
+    ((2, 70, 11, 64, 130, 3, 3, 1, 1), "w3s1_ar_c32_k128_p32"),     # three channel groups, two k tiles
+    ((1, 12, 21, 127, 40, 3, 3, 2, 1), "w3s2_ar_c32_k128_p32"),     # stride 2, rows of 64
+    ((2, 12, 57, 55, 130, 3, 3, 2, 1), "w3s2_ar_c32_k128_p28"),     # stride 2, rows of 28
+    ((3, 9, 4, 7, 33, 3, 3, 1, 1), "w3s1_ar_c32_k128_q7h"),         # 4 rows of 7 per chunk
+    ((5, 33, 7, 7, 70, 3, 3, 1, 1), "w3s1_ar_c32_k128_q7"),         # whole 7x7 maps per chunk
+    ((3, 20, 14, 14, 40, 3, 3, 1, 1), "w3s1_ar_c32_k128_q14h"),
+    ((2, 8, 22, 13, 16, 3, 3, 1, 1), "w3s1_ar_c32_k128_q13h"),
+    ((2, 2, 20, 40, 20, 3, 3, 1, 1), "w3s1_arpack1_k128_p32"),      # packed columns: 18 of 32
+    ((2, 1, 30, 30, 10, 7, 7, 2, 3), "w7s2_arpack5_k64_p64"),       # one channel
+    ((2, 3, 99, 227, 96, 11, 11, 4, 0), "w11s4_arpack12_k128_p32"),
+])
+def test_all_rows_variants_integer_inputs_bit_exact(oracle, shape, variant):
+    """Every variant whose waves own all filter rows (columns = consecutive floats of dw), on a shape
+    the planner gives to it."""
+    N, C, H, W, K, R, S, st, pd = shape
+    rng = np.random.default_rng(1000 + sum(shape))
+    x = rng.integers(-2, 3, (N, C, H, W)).astype(np.float32)
+    P, Q = oracle.out_dim(H, R, st, pd), oracle.out_dim(W, S, st, pd)
+    dy = rng.integers(-2, 3, (N, K, P, Q)).astype(np.float32)
+    got, info = _wgrad(x, dy, R, S, st, pd)
+    assert info["variant"] == variant
+    assert np.array_equal(got.astype(np.float64), oracle.conv_wgrad(x, dy, R, S, st, pd))
+
+
+def test_non_finite_lds_leftovers_do_not_leak():
+    """A chunk with an odd number of pixels reads one input position past its rows, times a zero of dy:
+    run a kernel that leaves NaNs in LDS first, then a 7x7 map (49 pixels per chunk)."""
+    N, C, H, W, K = 2, 32, 7, 7, 32
+    bad = torch.full((N, C, H, W), float("nan"), device="cuda")
+    dyb = torch.ones((N, K, H, W), device="cuda")
+    dwb = torch.empty((K, C, 3, 3), device="cuda")
+    plan = cd.Plan.wgrad(N, C, H, W, K, 3, 3, 1, 1)
+    for _ in range(3):
+        plan.run_wgrad(bad, dyb, dwb)      # fills the LDS of many CUs with NaNs
+    x = torch.ones((N, C, H, W), device="cuda")
+    dw = torch.empty((K, C, 3, 3), device="cuda")
+    plan.run_wgrad(x, dyb, dw)
+    torch.cuda.synchronize()
+    plan.destroy()
+    assert torch.isfinite(dw).all()
+    assert float(dw[0, 0, 1, 1]) == N * H * W
+
+
 def test_unsupported_stride_is_refused():
     with pytest.raises(cd.ConvDirectError) as e:
         cd.Plan.wgrad(2, 8, 40, 40, 8, 3, 3, 5, 1)
