@@ -364,7 +364,7 @@ int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
                              "variant=%s kind=wgrad N=%d C=%d H=%d W=%d K=%d R=%d S=%d stride=%d pad=%d P=%d Q=%d "
                              "ktiles=%d cgroups=%d splits=%d grid=%u threads=%d workspace_bytes=0",
                              plan->wv->name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, plan->ktiles,
-                             plan->wg_cgroups, plan->wg_splits, plan->grid, 64 * plan->wv->WK * plan->wv->WC);
+                             plan->wg_cgroups, plan->wg_splits, plan->grid, 64 * plan->wv->WK * plan->wv->WC * plan->wv->WB);
     }
     const Variant &v = *plan->v;
     const Shape &s = plan->s;
@@ -542,7 +542,7 @@ int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W
         const double pix = v.qw ? (double)s.P * s.Q / ((double)cdiv(s.P, v.PXC / v.qw) * v.PXC) : (double)s.Q / ((double)cdiv(s.Q, v.PXC) * v.PXC);
         // (two workgroups per CU keep the matrix pipes busier than one: a wave's waits are covered)
         const double score = pix * (v.per_cu == 2 ? 1.12 : 1.0) *
-                             ((double)K / ((double)cdiv(K, 32 * v.WK) * 32 * v.WK)) * cols * (v.WK * v.WC == 4 ? 1.0 : 0.98) * (v.S == 0 ? 0.5 : 1.0) * (v.allr ? 1.25 : 1.0);   // (coalesced atomic additions, dy staged once for all filter rows: measured 1.2 to 1.3)
+                             ((double)K / ((double)cdiv(K, 32 * v.WK) * 32 * v.WK)) * cols * (v.WK * v.WC * v.WB >= 4 ? 1.0 : 0.98) * (v.S == 0 ? 0.5 : 1.0) * (v.allr ? 1.25 * (v.WB > 1 ? 1.2 * (double)(v.CBW * S * R) / ((double)cdiv(v.CBW * S * R, v.WB) * v.WB) : 1.0) : 1.0);   // (coalesced atomic additions, dy staged once for all filter rows: measured 1.2 to 1.3)
         if (!best || score > best_score) {
             best = &v;
             best_score = score;
@@ -561,7 +561,7 @@ int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W
     // evenly, but every one adds a full set of atomic additions into dw.  One or two workgroups run
     // per CU at a time (their LDS).  Estimated clocks: rounds * (chunks of a workgroup * MFMA clocks of a
     // chunk + the atomics of its accumulators), the constants fitted to measurements.
-    const int nblk = best->pack ? best->pack : best->CBW * (best->S == 0 ? 1 : S) * (best->allr ? R : 1);
+    const int nblk = cdiv(best->pack ? best->pack : best->CBW * (best->S == 0 ? 1 : S) * (best->allr ? R : 1), best->WB);
     const int npx = best->qw ? (best->PXC / best->qw) * best->qw : best->PXC;
     const int64_t units = best->qw ? (int64_t)N * cdiv(s.P, best->PXC / best->qw) : (int64_t)N * s.P;
     const int64_t chunks_per_unit = best->qw ? 1 : cdiv(s.Q, best->PXC);

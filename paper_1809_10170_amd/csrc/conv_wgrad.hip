@@ -57,14 +57,20 @@ namespace convd {
 // WC > 1: the waves of a workgroup also spread over WC groups of 32*CBW input channels (wave = k-block +
 // WK * channel group), which all read the same staged dy: a tile of 32*WK output x 32*CBW*WC input
 // channels whose accumulators are shared out over WK*WC waves.
-template <int S_, int ST_, int CBW_, int WK_, int PXC_, int PACK_ = 0, int QW_ = 0, int AR_ = 0, int WC_ = 1>
+//
+// WB > 1 (all-rows mode): the column blocks of the workgroup's channels are dealt out to WB waves per
+// k-block (block wb, wb + WB, ...), for filters whose S*S taps times 32 channels are more blocks than one
+// wave can hold (25 for 5x5).  A wave whose last block does not exist computes it on any valid operands
+// and drops it.
+template <int S_, int ST_, int CBW_, int WK_, int PXC_, int PACK_ = 0, int QW_ = 0, int AR_ = 0, int WC_ = 1, int WB_ = 1>
 struct WgGeom {
-    static constexpr int S = S_, ST = ST_, CBW = CBW_, WK = WK_, PXC = PXC_, PACK = PACK_, QW = QW_, AR = AR_, WC = WC_;
-    static constexpr int NW = WK_ * WC_;                 // waves per workgroup
+    static constexpr int S = S_, ST = ST_, CBW = CBW_, WK = WK_, PXC = PXC_, PACK = PACK_, QW = QW_, AR = AR_, WC = WC_, WB = WB_;
+    static constexpr int NW = WK_ * WC_ * WB_;           // waves per workgroup
     static constexpr bool RT = S_ == 0;
     static constexpr int SB = RT ? 1 : S_;               // filter columns a wave owns
     static constexpr int NR = AR ? S_ : 1;               // filter rows a wave owns
-    static constexpr int NBLK = PACK ? PACK : CBW * SB * NR;  // accumulator blocks per wave
+    static constexpr int NCOLB = PACK ? PACK : CBW * SB * NR; // column blocks of the wave's channels
+    static constexpr int NBLK = (NCOLB + WB - 1) / WB;        // accumulator blocks per wave
     static constexpr int RPC = QW ? PXC / QW : 1;        // output rows per chunk
     static constexpr int NPX = QW ? RPC * QW : PXC;      // pixels per chunk
     static constexpr int PXR = AR_ ? 32 + S_ : 32;       // QW: LDS words from one input row to the next (all-rows mode: = S mod 32)
@@ -87,6 +93,7 @@ struct WgGeom {
                                  : QW ? RPC * PXR + 1 : NLX * 64 + 1;
     static_assert(!AR || (!RT && (QW == 0 || (ST == 1 && PACK == 0))), "all-rows mode: small-map chunks at stride 1, unpacked");
     static_assert(WC == 1 || (PACK == 0 && 32 % WC == 0), "channel groups of waves: whole dy rows per wave");
+    static_assert(WB == 1 || (AR && PACK == 0 && WC == 1 && 32 % WB == 0), "column blocks dealt out to waves: all-rows mode");
     static_assert(!QW || (WX <= PXR && RPC >= 1 && PACK == 0), "small-map chunks: an input row fits 32 words");
     static constexpr int ABUF = KT * PA, XBUF = CT * PX;  // floats
     static constexpr int BUF = ABUF + XBUF;
@@ -94,16 +101,19 @@ struct WgGeom {
                                                                                   // a few words past the last input row)
     static_assert(PXC <= 64 && PXC % 2 == 0, "a dy row segment is staged by one 64-lane load");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
+    // workgroups per CU the kernel is sized for: two if their LDS fits and they are at most four waves each
+    static constexpr int PER_CU = (LDS_BYTES <= 80 * 1024 && NW <= 4) ? 2 : 1;
+    static constexpr int WPE = PER_CU * NW >= 4 ? PER_CU * NW / 4 : 1;   // waves per SIMD the register budget must allow
 };
 
 template <class G>
-__global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv_wgrad_kernel(const WgradArgs a)
+__global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradArgs a)
 {
     extern __shared__ __align__(16) float lds[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     __builtin_assume(wave >= 0 && wave < G::NW);
-    const int wk = wave % G::WK, wc = wave / G::WK;   // k-block and channel group of the wave
+    const int wk = wave % G::WK, wc = (wave / G::WK) % G::WC, wb = wave / (G::WK * G::WC);   // k-block, channel group, first column block
     const int h = lane >> 5, j = lane & 31;
     const int N = a.s.N, C = a.s.C, H = a.s.H, W = a.s.W, K = a.s.K, R = a.s.R, P = a.s.P, Q = a.s.Q, pad = a.s.pad;
     const int st = G::RT ? a.s.stride : G::ST;       // (a compile-time constant except in the fallback)
@@ -280,7 +290,8 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
         } else if (G::AR) {
             constexpr int SS = G::SB * G::NR;                         // taps per channel
             // (packed: the columns are all C*S*S (channel, tap) pairs; those past them read any valid position)
-            const int col = (!G::PACK || b * 32 + j < C * SS) ? b * 32 + j : 0, tap = col % SS;
+            const int colb = (wb + G::WB * b) * 32 + j;               // (blocks dealt out to WB waves)
+            const int col = ((!G::PACK || colb < C * SS) && colb < G::NCOLB * 32) ? colb : 0, tap = col % SS;
             xoff[b] = (wc * 32 * G::CBW + col / SS) * G::PX + (tap / G::SB) * (G::QW ? G::PXR : G::RP) + tap % G::SB + (G::QW ? 0 : h * G::ST);
         } else {
             xoff[b] = ((wc * G::CBW + b / G::SB) * 32 + j) * G::PX + b % G::SB + (G::QW ? 0 : h * st);
@@ -366,8 +377,9 @@ __global__ void __launch_bounds__(G::NT, G::LDS_BYTES <= 80 * 1024 ? 2 : 1) conv
         // column b*32 + j is float b*32 + j of the run dw[k][c0 .. c0 + CT)[.][.]
 #pragma unroll
         for (int b = 0; b < G::NBLK; ++b) {
-            const int col = b * 32 + j;
-            const bool cok = G::PACK ? col < C * G::SB * G::NR : c0 + wc * 32 * G::CBW + col / (G::SB * G::NR) < C;
+            const int col = (wb + G::WB * b) * 32 + j;
+            const bool cok = col < G::NCOLB * 32 &&
+                             (G::PACK ? col < C * G::SB * G::NR : c0 + wc * 32 * G::CBW + col / (G::SB * G::NR) < C);
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int k = k0 + wk * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
@@ -409,7 +421,7 @@ static hipError_t launch_wg(const WgradArgs &a, unsigned grid, hipStream_t strea
 template <class G>
 constexpr WgradVariant make_wg(const char *name)
 {
-    return WgradVariant{name, G::S, G::ST, G::CBW, G::WK, G::PXC, G::PACK, G::QW, G::LDS_BYTES <= 80 * 1024 ? 2 : 1, &launch_wg<G>, G::AR, G::WC};
+    return WgradVariant{name, G::S, G::ST, G::CBW, G::WK, G::PXC, G::PACK, G::QW, G::PER_CU, &launch_wg<G>, G::AR, G::WC, G::WB};
 }
 
 // name: w<S>s<stride>_c<channels per workgroup>_k<output channels per workgroup>_p<pixels per chunk>
@@ -429,6 +441,8 @@ static WgradVariant g_wgrad[] = {
     make_wg<WgGeom<3, 1, 1, 4, 32, 0, 0, 1>>("w3s1_ar_c32_k128_p32"),
     make_wg<WgGeom<3, 1, 1, 2, 32, 0, 0, 1, 2>>("w3s1_ar_c64_k64_p32"),
     make_wg<WgGeom<3, 1, 1, 4, 28, 0, 0, 1>>("w3s1_ar_c32_k128_p28"),
+    make_wg<WgGeom<5, 1, 1, 2, 32, 0, 0, 1, 1, 4>>("w5s1_ar_c32_k64_p32"),
+    make_wg<WgGeom<5, 1, 1, 2, 28, 0, 0, 1, 1, 4>>("w5s1_ar_c32_k64_p28"),
     make_wg<WgGeom<3, 2, 1, 4, 28, 0, 0, 1>>("w3s2_ar_c32_k128_p28"),
     make_wg<WgGeom<3, 2, 1, 4, 32, 0, 0, 1>>("w3s2_ar_c32_k128_p32"),
     // first layers: all (channel, tap) pairs of C <= 4 channels packed into blocks of 32 columns

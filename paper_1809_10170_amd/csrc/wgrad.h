@@ -24,6 +24,7 @@ struct WgradVariant {
     hipError_t (*launch)(const WgradArgs &, unsigned grid, hipStream_t stream);
     int allr;           // 1: a workgroup owns all filter rows (needs R == S, stride 1); the filter row is no grid dimension
     int WC;             // groups of 32*CBW input channels per workgroup (their waves share the staged dy)
+    int WB;             // waves per k-block that share out the column blocks of the same channels
 };
 
 const WgradVariant *wgrad_table(int *count);

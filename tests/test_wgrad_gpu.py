@@ -80,6 +80,8 @@ def test_small_shapes_random_inputs(oracle, shape):
     ((3, 20, 14, 14, 40, 3, 3, 1, 1), "w3s1_ar_c32_k128_q14h"),
     ((2, 8, 22, 13, 16, 3, 3, 1, 1), "w3s1_ar_c32_k128_q13h"),
     ((2, 2, 20, 40, 20, 3, 3, 1, 1), "w3s1_arpack1_k128_p32"),      # packed columns: 18 of 32
+    ((1, 40, 9, 64, 70, 5, 5, 1, 2), "w5s1_ar_c32_k64_p32"),        # 25 column blocks dealt out to four waves per k-block
+    ((2, 10, 27, 27, 40, 5, 5, 1, 2), "w5s1_ar_c32_k64_p28"),
     ((2, 1, 30, 30, 10, 7, 7, 2, 3), "w7s2_arpack5_k64_p64"),       # one channel
     ((2, 3, 99, 227, 96, 11, 11, 4, 0), "w11s4_arpack12_k128_p32"),
 ])
