@@ -540,8 +540,10 @@ int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W
         // used fraction of the MFMA work: pixels of a row over whole chunks, output and input channels over whole tiles
         const double cols = v.pack ? (double)C * S * (v.allr ? R : 1) / (32.0 * v.pack) : (double)C / ((double)cdiv(C, 32 * v.CBW * v.WC) * 32 * v.CBW * v.WC);
         const double pix = v.qw ? (double)s.P * s.Q / ((double)cdiv(s.P, v.PXC / v.qw) * v.PXC) : (double)s.Q / ((double)cdiv(s.Q, v.PXC) * v.PXC);
-        // (two workgroups per CU keep the matrix pipes busier than one: a wave's waits are covered)
-        const double score = pix * (v.per_cu == 2 ? 1.12 : 1.0) *
+        // (eight waves per CU keep the matrix pipes busier than four: a wave's waits are covered; as one
+        // workgroup they also stage dy once for twice the channels: measured 1.04)
+        const int nwaves = v.WK * v.WC * v.WB;
+        const double score = pix * (v.per_cu * nwaves >= 8 ? 1.12 : 1.0) * (nwaves >= 8 ? 1.03 : 1.0) *
                              ((double)K / ((double)cdiv(K, 32 * v.WK) * 32 * v.WK)) * cols * (v.WK * v.WC * v.WB >= 4 ? 1.0 : 0.98) * (v.S == 0 ? 0.5 : 1.0) * (v.allr ? 1.25 * (v.WB > 1 ? 1.2 * (double)(v.CBW * S * R) / ((double)cdiv(v.CBW * S * R, v.WB) * v.WB) : 1.0) : 1.0);   // (coalesced atomic additions, dy staged once for all filter rows: measured 1.2 to 1.3)
         if (!best || score > best_score) {
             best = &v;

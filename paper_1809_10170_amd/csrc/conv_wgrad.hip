@@ -441,6 +441,14 @@ static WgradVariant g_wgrad[] = {
     make_wg<WgGeom<3, 1, 1, 4, 32, 0, 0, 1>>("w3s1_ar_c32_k128_p32"),
     make_wg<WgGeom<3, 1, 1, 2, 32, 0, 0, 1, 2>>("w3s1_ar_c64_k64_p32"),
     make_wg<WgGeom<3, 1, 1, 4, 28, 0, 0, 1>>("w3s1_ar_c32_k128_p28"),
+    // eight waves, one workgroup per CU: dy staged once for 64 channels
+    make_wg<WgGeom<3, 1, 1, 4, 28, 0, 0, 1, 2>>("w3s1_ar_c64_k128_p28"),
+    make_wg<WgGeom<3, 1, 1, 4, 32, 0, 0, 1, 2>>("w3s1_ar_c64_k128_p32"),
+    // 1x1: small chunks, two workgroups per CU (these layers are bound by reading x and dy once)
+    make_wg<WgGeom<1, 1, 2, 2, 32, 0, 0, 1, 2>>("w1s1_ar_c128_k64_p32"),
+    make_wg<WgGeom<1, 1, 2, 2, 28, 0, 0, 1, 2>>("w1s1_ar_c128_k64_p28"),
+    make_wg<WgGeom<1, 1, 2, 4, 32, 0, 0, 1, 1>>("w1s1_ar_c64_k128_p32"),
+    make_wg<WgGeom<1, 1, 2, 4, 28, 0, 0, 1, 1>>("w1s1_ar_c64_k128_p28"),
     make_wg<WgGeom<5, 1, 1, 2, 32, 0, 0, 1, 1, 4>>("w5s1_ar_c32_k64_p32"),
     make_wg<WgGeom<5, 1, 1, 2, 28, 0, 0, 1, 1, 4>>("w5s1_ar_c32_k64_p28"),
     make_wg<WgGeom<3, 2, 1, 4, 28, 0, 0, 1>>("w3s2_ar_c32_k128_p28"),

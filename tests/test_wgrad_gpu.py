@@ -73,6 +73,8 @@ def test_small_shapes_random_inputs(oracle, shape):
     ((2, 40, 20, 64, 48, 3, 3, 1, 1), "w3s1_ar_c64_k64_p32"),       # waves spread over two channel groups
     ((2, 20, 9, 56, 70, 3, 3, 1, 1), "w3s1_ar_c32_k128_p28"),       # rows of two 28-pixel chunks
     ((2, 70, 11, 64, 130, 3, 3, 1, 1), "w3s1_ar_c32_k128_p32"),     # three channel groups, two k tiles
+    ((2, 64, 9, 56, 128, 3, 3, 1, 1), "w3s1_ar_c64_k128_p28"),       # eight waves: four k-blocks x two channel groups
+    ((1, 128, 6, 64, 100, 3, 3, 1, 1), "w3s1_ar_c64_k128_p32"),
     ((1, 12, 21, 127, 40, 3, 3, 2, 1), "w3s2_ar_c32_k128_p32"),     # stride 2, rows of 64
     ((2, 12, 57, 55, 130, 3, 3, 2, 1), "w3s2_ar_c32_k128_p28"),     # stride 2, rows of 28
     ((3, 9, 4, 7, 33, 3, 3, 1, 1), "w3s1_ar_c32_k128_q7h"),         # 4 rows of 7 per chunk
@@ -80,6 +82,10 @@ def test_small_shapes_random_inputs(oracle, shape):
     ((3, 20, 14, 14, 40, 3, 3, 1, 1), "w3s1_ar_c32_k128_q14h"),
     ((2, 8, 22, 13, 16, 3, 3, 1, 1), "w3s1_ar_c32_k128_q13h"),
     ((2, 2, 20, 40, 20, 3, 3, 1, 1), "w3s1_arpack1_k128_p32"),      # packed columns: 18 of 32
+    ((2, 100, 9, 56, 40, 1, 1, 1, 0), "w1s1_ar_c128_k64_p28"),       # 1x1: two channel groups of 64
+    ((2, 100, 9, 64, 40, 1, 1, 1, 0), "w1s1_ar_c128_k64_p32"),
+    ((2, 37, 10, 64, 130, 1, 1, 1, 0), "w1s1_ar_c64_k128_p32"),
+    ((2, 37, 19, 23, 65, 1, 1, 1, 0), "w1s1_ar_c64_k128_p28"),
     ((1, 40, 9, 64, 70, 5, 5, 1, 2), "w5s1_ar_c32_k64_p32"),        # 25 column blocks dealt out to four waves per k-block
     ((2, 10, 27, 27, 40, 5, 5, 1, 2), "w5s1_ar_c32_k64_p28"),
     ((2, 1, 30, 30, 10, 7, 7, 2, 3), "w7s2_arpack5_k64_p64"),       # one channel
