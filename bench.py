@@ -102,7 +102,7 @@ def main():
     ap.add_argument("--workload", default="suite_batched")
     ap.add_argument("--variant", default=None, help="force a kernel variant (single-layer workloads)")
     ap.add_argument("--direction", default="forward", choices=["forward", "dgrad", "wgrad"],
-                    help="dgrad: the data gradient of the suite's stride-1 layers (filter transform + convolution "
+                    help="dgrad: the data gradient of the suite's layers behind the first one (filter transform + convolution "
                          "of dy per step); wgrad: the weight gradient of every layer (clear + reduction per step); "
                          "plain layouts")
     ap.add_argument("--layout", default="plain", choices=["plain", "blocked"],
@@ -133,8 +133,13 @@ def main():
     wgrad = args.direction == "wgrad"
     if (dgrad or wgrad) and blocked:
         sys.exit("bench.py: the gradients run in plain layouts")
-    if dgrad:
-        layers = [l for l in layers if l.stride == 1 and l.R == l.S and l.pad <= l.R - 1]
+    if dgrad and len(layers) > 1:
+        # a suite: the layers whose data gradient runs on the compiled kernels (stride 1, or a strided layer as one
+        # small convolution per phase), first layers left out (no network needs the gradient of its input image);
+        # a layer named alone runs whatever its path
+        layers = [l for l in layers if l.R == l.S and l.pad <= l.R - 1 and l.C >= 16]
+    if not layers:
+        sys.exit("bench.py: no layer left to run")
     dev = torch.device("cuda:0")
 
     items = []
@@ -154,7 +159,7 @@ def main():
             g = torch.Generator(device="cpu").manual_seed(4242 + l.K)
             dy = (torch.rand((l.N, l.K, l.P, l.Q), generator=g) * 2 - 1).to(dev)
             plan = cd.Plan.dgrad(*l.dims())
-            wt = torch.empty((l.C, l.K, l.R, l.S), device=dev)
+            wt = torch.empty((plan.dgrad_wt_elems(),), device=dev)
             dx = torch.empty((l.N, l.C, l.H, l.W), device=dev)
             items.append((l, plan, dy, wt, dx, wd))
             del x, w
@@ -183,7 +188,7 @@ def main():
         if isinstance(w_plain, str):   # wgrad: (x, dy) -> dw
             return plan.run_wgrad(xd, wd, out, stream.cuda_stream)
         if w_plain is not None:   # dgrad: the filter transform belongs to the step (weights change every update)
-            cd.dgrad_filter(w_plain, wd, stream.cuda_stream)
+            plan.dgrad_prepare(w_plain, wd, stream.cuda_stream)
         plan.run(xd, wd, out, stream.cuda_stream)
 
     for _ in range(args.warmup):

@@ -178,9 +178,25 @@ int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, 
  *   conv_direct_dgrad_filter(w, wt, K, C, R, S, stream);                 // wt: a caller buffer, once per weight update
  *   conv_direct_run(plan, dy, wt, dx, stream);                           // dx [N][C][H][W], every element written
  *
- * Strided layers, filters with R != S and pad > R-1 are served too, by the slow
- * runtime-shape kernel (dy read as if zeros stood between its elements): same three
- * calls.  conv_direct_output_dims of the plan gives (H, W).
+ * A strided layer with a square filter is stride*stride such convolutions, one per
+ * phase (a, b) of the input positions: with h + pad = stride*u + a only the taps
+ * r = a + stride*i reach row h, so dx at those rows is the stride-1 convolution of dy with
+ * the RT = ceil(R/stride) taps of phase a (zeros where a + stride*i >= R), and likewise
+ * along the columns.  The plan then takes stride*stride filters of RT x RT taps,
+ *   wt[a*stride + b][c][k][j][l] = w[k][c][a + stride*(RT-1-j)][b + stride*(RT-1-l)],
+ * and conv_direct_run launches a fill that clears dx and one convolution per phase, each
+ * storing to its own positions of dx: no workspace.  Because wt's size and contents depend
+ * on the plan, ask the plan:
+ *
+ *   size_t n = conv_direct_dgrad_wt_elems(plan);                         // floats of wt for this plan
+ *   conv_direct_dgrad_prepare(plan, w, wt, stream);                      // w [K][C][R][S] -> wt, any data-gradient plan
+ *   conv_direct_run(plan, dy, wt, dx, stream);
+ *
+ * (for stride 1 conv_direct_dgrad_prepare is conv_direct_dgrad_filter).  Filters with
+ * R != S, pad > R-1 and strided shapes no compiled variant serves go to the slow
+ * runtime-shape kernel (dy read as if zeros stood between its elements), with the
+ * stride-1 form of wt.  conv_direct_output_dims of the plan gives (H, W).  A fused tail
+ * is refused for a phase plan (CONV_DIRECT_EINVAL).
  *
  * Weight gradient (the backward pass "to update ... the kernel"), plain layouts, any
  * filter, strides up to 4 (compiled variants for the filter widths and strides of the forward
@@ -200,6 +216,8 @@ int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, 
 int conv_direct_create_dgrad(conv_direct_plan **plan,
                              int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 int conv_direct_dgrad_filter(const float *w, float *wt, int K, int C, int R, int S, void *stream);
+size_t conv_direct_dgrad_wt_elems(const conv_direct_plan *plan);   /* 0 for a plan that is no data gradient */
+int conv_direct_dgrad_prepare(const conv_direct_plan *plan, const float *w, float *wt, void *stream);
 int conv_direct_create_wgrad(conv_direct_plan **plan,
                              int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 int conv_direct_run_wgrad(const conv_direct_plan *plan,

@@ -81,6 +81,10 @@ def lib():
         l.conv_direct_run_wgrad.restype = i
         l.conv_direct_create_dgrad.argtypes = [pp] + [i] * 9
         l.conv_direct_create_dgrad.restype = i
+        l.conv_direct_dgrad_wt_elems.argtypes = [vp]
+        l.conv_direct_dgrad_wt_elems.restype = ctypes.c_size_t
+        l.conv_direct_dgrad_prepare.argtypes = [vp, vp, vp, vp]
+        l.conv_direct_dgrad_prepare.restype = i
         for nm in ("conv_direct_pack_act", "conv_direct_unpack_act", "conv_direct_pack_w", "conv_direct_dgrad_filter"):
             getattr(l, nm).argtypes = [vp, vp] + [i] * 4 + [vp]
             getattr(l, nm).restype = i
@@ -150,9 +154,27 @@ class Plan:
         if rc != OK:
             self._p = ctypes.c_void_p()
             raise ConvDirectError(rc, "conv_direct_create_dgrad")
-        P, Q = H + 2 * pad - R + 1, W + 2 * pad - S + 1
-        self.dims = (int(N), int(K), P, Q, int(C), int(R), int(S), 1, R - 1 - pad)   # the forward problem it runs
+        P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+        self.dims = (int(N), int(K), P, Q, int(C), int(R), int(S), 1, R - 1 - pad)   # the forward problem it runs (over dy)
+        self._dgrad = True
         return self
+
+    def dgrad_wt_elems(self) -> int:
+        """Floats of the transformed filter a data-gradient plan takes (see dgrad_prepare)."""
+        return int(lib().conv_direct_dgrad_wt_elems(self._p))
+
+    def dgrad_prepare(self, w, wt, stream: int | None = None) -> None:
+        """w [K,C,R,S] -> wt (a flat or shaped device tensor of dgrad_wt_elems() floats): the filter(s) this
+        data-gradient plan runs with; once per weight update."""
+        import torch
+        for t, n, nm in ((w, None, "w"), (wt, self.dgrad_wt_elems(), "wt")):
+            if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and (n is None or t.numel() == n)):
+                raise ValueError(f"{nm}: need a contiguous fp32 device tensor" + (f" of {n} elements" if n else ""))
+        if stream is None:
+            stream = torch.cuda.current_stream().cuda_stream
+        rc = lib().conv_direct_dgrad_prepare(self._p, w.data_ptr(), wt.data_ptr(), stream)
+        if rc != OK:
+            raise ConvDirectError(rc, "conv_direct_dgrad_prepare")
 
     @classmethod
     def wgrad(cls, N, C, H, W, K, R, S, stride, pad):
@@ -223,7 +245,12 @@ class Plan:
                  ((N, -(-C // cb), H, W, cb), (-(-K // kb), -(-C // cb), R, S, cb, kb))
         os_ = (N, K, P, Q) if self.out_layout == PLAIN else (N, -(-K // cb), P, Q, cb)
         for t, shape, nm in ((x, xs, "in"), (w, ws, "w"), (out, os_, "out")):
-            if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == shape):
+            if nm == "w" and getattr(self, "_dgrad", False):   # the transformed filter(s): size by the plan, any shape
+                ok = t.numel() == self.dgrad_wt_elems()
+                shape = (self.dgrad_wt_elems(),)
+            else:
+                ok = tuple(t.shape) == shape
+            if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and ok):
                 raise ValueError(f"{nm}: need a contiguous fp32 device tensor of shape {shape}")
         if stream is None:
             stream = torch.cuda.current_stream().cuda_stream

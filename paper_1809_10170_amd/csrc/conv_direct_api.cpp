@@ -31,6 +31,9 @@ struct conv_direct_plan {
     int in_blocked, out_blocked;   // layouts of in + w, and of out (paper, Section 4)
     int pw_flat;                   // pointwise kernels: tiles run over the pixels of all images
     int dil, pad_h, pad_w;         // data gradients on the runtime-shape kernel (dil >= 1), see variant.h
+    int ph_stride, ph_pad, ph_H, ph_W;   // data gradient of a strided layer as ph_stride^2 stride-1 convolutions of dy
+                                   // (ph_stride >= 2), one per phase; the forward layer's pad and input size
+    int fwd_K, fwd_C, fwd_R, fwd_S;      // data-gradient plans: the forward layer's filter dims (0 otherwise)
     const convd::WgradVariant *wv; // weight-gradient plans only (v is then NULL)
     int wg_cgroups, wg_splits;
 };
@@ -166,6 +169,7 @@ double cost(const conv_direct_plan &p)
     const Variant &v = *p.v;
     const Shape &s = p.s;
     const int wpw = v.threads / 64;                                // waves per workgroup
+    const int64_t grid = (int64_t)p.grid * (p.ph_stride ? p.ph_stride * p.ph_stride : 1);   // (a data gradient's phases: one launch)
     const double useful = (double)s.N * s.K * s.P * s.Q * ((double)s.C * s.R * s.S);
     const double mfma_per_wave = useful / p.mfma_efficiency / p.grid / wpw / 2048.0;   // 32*32*2 MACs each
     auto round_time = [&](int wgs_per_cu) {
@@ -178,12 +182,12 @@ double cost(const conv_direct_plan &p)
     if (occ > lds_fit) occ = lds_fit;
     if (occ < 1) occ = 1;
     const int64_t slots = (int64_t)kNumCU * occ;
-    const int64_t full = p.grid / slots, rem = p.grid % slots;
+    const int64_t full = grid / slots, rem = grid % slots;
     double c = full * round_time(occ);
     if (rem) c += round_time((int)cdiv64(rem, kNumCU));
     // prologue and epilogue of each workgroup, mostly hidden behind its CU neighbours
     // (per round every resident workgroup of a CU pays it: small workgroups, many per CU, pay more)
-    c += 12000.0 * (occ > 2 ? occ / 2.0 : 1.0) * (double)cdiv64(p.grid, slots);
+    c += 12000.0 * (occ > 2 ? occ / 2.0 : 1.0) * (double)cdiv64(grid, slots);
     // input staging traffic
     double staged;   // floats one workgroup stages in total
     if (v.R == 0) {
@@ -193,11 +197,11 @@ double cost(const conv_direct_plan &p)
     } else {
         staged = (double)cdiv(s.C, v.CB) * v.CB * v.window;
     }
-    c += staged * 4.0 * p.grid / 16384.0;   // bytes / (64 B per clock and CU, all CUs at once)
+    c += staged * 4.0 * grid / 16384.0;   // bytes / (64 B per clock and CU, all CUs at once)
     // filter traffic: every wave fetches the whole filter slice of its 32-channel blocks,
     // however few pixels it owns (what makes very small pixel tiles expensive)
     if (v.R != 0) {
-        c += (double)p.grid * wpw * 32.0 * s.C * s.R * s.S * 4.0 / 16384.0;
+        c += (double)grid * wpw * 32.0 * s.C * s.R * s.S * 4.0 / 16384.0;
     }
     if (v.R == 0) c *= 3.0;   // the runtime-shape fallback synchronises far more often
     return c;
@@ -231,14 +235,14 @@ void tuned_store(const int (&key)[11], const char *variant)
 }
 
 int make_plan(conv_direct_plan **plan, const char *forced, int N, int C, int H, int W, int K, int R,
-              int S, int stride, int pad, int in_blocked = 0, int out_blocked = 0)
+              int S, int stride, int pad, int in_blocked = 0, int out_blocked = 0, bool pair_family_only = false, int phase_stride = 0)
 {
     if (!plan) return CONV_DIRECT_EINVAL;
     *plan = nullptr;
     Shape s;
     const int rc = validate(N, C, H, W, K, R, S, stride, pad, &s);
     if (rc != CONV_DIRECT_OK) return rc;
-    if (!forced) {
+    if (!forced && !pair_family_only) {
         // a measured choice for exactly this problem wins over the model, if it still names a variant that can run it
         const int key[11] = {N, C, H, W, K, R, S, stride, pad, in_blocked, out_blocked};
         if (const TunedEntry *e = tuned_lookup(key)) {
@@ -257,10 +261,12 @@ int make_plan(conv_direct_plan **plan, const char *forced, int N, int C, int H, 
         const Variant &v = *table[i];
         if (forced && std::strcmp(forced, v.name) != 0) continue;
         if (!applicable(v, s, in_blocked, out_blocked)) continue;
+        if (pair_family_only && (v.pair != convd::PAIR_C || v.pointwise || v.R == 0)) continue;
         conv_direct_plan cand{};
         fill(&cand, s, v);
         cand.in_blocked = in_blocked;
         cand.out_blocked = out_blocked;
+        cand.ph_stride = phase_stride;
         const double c = cost(cand);
         if (!have || c < best_cost) {
             best = cand;
@@ -331,6 +337,19 @@ int conv_direct_run_fused(const conv_direct_plan *plan, const float *in, const f
     a.bias = bias;
     a.residual = residual;
     a.relu = relu ? 1 : 0;
+    if (plan->ph_stride) {
+        // data gradient of a strided layer: clear dx (positions no window of the forward pass touches stay
+        // zero), then one stride-1 convolution of dy per phase, each storing to its own positions of dx
+        if (bias || residual || relu) return CONV_DIRECT_EINVAL;
+        const int st = plan->ph_stride, RT = plan->s.R;
+        hipError_t e = convd::launch_fill_zero(out, (long long)plan->s.N * plan->s.K * plan->ph_H * plan->ph_W, (hipStream_t)stream);
+        a.dil = st;                                       // (the channel-pair kernels' output re-mapping, see KernelArgs)
+        a.in_blocked = plan->ph_H | (plan->ph_W << 16);
+        a.pad_h = a.pad_w = -plan->ph_pad;
+        (void)RT;
+        if (e == hipSuccess) e = plan->v->launch(a, plan->grid * (unsigned)(st * st), (hipStream_t)stream);
+        return launched(e);
+    }
     const hipError_t e = plan->v->launch(a, plan->grid, (hipStream_t)stream);
     if (e != hipSuccess) {
         t_last_hip_error = (int)e;
@@ -348,8 +367,8 @@ int conv_direct_destroy(conv_direct_plan *plan)
 int conv_direct_output_dims(const conv_direct_plan *plan, int *P, int *Q)
 {
     if (!plan || !P || !Q || !plan->v) return CONV_DIRECT_EINVAL;
-    *P = plan->s.P;
-    *Q = plan->s.Q;
+    *P = plan->ph_stride ? plan->ph_H : plan->s.P;
+    *Q = plan->ph_stride ? plan->ph_W : plan->s.Q;
     return CONV_DIRECT_OK;
 }
 
@@ -372,12 +391,12 @@ int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
                          "variant=%s N=%d C=%d H=%d W=%d K=%d R=%d S=%d stride=%d pad=%d P=%d Q=%d "
                          "TP=%d TQ=%d KT=%d NPB=%d CB=%d pair=%s tilesP=%d tilesQ=%d ktiles=%d grid=%u "
                          "threads=%d lds_bytes=%zu occupancy=%d flat=%d pointwise=%d mfma_efficiency=%.6g in_layout=%s "
-                         "out_layout=%s workspace_bytes=0",
+                         "out_layout=%s dgrad_phases=%d workspace_bytes=0",
                          v.name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, v.TP, v.TQ,
                          v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : "r", plan->tilesP,
                          plan->tilesQ, plan->ktiles, plan->grid, v.threads, plan->lds_bytes, v.occupancy,
                          (v.img != 0 || plan->pw_flat) ? 1 : 0, v.pointwise, plan->mfma_efficiency, plan->in_blocked ? "blocked" : "plain",
-                         plan->out_blocked ? "blocked" : "plain");
+                         plan->out_blocked ? "blocked" : "plain", plan->ph_stride * plan->ph_stride);
 }
 
 const char *conv_direct_strerror(int code)
@@ -614,7 +633,29 @@ int conv_direct_create_dgrad(conv_direct_plan **plan, int N, int C, int H, int W
     if (rc != CONV_DIRECT_OK) return rc;
     if (stride == 1 && R == S && pad <= R - 1) {
         // the forward problem that computes dx: input dy [N][K][P][Q], C output channels
-        return make_plan(plan, nullptr, N, K, fwd.P, fwd.Q, C, R, S, 1, R - 1 - pad);
+        const int rc1 = make_plan(plan, nullptr, N, K, fwd.P, fwd.Q, C, R, S, 1, R - 1 - pad);
+        if (rc1 == CONV_DIRECT_OK) {
+            (*plan)->fwd_K = K;  (*plan)->fwd_C = C;  (*plan)->fwd_R = R;  (*plan)->fwd_S = S;
+        }
+        return rc1;
+    }
+    if (stride > 1 && R == S && H < 65536 && W < 32768 && (int64_t)N * C * H * W < kMaxElems) {
+        // Strided layer, square filter.  With t = h + pad = stride*u + a, only the taps r = a + stride*i reach
+        // row h: dx[h] = sum_i dy[u - i] * w[a + stride*i], a stride-1 convolution of dy with the RT = ceil(R/stride)
+        // taps of phase a (zeros where a + stride*i >= R), padding RT - 1, whose result u belongs at
+        // h = stride*u + a - pad.  So stride^2 convolutions, one per phase (a, b), on the channel-pair kernels,
+        // which store with that re-mapping; no workspace.
+        const int RT = cdiv(R, stride);
+        conv_direct_plan *sub = nullptr;
+        if (make_plan(&sub, nullptr, N, K, fwd.P, fwd.Q, C, RT, RT, 1, RT - 1, 0, 0, true, stride) == CONV_DIRECT_OK) {
+            sub->ph_stride = stride;
+            sub->ph_pad = pad;
+            sub->ph_H = H;
+            sub->ph_W = W;
+            sub->fwd_K = K;  sub->fwd_C = C;  sub->fwd_R = R;  sub->fwd_S = S;
+            *plan = sub;
+            return CONV_DIRECT_OK;
+        }
     }
     // Otherwise (strided layer, unequal filter sides, pad > R-1): the same forward problem over dy
     // with zeros between its elements and paddings R-1-pad, S-1-pad (negative: a crop), on the
@@ -634,8 +675,27 @@ int conv_direct_create_dgrad(conv_direct_plan **plan, int N, int C, int H, int W
     p->dil = stride;
     p->pad_h = R - 1 - pad;
     p->pad_w = S - 1 - pad;
+    p->fwd_K = K;  p->fwd_C = C;  p->fwd_R = R;  p->fwd_S = S;
     *plan = p;
     return CONV_DIRECT_OK;
+}
+
+size_t conv_direct_dgrad_wt_elems(const conv_direct_plan *plan)
+{
+    if (!plan || !plan->v || !plan->fwd_K) return 0;
+    if (plan->ph_stride)
+        return (size_t)plan->ph_stride * plan->ph_stride * plan->fwd_C * plan->fwd_K * plan->s.R * plan->s.S;
+    return (size_t)plan->fwd_K * plan->fwd_C * plan->fwd_R * plan->fwd_S;
+}
+
+int conv_direct_dgrad_prepare(const conv_direct_plan *plan, const float *w, float *wt, void *stream)
+{
+    if (!plan || !plan->v || !plan->fwd_K || !w || !wt) return CONV_DIRECT_EINVAL;
+    if (((uintptr_t)w | (uintptr_t)wt) & 3u) return CONV_DIRECT_EALIGN;
+    if (plan->ph_stride)
+        return launched(convd::launch_dgrad_phase_filter(w, wt, plan->fwd_K, plan->fwd_C, plan->fwd_R, plan->fwd_S,
+                                                         plan->ph_stride, (hipStream_t)stream));
+    return launched(convd::launch_dgrad_filter(w, wt, plan->fwd_K, plan->fwd_C, plan->fwd_R, plan->fwd_S, (hipStream_t)stream));
 }
 
 size_t conv_direct_blocked_act_elems(int N, int C, int H, int W)

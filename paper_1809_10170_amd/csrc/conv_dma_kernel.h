@@ -298,9 +298,12 @@ __device__ __forceinline__ void write_block(bool blocked, bool fast, __amdgpu_bu
 // channels; its filter values are fetched one by one (never past the tensor) and
 // cleared where the channel does not exist.  TAILC = false needs C % CB == 0 and
 // keeps the steady state free of branches and of per-value work.
-template <class G, bool TAILC, bool FUSED>
-__global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArgs a)
+// MODE: 0 plain, 1 with the fused point-wise tail, 2 with the output re-mapping (see KernelArgs); three
+// instantiations, so that the plain kernel carries none of the other two's registers or instructions.
+template <class G, bool TAILC, int MODE>
+__device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
 {
+    constexpr bool FUSED = MODE == 1, REMAP = MODE == 2;
     extern __shared__ __align__(16) float lds[];
 
     const int lane = threadIdx.x & 63;
@@ -324,6 +327,15 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
         const unsigned g8 = gridDim.x & ~7u;
         if (bid < g8) bid = (bid & 7u) * (g8 >> 3) + (bid >> 3);
     }
+    // output re-mapping: the phases are one more grid dimension, fastest, so that the workgroups that read the same
+    // tile of the input run side by side; phase ph has a filter of its own and its own offsets
+    int ph = 0;
+    if constexpr (REMAP) {
+        const unsigned nph = (unsigned)(a.dil * a.dil);
+        ph = (int)(bid % nph);
+        bid /= nph;
+    }
+    const float *const wp_ = a.w + (REMAP ? (size_t)ph * K * C * G::RS : 0);   // the filter of this workgroup
     const int kt = bid % a.ktiles;  bid /= a.ktiles;
     const int k0 = kt * G::KT;
     // rectangular: image n, tile origin (p0, q0).  flat: first pixel m0 of M, which
@@ -407,7 +419,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
     // are computed and discarded), input channels c0 + h*HC .. + HC, all taps.
     int krow = k0 + wk * 32 + j;
     krow = krow < K ? krow : K - 1;
-    const float *w_lane = a.w + ((size_t)krow * C + h * G::HC) * G::RS;
+    const float *w_lane = wp_ + ((size_t)krow * C + h * G::HC) * G::RS;
     const long long w_total = (long long)K * C * G::RS;
     const long long w_lane_idx = ((long long)krow * C + h * G::HC) * G::RS;
     // blocked weights: the 32 output channels of the wave are one block row kb; lane (j, h)
@@ -416,7 +428,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
     const unsigned wb_lane = (unsigned)((2 * h * 32 + j) * 4);
     // (a wave whose 32 channels all lie past K reads the last block that exists; its results are discarded)
     const int kblk = (k0 + wk * 32) / 32 < (K + 31) / 32 ? (k0 + wk * 32) / 32 : (K + 31) / 32 - 1;
-    const float *wb_row = a.w + (size_t)kblk * (CI / 4) * (G::RS * 128);
+    const float *wb_row = wp_ + (size_t)kblk * (CI / 4) * (G::RS * 128);
     auto load_a = [&](float (&dst)[G::NA], int c0) {
         if constexpr (G::BLK != 0) {
             __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(
@@ -445,7 +457,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
 #pragma unroll
             for (int e = 0; e < G::NA; ++e) {
                 const long long idx = base + e;
-                dst[e] = a.w[idx < w_total ? idx : w_total - 1];
+                dst[e] = wp_[idx < w_total ? idx : w_total - 1];
             }
         }
     };
@@ -613,10 +625,14 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
         // ---- epilogue (see write_block) ----
         const int kw = k0 + wk * 32;
         const int KO = a.out_blocked ? (K + 3) / 4 * 4 : K;      // channels an output image occupies
-        const bool fast = (kw + 32 <= K) & ((long long)KO * P * Q * 4 * G::NSI < (1ll << 31));
-        float *out_n = a.out + (size_t)n * KO * P * Q;
+        // output re-mapping, see KernelArgs
+        const int ost = a.dil, OH = a.in_blocked & 0xffff, OW = a.in_blocked >> 16;
+        const int ooh = REMAP ? a.pad_h + ph / ost : 0, oow = REMAP ? a.pad_w + ph % ost : 0;   // (pad_h, pad_w: those of phase 0)
+        const int OPQ = REMAP ? OH * OW : P * Q;                 // pixels of an output channel plane
+        const bool fast = (kw + 32 <= K) & ((long long)KO * OPQ * 4 * G::NSI < (1ll << 31));
+        float *out_n = a.out + (size_t)n * KO * OPQ;
         __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(out_n), 0, 0x7fffffff, 0x00020000);
-        const Tail tail{a.bias, a.residual ? a.residual + (size_t)n * KO * P * Q : nullptr, a.relu};
+        const Tail tail{a.bias, a.residual ? a.residual + (size_t)n * KO * OPQ : nullptr, a.relu};
 #pragma unroll
         for (int pb = 0; pb < PBW; ++pb) {
             const int t = (wp * G::PBW + pb) * 32 + j;   // (the first pixel group always owns G::PBW blocks)
@@ -634,17 +650,48 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArg
                 live = t < G::NPIX && p < P && q < Q;
                 pix = p * Q + q;
             }
-            write_block<FUSED>(a.out_blocked != 0, fast, orsrc, out_n, K, P * Q, kw, h, live, ni, pix, acc[pb], tail);
+            if constexpr (REMAP) {
+                const int pp = pix / Q, qq = pix - pp * Q;
+                const int oh = pp * ost + ooh, ow = qq * ost + oow;
+                live = live && (unsigned)oh < (unsigned)OH && (unsigned)ow < (unsigned)OW;
+                pix = live ? oh * OW + ow : 0;
+            }
+            write_block<FUSED>(a.out_blocked != 0, fast, orsrc, out_n, K, OPQ, kw, h, live, ni, pix, acc[pb], tail);
         }
     };
     if (G::PBW2 > 0 && wp == 1) body(IntTag<(G::PBW2 > 0 ? G::PBW2 : G::PBW)>{});
     else body(IntTag<G::PBW>{});
 }
 
+template <class G, bool TAILC, bool FUSED>
+__global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_kernel(const KernelArgs a)
+{
+    conv_dma_body<G, TAILC, FUSED ? 1 : 0>(a);
+}
+
+// the same with the output re-mapping (the phases of a strided layer's data gradient)
+template <class G, bool TAILC>
+__global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_remap_kernel(const KernelArgs a)
+{
+    conv_dma_body<G, TAILC, 2>(a);
+}
+
 // ---------------------------------------------------------------------------
 // Host side: launcher and the table entry of one compiled variant.
 // ---------------------------------------------------------------------------
 inline bool has_tail(const KernelArgs &a) { return a.bias != nullptr || a.residual != nullptr || a.relu != 0; }
+
+template <class G, bool TAILC>
+static hipError_t launch_dma_remap(const KernelArgs &a, unsigned grid, hipStream_t stream)
+{
+    if (G::LDS_BYTES > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_dma_remap_kernel<G, TAILC>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((conv_dma_remap_kernel<G, TAILC>), dim3(grid), dim3(G::NT), G::LDS_BYTES, stream, a);
+    return hipGetLastError();
+}
 
 template <class G, bool TAILC, bool FUSED>
 static hipError_t launch_dma_tf(const KernelArgs &a, unsigned grid, hipStream_t stream)
@@ -662,6 +709,13 @@ static hipError_t launch_dma_tf(const KernelArgs &a, unsigned grid, hipStream_t 
 template <class G, bool TAILC>
 static hipError_t launch_dma_t(const KernelArgs &a, unsigned grid, hipStream_t stream)
 {
+    if (a.dil) {   // output re-mapping: compiled for the plain-layout stride-1 variants of small filters only
+        if constexpr (G::BLK == 0 && G::ST == 1 && G::R <= 4) {
+            return has_tail(a) ? hipErrorInvalidValue : launch_dma_remap<G, TAILC>(a, grid, stream);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
     return has_tail(a) ? launch_dma_tf<G, TAILC, true>(a, grid, stream) : launch_dma_tf<G, TAILC, false>(a, grid, stream);
 }
 

@@ -77,6 +77,30 @@ __global__ void __launch_bounds__(256) dgrad_filter_kernel(const float *__restri
     }
 }
 
+// Filters of the data gradient of a strided layer with a square filter (see conv_direct_create_dgrad): one
+// RT x RT filter (RT = ceil(R / stride)) per phase (a, b) of the input positions,
+//   wt[a*stride + b][c][k][j][l] = w[k][c][a + stride*(RT-1-j)][b + stride*(RT-1-l)]   (0 where that tap does not exist)
+// one thread per destination element
+__global__ void __launch_bounds__(256) dgrad_phase_filter_kernel(const float *__restrict__ src, float *__restrict__ dst,
+                                                                 int K, int C, int R, int S, int st, int RT,
+                                                                 long long elems)
+{
+    for (long long t = blockIdx.x * 256ll + threadIdx.x; t < elems; t += gridDim.x * 256ll) {
+        const int l = (int)(t % RT);
+        const int j = (int)(t / RT % RT);
+        const int k = (int)(t / ((long long)RT * RT) % K);
+        const int c = (int)(t / ((long long)RT * RT * K) % C);
+        const int ph = (int)(t / ((long long)RT * RT * K * C));
+        const int r = ph / st + st * (RT - 1 - j), s = ph % st + st * (RT - 1 - l);
+        dst[t] = (r < R && s < S) ? src[(((long long)k * C + c) * R + r) * S + s] : 0.f;
+    }
+}
+
+__global__ void __launch_bounds__(256) fill_zero_kernel(float *dst, long long elems)
+{
+    for (long long t = blockIdx.x * 256ll + threadIdx.x; t < elems; t += gridDim.x * 256ll) dst[t] = 0.f;
+}
+
 static unsigned blocks_for(long long items)
 {
     const long long b = (items + 255) / 256;
@@ -108,6 +132,22 @@ hipError_t launch_dgrad_filter(const float *w, float *wt, int K, int C, int R, i
 {
     const long long elems = (long long)K * C * R * S;
     hipLaunchKernelGGL(dgrad_filter_kernel, dim3(blocks_for(elems)), dim3(256), 0, stream, w, wt, K, C, R, S, elems);
+    return hipGetLastError();
+}
+
+hipError_t launch_dgrad_phase_filter(const float *w, float *wt, int K, int C, int R, int S, int stride, hipStream_t stream)
+{
+    const int RT = (R + stride - 1) / stride;
+    const long long elems = (long long)stride * stride * C * K * RT * RT;
+    hipLaunchKernelGGL(dgrad_phase_filter_kernel, dim3(blocks_for(elems)), dim3(256), 0, stream, w, wt, K, C, R, S, stride, RT,
+                       elems);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(float *dst, long long elems, hipStream_t stream)
+{
+    long long b = (elems + 255) / 256;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)(b < 1 ? 1 : b > 8192 ? 8192 : b)), dim3(256), 0, stream, dst, elems);
     return hipGetLastError();
 }
 

@@ -7,4 +7,6 @@ hipError_t launch_pack_act(const float *plain, float *blocked, int N, int C, int
 hipError_t launch_unpack_act(const float *blocked, float *plain, int N, int C, int H, int W, hipStream_t stream);
 hipError_t launch_pack_w(const float *plain, float *blocked, int K, int C, int R, int S, hipStream_t stream);
 hipError_t launch_dgrad_filter(const float *w, float *wt, int K, int C, int R, int S, hipStream_t stream);
+hipError_t launch_dgrad_phase_filter(const float *w, float *wt, int K, int C, int R, int S, int stride, hipStream_t stream);
+hipError_t launch_fill_zero(float *dst, long long elems, hipStream_t stream);
 }  // namespace convd

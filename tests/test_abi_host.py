@@ -224,9 +224,21 @@ def test_layout_gradient_and_tail_entry_points_check_arguments_before_any_launch
         assert fn(4098, 8192, 2, 3, 4, 5, None) == cd.EALIGN
     assert L.conv_direct_pack_act(4096, 8196, 2, 3, 4, 5, None) == cd.EALIGN      # blocked destination: 16 bytes
     # gradients
-    sd = cd.Plan.dgrad(2, 8, 20, 20, 8, 3, 3, 2, 1)                      # strided: the runtime-shape kernel
-    assert sd.info()["variant"].startswith("generic") and sd.output_dims() == (20, 20)
+    sd = cd.Plan.dgrad(2, 8, 20, 20, 8, 3, 3, 2, 1)                      # strided, square filter: one 2x2 convolution per phase
+    assert sd.info()["variant"].startswith("d2s1") and sd.info()["dgrad_phases"] == 4 and sd.output_dims() == (20, 20)
+    assert sd.dgrad_wt_elems() == 4 * 8 * 8 * 2 * 2 and sd.workspace_bytes() == 0
+    assert L.conv_direct_dgrad_prepare(sd._p, None, 4096, None) == cd.EINVAL
+    assert L.conv_direct_dgrad_prepare(sd._p, 4098, 4096, None) == cd.EALIGN
     sd.destroy()
+    sd = cd.Plan.dgrad(2, 8, 20, 21, 8, 3, 5, 2, 1)                      # R != S: the runtime-shape kernel, stride-1 form of wt
+    assert sd.info()["variant"].startswith("generic") and sd.output_dims() == (20, 21) and sd.dgrad_wt_elems() == 8 * 8 * 15
+    sd.destroy()
+    s1 = cd.Plan.dgrad(*dims)
+    assert s1.dgrad_wt_elems() == 8 * 8 * 9 and s1.info()["dgrad_phases"] == 0
+    s1.destroy()
+    fw = cd.Plan(*dims)
+    assert fw.dgrad_wt_elems() == 0 and L.conv_direct_dgrad_prepare(fw._p, 4096, 8192, None) == cd.EINVAL   # not a data gradient
+    fw.destroy()
     assert L.conv_direct_create_dgrad(ctypes.byref(p), 2, 8, 20, 20, 8, 3, 3, 0, 1) == cd.EINVAL
     assert L.conv_direct_create_wgrad(ctypes.byref(p), 2, 8, 40, 40, 8, 3, 4, 5, 1) == cd.EUNSUPPORTED and not p
     assert L.conv_direct_create_wgrad(ctypes.byref(p), 2, 8, 20, 20, 0, 3, 3, 1, 1) == cd.EINVAL

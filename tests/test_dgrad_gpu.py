@@ -71,20 +71,31 @@ GENERAL = [
     (1, 3, 51, 47, 12, 11, 11, 4, 0),
     (2, 4, 17, 19, 5, 2, 4, 3, 2),
     (1, 7, 16, 16, 6, 1, 1, 2, 0),
+    (2, 40, 29, 29, 70, 3, 3, 2, 1),       # phases: ragged channel chunks, several tiles per image
+    (3, 16, 56, 56, 33, 3, 3, 2, 1),       # dy 28x28: the flat tiling, tiles across images
+    (2, 9, 30, 33, 12, 4, 4, 2, 1),        # 4x4 stride 2: every phase has all four taps
+    (2, 6, 21, 20, 8, 3, 3, 2, 0),         # trailing input rows that no window of the forward pass reaches
+    (1, 5, 25, 26, 7, 5, 5, 3, 2),         # stride 3: nine phases of 2x2 taps
+    (2, 5, 40, 40, 9, 3, 3, 3, 1),         # R = stride: one tap per phase
 ]
 
 
 @pytest.mark.parametrize("shape", GENERAL)
-def test_general_cases_on_the_runtime_shape_kernel(oracle, shape):
+def test_general_cases_strided_unequal_sides_large_pads(oracle, shape):
     N, C, H, W, K, R, S, st, pd = shape
     rng = np.random.default_rng(650 + sum(shape))
     w = rng.integers(-4, 5, (K, C, R, S)).astype(np.float32)
     P, Q = oracle.out_dim(H, R, st, pd), oracle.out_dim(W, S, st, pd)
     dy = rng.integers(-4, 5, (N, K, P, Q)).astype(np.float32)
     plan = cd.Plan.dgrad(*shape)
-    assert plan.output_dims() == (H, W) and plan.info()["variant"].startswith("generic")
-    wt = torch.full((C, K, R, S), float("nan"), device="cuda")
-    cd.dgrad_filter(torch.from_numpy(w).cuda(), wt)
+    info = plan.info()
+    # strided layers with a square filter run as stride^2 small stride-1 convolutions (one per phase of the
+    # input positions) on the compiled kernels; the rest on the runtime-shape kernel
+    phases = st > 1 and R == S and -(-R // st) != 4       # (no 4x4 stride-1 variant is compiled: 7x7 stride 2 falls back)
+    assert plan.output_dims() == (H, W)
+    assert info["dgrad_phases"] == (st * st if phases else 0) and info["variant"].startswith("generic") == (not phases)
+    wt = torch.full((plan.dgrad_wt_elems(),), float("nan"), device="cuda")
+    plan.dgrad_prepare(torch.from_numpy(w).cuda(), wt)
     dx = torch.full((N, C, H, W), float("nan"), device="cuda")
     assert cd.lib().conv_direct_run(plan._p, torch.from_numpy(dy).cuda().data_ptr(), wt.data_ptr(), dx.data_ptr(), None) == cd.OK
     torch.cuda.synchronize()
@@ -108,3 +119,26 @@ def test_benchmark_layers_full_size_sampled(oracle, name):
     want = oracle.conv_forward_points(dy, wt, pts, 1, l.R - 1 - l.pad)
     err = np.abs(got[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.float64) - want).max()
     assert err <= oracle.tolerance(l.K, l.R, l.S), (info["variant"], err)
+
+
+def test_strided_benchmark_layer_full_size_two_images(oracle):
+    """The 3x3 stride-2 layer of the suite at full size (four 2x2 phase convolutions on the flat tiling):
+    two whole images of dx against the oracle's adjoint (images are independent)."""
+    l = workloads.BY_NAME["s2_c128_56_k256_3x3_n64"]
+    _, w = workloads.make_inputs(l)
+    rng = np.random.default_rng(12)
+    dy = rng.uniform(-1, 1, (l.N, l.K, l.P, l.Q)).astype(np.float32)
+    plan = cd.Plan.dgrad(*l.dims())
+    info = plan.info()
+    assert info["dgrad_phases"] == 4 and info["variant"].startswith("d2s1_flat28_k128") and plan.workspace_bytes() == 0
+    wt = torch.empty((plan.dgrad_wt_elems(),), device="cuda")
+    plan.dgrad_prepare(torch.from_numpy(w).cuda(), wt)
+    dx = torch.full((l.N, l.C, l.H, l.W), float("nan"), device="cuda")
+    plan.run(torch.from_numpy(dy).cuda(), wt, dx)
+    torch.cuda.synchronize()
+    plan.destroy()
+    assert torch.isfinite(dx).all()
+    for n in (0, l.N - 1):
+        want = oracle.conv_dgrad(np.ascontiguousarray(dy[n:n + 1]), w, l.H, l.W, l.stride, l.pad)
+        err = np.abs(dx[n:n + 1].cpu().numpy().astype(np.float64) - want).max()
+        assert err <= oracle.tolerance(l.K, l.R, l.S), err

@@ -77,8 +77,8 @@ def test_data_gradient(oracle, shape):
     w = _ints(rng, (K, C, R, S))
     dy = _ints(rng, (N, K, oracle.out_dim(H, R, st, pd), oracle.out_dim(W, S, st, pd)))
     plan = cd.Plan.dgrad(*shape)
-    wt = torch.empty((C, K, R, S), device="cuda")
-    cd.dgrad_filter(torch.from_numpy(w).cuda(), wt)
+    wt = torch.empty((plan.dgrad_wt_elems(),), device="cuda")
+    plan.dgrad_prepare(torch.from_numpy(w).cuda(), wt)
     dx = torch.full((N, C, H, W), float("nan"), device="cuda")
     dyd = torch.from_numpy(dy).cuda()
     assert cd.lib().conv_direct_run(plan._p, dyd.data_ptr(), wt.data_ptr(), dx.data_ptr(), None) == cd.OK
