@@ -197,6 +197,9 @@ int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, 
  * runtime-shape kernel (dy read as if zeros stood between its elements), with the
  * stride-1 form of wt.  conv_direct_output_dims of the plan gives (H, W).  A fused tail
  * is refused for a phase plan (CONV_DIRECT_EINVAL).
+ * In the blocked layouts the stride-1 data gradient is served by the layout-aware forward
+ * entry points as it stands: conv_direct_create_layout(&plan, N, K, P, Q, C, R, S, 1, R-1-pad,
+ * BLOCKED, BLOCKED), wt from conv_direct_dgrad_filter re-arranged by conv_direct_pack_w(wt, wtb, C, K, R, S).
  *
  * Weight gradient (the backward pass "to update ... the kernel"), plain layouts, any
  * filter, strides up to 4 (compiled variants for the filter widths and strides of the forward

@@ -177,3 +177,30 @@ def test_benchmark_layers_blocked_full_size(oracle, layer):
     want = oracle.conv_forward_points(x, w, pts, l.stride, l.pad)
     err = np.abs(got[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.float64) - want).max()
     assert err <= oracle.tolerance(l.C, l.R, l.S), err
+
+
+@pytest.mark.parametrize("shape", [(2, 21, 30, 28, 40, 3, 3, 1, 1), (3, 8, 13, 13, 70, 3, 3, 1, 1), (2, 37, 20, 23, 33, 1, 1, 1, 0)])
+def test_data_gradient_in_blocked_layouts(oracle, shape):
+    """The stride-1 data gradient with dy, the filter and dx in the blocked layouts: it is the forward problem over
+    dy (C output channels, padding R-1-pad), so the layout-aware forward entry points serve it; the transformed
+    filter wt is re-arranged like any weights."""
+    N, C, H, W, K, R, S, st, pd = shape
+    rng = np.random.default_rng(1200 + sum(shape))
+    w = rng.integers(-4, 5, (K, C, R, S)).astype(np.float32)
+    P, Q = oracle.out_dim(H, R, st, pd), oracle.out_dim(W, S, st, pd)
+    dy = rng.integers(-4, 5, (N, K, P, Q)).astype(np.float32)
+    plan = cd.Plan(N, K, P, Q, C, R, S, 1, R - 1 - pd, in_layout=cd.BLOCKED, out_layout=cd.BLOCKED)
+    assert plan.output_dims() == (H, W) and plan.workspace_bytes() == 0
+    wt = torch.empty((C, K, R, S), device="cuda")
+    cd.dgrad_filter(_dev(w), wt)
+    wtb = _nan((-(-C // KB), -(-K // CB), R, S, CB, KB))
+    cd.pack_w(wt, wtb)
+    dyb = _nan((N, -(-K // CB), P, Q, CB))
+    cd.pack_act(_dev(dy), dyb)
+    dxb = _nan((N, -(-C // CB), H, W, CB))
+    plan.run(dyb, wtb, dxb)
+    dx = _nan((N, C, H, W))
+    cd.unpack_act(dxb, dx)
+    torch.cuda.synchronize()
+    plan.destroy()
+    assert np.array_equal(dx.cpu().numpy().astype(np.float64), oracle.conv_dgrad(dy, w, H, W, st, pd))
