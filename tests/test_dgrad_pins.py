@@ -92,3 +92,34 @@ def test_agrees_with_autograd_in_float64(oracle, shape):
     y.backward(torch.from_numpy(dy).double())
     got = oracle.conv_dgrad(dy, w, H, W, st, pd)
     assert np.abs(got - xt.grad.numpy()).max() <= 1e-10
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 11, 12, 4, 3, 3, 2, 1), (1, 2, 13, 10, 3, 5, 5, 3, 2), (2, 2, 9, 9, 3, 4, 4, 2, 1),
+                                   (1, 3, 12, 11, 2, 3, 3, 2, 0), (1, 2, 10, 10, 2, 3, 3, 3, 1), (1, 2, 9, 8, 3, 1, 1, 2, 0)])
+def test_strided_layer_is_one_small_convolution_per_phase(oracle, shape):
+    """The identity the GPU path for strided layers rests on, on the oracle alone: with h + pad = st*u + a, dx at the
+    rows of phase a is the stride-1 convolution of dy with the taps a, a+st, ... (flipped, zero where past the
+    filter), padding RT-1, result u stored at h = st*u + a - pad; rows no window reaches stay zero."""
+    N, C, H, W, K, R, S, st, pd = shape
+    rng = np.random.default_rng(77 + sum(shape))
+    w = rng.integers(-3, 4, (K, C, R, S)).astype(np.float64)
+    P, Q = oracle.out_dim(H, R, st, pd), oracle.out_dim(W, S, st, pd)
+    dy = rng.integers(-3, 4, (N, K, P, Q)).astype(np.float64)
+    RT = -(-R // st)
+    dx = np.zeros((N, C, H, W))
+    for a in range(st):
+        for b in range(st):
+            wf = np.zeros((C, K, RT, RT))
+            for j in range(RT):
+                for l in range(RT):
+                    r, s = a + st * (RT - 1 - j), b + st * (RT - 1 - l)
+                    if r < R and s < S:
+                        wf[:, :, j, l] = w[:, :, r, s].T
+            sub = oracle.conv_forward(dy.astype(np.float32), wf.astype(np.float32), 1, RT - 1)   # [N][C][P+RT-1][Q+RT-1]
+            for u in range(sub.shape[2]):
+                for v in range(sub.shape[3]):
+                    h, x = st * u + a - pd, st * v + b - pd
+                    if 0 <= h < H and 0 <= x < W:
+                        dx[:, :, h, x] = sub[:, :, u, v]
+    want = oracle.conv_dgrad(dy.astype(np.float32), w.astype(np.float32), H, W, st, pd)
+    assert np.array_equal(dx, want)
