@@ -77,6 +77,8 @@ GENERAL = [
     (2, 6, 21, 20, 8, 3, 3, 2, 0),         # trailing input rows that no window of the forward pass reaches
     (1, 5, 25, 26, 7, 5, 5, 3, 2),         # stride 3: nine phases of 2x2 taps
     (2, 5, 40, 40, 9, 3, 3, 3, 1),         # R = stride: one tap per phase
+    (16, 64, 28, 28, 70, 3, 3, 2, 1),      # dy 14x14: the split flat tiling for 15x15 phase results
+    (16, 64, 14, 14, 70, 3, 3, 2, 1),      # dy 7x7
 ]
 
 
