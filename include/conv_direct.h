@@ -182,10 +182,11 @@ int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, 
  * phase (a, b) of the input positions: with h + pad = stride*u + a only the taps
  * r = a + stride*i reach row h, so dx at those rows is the stride-1 convolution of dy with
  * the RT = ceil(R/stride) taps of phase a (zeros where a + stride*i >= R), and likewise
- * along the columns.  The plan then takes stride*stride filters of RT x RT taps,
- *   wt[a*stride + b][c][k][j][l] = w[k][c][a + stride*(RT-1-j)][b + stride*(RT-1-l)],
- * and conv_direct_run launches a fill that clears dx and one convolution per phase, each
- * storing to its own positions of dx: no workspace.  Because wt's size and contents depend
+ * along the columns.  The plan then takes nb*nb filters of RT x RT taps, nb = min(stride, R)
+ * (phases a >= R have no tap; their positions of dx are zero),
+ *   wt[a*nb + b][c][k][j][l] = w[k][c][a + stride*(RT-1-j)][b + stride*(RT-1-l)],
+ * and conv_direct_run launches a fill that clears dx and the convolutions of all phases as one
+ * grid, each storing to its own positions of dx: no workspace.  Because wt's size and contents depend
  * on the plan, ask the plan:
  *
  *   size_t n = conv_direct_dgrad_wt_elems(plan);                         // floats of wt for this plan

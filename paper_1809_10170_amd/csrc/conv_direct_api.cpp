@@ -169,7 +169,7 @@ double cost(const conv_direct_plan &p)
     const Variant &v = *p.v;
     const Shape &s = p.s;
     const int wpw = v.threads / 64;                                // waves per workgroup
-    const int64_t grid = (int64_t)p.grid * (p.ph_stride ? p.ph_stride * p.ph_stride : 1);   // (a data gradient's phases: one launch)
+    const int64_t grid = (int64_t)p.grid * (p.ph_stride ? p.ph_stride * p.ph_stride : 1);   // (at most: phases without a tap are not launched)   // (a data gradient's phases: one launch)
     const double useful = (double)s.N * s.K * s.P * s.Q * ((double)s.C * s.R * s.S);
     const double mfma_per_wave = useful / p.mfma_efficiency / p.grid / wpw / 2048.0;   // 32*32*2 MACs each
     auto round_time = [&](int wgs_per_cu) {
@@ -343,11 +343,12 @@ int conv_direct_run_fused(const conv_direct_plan *plan, const float *in, const f
         if (bias || residual || relu) return CONV_DIRECT_EINVAL;
         const int st = plan->ph_stride, RT = plan->s.R;
         hipError_t e = convd::launch_fill_zero(out, (long long)plan->s.N * plan->s.K * plan->ph_H * plan->ph_W, (hipStream_t)stream);
-        a.dil = st;                                       // (the channel-pair kernels' output re-mapping, see KernelArgs)
+        const int nb = st < plan->fwd_R ? st : plan->fwd_R;   // phases per dimension that have a tap
+        a.dil = st | (nb << 8);                           // (the channel-pair kernels' output re-mapping, see KernelArgs)
         a.in_blocked = plan->ph_H | (plan->ph_W << 16);
         a.pad_h = a.pad_w = -plan->ph_pad;
         (void)RT;
-        if (e == hipSuccess) e = plan->v->launch(a, plan->grid * (unsigned)(st * st), (hipStream_t)stream);
+        if (e == hipSuccess) e = plan->v->launch(a, plan->grid * (unsigned)(nb * nb), (hipStream_t)stream);
         return launched(e);
     }
     const hipError_t e = plan->v->launch(a, plan->grid, (hipStream_t)stream);
@@ -396,7 +397,8 @@ int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
                          v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : "r", plan->tilesP,
                          plan->tilesQ, plan->ktiles, plan->grid, v.threads, plan->lds_bytes, v.occupancy,
                          (v.img != 0 || plan->pw_flat) ? 1 : 0, v.pointwise, plan->mfma_efficiency, plan->in_blocked ? "blocked" : "plain",
-                         plan->out_blocked ? "blocked" : "plain", plan->ph_stride * plan->ph_stride);
+                         plan->out_blocked ? "blocked" : "plain",
+                         plan->ph_stride ? (plan->ph_stride < plan->fwd_R ? plan->ph_stride : plan->fwd_R) * (plan->ph_stride < plan->fwd_R ? plan->ph_stride : plan->fwd_R) : 0);
 }
 
 const char *conv_direct_strerror(int code)
@@ -683,8 +685,10 @@ int conv_direct_create_dgrad(conv_direct_plan **plan, int N, int C, int H, int W
 size_t conv_direct_dgrad_wt_elems(const conv_direct_plan *plan)
 {
     if (!plan || !plan->v || !plan->fwd_K) return 0;
-    if (plan->ph_stride)
-        return (size_t)plan->ph_stride * plan->ph_stride * plan->fwd_C * plan->fwd_K * plan->s.R * plan->s.S;
+    if (plan->ph_stride) {
+        const int nb = plan->ph_stride < plan->fwd_R ? plan->ph_stride : plan->fwd_R;
+        return (size_t)nb * nb * plan->fwd_C * plan->fwd_K * plan->s.R * plan->s.S;
+    }
     return (size_t)plan->fwd_K * plan->fwd_C * plan->fwd_R * plan->fwd_S;
 }
 

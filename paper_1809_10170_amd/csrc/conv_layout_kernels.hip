@@ -78,12 +78,12 @@ __global__ void __launch_bounds__(256) dgrad_filter_kernel(const float *__restri
 }
 
 // Filters of the data gradient of a strided layer with a square filter (see conv_direct_create_dgrad): one
-// RT x RT filter (RT = ceil(R / stride)) per phase (a, b) of the input positions,
-//   wt[a*stride + b][c][k][j][l] = w[k][c][a + stride*(RT-1-j)][b + stride*(RT-1-l)]   (0 where that tap does not exist)
+// RT x RT filter (RT = ceil(R / stride)) per phase (a, b) of the input positions that has a tap, a, b < nb = min(stride, R),
+//   wt[a*nb + b][c][k][j][l] = w[k][c][a + stride*(RT-1-j)][b + stride*(RT-1-l)]   (0 where that tap does not exist)
 // one thread per destination element
 __global__ void __launch_bounds__(256) dgrad_phase_filter_kernel(const float *__restrict__ src, float *__restrict__ dst,
                                                                  int K, int C, int R, int S, int st, int RT,
-                                                                 long long elems)
+                                                                 int nb, long long elems)
 {
     for (long long t = blockIdx.x * 256ll + threadIdx.x; t < elems; t += gridDim.x * 256ll) {
         const int l = (int)(t % RT);
@@ -91,7 +91,7 @@ __global__ void __launch_bounds__(256) dgrad_phase_filter_kernel(const float *__
         const int k = (int)(t / ((long long)RT * RT) % K);
         const int c = (int)(t / ((long long)RT * RT * K) % C);
         const int ph = (int)(t / ((long long)RT * RT * K * C));
-        const int r = ph / st + st * (RT - 1 - j), s = ph % st + st * (RT - 1 - l);
+        const int r = ph / nb + st * (RT - 1 - j), s = ph % nb + st * (RT - 1 - l);
         dst[t] = (r < R && s < S) ? src[(((long long)k * C + c) * R + r) * S + s] : 0.f;
     }
 }
@@ -138,9 +138,10 @@ hipError_t launch_dgrad_filter(const float *w, float *wt, int K, int C, int R, i
 hipError_t launch_dgrad_phase_filter(const float *w, float *wt, int K, int C, int R, int S, int stride, hipStream_t stream)
 {
     const int RT = (R + stride - 1) / stride;
-    const long long elems = (long long)stride * stride * C * K * RT * RT;
+    const int nb = stride < R ? stride : R;
+    const long long elems = (long long)nb * nb * C * K * RT * RT;
     hipLaunchKernelGGL(dgrad_phase_filter_kernel, dim3(blocks_for(elems)), dim3(256), 0, stream, w, wt, K, C, R, S, stride, RT,
-                       elems);
+                       nb, elems);
     return hipGetLastError();
 }
 
