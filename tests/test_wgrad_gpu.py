@@ -150,7 +150,7 @@ def test_wgrad_plan_is_not_a_forward_plan():
     plan.destroy()
 
 
-@pytest.mark.parametrize("name", ["alex_conv3_n64", "vgg_c256_56_k256_n32"])
+@pytest.mark.parametrize("name", [l.name for l in workloads.ALL_LAYERS if l.N >= 32])
 def test_benchmark_layers_full_size_sampled(oracle, name):
     """Full-size layers: a sample of dw's output channels in full against the oracle (its cost is that of
     the forward pass per output channel)."""
