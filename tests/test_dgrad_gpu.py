@@ -105,7 +105,7 @@ def test_general_cases_strided_unequal_sides_large_pads(oracle, shape):
     assert np.array_equal(dx.cpu().numpy().astype(np.float64), oracle.conv_dgrad(dy, w, H, W, st, pd))
 
 
-@pytest.mark.parametrize("name", ["alex_conv3_n64", "vgg_c256_56_k256_n32", "pw_c256_56_k64_n64"])
+@pytest.mark.parametrize("name", [l.name for l in workloads.ALL_LAYERS if l.N >= 32 and l.stride == 1 and l.C >= 16])
 def test_benchmark_layers_full_size_sampled(oracle, name):
     """Full-size layers: sampled dx elements against the oracle.  The sample is computed through the
     flipped-filter identity (pinned on the CPU against the adjoint definition), which lets the oracle
