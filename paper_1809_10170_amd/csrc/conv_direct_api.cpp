@@ -345,6 +345,7 @@ int conv_direct_run_fused(const conv_direct_plan *plan, const float *in, const f
     a.bias = bias;
     a.residual = residual;
     a.relu = relu ? 1 : 0;
+    a.ost = a.onb = a.ooh = a.oow = a.OH = a.OW = 0;
     if (plan->ph_stride) {
         // data gradient of a strided layer: clear dx (positions no window of the forward pass touches stay
         // zero), then one stride-1 convolution of dy per phase, each storing to its own positions of dx
@@ -352,9 +353,11 @@ int conv_direct_run_fused(const conv_direct_plan *plan, const float *in, const f
         const int st = plan->ph_stride, RT = plan->s.R;
         hipError_t e = convd::launch_fill_zero(out, (long long)plan->s.N * plan->s.K * plan->ph_H * plan->ph_W, (hipStream_t)stream);
         const int nb = st < plan->fwd_R ? st : plan->fwd_R;   // phases per dimension that have a tap
-        a.dil = st | (nb << 8);                           // (the channel-pair kernels' output re-mapping, see KernelArgs)
-        a.in_blocked = plan->ph_H | (plan->ph_W << 16);
-        a.pad_h = a.pad_w = -plan->ph_pad;
+        a.ost = st;                                       // (the channel-pair kernels' output re-mapping, see KernelArgs)
+        a.onb = nb;
+        a.OH = plan->ph_H;
+        a.OW = plan->ph_W;
+        a.ooh = a.oow = -plan->ph_pad;
         (void)RT;
         if (e == hipSuccess) e = plan->v->launch(a, plan->grid * (unsigned)(nb * nb), (hipStream_t)stream);
         return launched(e);
@@ -649,7 +652,7 @@ int conv_direct_create_dgrad(conv_direct_plan **plan, int N, int C, int H, int W
         }
         return rc1;
     }
-    if (stride > 1 && R == S && H < 65536 && W < 32768 && (int64_t)N * C * H * W < kMaxElems) {
+    if (stride > 1 && R == S && (int64_t)N * C * H * W < kMaxElems) {
         // Strided layer, square filter.  With t = h + pad = stride*u + a, only the taps r = a + stride*i reach
         // row h: dx[h] = sum_i dy[u - i] * w[a + stride*i], a stride-1 convolution of dy with the RT = ceil(R/stride)
         // taps of phase a (zeros where a + stride*i >= R), padding RT - 1, whose result u belongs at

@@ -331,7 +331,7 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
     // tile of the input run side by side; phase ph has a filter of its own and its own offsets
     int ph = 0;
     if constexpr (REMAP) {
-        const unsigned nb = (unsigned)a.dil >> 8, nph = nb * nb;   // phases per dimension that have a tap at all
+        const unsigned nb = (unsigned)a.onb, nph = nb * nb;      // phases per dimension that have a tap at all
         ph = (int)(bid % nph);
         bid /= nph;
     }
@@ -626,8 +626,8 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
         const int kw = k0 + wk * 32;
         const int KO = a.out_blocked ? (K + 3) / 4 * 4 : K;      // channels an output image occupies
         // output re-mapping, see KernelArgs
-        const int ost = a.dil & 0xff, nb = a.dil >> 8, OH = a.in_blocked & 0xffff, OW = a.in_blocked >> 16;
-        const int ooh = REMAP ? a.pad_h + ph / nb : 0, oow = REMAP ? a.pad_w + ph % nb : 0;   // (pad_h, pad_w: those of phase 0)
+        const int ost = REMAP ? a.ost : 0, nb = REMAP ? a.onb : 1, OH = REMAP ? a.OH : 0, OW = REMAP ? a.OW : 0;
+        const int ooh = REMAP ? a.ooh + ph / nb : 0, oow = REMAP ? a.oow + ph % nb : 0;   // (ooh, oow: those of phase 0)
         const int OPQ = REMAP ? OH * OW : P * Q;                 // pixels of an output channel plane
         const bool fast = (kw + 32 <= K) & ((long long)KO * OPQ * 4 * G::NSI < (1ll << 31));
         float *out_n = a.out + (size_t)n * KO * OPQ;
@@ -709,7 +709,7 @@ static hipError_t launch_dma_tf(const KernelArgs &a, unsigned grid, hipStream_t 
 template <class G, bool TAILC>
 static hipError_t launch_dma_t(const KernelArgs &a, unsigned grid, hipStream_t stream)
 {
-    if (a.dil) {   // output re-mapping: compiled for the plain-layout stride-1 variants of small filters only
+    if (a.ost) {   // output re-mapping: compiled for the plain-layout stride-1 variants of small filters only
         if constexpr (G::BLK == 0 && G::ST == 1 && G::R <= 4) {
             return has_tail(a) ? hipErrorInvalidValue : launch_dma_remap<G, TAILC>(a, grid, stream);
         } else {

@@ -20,19 +20,18 @@ struct KernelArgs {
     int dil, pad_h, pad_w;        // runtime-shape fallback as a data gradient: dil >= 1 marks the mode (input dilation,
                                   // separate and possibly negative paddings); dil = 0: an ordinary forward pass
     int in_blocked;               // runtime-shape fallback only (the compiled variants fix it at compile time)
-    // The channel-pair kernels read the same four fields as an OUTPUT RE-MAPPING (dil = 0: none), with st = dil & 0xff
-    // and nb = dil >> 8: result (p, q) is stored at row p*st + pad_h, column q*st + pad_w of an OH x OW map,
-    // OH = in_blocked & 0xffff, OW = in_blocked >> 16, if that position exists, and nowhere otherwise.  A strided
-    // layer's data gradient is one stride-1 convolution of dy per phase (a, b) of the input positions, a, b < nb =
-    // min(st, R) (further phases have no tap: their positions keep the zeros of the fill), written this way in ONE
-    // launch: the grid is nb*nb times the tiles, workgroup id % (nb*nb) is the phase ph = a*nb + b, whose filter is
-    // w + ph*K*C*R*S and whose offsets are pad_h + a, pad_w + b.  (The fields are shared rather than
-    // added: a larger argument block cost two kernels their last scalar registers.)
     int out_blocked;              // 0: out[N][K][P][Q]; 1: out[N][ceil(K/4)][P][Q][4] (paper, Section 4.1)
     // fused point-wise tail (all optional): out = relu?(conv + bias[k] + residual[same position as out])
     const float *bias;            // K floats, or NULL
     const float *residual;        // a tensor of out's layout and size, or NULL
     int relu;
+    // Output re-mapping (channel-pair kernels, instantiated for it separately; ost = 0: none): result (p, q) is
+    // stored at row p*ost + ooh, column q*ost + oow of an OH x OW map if that position exists, and nowhere
+    // otherwise.  A strided layer's data gradient is one stride-1 convolution of dy per phase (a, b) of the input
+    // positions, a, b < onb = min(stride, R) (further phases have no tap: their positions keep the zeros of the
+    // fill), written this way in ONE launch: the grid is onb*onb times the tiles, workgroup id % (onb*onb) is the
+    // phase ph = a*onb + b, whose filter is w + ph*K*C*R*S and whose offsets are ooh + a, oow + b.
+    int ost, onb, ooh, oow, OH, OW;
 };
 
 // which reduction index the two k-lanes of one MFMA span: two input channels, or
