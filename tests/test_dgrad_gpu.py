@@ -74,6 +74,8 @@ GENERAL = [
     (2, 40, 29, 29, 70, 3, 3, 2, 1),       # phases: ragged channel chunks, several tiles per image
     (3, 16, 56, 56, 33, 3, 3, 2, 1),       # dy 28x28: the flat tiling, tiles across images
     (2, 9, 30, 33, 12, 4, 4, 2, 1),        # 4x4 stride 2: every phase has all four taps
+    (2, 20, 31, 29, 33, 8, 8, 2, 3),       # 8x8 stride 2: 4x4 taps per phase
+    (3, 24, 26, 30, 40, 4, 4, 1, 2),       # 4x4 stride 1 (one convolution; the 4x4 variant, or the fallback for so small a problem)
     (2, 6, 21, 20, 8, 3, 3, 2, 0),         # trailing input rows that no window of the forward pass reaches
     (1, 5, 25, 26, 7, 5, 5, 3, 2),         # stride 3: nine phases of 2x2 taps
     (2, 5, 40, 40, 9, 3, 3, 3, 1),         # R = stride: one tap per phase
@@ -93,9 +95,12 @@ def test_general_cases_strided_unequal_sides_large_pads(oracle, shape):
     info = plan.info()
     # strided layers with a square filter run as stride^2 small stride-1 convolutions (one per phase of the
     # input positions) on the compiled kernels; the rest on the runtime-shape kernel
-    phases = st > 1 and R == S and -(-R // st) != 4       # (no 4x4 stride-1 variant is compiled: 7x7 stride 2 falls back)
+    phases = st > 1 and R == S
     assert plan.output_dims() == (H, W)
-    assert info["dgrad_phases"] == (min(st, R) ** 2 if phases else 0) and info["variant"].startswith("generic") == (not phases)   # (phases a >= R have no tap)
+    if phases:
+        assert info["dgrad_phases"] == min(st, R) ** 2 and not info["variant"].startswith("generic")   # (phases a >= R have no tap)
+    else:
+        assert info["dgrad_phases"] == 0
     wt = torch.full((plan.dgrad_wt_elems(),), float("nan"), device="cuda")
     plan.dgrad_prepare(torch.from_numpy(w).cuda(), wt)
     dx = torch.full((N, C, H, W), float("nan"), device="cuda")
