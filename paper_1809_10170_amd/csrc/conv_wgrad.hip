@@ -451,6 +451,13 @@ static WgradVariant g_wgrad[] = {
     make_wg<WgGeom<1, 1, 2, 4, 28, 0, 0, 1, 1>>("w1s1_ar_c64_k128_p28"),
     make_wg<WgGeom<5, 1, 1, 2, 32, 0, 0, 1, 1, 4>>("w5s1_ar_c32_k64_p32"),
     make_wg<WgGeom<5, 1, 1, 2, 28, 0, 0, 1, 1, 4>>("w5s1_ar_c32_k64_p28"),
+    make_wg<WgGeom<5, 2, 1, 2, 32, 0, 0, 1, 1, 4>>("w5s2_ar_c32_k64_p32"),
+    make_wg<WgGeom<5, 2, 1, 2, 28, 0, 0, 1, 1, 4>>("w5s2_ar_c32_k64_p28"),
+    // 4x4: 16 column blocks, two waves per k-block
+    make_wg<WgGeom<4, 1, 1, 4, 32, 0, 0, 1, 1, 2>>("w4s1_ar_c32_k128_p32"),
+    make_wg<WgGeom<4, 1, 1, 4, 28, 0, 0, 1, 1, 2>>("w4s1_ar_c32_k128_p28"),
+    make_wg<WgGeom<4, 2, 1, 4, 32, 0, 0, 1, 1, 2>>("w4s2_ar_c32_k128_p32"),
+    make_wg<WgGeom<4, 2, 1, 4, 28, 0, 0, 1, 1, 2>>("w4s2_ar_c32_k128_p28"),
     make_wg<WgGeom<3, 2, 1, 4, 28, 0, 0, 1>>("w3s2_ar_c32_k128_p28"),
     make_wg<WgGeom<3, 2, 1, 4, 32, 0, 0, 1>>("w3s2_ar_c32_k128_p32"),
     // first layers: all (channel, tap) pairs of C <= 4 channels packed into blocks of 32 columns

@@ -88,6 +88,12 @@ def test_small_shapes_random_inputs(oracle, shape):
     ((2, 37, 19, 23, 65, 1, 1, 1, 0), "w1s1_ar_c64_k128_p28"),
     ((1, 40, 9, 64, 70, 5, 5, 1, 2), "w5s1_ar_c32_k64_p32"),        # 25 column blocks dealt out to four waves per k-block
     ((2, 10, 27, 27, 40, 5, 5, 1, 2), "w5s1_ar_c32_k64_p28"),
+    ((2, 40, 30, 127, 70, 5, 5, 2, 2), "w5s2_ar_c32_k64_p32"),
+    ((2, 40, 30, 55, 70, 5, 5, 2, 2), "w5s2_ar_c32_k64_p28"),
+    ((2, 40, 30, 64, 70, 4, 4, 1, 1), "w4s1_ar_c32_k128_p32"),      # 4x4: 16 column blocks, two waves per k-block
+    ((2, 40, 20, 53, 70, 4, 4, 1, 1), "w4s1_ar_c32_k128_p28"),
+    ((2, 40, 41, 128, 70, 4, 4, 2, 1), "w4s2_ar_c32_k128_p32"),
+    ((2, 40, 30, 56, 70, 4, 4, 2, 1), "w4s2_ar_c32_k128_p28"),
     ((2, 1, 30, 30, 10, 7, 7, 2, 3), "w7s2_arpack5_k64_p64"),       # one channel
     ((2, 3, 99, 227, 96, 11, 11, 4, 0), "w11s4_arpack12_k128_p32"),
 ])
