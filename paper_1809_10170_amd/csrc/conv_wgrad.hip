@@ -84,6 +84,9 @@ struct WgGeom {
     // workgroups fit the LDS of a CU.
     static constexpr int PA = PXC <= 32 ? 33 : 65;
     static constexpr bool HALF_A = PA == 33;
+    // chunks of at most 31 pixels: one 64-lane load stages TWO dy rows (lanes 0.. the first, lanes 33.. the second,
+    // which starts 33 words on; the lanes between and behind load zeros into words no one reads)
+    static constexpr bool DUAL_A = HALF_A && (QW_ ? (PXC_ / QW_) * QW_ : PXC_) <= 31 && (32 * WK_ / (WK_ * WC_ * WB_)) % 2 == 0;
     static constexpr int WX = ((QW ? QW : PXC) - 1) * ST + SB;  // input columns a chunk needs (fallback: at most)
     static_assert(!RT || (PACK == 0 && QW == 0), "the fallback uses plain row chunks");
     static constexpr int NLX = (WX + 63) / 64;            // 64-lane loads per input channel (row chunks)
@@ -179,7 +182,19 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
             const float *base = dyp + (((size_t)sn * K + k0) * P + sp) * Q + sq0;
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
             const int plane = P * Q * 4;
-            if (!G::HALF_A || lane < 32) {   // (a disabled lane writes nothing: rows 33 words apart do not overlap)
+            if constexpr (G::DUAL_A) {
+                const int l2 = lane - G::PA;                      // lane's pixel in the second row of its pair
+                const int np = npix < G::NPX ? npix : G::NPX;     // (the rest of a long row is more than a chunk)
+                const unsigned voff2 = lane < np ? (unsigned)lane * 4u
+                                       : (l2 >= 0 && l2 < np) ? (unsigned)plane + (unsigned)l2 * 4u : 0x80000000u;
+#pragma unroll
+                for (int i = 0; i < G::KT / G::NW / 2; ++i) {
+                    const int row = (i * G::NW + wave) * 2;
+                    if (k0 + row < K)   // (a second row past K is not loaded: the single-row offsets)
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(abuf + row * G::PA), 4,
+                                                                 k0 + row + 1 < K ? voff2 : voff, row * plane, 0, 0);
+                }
+            } else if (!G::HALF_A || lane < 32) {   // (a disabled lane writes nothing: rows 33 words apart do not overlap)
 #pragma unroll
                 for (int i = 0; i < G::KT / G::NW; ++i) {
                     const int row = i * G::NW + wave;
