@@ -25,7 +25,7 @@ def _shapes(count, seed):
     return out
 
 
-SHAPES = _shapes(48, 20260)
+SHAPES = _shapes(48, 20260) + _shapes(32, 20261)
 
 
 def _ints(rng, shape, amp=3):
