@@ -98,6 +98,8 @@ struct WgGeom {
     static_assert(WC == 1 || (PACK == 0 && 32 % WC == 0), "channel groups of waves: whole dy rows per wave");
     static_assert(WB == 1 || (AR && PACK == 0 && WC == 1 && 32 % WB == 0), "column blocks dealt out to waves: all-rows mode");
     static_assert(!QW || (WX <= PXR && RPC >= 1 && PACK == 0), "small-map chunks: an input row fits 32 words");
+    // small-map chunks: one 64-lane load stages TWO input rows of a channel (the second starts PXR words on)
+    static constexpr bool DUAL_X = QW_ != 0 && XROWS % 2 == 0 && WX + PXR <= 64;
     static constexpr int ABUF = KT * PA, XBUF = CT * PX;  // floats
     static constexpr int BUF = ABUF + XBUF;
     static constexpr size_t LDS_BYTES = sizeof(float) * (2 * (size_t)BUF + 64);   // (+ slack: an odd last pixel pair reads
@@ -211,7 +213,26 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
             const int plane = H * W * 4;
             const int iw = lane - pad;
             const bool colok = lane < G::WX && (unsigned)iw < (unsigned)W;
-            if (lane < G::PXR) {
+            if constexpr (G::DUAL_X) {
+                const int l2 = lane - G::PXR, iw2 = l2 - pad;      // the lane's column in the second row of a pair
+                const bool colok2 = l2 >= 0 && l2 < G::WX && (unsigned)iw2 < (unsigned)W;
+#pragma unroll
+                for (int i = 0; i < G::CT / G::NW; ++i) {
+                    const int ch = i * G::NW + wave;
+                    if (c0 + ch < C) {
+#pragma unroll
+                        for (int ri = 0; ri < G::XROWS; ri += 2) {
+                            const int ih0 = (sp + ri) * G::ST + r - pad, ih1 = ih0 + G::ST;
+                            const bool ok0 = (unsigned)ih0 < (unsigned)H, ok1 = (unsigned)ih1 < (unsigned)H;
+                            const unsigned voff = (colok && ok0)    ? (unsigned)(ih0 * W + iw) * 4u
+                                                  : (colok2 && ok1) ? (unsigned)(ih1 * W + iw2) * 4u
+                                                                    : 0x80000000u;
+                            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(xbuf + ch * G::PX + ri * G::PXR), 4, voff,
+                                                                     ch * plane, 0, 0);
+                        }
+                    }
+                }
+            } else if (lane < G::PXR) {
 #pragma unroll
                 for (int i = 0; i < G::CT / G::NW; ++i) {
                     const int ch = i * G::NW + wave;
