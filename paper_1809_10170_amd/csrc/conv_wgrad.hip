@@ -498,7 +498,9 @@ static WgradVariant g_wgrad[] = {
     make_wg<WgGeom<3, 2, 1, 4, 32, 0, 0, 1>>("w3s2_ar_c32_k128_p32"),
     // first layers: all (channel, tap) pairs of C <= 4 channels packed into blocks of 32 columns
     make_wg<WgGeom<7, 2, 1, 2, 64, 5, 0, 1>>("w7s2_arpack5_k64_p64"),
+    make_wg<WgGeom<7, 2, 1, 2, 56, 5, 0, 1>>("w7s2_arpack5_k64_p56"),
     make_wg<WgGeom<11, 4, 1, 4, 32, 12, 0, 1>>("w11s4_arpack12_k128_p32"),
+    make_wg<WgGeom<11, 4, 1, 4, 28, 12, 0, 1>>("w11s4_arpack12_k128_p28"),
     make_wg<WgGeom<3, 1, 1, 4, 32, 1, 0, 1>>("w3s1_arpack1_k128_p32"),
     make_wg<WgGeom<3, 1, 1, 4, 56, 0, 7, 1>>("w3s1_ar_c32_k128_q7"),
     make_wg<WgGeom<3, 1, 1, 4, 32, 0, 13, 1>>("w3s1_ar_c32_k128_q13h"),

@@ -94,8 +94,10 @@ def test_small_shapes_random_inputs(oracle, shape):
     ((2, 40, 20, 53, 70, 4, 4, 1, 1), "w4s1_ar_c32_k128_p28"),
     ((2, 40, 41, 128, 70, 4, 4, 2, 1), "w4s2_ar_c32_k128_p32"),
     ((2, 40, 30, 56, 70, 4, 4, 2, 1), "w4s2_ar_c32_k128_p28"),
-    ((2, 1, 30, 30, 10, 7, 7, 2, 3), "w7s2_arpack5_k64_p64"),       # one channel
-    ((2, 3, 99, 227, 96, 11, 11, 4, 0), "w11s4_arpack12_k128_p32"),
+    ((2, 1, 30, 30, 10, 7, 7, 2, 3), "w7s2_arpack5_k64_p56"),       # one channel
+    ((2, 3, 75, 230, 64, 7, 7, 2, 3), "w7s2_arpack5_k64_p64"),
+    ((2, 3, 99, 227, 96, 11, 11, 4, 0), "w11s4_arpack12_k128_p28"),
+    ((1, 3, 51, 135, 40, 11, 11, 4, 0), "w11s4_arpack12_k128_p32"),
 ])
 def test_all_rows_variants_integer_inputs_bit_exact(oracle, shape, variant):
     """Every variant whose waves own all filter rows (columns = consecutive floats of dw), on a shape
