@@ -246,6 +246,15 @@ def main():
                 err = float(abs(out.cpu().numpy()[ks] - want).max())
                 assert err <= 1e-4 * (l.N * l.P * l.Q) ** 0.5, (l.name, err)
                 continue
+            if w_plain is not None and not (l.stride == 1 and l.R == l.S and l.pad <= l.R - 1):
+                # no single-element form for these: two whole images against the oracle's adjoint (images are independent)
+                import numpy as np
+                dyh, wh = xd.cpu().numpy(), w_plain.cpu().numpy()
+                for n in sorted({0, l.N - 1}):
+                    want = oracle.conv_dgrad(np.ascontiguousarray(dyh[n:n + 1]), wh, l.H, l.W, l.stride, l.pad)
+                    err = float(abs(out[n:n + 1].cpu().numpy() - want).max())
+                    assert err <= oracle.tolerance(l.K, l.R, l.S), (l.name, err)
+                continue
             if w_plain is not None:
                 # sampled dx elements through the flipped-filter identity (pinned on the CPU against the adjoint definition)
                 import numpy as np
