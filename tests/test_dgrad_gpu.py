@@ -112,25 +112,29 @@ def test_general_cases_strided_unequal_sides_large_pads(oracle, shape):
 
 @pytest.mark.parametrize("name", [l.name for l in workloads.ALL_LAYERS if l.N >= 32 and l.stride == 1 and l.C >= 16])
 def test_benchmark_layers_full_size_sampled(oracle, name):
-    """Full-size layers: sampled dx elements against the oracle.  The sample is computed through the
-    flipped-filter identity (pinned on the CPU against the adjoint definition), which lets the oracle
-    evaluate single elements."""
+    """Full-size layers: 10^5 sampled dx elements and three whole images against the oracle.  The sample is
+    computed through the flipped-filter identity (pinned on the CPU against the adjoint definition), which
+    lets the oracle evaluate single elements; the whole images through the adjoint definition itself."""
     l = workloads.BY_NAME[name]
     _, w = workloads.make_inputs(l)
     rng = np.random.default_rng(11)
     dy = rng.uniform(-1, 1, (l.N, l.K, l.P, l.Q)).astype(np.float32)
     got, _, info = _dgrad(dy, w, l.H, l.W, l.pad)
     assert not np.isnan(got).any()
-    pts = np.stack([rng.integers(0, d, 4000) for d in (l.N, l.C, l.H, l.W)], axis=1).astype(np.int32)
+    pts = np.stack([rng.integers(0, d, 100000) for d in (l.N, l.C, l.H, l.W)], axis=1).astype(np.int32)
     wt = np.ascontiguousarray(w[:, :, ::-1, ::-1].transpose(1, 0, 2, 3))
     want = oracle.conv_forward_points(dy, wt, pts, 1, l.R - 1 - l.pad)
     err = np.abs(got[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.float64) - want).max()
     assert err <= oracle.tolerance(l.K, l.R, l.S), (info["variant"], err)
+    for n in sorted({0, l.N // 2, l.N - 1}):   # three whole images against the adjoint definition itself
+        want = oracle.conv_dgrad(np.ascontiguousarray(dy[n:n + 1]), w, l.H, l.W, 1, l.pad)
+        err = np.abs(got[n:n + 1].astype(np.float64) - want).max()
+        assert err <= oracle.tolerance(l.K, l.R, l.S), (info["variant"], n, err)
 
 
-def test_strided_benchmark_layer_full_size_two_images(oracle):
+def test_strided_benchmark_layer_full_size_whole_images(oracle):
     """The 3x3 stride-2 layer of the suite at full size (four 2x2 phase convolutions on the flat tiling):
-    two whole images of dx against the oracle's adjoint (images are independent)."""
+    three whole images of dx against the oracle's adjoint (images are independent)."""
     l = workloads.BY_NAME["s2_c128_56_k256_3x3_n64"]
     _, w = workloads.make_inputs(l)
     rng = np.random.default_rng(12)
@@ -145,7 +149,7 @@ def test_strided_benchmark_layer_full_size_two_images(oracle):
     torch.cuda.synchronize()
     plan.destroy()
     assert torch.isfinite(dx).all()
-    for n in (0, l.N - 1):
+    for n in (0, l.N // 2, l.N - 1):
         want = oracle.conv_dgrad(np.ascontiguousarray(dy[n:n + 1]), w, l.H, l.W, l.stride, l.pad)
         err = np.abs(dx[n:n + 1].cpu().numpy().astype(np.float64) - want).max()
         assert err <= oracle.tolerance(l.K, l.R, l.S), err

@@ -158,7 +158,7 @@ BLOCKED_LAYERS = [l for l in workloads.ALL_LAYERS if l.N >= 32 and l.C >= 4]
 @pytest.mark.parametrize("layer", BLOCKED_LAYERS, ids=lambda l: l.name)
 def test_benchmark_layers_blocked_full_size(oracle, layer):
     """Full-size layers, blocked in and out, in the configuration the benchmark's blocked
-    suite times: a seeded sample of outputs against the oracle."""
+    suite times: 10^5 seeded sampled outputs and three whole images against the oracle."""
     l = layer
     x, w = workloads.make_inputs(l)
     plan = cd.Plan(*l.dims(), in_layout=cd.BLOCKED, out_layout=cd.BLOCKED)
@@ -173,10 +173,14 @@ def test_benchmark_layers_blocked_full_size(oracle, layer):
     plan.destroy()
     got = plain.cpu().numpy()
     assert not np.isnan(got).any(), "an output element was never written"
-    pts = workloads.sample_points(l, 20000)
+    pts = workloads.sample_points(l, 100000)
     want = oracle.conv_forward_points(x, w, pts, l.stride, l.pad)
     err = np.abs(got[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.float64) - want).max()
     assert err <= oracle.tolerance(l.C, l.R, l.S), err
+    for n in sorted({0, l.N // 2, l.N - 1}):   # the first, the middle and the last image in full
+        want = oracle.conv_forward(x[n:n + 1], w, l.stride, l.pad)
+        err = np.abs(got[n:n + 1].astype(np.float64) - want).max()
+        assert err <= oracle.tolerance(l.C, l.R, l.S), (n, err)
 
 
 @pytest.mark.parametrize("shape", [(2, 21, 30, 28, 40, 3, 3, 1, 1), (3, 8, 13, 13, 70, 3, 3, 1, 1), (2, 37, 20, 23, 33, 1, 1, 1, 0)])

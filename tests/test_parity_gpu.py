@@ -89,26 +89,34 @@ def _variant_shape(name):
 
 
 # (variants for the blocked layouts, named b..., have their own tests in test_layout_gpu.py)
+@pytest.mark.parametrize("channels", ["ragged", "whole"])
 @pytest.mark.parametrize("name", [n for n in cd.variant_names() if not n.startswith("b")])
-def test_every_variant_on_ragged_shape(oracle, name):
+def test_every_variant_on_ragged_shape(oracle, name, channels):
     """Each compiled variant, forced, on a shape that leaves ragged tiles in every
-    dimension (K, C, rows, columns) and spans several tiles."""
+    dimension (K, rows, columns) and spans several tiles.  Two passes over the input
+    channels: C = 11 leaves a ragged last channel chunk (the kernels' instantiation with a
+    channel tail), C = 32 is a whole number of chunks of every variant (the instantiation
+    without one, which is what the benchmark's layers run)."""
     R, st = _variant_shape(name)
-    N, C, K = 2, 11, 161
+    N, C, K = 2, (11 if channels == "ragged" else 32), 161
     H, W = 61, 67
+    few = R >= 7 or name.startswith("r")   # the row-pair family stages all channels at once and takes only a few
+    if few and channels == "whole":
+        pytest.skip("first-layer variants take at most 4 channels: one instantiation, covered by the other pass")
     if R >= 7:
         C = 3
         H, W = 83, 241
-    elif name.startswith("r"):
-        C = 3   # the row-pair family stages all channels at once and takes only a few
+    elif few:
+        C = 3
     fl = re.search(r"_flat(\d+)_", name)   # flat tiling is compiled for one image size; many
     if fl:                                   # images, so that tiles straddle several of them
         H = W = int(fl.group(1))
         N = 9
     pd = R // 2
-    rng = np.random.default_rng(300 + R + st)
+    rng = np.random.default_rng(300 + R + st + C)
     x = rng.integers(-4, 5, (N, C, H, W)).astype(np.float32)
     w = rng.integers(-4, 5, (K, C, R, R)).astype(np.float32)
+    assert C * R * R * 16 < 2 ** 24
     got, info = _run(x, w, st, pd, variant=name)
     assert info["variant"] == name
     want = oracle.conv_forward(x, w, st, pd)
@@ -126,25 +134,41 @@ def test_toy_config_full(oracle):
     _assert_close(got, oracle.conv_forward(x, w, l.stride, l.pad), oracle.tolerance(l.C, l.R, l.S), l.name)
 
 
+def _whole_images(l):
+    """The images compared in full at full size: the first, the middle and the last one (a tile of
+    the flat tilings that straddles two images in the middle of the batch is then covered too)."""
+    return sorted({0, l.N // 2, l.N - 1})
+
+
 @pytest.mark.parametrize("layer", [l for l in workloads.ALL_LAYERS if l is not workloads.TOY] + workloads.INCEPTION,
                          ids=lambda l: l.name)
 def test_benchmark_layers_full_size(oracle, layer):
-    """Full-size layers in the launch configuration the benchmark times: the first and
-    last image in full where that is cheap, and a seeded sample of outputs everywhere."""
+    """Full-size layers in the launch configuration the benchmark times: the first, the middle
+    and the last image in full, and 10^5 seeded sampled outputs over the whole batch."""
     l = layer
     x, w = workloads.make_inputs(l)
     got, info = _run(x, w, l.stride, l.pad)
     assert got.shape == (l.N, l.K, l.P, l.Q)
     tol = oracle.tolerance(l.C, l.R, l.S)
-    pts = workloads.sample_points(l, 20000)
+    pts = workloads.sample_points(l, 100000)
     want = oracle.conv_forward_points(x, w, pts, l.stride, l.pad)
     _assert_close(got[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]], want, tol, f"{l.name} sample")
-    per_image_flops = l.flops // l.N
-    if per_image_flops <= 1.0e9:
-        for n in sorted({0, l.N - 1}):
-            want = oracle.conv_forward(x[n:n + 1], w, l.stride, l.pad)
-            _assert_close(got[n:n + 1], want, tol, f"{l.name} image {n} via {info['variant']}")
+    for n in _whole_images(l):
+        want = oracle.conv_forward(x[n:n + 1], w, l.stride, l.pad)
+        _assert_close(got[n:n + 1], want, tol, f"{l.name} image {n} via {info['variant']}")
     assert not np.isnan(got).any(), "an output element was never written"
+
+
+@pytest.mark.parametrize("layer", [l for l in workloads.ALL_LAYERS if l.N >= 32 and l.crs * 16 < 2 ** 24], ids=lambda l: l.name)
+def test_benchmark_layers_full_size_integer_inputs_bit_exact(oracle, layer):
+    """The same launch configuration on small-integer inputs, for which every summation order gives the same
+    bits: the first, the middle and the last image, every element equal to the oracle's."""
+    l = layer
+    x, w = workloads.make_integer_inputs(l)
+    got, info = _run(x, w, l.stride, l.pad)
+    for n in _whole_images(l):
+        want = oracle.conv_forward(x[n:n + 1], w, l.stride, l.pad)
+        assert np.array_equal(got[n:n + 1].astype(np.float64), want), f"{l.name} image {n} via {info['variant']}"
 
 
 def test_zero_workspace_and_no_allocation():
