@@ -6,7 +6,7 @@
  * call it; only tests, the smoke check and the benchmark's cpu_baseline leg do.
  * It shares no code, headers, tables or helpers with the HIP implementation.
  *
- * What it computes (paper: Section 3, Algorithm 1 "Naive Convolution", the single
+ * What it computes (paper: Section 3, Algorithm 1, the single
  * multiply-accumulate statement inside six nested loops), extended with a batch
  * dimension and symmetric zero padding:
  *
@@ -133,11 +133,11 @@ int conv_ref_forward_points(const float *in, const float *w, const int32_t *idx,
 
 /*
  * Second evaluation order, for self-checking only (paper: Section 3.1.2,
- * Algorithm 2 "Reorder Convolution"): per image the loops run output row, filter
+ * Algorithm 2): per image the loops run output row, filter
  * row, filter column, input channel, output column, output channel, and every
  * statement adds into out, which therefore starts at zero.  On inputs whose
  * partial sums are all exactly representable this must equal conv_ref_forward
- * bit for bit ("any permutation of the loops is correct").  Serial on purpose.
+ * bit for bit (Section 3: the loops may run in any order).  Serial on purpose.
  */
 int conv_ref_forward_reordered(const float *in, const float *w, double *out,
                                int N, int C, int H, int W, int K, int R, int S, int stride, int pad)
@@ -170,8 +170,8 @@ int conv_ref_forward_reordered(const float *in, const float *w, double *out,
 }
 
 /*
- * Data gradient of the layer (the "backward process to update the image" that the
- * paper's closing section names as a direction; not an algorithm of the paper): the
+ * Data gradient of the layer (the backward pass with respect to the input image, which
+ * the paper's closing section names as a direction; not an algorithm of the paper): the
  * adjoint of the forward map in its input argument, i.e. every product of the
  * definition above, scattered back to the input element it read:
  *
@@ -189,7 +189,9 @@ int conv_ref_dgrad(const float *dy, const float *w, double *dx,
 {
     int P, Q;
     if (check_dims(N, C, H, W, K, R, S, stride, pad, &P, &Q)) return -1;
+#ifdef _OPENMP
 #pragma omp parallel for collapse(2) schedule(static)
+#endif
     for (int n = 0; n < N; ++n)
         for (int c = 0; c < C; ++c)
             for (int h = 0; h < H; ++h)
@@ -211,7 +213,7 @@ int conv_ref_dgrad(const float *dy, const float *w, double *dx,
 }
 
 /*
- * Weight gradient of the layer (the "backward process to update the ... kernel" of the
+ * Weight gradient of the layer (the backward pass with respect to the filter, named in the
  * paper's closing section; not an algorithm of the paper): the adjoint of the forward map
  * in its filter argument, i.e. every product of the definition, collected per filter
  * element:
@@ -228,7 +230,9 @@ int conv_ref_wgrad(const float *x, const float *dy, double *dw,
 {
     int P, Q;
     if (check_dims(N, C, H, W, K, R, S, stride, pad, &P, &Q)) return -1;
+#ifdef _OPENMP
 #pragma omp parallel for collapse(2) schedule(static)
+#endif
     for (int k = 0; k < K; ++k)
         for (int c = 0; c < C; ++c)
             for (int r = 0; r < R; ++r)
