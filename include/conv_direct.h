@@ -1,8 +1,8 @@
 /*
  * conv_direct.h -- C ABI of the MI355X (gfx950) zero-workspace direct convolution.
  *
- * The operation (paper: Section 3, Algorithm 1; "Input I, Kernel Weights F,
- * stride s -> Output O"), with a batch dimension and symmetric zero padding added:
+ * The operation (paper: Section 3, Algorithm 1: an input image, filter weights and a
+ * stride give the output image), with a batch dimension and symmetric zero padding added:
  *
  *   P = floor((H + 2*pad - R) / stride) + 1,  Q = floor((W + 2*pad - S) / stride) + 1
  *   out[n][k][p][q] = sum over c, r, s of
@@ -10,8 +10,8 @@
  *
  * Taps outside the image contribute zero; the filter is not flipped; there is no
  * bias, grouping or dilation; stride and pad are the same in both dimensions.
- * The convolution is computed directly from the plain tensors (paper: Sections 1
- * and 4, "zero memory overhead"): the library never allocates, frees or copies
+ * The convolution is computed directly from the plain tensors, with no memory beyond
+ * them (the paper's central claim, Sections 1 and 4): the library never allocates, frees or copies
  * device memory, makes no packed or lowered copy of the input or the weights, and
  * its kernels use no private scratch.  All arithmetic is fp32 (fp32 MFMA
  * accumulation); the order of the C*R*S additions is unspecified.
@@ -89,8 +89,9 @@ size_t conv_direct_workspace_bytes(const conv_direct_plan *plan);
 
 /*
  * Write a one-line, space-separated key=value description of the plan into buf
- * (variant name, tile, grid, LDS bytes, threads ...), NUL-terminated and truncated
- * to n bytes.  Returns the untruncated length, or a negative error code.
+ * (variant name, tile, grid, LDS bytes, threads ...; for a data-gradient plan also
+ * extra_caller_bytes, the size of the transformed-filter buffer wt the caller provides),
+ * NUL-terminated and truncated to n bytes.  Returns the untruncated length, or a negative error code.
  */
 int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n);
 
@@ -163,8 +164,8 @@ int conv_direct_unpack_act(const float *blocked, float *plain, int N, int C, int
 int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, int S, void *stream);
 
 /* ------------------------------------------------------------------------
- * Data gradient (the backward pass "to update the image" that the paper's closing
- * section names as a direction), plain layouts:
+ * Data gradient (the backward pass with respect to the input image, which the paper's
+ * closing section names as a direction), plain layouts:
  *
  *   dx[n][c][h][w] = sum over k, r, s of dy[n][k][h + pad - r][w + pad - s] * w[k][c][r][s]
  *
@@ -202,7 +203,7 @@ int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, 
  * entry points as it stands: conv_direct_create_layout(&plan, N, K, P, Q, C, R, S, 1, R-1-pad,
  * BLOCKED, BLOCKED), wt from conv_direct_dgrad_filter re-arranged by conv_direct_pack_w(wt, wtb, C, K, R, S).
  *
- * Weight gradient (the backward pass "to update ... the kernel"), plain layouts, any
+ * Weight gradient (the backward pass with respect to the filter), plain layouts, any
  * filter, strides up to 4 (compiled variants for the filter widths and strides of the forward
  * variants, a slower run-time-shape variant for the rest):
  *
@@ -241,7 +242,9 @@ int conv_direct_run_wgrad(const conv_direct_plan *plan,
  *     N C H W K R S stride pad in_layout out_layout variant
  * A loaded entry that names an unknown variant, or one that cannot run its shape, is
  * ignored (the analytical planner decides).  conv_direct_tuning_clear empties the table.
- * The functions that touch the table are not thread-safe against each other.
+ * Every create function reads the table; conv_direct_create_tuned, _tuning_load and
+ * _tuning_clear write it.  Readers and writers are not synchronised: do not call a writer
+ * while another thread is inside any create function.
  * ------------------------------------------------------------------------ */
 int conv_direct_create_tuned(conv_direct_plan **plan,
                              int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
@@ -251,6 +254,24 @@ int conv_direct_tuning_save(const char *path);   /* CONV_DIRECT_EINVAL if the fi
 int conv_direct_tuning_load(const char *path);   /* CONV_DIRECT_EINVAL if the file cannot be read or a line is malformed */
 int conv_direct_tuning_clear(void);
 int conv_direct_tuning_size(void);               /* number of entries */
+
+/* ------------------------------------------------------------------------
+ * Measurement aid: the fp32 MFMA rate this chip sustains right now.  The benchmark states
+ * each layer as a fraction of the nominal fp32 MFMA peak (256 CUs x 256 flop per clock x
+ * 2.4 GHz); under a saturated matrix load the clock is a few per cent lower, and this call
+ * measures by how much.  It enqueues, on `stream`, one kernel of independent
+ * v_mfma_f32_32x32x2_f32 chains on every SIMD: CONV_DIRECT_PROBE_FLOP_PER_ITER * iters flop
+ * in all, to be timed by the caller with events on that stream; rate / 65536 flop per clock
+ * is the shader clock under that load.
+ *   buf : device, the caller's, CONV_DIRECT_PROBE_BYTES bytes, 8-byte aligned.  On return of
+ *         the kernel it holds 512 * 256 floats (sums, of no interest) followed by 512 pairs
+ *         of int64: per workgroup the shader-clock counter's and the constant-rate (100 MHz)
+ *         counter's advance around its loop.
+ * CONV_DIRECT_EINVAL for a NULL buffer or iters < 1, CONV_DIRECT_EALIGN, CONV_DIRECT_EHIP.
+ * ------------------------------------------------------------------------ */
+#define CONV_DIRECT_PROBE_BYTES (512 * 256 * 4 + 512 * 2 * 8)
+#define CONV_DIRECT_PROBE_FLOP_PER_ITER (512.0 * 4 * 8 * 7 * 4096)
+int conv_direct_mfma_probe(void *buf, int iters, void *stream);
 
 #ifdef __cplusplus
 }

@@ -63,6 +63,7 @@ def _units(only=None):
     units.append(("generic", "conv_generic_kernel.hip", defs, COMMON_DEPS, ",".join(sorted(only or []))))
     units.append(("wgrad", "conv_wgrad.hip", [], COMMON_DEPS + [os.path.join(CSRC, "wgrad.h"), os.path.join(CSRC, "conv_dma_kernel.h")], ""))
     units.append(("layout", "conv_layout_kernels.hip", [], COMMON_DEPS + [os.path.join(CSRC, "layout.h")], ""))
+    units.append(("probe", "conv_probe.hip", [], COMMON_DEPS + [os.path.join(CSRC, "layout.h")], ""))
     units.append(("api", "conv_direct_api.cpp", [], COMMON_DEPS + [os.path.join(CSRC, "layout.h"), os.path.join(CSRC, "wgrad.h")], ""))
     return units
 

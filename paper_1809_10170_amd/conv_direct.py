@@ -85,6 +85,8 @@ def lib():
         l.conv_direct_dgrad_wt_elems.restype = ctypes.c_size_t
         l.conv_direct_dgrad_prepare.argtypes = [vp, vp, vp, vp]
         l.conv_direct_dgrad_prepare.restype = i
+        l.conv_direct_mfma_probe.argtypes = [vp, i, vp]
+        l.conv_direct_mfma_probe.restype = i
         for nm in ("conv_direct_pack_act", "conv_direct_unpack_act", "conv_direct_pack_w", "conv_direct_dgrad_filter"):
             getattr(l, nm).argtypes = [vp, vp] + [i] * 4 + [vp]
             getattr(l, nm).restype = i
@@ -154,9 +156,10 @@ class Plan:
         if rc != OK:
             self._p = ctypes.c_void_p()
             raise ConvDirectError(rc, "conv_direct_create_dgrad")
-        P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
-        self.dims = (int(N), int(K), P, Q, int(C), int(R), int(S), 1, R - 1 - pad)   # the forward problem it runs (over dy)
         self._dgrad = True
+        self.fwd_dims = tuple(int(v) for v in (N, C, H, W, K, R, S, stride, pad))
+        i = self.info()   # the problem the plan runs is a forward pass over dy [N][K][P][Q]: its "input" size is P x Q
+        self.dims = (int(N), int(K), i["H"], i["W"], int(C), int(R), int(S), 1, R - 1 - pad)
         return self
 
     def dgrad_wt_elems(self) -> int:
@@ -193,7 +196,8 @@ class Plan:
     def run_wgrad(self, x, dy, dw, stream: int | None = None) -> None:
         import torch
         N, C, H, W, K, R, S, st, pd = self.dims
-        P, Q = (H + 2 * pd - R) // st + 1, (W + 2 * pd - S) // st + 1
+        i = self.info()
+        P, Q = i["P"], i["Q"]
         for t, shape, nm in ((x, (N, C, H, W), "x"), (dy, (N, K, P, Q), "dy"), (dw, (K, C, R, S), "dw")):
             if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == shape):
                 raise ValueError(f"{nm}: need a contiguous fp32 device tensor of shape {shape}")
@@ -330,6 +334,19 @@ def pack_w(plain, blocked, stream=None):
 def dgrad_filter(w, wt, stream=None):
     """w [K][C][R][S] -> wt [C][K][R][S] with wt[c][k][r][s] = w[k][c][R-1-r][S-1-s] (device tensors)."""
     return _rearrange(lib().conv_direct_dgrad_filter, "conv_direct_dgrad_filter", w, wt, w.shape, stream)
+
+
+PROBE_BYTES = 512 * 256 * 4 + 512 * 2 * 8          # CONV_DIRECT_PROBE_BYTES
+PROBE_FLOP_PER_ITER = 512.0 * 4 * 8 * 7 * 4096      # CONV_DIRECT_PROBE_FLOP_PER_ITER
+
+
+def mfma_probe(buf, iters: int, stream=None) -> None:
+    """Enqueue the bare-MFMA measurement kernel (buf: a device tensor of at least PROBE_BYTES bytes)."""
+    if buf.numel() * buf.element_size() < PROBE_BYTES:
+        raise ValueError(f"buf: need {PROBE_BYTES} bytes")
+    rc = lib().conv_direct_mfma_probe(buf.data_ptr(), int(iters), _stream(stream))
+    if rc != OK:
+        raise ConvDirectError(rc, "conv_direct_mfma_probe")
 
 
 def tuning_save(path: str) -> None:

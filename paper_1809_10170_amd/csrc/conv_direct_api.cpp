@@ -101,6 +101,9 @@ bool applicable(const Variant &v, const Shape &s, int in_blocked, int out_blocke
         const int64_t reach = v.img != 0 ? 4 * (int64_t)s.C * plane
                               : (v.pair == convd::PAIR_R || v.pointwise) ? (int64_t)s.C * plane : (int64_t)v.CB * plane;
         if (reach >= ((int64_t)1 << 31)) return false;
+        // rectangular channel-pair tiles bound their loads by the bytes from the chunk's first channel to the
+        // image's end, a 32-bit quantity
+        if (v.img == 0 && v.pair == convd::PAIR_C && !v.pointwise && (int64_t)s.C * plane >= ((int64_t)1 << 32)) return false;
     }
     const int64_t grid = v.img != 0
                              ? (int64_t)cdiv(s.K, v.KT) * ((((int64_t)s.N * s.P * s.Q) + v.NPB * 32 - 1) / (v.NPB * 32))
@@ -403,13 +406,14 @@ int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
                          "variant=%s N=%d C=%d H=%d W=%d K=%d R=%d S=%d stride=%d pad=%d P=%d Q=%d "
                          "TP=%d TQ=%d KT=%d NPB=%d CB=%d pair=%s tilesP=%d tilesQ=%d ktiles=%d grid=%u "
                          "threads=%d lds_bytes=%zu occupancy=%d flat=%d pointwise=%d mfma_efficiency=%.6g in_layout=%s "
-                         "out_layout=%s dgrad_phases=%d workspace_bytes=0",
+                         "out_layout=%s dgrad_phases=%d extra_caller_bytes=%zu workspace_bytes=0",
                          v.name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, v.TP, v.TQ,
                          v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : "r", plan->tilesP,
                          plan->tilesQ, plan->ktiles, plan->grid, v.threads, plan->lds_bytes, v.occupancy,
                          (v.img != 0 || plan->pw_flat) ? 1 : 0, v.pointwise, plan->mfma_efficiency, plan->in_blocked ? "blocked" : "plain",
                          plan->out_blocked ? "blocked" : "plain",
-                         plan->ph_stride ? (plan->ph_stride < plan->fwd_R ? plan->ph_stride : plan->fwd_R) * (plan->ph_stride < plan->fwd_R ? plan->ph_stride : plan->fwd_R) : 0);
+                         plan->ph_stride ? (plan->ph_stride < plan->fwd_R ? plan->ph_stride : plan->fwd_R) * (plan->ph_stride < plan->fwd_R ? plan->ph_stride : plan->fwd_R) : 0,
+                         conv_direct_dgrad_wt_elems(plan) * sizeof(float));
 }
 
 const char *conv_direct_strerror(int code)
@@ -640,7 +644,8 @@ int conv_direct_run_wgrad(const conv_direct_plan *plan, const float *x, const fl
 int conv_direct_create_dgrad(conv_direct_plan **plan, int N, int C, int H, int W, int K, int R, int S, int stride,
                              int pad)
 {
-    if (plan) *plan = nullptr;
+    if (!plan) return CONV_DIRECT_EINVAL;
+    *plan = nullptr;
     Shape fwd;
     const int rc = validate(N, C, H, W, K, R, S, stride, pad, &fwd);
     if (rc != CONV_DIRECT_OK) return rc;
@@ -649,8 +654,10 @@ int conv_direct_create_dgrad(conv_direct_plan **plan, int N, int C, int H, int W
         const int rc1 = make_plan(plan, nullptr, N, K, fwd.P, fwd.Q, C, R, S, 1, R - 1 - pad);
         if (rc1 == CONV_DIRECT_OK) {
             (*plan)->fwd_K = K;  (*plan)->fwd_C = C;  (*plan)->fwd_R = R;  (*plan)->fwd_S = S;
+            return rc1;
         }
-        return rc1;
+        if (rc1 != CONV_DIRECT_EUNSUPPORTED) return rc1;
+        // (no variant serves that forward problem: the runtime-shape path below)
     }
     if (stride > 1 && R == S && (int64_t)N * C * H * W < kMaxElems) {
         // Strided layer, square filter.  With t = h + pad = stride*u + a, only the taps r = a + stride*i reach
@@ -711,6 +718,16 @@ int conv_direct_dgrad_prepare(const conv_direct_plan *plan, const float *w, floa
         return launched(convd::launch_dgrad_phase_filter(w, wt, plan->fwd_K, plan->fwd_C, plan->fwd_R, plan->fwd_S,
                                                          plan->ph_stride, (hipStream_t)stream));
     return launched(convd::launch_dgrad_filter(w, wt, plan->fwd_K, plan->fwd_C, plan->fwd_R, plan->fwd_S, (hipStream_t)stream));
+}
+
+int conv_direct_mfma_probe(void *buf, int iters, void *stream)
+{
+    if (!buf || iters < 1) return CONV_DIRECT_EINVAL;
+    if ((uintptr_t)buf & 7u) return CONV_DIRECT_EALIGN;
+    static_assert(CONV_DIRECT_PROBE_BYTES == convd::PROBE_BLOCKS * (256 * 4 + 2 * 8), "the header states the buffer's size");
+    float *sums = static_cast<float *>(buf);
+    long long *ticks = reinterpret_cast<long long *>(sums + convd::PROBE_BLOCKS * 256);
+    return launched(convd::launch_mfma_probe(sums, ticks, iters, (hipStream_t)stream));
 }
 
 size_t conv_direct_blocked_act_elems(int N, int C, int H, int W)

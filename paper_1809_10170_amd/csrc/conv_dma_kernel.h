@@ -20,9 +20,9 @@
 // B = input (j = output pixel).  The two kk lanes of an instruction take input
 // channels c and c + CB/2 of the chunk at one filter tap, so the filter values one
 // lane needs for a chunk are (CB/2)*R*S consecutive floats of w[k][c..][.][.]: they
-// are loaded from global memory directly into registers and never touch LDS.  Any
-// order of the C*R*S additions is a correct convolution (Section 3, "any
-// permutation of the loops").
+// are loaded from global memory directly into registers and never touch LDS.  The
+// order of the C*R*S additions is free: every loop order computes the same
+// convolution (Section 3).
 //
 // Input staging uses buffer_load_dword ... lds: 64 lanes write 64 consecutive LDS
 // words, out-of-range lanes (zero padding, channels past C) read past the buffer
@@ -31,6 +31,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 
 #include "variant.h"
@@ -135,6 +136,13 @@ __device__ __forceinline__ void *uniform_ptr(const void *p)
                     (uintptr_t)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)pa));
 }
 
+// Wait until every vector-memory operation this wave has issued is complete
+// (s_waitcnt vmcnt(0); expcnt and lgkmcnt left at their maxima).  LDS-direct loads
+// (buffer_load ... lds) are counted by vmcnt, not by lgkmcnt: a wave that hands
+// LDS filled by such loads to another wave (through a barrier or a release) states
+// this wait itself instead of relying on what the compiler inserts for the fence.
+__device__ __forceinline__ void wait_vmem_done() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 // Epilogue stores of one 32 x 32 accumulator block whose 32 output channels all exist:
 // buffer stores with the channel row as a scalar offset and one precomputed 32-bit
 // register per lane (byte offset of out[.][4h][p][q] from the resource base, or an
@@ -181,7 +189,7 @@ __device__ __forceinline__ void store_block_pencils(__amdgpu_buffer_rsrc_t rsrc,
 // ALU work; otherwise plain guarded stores.  Each output element is written exactly once.
 //
 // Point-wise layers that follow a convolution (bias, skip connection, activation) fold
-// into this store (paper, Section 4.3: they "should not require any significant change"):
+// into this store (paper, Section 4.3: such layers need no change of the algorithm):
 // with a tail, every value becomes relu?(acc + bias[k] + residual[where it is stored])
 // before it is written.  Without one (the uniform test below) nothing changes.
 struct Tail {
@@ -517,15 +525,25 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
         constexpr int NW = G::NWG;
         unsigned *meet = reinterpret_cast<unsigned *>(lds + goffs + 3 * G::BUF);  // arrivals so far, all chunks
         auto arrive = [&]() {
-            // release: everything this wave has issued, the LDS-direct loads included, is complete
+            // everything this wave has issued, the LDS-direct loads of the next chunk included, is
+            // complete (the only vector-memory operations in flight here are those loads), then release
+            wait_vmem_done();
             if (lane == 0) __hip_atomic_fetch_add(meet, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         };
+        // The wait is bounded so that no wave can hang the GPU.  In a correct run the bound is never
+        // reached: every wave of the group executes the same number of chunks and arrives exactly once
+        // per chunk without waiting for anybody, so the count reaches every target after at most one
+        // chunk's work of the slowest wave (microseconds; the bound is some 0.1 s).  Should it expire
+        // all the same, the wave remembers it and stores NaN instead of sums over data it could not
+        // know to be complete: a parity check or the caller sees the failure.
+        bool late = false;
         auto all_arrived = [&](unsigned target) {
-            // bounded: a wave that never saw the count would go on (to wrong results) rather than hang
+            bool seen = false;
             for (int spin = 0; spin < (1 << 22); ++spin) {
-                if (__hip_atomic_load(meet, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= target) break;
+                if (__hip_atomic_load(meet, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= target) { seen = true; break; }
                 __builtin_amdgcn_s_sleep(1);
             }
+            late |= !seen;
         };
         auto step_off = [](int t) {   // LDS offset (floats) of reduction step t of a chunk
             if (G::BLK) return ((t / 2 / G::S) * G::LW + (t / 2) % G::S) * 4 + t % 2;   // tap t/2, channel t%2 of the half
@@ -587,6 +605,7 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
         load_a(a0, chan0(0));
         stage_b(b1, chan0(1));
         load_a(a1, chan0(1));
+        wait_vmem_done();   // this wave's part of the first two stage buffers has landed
         __syncthreads();
     #pragma unroll
         for (int d = 0; d < G::PF; ++d) fetch(b0, d, bq[d]);
@@ -598,7 +617,10 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
 
         if (G::SC > 1) {
             // Sum the split groups' partial tiles into group 0: groups 1.. write theirs to LDS
-            // (the stage buffers are free once every wave is here), group 0 adds them up.
+            // (the stage buffers are free once every wave is here), group 0 adds them up.  Past its last
+            // chunk a wave has staged that chunk again into buffers nothing reads: those loads must have
+            // landed before the buffers are written as the exchange area.
+            wait_vmem_done();
             __syncthreads();
             float *red = lds;
             if (sc > 0) {
@@ -623,6 +645,12 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
         }
 
         // ---- epilogue (see write_block) ----
+        if (late) {   // a meeting's bounded wait expired (see all_arrived): no sums, NaN
+#pragma unroll
+            for (int pb = 0; pb < PBW; ++pb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[pb][v] = __builtin_nanf("");
+        }
         const int kw = k0 + wk * 32;
         const int KO = a.out_blocked ? (K + 3) / 4 * 4 : K;      // channels an output image occupies
         // output re-mapping, see KernelArgs
@@ -681,14 +709,29 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_dma_remap_kernel(const Ker
 // ---------------------------------------------------------------------------
 inline bool has_tail(const KernelArgs &a) { return a.bias != nullptr || a.residual != nullptr || a.relu != 0; }
 
+// Workgroups above the 64 KB default need the kernel's dynamic LDS limit raised (no allocation
+// involved).  Once per kernel and device is enough: `done` is the calling launcher's own bit mask of
+// the devices it has been raised on (devices past 63 are asked every time).
+inline hipError_t raise_lds_limit(const void *kernel, size_t bytes, std::atomic<unsigned long long> &done)
+{
+    if (bytes <= 64 * 1024) return hipSuccess;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = dev >= 0 && dev < 64 ? 1ull << dev : 0ull;
+    if (bit && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
+
 template <class G, bool TAILC>
 static hipError_t launch_dma_remap(const KernelArgs &a, unsigned grid, hipStream_t stream)
 {
-    if (G::LDS_BYTES > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_dma_remap_kernel<G, TAILC>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES);
-        if (e != hipSuccess) return e;
-    }
+    static std::atomic<unsigned long long> raised{0};
+    if (hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(&conv_dma_remap_kernel<G, TAILC>), G::LDS_BYTES, raised);
+        e != hipSuccess)
+        return e;
     hipLaunchKernelGGL((conv_dma_remap_kernel<G, TAILC>), dim3(grid), dim3(G::NT), G::LDS_BYTES, stream, a);
     return hipGetLastError();
 }
@@ -696,12 +739,10 @@ static hipError_t launch_dma_remap(const KernelArgs &a, unsigned grid, hipStream
 template <class G, bool TAILC, bool FUSED>
 static hipError_t launch_dma_tf(const KernelArgs &a, unsigned grid, hipStream_t stream)
 {
-    if (G::LDS_BYTES > 64 * 1024) {
-        // workgroups above the 64 KB default need the limit raised (no allocation involved)
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_dma_kernel<G, TAILC, FUSED>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES);
-        if (e != hipSuccess) return e;
-    }
+    static std::atomic<unsigned long long> raised{0};
+    if (hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(&conv_dma_kernel<G, TAILC, FUSED>), G::LDS_BYTES, raised);
+        e != hipSuccess)
+        return e;
     hipLaunchKernelGGL((conv_dma_kernel<G, TAILC, FUSED>), dim3(grid), dim3(G::NT), G::LDS_BYTES, stream, a);
     return hipGetLastError();
 }

@@ -217,7 +217,8 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
 
         float a0[G::KBW][G::NA], a1[G::KBW][G::NA];
         load_a(a0, 0, 0);
-        __syncthreads();   // the staged window is complete (the compiler waits for the LDS-direct loads)
+        wait_vmem_done();  // this wave's part of the staged window has landed
+        __syncthreads();   // ... and so has everybody else's
         for (int c = 0; c < C; ++c) {
             const float *chan = lds + c * G::PSP;
     #pragma unroll
@@ -261,11 +262,10 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
 template <class G, bool FUSED>
 static hipError_t launch_rows_f(const KernelArgs &a, unsigned grid, hipStream_t stream)
 {
-    if (G::LDS_BYTES > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_rows_kernel<G, FUSED>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES);
-        if (e != hipSuccess) return e;
-    }
+    static std::atomic<unsigned long long> raised{0};
+    if (hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(&conv_rows_kernel<G, FUSED>), G::LDS_BYTES, raised);
+        e != hipSuccess)
+        return e;
     hipLaunchKernelGGL((conv_rows_kernel<G, FUSED>), dim3(grid), dim3(G::NT), G::LDS_BYTES, stream, a);
     return hipGetLastError();
 }

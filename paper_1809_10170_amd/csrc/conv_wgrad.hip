@@ -2,8 +2,8 @@
 //
 //   dw[k][c][r][s] = sum over n, p, q of  dy[n][k][p][q] * x[n][c][p*stride + r - pad][q*stride + s - pad]
 //
-// (taps outside the image contribute nothing).  The paper names the backward pass "to
-// update ... the kernel" as a direction (closing section) and gives no algorithm; this is
+// (taps outside the image contribute nothing).  The paper names the backward pass with
+// respect to the filter as a direction (closing section) and gives no algorithm; this is
 // the same direct scheme turned around: a dense contraction whose reduction runs over the
 // output pixels, computed from the plain tensors with the input window of a row of
 // pixels staged in LDS, so that the S taps of a filter row read it at S constant offsets
@@ -357,8 +357,8 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
     // chunk's loads, multiply
     auto chunk_body = [&](int bf, int aoffc, const int (&xoffc)[G::NBLK]) __attribute__((always_inline)) {
         advance();                                            // (n, p, q0) is now the next chunk
-        __syncthreads();   // chunk bf has landed (the barrier's fence waits for the LDS-direct loads) and
-                           // every wave has left the other buffer
+        wait_vmem_done();  // this wave's loads of chunk bf (the only ones in flight) have landed
+        __syncthreads();   // chunk bf is complete and every wave has left the other buffer
         if (n < N) stage(bf ^ 1, n, p, q0);
         // operands of step t+1 are fetched from LDS while step t multiplies
         float an = lds[aoffc], bn[G::NBLK];
@@ -445,11 +445,9 @@ __global__ void __launch_bounds__(256) wgrad_clear_kernel(float *dw, long long e
 template <class G>
 static hipError_t launch_wg(const WgradArgs &a, unsigned grid, hipStream_t stream)
 {
-    if (G::LDS_BYTES > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_wgrad_kernel<G>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES);
-        if (e != hipSuccess) return e;
-    }
+    static std::atomic<unsigned long long> raised{0};
+    if (hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(&conv_wgrad_kernel<G>), G::LDS_BYTES, raised); e != hipSuccess)
+        return e;
     hipLaunchKernelGGL((conv_wgrad_kernel<G>), dim3(grid), dim3(G::NT), G::LDS_BYTES, stream, a);
     return hipGetLastError();
 }

@@ -9,4 +9,8 @@ hipError_t launch_pack_w(const float *plain, float *blocked, int K, int C, int R
 hipError_t launch_dgrad_filter(const float *w, float *wt, int K, int C, int R, int S, hipStream_t stream);
 hipError_t launch_dgrad_phase_filter(const float *w, float *wt, int K, int C, int R, int S, int stride, hipStream_t stream);
 hipError_t launch_fill_zero(float *dst, long long elems, hipStream_t stream);
+// Bare MFMA chains on every SIMD (conv_probe.hip): PROBE_BLOCKS workgroups of 256 threads, two per CU; every thread
+// writes one float of sums, every workgroup two counters of ticks (shader clock, constant-rate clock).
+constexpr int PROBE_BLOCKS = 512;
+hipError_t launch_mfma_probe(float *sums, long long *ticks, int iters, hipStream_t stream);
 }  // namespace convd

@@ -261,3 +261,50 @@ def test_layout_gradient_and_tail_entry_points_check_arguments_before_any_launch
     assert L.conv_direct_create_tuned(ctypes.byref(p), *dims, 0, 0, None, 8192, 12288, None, 3) == cd.EINVAL
     assert L.conv_direct_create_tuned(ctypes.byref(p), *dims, 0, 0, 4096, 8192, 12288, None, 0) == cd.EINVAL
     assert L.conv_direct_create_tuned(ctypes.byref(p), *dims, 0, 3, 4096, 8192, 12288, None, 3) == cd.EINVAL
+
+
+def test_data_gradient_create_rejects_a_null_plan_pointer():
+    L = cd.lib()
+    for dims in ([2, 8, 20, 20, 9, 3, 3, 1, 1], [2, 8, 20, 20, 9, 3, 3, 2, 1], [2, 5, 23, 31, 7, 3, 5, 1, 1]):
+        assert L.conv_direct_create_dgrad(None, *dims) == cd.EINVAL
+
+
+def test_images_of_four_gigabytes_are_not_given_to_32_bit_spans():
+    """One image of C*H*W*4 >= 2^32 bytes (the whole tensor still below 2^31 elements): the rectangular
+    channel-pair tiles bound their loads by a 32-bit byte count from the chunk's first channel to the
+    image's end, so the planner must not choose them."""
+    N, C, H, W = 1, 1024, 1024, 1024
+    assert C * H * W * 4 >= 2 ** 32 and N * C * H * W < 2 ** 31
+    L = cd.lib()
+    p = ctypes.c_void_p()
+    rc = L.conv_direct_create(ctypes.byref(p), N, C, H, W, 1, 3, 3, 1, 1)
+    if rc == cd.OK:
+        buf = ctypes.create_string_buffer(1024)
+        L.conv_direct_plan_info(p, buf, len(buf))
+        assert b"variant=generic" in buf.value, buf.value
+        L.conv_direct_destroy(p)
+    else:
+        assert rc == cd.EUNSUPPORTED
+    for nm in cd.variant_names():
+        if nm.startswith("d3s1") and "flat" not in nm:
+            assert L.conv_direct_create_with_variant(ctypes.byref(p), nm.encode(), N, C, H, W, 1, 3, 3, 1, 1) == cd.EUNSUPPORTED
+
+
+def test_probe_rejects_bad_arguments_before_any_launch():
+    L = cd.lib()
+    assert L.conv_direct_mfma_probe(None, 10, None) == cd.EINVAL
+    assert L.conv_direct_mfma_probe(4096, 0, None) == cd.EINVAL
+    assert L.conv_direct_mfma_probe(4100, 10, None) == cd.EALIGN
+
+
+def test_plan_info_states_the_data_gradient_s_extra_buffer():
+    plan = cd.Plan.dgrad(2, 8, 20, 20, 9, 3, 3, 1, 1)
+    assert plan.info()["extra_caller_bytes"] == 4 * 9 * 8 * 3 * 3 == 4 * plan.dgrad_wt_elems()
+    assert plan.dims[:4] == (2, 9, 20, 20)
+    plan.destroy()
+    plan = cd.Plan.dgrad(2, 8, 20, 20, 9, 3, 3, 2, 1)     # four phase filters of 2 x 2 taps
+    assert plan.info()["extra_caller_bytes"] == 4 * 4 * 9 * 8 * 2 * 2
+    plan.destroy()
+    fwd = cd.Plan(2, 8, 20, 20, 9, 3, 3, 1, 1)
+    assert fwd.info()["extra_caller_bytes"] == 0 and fwd.info()["workspace_bytes"] == 0
+    fwd.destroy()
