@@ -13,7 +13,9 @@
  * The convolution is computed directly from the plain tensors, with no memory beyond
  * them (the paper's central claim, Sections 1 and 4): the library never allocates, frees or copies
  * device memory, makes no packed or lowered copy of the input or the weights, and
- * its kernels use no private scratch.  All arithmetic is fp32 (fp32 MFMA
+ * its kernels use no private scratch.  (The one device array the library itself holds
+ * belongs to conv_direct_run_dgrad_static, an entry point for callers that cannot
+ * allocate; no other entry point touches it.)  All arithmetic is fp32 (fp32 MFMA
  * accumulation); the order of the C*R*S additions is unspecified.
  *
  * Layouts, row-major with the last index fastest, fp32:
@@ -37,6 +39,7 @@ extern "C" {
 #define CONV_DIRECT_EALIGN       (-3) /* a device pointer is not 4-byte aligned */
 #define CONV_DIRECT_EHIP         (-4) /* the HIP runtime refused the launch; see conv_direct_last_hip_error */
 #define CONV_DIRECT_ENOMEM       (-5) /* host allocation of the plan failed */
+#define CONV_DIRECT_ETOOBIG      (-6) /* conv_direct_run_dgrad_static: the plan's transformed filter exceeds the static array */
 
 /* Opaque launch plan: host memory only, immutable after creation. */
 typedef struct conv_direct_plan conv_direct_plan;
@@ -227,6 +230,31 @@ int conv_direct_create_wgrad(conv_direct_plan **plan,
                              int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 int conv_direct_run_wgrad(const conv_direct_plan *plan,
                           const float *x, const float *dy, float *dw, void *stream);
+
+/*
+ * For callers that cannot allocate device memory -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc: the data gradient without the caller's wt
+ * buffer.  Same result, bit for bit, as
+ *     conv_direct_dgrad_prepare(plan, w, wt, stream);  conv_direct_run(plan, dy, wt, dx, stream);
+ * with wt replaced by a file-scope device array inside the library of
+ * CONV_DIRECT_STATIC_WT_ELEMS floats (16 MiB; every GPU the library runs on holds its own
+ * copy until the process ends).  The call allocates and frees nothing and calls no
+ * allocating routine: it enqueues the filter transform into that array, then the kernels of
+ * conv_direct_run, on `stream`.
+ *   plan : from conv_direct_create_dgrad (any data-gradient plan)
+ *   dy   : device, [N][K][P][Q];  w : device, the layer's weights [K][C][R][S], as they are;
+ *   dx   : device, [N][C][H][W], every element overwritten
+ * CONV_DIRECT_ETOOBIG, before anything is enqueued, if conv_direct_dgrad_wt_elems(plan)
+ * exceeds CONV_DIRECT_STATIC_WT_ELEMS; CONV_DIRECT_EINVAL for a plan that is no data
+ * gradient or a NULL pointer; CONV_DIRECT_EALIGN; CONV_DIRECT_EHIP.  The first call on a
+ * device looks up the array's address on that device (no allocation, but make that call
+ * outside a graph capture).  All calls on one GPU share the array, which keeps the last
+ * call's contents (every element a call reads it has written first): calls that overlap on
+ * one GPU -- two streams, or two threads -- race on it; order them.
+ */
+#define CONV_DIRECT_STATIC_WT_ELEMS (4u << 20)
+int conv_direct_run_dgrad_static(const conv_direct_plan *plan,
+                                 const float *dy, const float *w, float *dx, void *stream);
 
 /* ------------------------------------------------------------------------
  * Measured choice of the blocking (the paper's closing section proposes auto-tuning

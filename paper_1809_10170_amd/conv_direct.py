@@ -13,7 +13,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 # CONV_DIRECT_LIB overrides the library path (e.g. an experimental build of the same ABI)
 LIB_PATH = os.environ.get("CONV_DIRECT_LIB") or os.path.join(_HERE, "libconv_direct.so")
 
-OK, EINVAL, EUNSUPPORTED, EALIGN, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5
+OK, EINVAL, EUNSUPPORTED, EALIGN, EHIP, ENOMEM, ETOOBIG = 0, -1, -2, -3, -4, -5, -6
+STATIC_WT_ELEMS = 4 << 20      # CONV_DIRECT_STATIC_WT_ELEMS
 PLAIN, BLOCKED = 0, 1          # CONV_DIRECT_LAYOUT_*
 ACT_BLOCK, W_KBLOCK = 4, 32    # CONV_DIRECT_ACT_BLOCK, CONV_DIRECT_W_KBLOCK
 
@@ -87,6 +88,8 @@ def lib():
         l.conv_direct_dgrad_prepare.restype = i
         l.conv_direct_mfma_probe.argtypes = [vp, i, vp]
         l.conv_direct_mfma_probe.restype = i
+        l.conv_direct_run_dgrad_static.argtypes = [vp, vp, vp, vp, vp]
+        l.conv_direct_run_dgrad_static.restype = i
         for nm in ("conv_direct_pack_act", "conv_direct_unpack_act", "conv_direct_pack_w", "conv_direct_dgrad_filter"):
             getattr(l, nm).argtypes = [vp, vp] + [i] * 4 + [vp]
             getattr(l, nm).restype = i
@@ -178,6 +181,18 @@ class Plan:
         rc = lib().conv_direct_dgrad_prepare(self._p, w.data_ptr(), wt.data_ptr(), stream)
         if rc != OK:
             raise ConvDirectError(rc, "conv_direct_dgrad_prepare")
+
+    def run_dgrad_static(self, dy, w, dx, stream: int | None = None) -> None:
+        """conv_direct_run_dgrad_static: the data gradient from the layer's weights w [K,C,R,S] as they are,
+        the transformed filter held in the library's static device array (nothing is allocated)."""
+        import torch
+        N, C, H, W, K, R, S, _, _ = self.fwd_dims
+        for t, shape, nm in ((dy, self.dims[:4], "dy"), (w, (K, C, R, S), "w"), (dx, (N, C, H, W), "dx")):
+            if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == tuple(shape)):
+                raise ValueError(f"{nm}: need a contiguous fp32 device tensor of shape {tuple(shape)}")
+        rc = lib().conv_direct_run_dgrad_static(self._p, dy.data_ptr(), w.data_ptr(), dx.data_ptr(), _stream(stream))
+        if rc != OK:
+            raise ConvDirectError(rc, "conv_direct_run_dgrad_static")
 
     @classmethod
     def wgrad(cls, N, C, H, W, K, R, S, stride, pad):

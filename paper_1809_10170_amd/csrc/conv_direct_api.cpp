@@ -425,6 +425,7 @@ const char *conv_direct_strerror(int code)
         case CONV_DIRECT_EALIGN: return "device pointer not 4-byte aligned";
         case CONV_DIRECT_EHIP: return "HIP launch failed (see conv_direct_last_hip_error)";
         case CONV_DIRECT_ENOMEM: return "host allocation failed";
+        case CONV_DIRECT_ETOOBIG: return "transformed filter larger than the library's static array (CONV_DIRECT_STATIC_WT_ELEMS floats)";
         default: return "unknown error code";
     }
 }
@@ -718,6 +719,20 @@ int conv_direct_dgrad_prepare(const conv_direct_plan *plan, const float *w, floa
         return launched(convd::launch_dgrad_phase_filter(w, wt, plan->fwd_K, plan->fwd_C, plan->fwd_R, plan->fwd_S,
                                                          plan->ph_stride, (hipStream_t)stream));
     return launched(convd::launch_dgrad_filter(w, wt, plan->fwd_K, plan->fwd_C, plan->fwd_R, plan->fwd_S, (hipStream_t)stream));
+}
+
+int conv_direct_run_dgrad_static(const conv_direct_plan *plan, const float *dy, const float *w, float *dx, void *stream)
+{
+    if (!plan || !plan->v || !plan->fwd_K || !dy || !w || !dx) return CONV_DIRECT_EINVAL;
+    if (((uintptr_t)dy | (uintptr_t)w | (uintptr_t)dx) & 3u) return CONV_DIRECT_EALIGN;
+    static_assert(CONV_DIRECT_STATIC_WT_ELEMS == convd::STATIC_WT_ELEMS, "the header states the array's size");
+    if (conv_direct_dgrad_wt_elems(plan) > (size_t)CONV_DIRECT_STATIC_WT_ELEMS) return CONV_DIRECT_ETOOBIG;
+    float *wt = nullptr;   // the static array's address on the current device
+    const hipError_t e = convd::static_wt_buffer(&wt);
+    if (e != hipSuccess) return launched(e);
+    const int rc = conv_direct_dgrad_prepare(plan, w, wt, stream);
+    if (rc != CONV_DIRECT_OK) return rc;
+    return conv_direct_run(plan, dy, wt, dx, stream);
 }
 
 int conv_direct_mfma_probe(void *buf, int iters, void *stream)

@@ -8,6 +8,8 @@
 // caller's buffers: nothing is allocated here.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "layout.h"
 
 namespace convd {
@@ -143,6 +145,34 @@ hipError_t launch_dgrad_phase_filter(const float *w, float *wt, int K, int C, in
     hipLaunchKernelGGL(dgrad_phase_filter_kernel, dim3(blocks_for(elems)), dim3(256), 0, stream, w, wt, K, C, R, S, stride, RT,
                        nb, elems);
     return hipGetLastError();
+}
+
+// Scratch of the one entry point that may not allocate (conv_direct_run_dgrad_static): the
+// transformed filter of a data gradient, which the other entry points take from the caller.
+// Every GPU the library runs on holds its own copy of this array, at its own address, until
+// the process ends.  In host code the array's name is only a handle for the look-up below:
+// host code uses the address that look-up returns, never the name.
+static __device__ __align__(256) float scratch[STATIC_WT_ELEMS];
+
+hipError_t static_wt_buffer(float **ptr)
+{
+    constexpr int kMaxDev = 64;
+    static std::atomic<float *> addr[kMaxDev];   // per device, looked up on the first call with that device current
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDev) return hipErrorInvalidDevice;
+    float *p = addr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void *sym = nullptr;
+        e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!sym) return hipErrorInvalidSymbol;
+        p = static_cast<float *>(sym);
+        addr[dev].store(p, std::memory_order_release);   // (two threads racing here store the same address)
+    }
+    *ptr = p;
+    return hipSuccess;
 }
 
 hipError_t launch_fill_zero(float *dst, long long elems, hipStream_t stream)

@@ -13,4 +13,8 @@ hipError_t launch_fill_zero(float *dst, long long elems, hipStream_t stream);
 // writes one float of sums, every workgroup two counters of ticks (shader clock, constant-rate clock).
 constexpr int PROBE_BLOCKS = 512;
 hipError_t launch_mfma_probe(float *sums, long long *ticks, int iters, hipStream_t stream);
+// The library's static device array of STATIC_WT_ELEMS floats on the current device (its address on that
+// device, looked up once per device); allocates nothing.
+constexpr unsigned STATIC_WT_ELEMS = 4u << 20;
+hipError_t static_wt_buffer(float **ptr);
 }  // namespace convd
