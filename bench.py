@@ -119,26 +119,27 @@ def copy_probe(nbytes=1 << 30, reps=5):
     print(json.dumps({"copy_probe_bytes_read": nbytes, "copy_probe_bytes_written": nbytes, "reps": reps}))
 
 
-def measure_clock(cd, torch, stream, iters=2000, reps=5):
-    """Bare-MFMA probe: the fp32 MFMA rate the chip sustains now, and the clock that rate implies."""
+def measure_clock(cd, torch, stream, iters=20000, reps=2):
+    """Bare-MFMA probe: the shader clock under a saturated fp32 matrix load, from the probe's own counters
+    (shader-clock ticks per tick of the constant 100 MHz counter around its loop), and the flop rate it
+    reaches.  The clock ramps up over the first tens of milliseconds of load, so each probe launch runs
+    for about 60 ms and the last one counts."""
     buf = torch.empty(cd.PROBE_BYTES // 8, device="cuda", dtype=torch.int64)
-    cd.mfma_probe(buf, 100, stream.cuda_stream)
+    cd.mfma_probe(buf, iters, stream.cuda_stream)
     torch.cuda.synchronize()
-    ms = []
     for _ in range(reps):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
         cd.mfma_probe(buf, iters, stream.cuda_stream)
         e1.record(stream)
         e1.synchronize()
-        ms.append(e0.elapsed_time(e1))
-    ms.sort()
-    tflops = cd.PROBE_FLOP_PER_ITER * iters / (ms[len(ms) // 2] * 1e-3) / 1e12
+        ms = e0.elapsed_time(e1)
+    tflops = cd.PROBE_FLOP_PER_ITER * iters / (ms * 1e-3) / 1e12
     ticks = buf[512 * 256 * 4 // 8:].cpu().numpy().reshape(512, 2)
-    ratio = sorted((ticks[:, 0] / ticks[:, 1]).tolist())[256]   # shader-clock ticks per tick of the 100 MHz counter
-    return {"probe": "bare v_mfma_f32_32x32x2_f32 chains, 2 waves per SIMD", "probe_tflops": round(tflops, 2),
-            "clock_mhz": round(tflops * 1e12 / FLOP_PER_CLOCK / 1e6, 1),
-            "clock_mhz_from_counters": round(ratio * 100.0, 1), "nominal_clock_mhz": PEAK_CLOCK_MHZ}
+    ratio = sorted((ticks[:, 0] / ticks[:, 1]).tolist())[256]
+    return {"probe": "bare v_mfma_f32_32x32x2_f32 chains, 2 waves per SIMD, 60 ms", "clock_mhz": round(ratio * 100.0, 1),
+            "probe_tflops": round(tflops, 2), "clock_mhz_from_rate": round(tflops * 1e12 / FLOP_PER_CLOCK / 1e6, 1),
+            "nominal_clock_mhz": PEAK_CLOCK_MHZ}
 
 
 class Runner:
