@@ -89,7 +89,7 @@ bool applicable(const Variant &v, const Shape &s, int in_blocked, int out_blocke
 {
     if (v.R != 0 && (v.in_blocked != 0) != (in_blocked != 0)) return false;   // (the runtime-shape fallback takes either)
     if (v.R != 0 && (v.R != s.R || v.S != s.S || v.stride != s.stride)) return false;
-    if (v.pair == convd::PAIR_R && s.C > v.CB) return false;   // stages all channels at once
+    if ((v.pair == convd::PAIR_R || v.pair == convd::PAIR_T) && s.C > v.CB) return false;   // stages all channels at once
     if (v.img != 0 && (s.H != v.img || s.W != v.img || s.pad != v.pad)) return false;   // flat tiling
     if (v.pointwise && s.pad != 0) return false;
     if (v.pointwise == 2 && (!pointwise_flat(v, s) || ((int64_t)s.H * s.W) % v.TQ == 0)) return false;
@@ -99,7 +99,7 @@ bool applicable(const Variant &v, const Shape &s, int in_blocked, int out_blocke
         // channel they stage: one chunk of channels (flat tiling: of up to 4 images, whole)
         const int64_t plane = (int64_t)s.H * s.W * 4;
         const int64_t reach = v.img != 0 ? 4 * (int64_t)s.C * plane
-                              : (v.pair == convd::PAIR_R || v.pointwise) ? (int64_t)s.C * plane : (int64_t)v.CB * plane;
+                              : (v.pair != convd::PAIR_C || v.pointwise) ? (int64_t)s.C * plane : (int64_t)v.CB * plane;
         if (reach >= ((int64_t)1 << 31)) return false;
         // rectangular channel-pair tiles bound their loads by the bytes from the chunk's first channel to the
         // image's end, a 32-bit quantity
@@ -147,6 +147,8 @@ void fill(conv_direct_plan *p, const Shape &s, const Variant &v)
         red = 2.0 * cdiv(s.C, 2);
     } else if (v.pair == convd::PAIR_C) {
         red = (double)cdiv(s.C, v.CB) * v.CB * s.R * s.S;
+    } else if (v.pair == convd::PAIR_T) {
+        red = (double)s.C * s.R * s.S;
     } else {
         red = (double)s.C * (2 * ((s.R + 1) / 2)) * s.S;
     }
@@ -203,7 +205,7 @@ double cost(const conv_direct_plan &p)
     double staged;   // floats one workgroup stages in total
     if (v.R == 0) {
         staged = (double)s.C * s.R * (2.0 * ((convd_generic_tq - 1) * s.stride + s.S)) * 2.0;
-    } else if (v.pair == convd::PAIR_R) {
+    } else if (v.pair != convd::PAIR_C) {
         staged = (double)s.C * v.window;
     } else {
         staged = (double)cdiv(s.C, v.CB) * v.CB * v.window;
@@ -408,7 +410,7 @@ int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
                          "threads=%d lds_bytes=%zu occupancy=%d flat=%d pointwise=%d mfma_efficiency=%.6g in_layout=%s "
                          "out_layout=%s dgrad_phases=%d extra_caller_bytes=%zu workspace_bytes=0",
                          v.name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, v.TP, v.TQ,
-                         v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : "r", plan->tilesP,
+                         v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : v.pair == convd::PAIR_R ? "r" : "t", plan->tilesP,
                          plan->tilesQ, plan->ktiles, plan->grid, v.threads, plan->lds_bytes, v.occupancy,
                          (v.img != 0 || plan->pw_flat) ? 1 : 0, v.pointwise, plan->mfma_efficiency, plan->in_blocked ? "blocked" : "plain",
                          plan->out_blocked ? "blocked" : "plain",

@@ -110,7 +110,8 @@ struct DmaGeom {
     static constexpr int NA = HC * RS;                   // filter values per lane and chunk
     static constexpr int STEPS = HC * RS;                // MFMA k-steps per chunk
     static constexpr int GRP = 3 * BUF + 16;             // floats per split group: three stage buffers, arrival counter
-    static constexpr int RED = (SC - 1) * NWG * PBW * 1024;   // floats of the final sum's exchange
+    static constexpr int RED = (SC / 2) * NWG * PBW * 1024;   // floats of the final sum's exchange (a tree: half the groups write)
+    static_assert((SC & (SC - 1)) == 0, "the split groups' tiles are summed as a binary tree");
     static constexpr size_t LDS_BYTES = sizeof(float) * (size_t)(SC * GRP > RED ? SC * GRP : RED);
     static_assert(CB % 2 == 0, "channel pairing needs an even chunk");
     static_assert(!BLK || CB == 4, "blocked layout: a chunk is one block of 4 channels");
@@ -616,32 +617,37 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
         }
 
         if (G::SC > 1) {
-            // Sum the split groups' partial tiles into group 0: groups 1.. write theirs to LDS
-            // (the stage buffers are free once every wave is here), group 0 adds them up.  Past its last
-            // chunk a wave has staged that chunk again into buffers nothing reads: those loads must have
-            // landed before the buffers are written as the exchange area.
+            // Sum the split groups' partial tiles into group 0, as a tree: at every level the upper half of
+            // the groups still in play write their tiles to LDS (the stage buffers are free once every wave
+            // is here) and the lower half add them, group g taking group g + half's.  The order of the
+            // additions is fixed, so the result does not depend on timing.  Past its last chunk a wave has
+            // staged that chunk again into buffers nothing reads: those loads must have landed before the
+            // buffers are written as the exchange area.
             wait_vmem_done();
             __syncthreads();
             float *red = lds;
-            if (sc > 0) {
-                float *mine = red + ((sc - 1) * G::NWG + wave) * PBW * 1024;
     #pragma unroll
-                for (int pb = 0; pb < PBW; ++pb)
+            for (int half = G::SC / 2; half >= 1; half /= 2) {
+                if (sc >= half && sc < 2 * half) {
+                    float *mine = red + ((sc - half) * G::NWG + wave) * PBW * 1024;
     #pragma unroll
-                    for (int v = 0; v < 16; ++v) mine[(pb * 16 + v) * 64 + lane] = acc[pb][v];
-            }
-            __syncthreads();
-            if (sc > 0) return;
+                    for (int pb = 0; pb < PBW; ++pb)
     #pragma unroll
-            for (int g = 1; g < G::SC; ++g) {
-                const float *theirs = red + ((g - 1) * G::NWG + wave) * PBW * 1024;
-    #pragma unroll
-                for (int pb = 0; pb < PBW; ++pb) {
-    #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[pb][v] += theirs[(pb * 16 + v) * 64 + lane];
-                    __builtin_amdgcn_sched_barrier(0);   // one block at a time: 16 loads in flight, not 16*PBW
+                        for (int v = 0; v < 16; ++v) mine[(pb * 16 + v) * 64 + lane] = acc[pb][v];
                 }
+                __syncthreads();
+                if (sc < half) {
+                    const float *theirs = red + (sc * G::NWG + wave) * PBW * 1024;
+    #pragma unroll
+                    for (int pb = 0; pb < PBW; ++pb) {
+    #pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[pb][v] += theirs[(pb * 16 + v) * 64 + lane];
+                        __builtin_amdgcn_sched_barrier(0);   // one block at a time: 16 loads in flight, not 16*PBW
+                    }
+                }
+                if (half > 1) __syncthreads();   // the next level writes where this one has read
             }
+            if (sc > 0) return;
         }
 
         // ---- epilogue (see write_block) ----

@@ -60,6 +60,49 @@ struct RowGeom {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
 };
 
+// Stage the whole input window of a pixel tile (all channels) into LDS, once.
+// One LDS-direct load brings 64 columns of one window row (channel, phase, row).
+// Which row is a scalar matter: its byte offset goes into the instruction's scalar
+// offset, rows outside the image take an all-lanes-unreachable vector offset.  The
+// vector offsets (column part; unreachable outside the image) are computed once per
+// phase and segment.  So the loop below costs no vector ALU work per load, which
+// matters: the wave shares its SIMD with waves issuing MFMAs back to back and gets
+// very few vector issue slots.  G supplies ST, LH, LWQ, NSEGR, LWP, CM and NW.
+template <class G>
+__device__ __forceinline__ void rows_stage_window(float *lds, const float *in, int n, int C, int H, int W, int ih0, int iw0,
+                                                  int wave, int lane)
+{
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        uniform_ptr(in + (size_t)n * C * H * W), 0, (int)((unsigned)(C * H * W) * 4u), 0x00020000);
+    unsigned voffc[G::ST][G::NSEGR];
+#pragma unroll
+    for (int ph = 0; ph < G::ST; ++ph)
+#pragma unroll
+        for (int sg = 0; sg < G::NSEGR; ++sg) {
+            const int cq = sg * 64 + lane, iw = iw0 + cq * G::ST + ph;
+            voffc[ph][sg] = ((cq < G::LWQ) & ((unsigned)iw < (unsigned)W)) ? (unsigned)iw * 4u : 0x80000000u;
+        }
+    const unsigned voob = 0x80000000u;
+#pragma unroll 1
+    for (int i = 0; i < G::ROWS_IT; ++i) {
+        const int row = i * G::NW + wave;            // (channel, window row), scalar
+        const int cc = row / G::LH, hh = row - cc * G::LH;
+        const int ih = ih0 + hh;
+        const bool ok = (cc < C) & ((unsigned)ih < (unsigned)H);
+        const int soff = ok ? ((cc * H + ih) * W) * 4 : 0;
+        if (cc < G::CM) {
+#pragma unroll
+            for (int ph = 0; ph < G::ST; ++ph)
+#pragma unroll
+                for (int sg = 0; sg < G::NSEGR; ++sg) {
+                    float *dst = lds + ((cc * G::ST + ph) * G::LH + hh) * G::LWP + sg * 64;
+                    if (ok) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, CONVD_LDS(dst), 4, voffc[ph][sg], soff, 0, 0);
+                    else __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, CONVD_LDS(dst), 4, voob, 0, 0, 0);
+                }
+        }
+    }
+}
+
 template <class G, bool FUSED>
 __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelArgs a)
 {
@@ -85,45 +128,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_rows_kernel(const KernelAr
     const int p0 = tp * G::TP, q0 = tq * G::TQ, k0 = kt * G::KT;
     const int ih0 = p0 * G::ST - a.s.pad, iw0 = q0 * G::ST - a.s.pad;
 
-    // ---- stage the whole window (all channels) once ----
-    // One LDS-direct load brings 64 columns of one window row (channel, phase, row).
-    // Which row is a scalar matter: its byte offset goes into the instruction's scalar
-    // offset, rows outside the image take an all-lanes-unreachable vector offset.  The
-    // vector offsets (column part; unreachable outside the image) are computed once per
-    // phase and segment.  So the loop below costs no vector ALU work per load, which
-    // matters: the wave shares its SIMD with waves issuing MFMAs back to back and gets
-    // very few vector issue slots.
-    {
-        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            uniform_ptr(a.in + (size_t)n * C * H * W), 0, (int)((unsigned)(C * H * W) * 4u), 0x00020000);
-        unsigned voffc[G::ST][G::NSEGR];
-#pragma unroll
-        for (int ph = 0; ph < G::ST; ++ph)
-#pragma unroll
-            for (int sg = 0; sg < G::NSEGR; ++sg) {
-                const int cq = sg * 64 + lane, iw = iw0 + cq * G::ST + ph;
-                voffc[ph][sg] = ((cq < G::LWQ) & ((unsigned)iw < (unsigned)W)) ? (unsigned)iw * 4u : 0x80000000u;
-            }
-        const unsigned voob = 0x80000000u;
-#pragma unroll 1
-        for (int i = 0; i < G::ROWS_IT; ++i) {
-            const int row = i * G::NW + wave;            // (channel, window row), scalar
-            const int cc = row / G::LH, hh = row - cc * G::LH;
-            const int ih = ih0 + hh;
-            const bool ok = (cc < C) & ((unsigned)ih < (unsigned)H);
-            const int soff = ok ? ((cc * H + ih) * W) * 4 : 0;
-            if (cc < G::CM) {
-#pragma unroll
-                for (int ph = 0; ph < G::ST; ++ph)
-#pragma unroll
-                    for (int sg = 0; sg < G::NSEGR; ++sg) {
-                        float *dst = lds + ((cc * G::ST + ph) * G::LH + hh) * G::LWP + sg * 64;
-                        if (ok) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, CONVD_LDS(dst), 4, voffc[ph][sg], soff, 0, 0);
-                        else __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, CONVD_LDS(dst), 4, voob, 0, 0, 0);
-                    }
-            }
-        }
-    }
+    rows_stage_window<G>(lds, a.in, n, C, H, W, ih0, iw0, wave, lane);
 
     // Everything below depends on how many pixel blocks the wave owns (see NFULL): the
     // body is compiled once per count and the wave takes its own.

@@ -35,8 +35,9 @@ struct KernelArgs {
 };
 
 // which reduction index the two k-lanes of one MFMA span: two input channels, or
-// filter rows r and r + ceil(R/2) of one channel
-enum Pair { PAIR_C = 0, PAIR_R = 2 };
+// filter rows r and r + ceil(R/2) of one channel; PAIR_T: none (one tap per MFMA, the two
+// halves of the instruction are two blocks of output channels; stages all channels like PAIR_R)
+enum Pair { PAIR_C = 0, PAIR_R = 2, PAIR_T = 3 };
 
 struct Variant {
     const char *name;
