@@ -125,6 +125,16 @@ struct DmaGeom {
 template <int V>
 struct IntTag { static constexpr int value = V; };
 
+// f(IntTag<T0>{}), f(IntTag<T0 + 1>{}), ... f(IntTag<T1 - 1>{}): a loop whose index is a compile-time constant
+template <int T0, int T1, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (T0 < T1) {
+        f(IntTag<T0>{});
+        static_for<T0 + 1, T1>(f);
+    }
+}
+
 #define CONVD_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 
 // A pointer that is the same in every lane, moved to scalar registers.

@@ -100,7 +100,15 @@ struct WgGeom {
     static_assert(!QW || (WX <= PXR && RPC >= 1 && PACK == 0), "small-map chunks: an input row fits 32 words");
     // small-map chunks: one 64-lane load stages TWO input rows of a channel (the second starts PXR words on)
     static constexpr bool DUAL_X = QW_ != 0 && XROWS % 2 == 0 && WX + PXR <= 64;
-    static constexpr int ABUF = KT * PA, XBUF = CT * PX;  // floats
+    // All-rows variants stage without lane masks: every load writes 64 consecutive LDS words, and what a load writes
+    // past its own row (zeros) lands in the row after it, which the SAME wave loads next (a wave's loads reach LDS in
+    // the order they were issued).  So a wave stages consecutive dy rows and consecutive input channels, in rising
+    // address order, and behind each wave's block lies a slack no one reads.
+    static constexpr int RPWV = KT / NW > 0 ? KT / NW : 1;     // dy rows a wave stages
+    static constexpr int CPWV = CT / NW > 0 ? CT / NW : 1;     // input channels a wave stages (packed first layers: one of CT <= NW)
+    static constexpr int ASL = (AR && HALF_A && !DUAL_A) ? 32 : 0;   // slack (floats) behind a wave's dy rows
+    static constexpr int XSL = AR ? 64 : 0;                           // ... behind a wave's input channels
+    static constexpr int ABUF = KT * PA + NW * ASL, XBUF = CT * PX + NW * XSL;  // floats
     static constexpr int BUF = ABUF + XBUF;
     static constexpr size_t LDS_BYTES = sizeof(float) * (2 * (size_t)BUF + 64);   // (+ slack: an odd last pixel pair reads
                                                                                   // a few words past the last input row)
@@ -161,15 +169,28 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
         }
         if (u >= rows_all) n = N;
     };
+    // (all-rows variants take every unit: the step from one unit of this split to the next is the same every time and
+    // needs no division)
+    const int step_n = splits / PG, step_g = splits - step_n * PG;
+    int ug = 0;                                              // the unit's index within its image (all-rows variants)
     auto advance = [&]() __attribute__((always_inline)) {
         q0 += G::PXC;
         if (G::QW || q0 >= Q) {
             q0 = 0;
             u += splits;
-            settle();
+            if constexpr (G::AR != 0) {
+                ug += step_g;
+                n += step_n;
+                if (ug >= PG) { ug -= PG; ++n; }
+                p = ug * G::RPC;
+                if (u >= rows_all) n = N;
+            } else {
+                settle();
+            }
         }
     };
     settle();
+    if (G::AR) ug = u - n * PG;
 
     // Stage the chunk (n, p, q0) into buffer b: dy rows wave, wave+WK, ... and input
     // channels likewise; lanes past the row's end or outside the image load zeros; rows
@@ -304,6 +325,120 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
         }
     };
 
+    // ---- all-rows variants: staging without vector ALU work per load, metered into the MFMA loop ----
+    // A wave that stages shares its SIMD with a wave that multiplies (or with its own MFMAs), and the
+    // address work of a chunk's 30-odd loads, done in one block behind the barrier, kept the matrix pipe
+    // waiting for a sixth of the time.  Here everything that differs from load to load is a scalar:
+    //   * a buffer resource that ends where the image's last channel ends, so that rows of output channels
+    //     >= K and input channels >= C read zeros (the range check covers the scalar offset too);
+    //   * for an input row outside the image, a scalar offset as large as the resource, which puts the whole load out of range;
+    //   * per-lane offsets that depend on the chunk only through its column position (recomputed once per
+    //     chunk: a handful of instructions) or not at all.
+    // and the loads of the next chunk are issued a few at a time between the MFMAs of this one.
+    struct ArSrc {
+        __amdgpu_buffer_rsrc_t ra, rx;          // dy, input
+        unsigned va;                            // dy: the lane's offset in its row (pair)
+        unsigned vx[G::NLX > 0 ? G::NLX : 1];   // input, row chunks: the lane's column
+        unsigned sx[G::XROWS];                  // input: scalar offset of each staged row from the resource's base; for a
+                                                // row outside the image the resource's size, which sends the load out of range
+        unsigned vd[G::XROWS / 2 > 0 ? G::XROWS / 2 : 1];   // small maps, two rows per load: the lane's offset per row pair
+    };
+    const int plane_dy = P * Q * 4, plane_x = H * W * 4;
+    // per-lane constants of the dy loads: the lane's pixel, full chunk / ragged last chunk of a row or image
+    auto dy_voff = [&](int np) -> unsigned {
+        if (G::DUAL_A) {
+            const int l2 = lane - G::PA;
+            return lane < np ? (unsigned)lane * 4u : (l2 >= 0 && l2 < np) ? (unsigned)plane_dy + (unsigned)l2 * 4u : 0x80000000u;
+        }
+        return lane < np ? (unsigned)lane * 4u : 0x80000000u;
+    };
+    const int np_rag = G::QW ? (P % G::RPC) * G::QW : Q % G::PXC;       // pixels of a ragged last chunk (0: there is none)
+    const unsigned va_full = dy_voff(G::NPX), va_rag = dy_voff(np_rag);
+    // small maps: per-lane parts of a load of two input rows (the second starts PXR words on)
+    unsigned vd_both = 0x80000000u, vd_first = 0x80000000u, vd_second = 0x80000000u;
+    if (G::QW != 0) {
+        const int iw = lane - pad, l2 = lane - G::PXR, iw2 = l2 - pad;
+        const bool c1 = lane < G::WX && lane < G::PXR && (unsigned)iw < (unsigned)W;
+        const bool c2 = l2 >= 0 && l2 < G::WX && (unsigned)iw2 < (unsigned)W;
+        vd_first = c1 ? (unsigned)iw * 4u : 0x80000000u;
+        vd_second = (G::DUAL_X && c2) ? (unsigned)(G::ST * W + iw2) * 4u : 0x80000000u;
+        vd_both = c1 ? vd_first : vd_second;
+    }
+    // (offsets inside one image fit 31 bits: conv_direct_create_wgrad refuses layers whose K*P*Q*4 or C*H*W*4 does not)
+    const int img_dy = (K - k0) * P * Q, img_x = (C - c0) * H * W;     // floats from the workgroup's first channel to the image's end
+    auto ar_source = [&](ArSrc &src, int sn, int sp, int sq0, bool more) __attribute__((always_inline)) {
+        // dy: from (sn, k0, sp, sq0) to the end of the image's last channel
+        const int a_in = sp * Q + sq0;
+        src.ra = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(dyp + ((size_t)sn * K + k0) * P * Q + a_in), 0, more ? (img_dy - a_in) * 4 : 0,
+                                                   0x00020000);
+        const int npix = G::QW ? (P - sp < G::RPC ? P - sp : G::RPC) * G::QW : Q - sq0;
+        src.va = npix >= G::NPX ? va_full : va_rag;
+        // input: from row ih0 (possibly above the image), column iw0 (row chunks: possibly left of it: the lanes there are
+        // sent out of range) of channel c0, to the end of the image's last channel
+        const int ih0 = sp * G::ST - pad, iw0 = G::QW ? 0 : sq0 * G::ST - pad;
+        const int x_in = ih0 * W + iw0;                                    // (may be negative)
+        const unsigned nrx = more ? (unsigned)(img_x - x_in) * 4u : 0u;
+        src.rx = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(xp + ((long long)sn * C + c0) * H * W + x_in), 0, (int)nrx, 0x00020000);
+        bool okx[G::XROWS];
+#pragma unroll
+        for (int ri = 0; ri < G::XROWS; ++ri) {
+            const int ih = ih0 + ri * (G::QW ? G::ST : 1);
+            okx[ri] = (unsigned)ih < (unsigned)H;
+            src.sx[ri] = (okx[ri] || (G::QW && G::DUAL_X)) ? (unsigned)(ih - ih0) * (unsigned)W * 4u : nrx;
+        }
+        if (G::QW == 0) {
+#pragma unroll
+            for (int u = 0; u < G::NLX; ++u) {
+                const int col = u * 64 + lane, iw = iw0 + col;
+                src.vx[u] = (col < G::WX && (unsigned)iw < (unsigned)W) ? (unsigned)col * 4u : 0x80000000u;
+            }
+        } else if (G::DUAL_X) {
+#pragma unroll
+            for (int rp = 0; rp < G::XROWS / 2; ++rp) {
+                const bool o0 = okx[2 * rp], o1 = okx[2 * rp + 1];
+                src.vd[rp] = (o0 && o1) ? vd_both : o0 ? vd_first : o1 ? vd_second : 0x80000000u;
+            }
+        }
+    };
+    // loads number [PART * NL / NPARTS, (PART + 1) * NL / NPARTS) of the NL loads of a chunk, into buffer b
+    constexpr int AR_NA = G::DUAL_A ? G::KT / G::NW / 2 : G::KT / G::NW;                 // dy loads of a wave
+    constexpr int AR_XR = G::QW ? (G::DUAL_X ? G::XROWS / 2 : G::XROWS) : G::NR * (G::NLX > 0 ? G::NLX : 1);   // input loads per channel
+    constexpr int AR_NX = (G::CT / G::NW > 0 ? G::CT / G::NW : 1) * AR_XR;
+    constexpr int AR_NL = AR_NA + AR_NX;
+    auto ar_stage = [&](auto part_tag, auto nparts_tag, int b, const ArSrc &src) __attribute__((always_inline)) {
+        constexpr int PART = decltype(part_tag)::value, NPARTS = decltype(nparts_tag)::value;
+        constexpr int L0 = PART * AR_NL / NPARTS, L1 = (PART + 1) * AR_NL / NPARTS;
+        float *abuf = lds + b * G::BUF + wave * G::ASL, *xbuf = lds + b * G::BUF + G::ABUF + wave * G::XSL;
+        // (no lane is masked: see the note on the slack in the geometry)
+#pragma unroll
+        for (int i = 0; i < AR_NA; ++i)
+            if (i >= L0 && i < L1) {
+                const int row = (wave * AR_NA + i) * (G::DUAL_A ? 2 : 1);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(src.ra, CONVD_LDS(abuf + row * G::PA), 4, src.va, row * plane_dy, 0, 0);
+            }
+#pragma unroll
+        for (int i = 0; i < G::CPWV; ++i) {
+            const int ch = wave * G::CPWV + i;
+#pragma unroll
+            for (int xr = 0; xr < AR_XR; ++xr) {
+                const int li = AR_NA + i * AR_XR + xr;
+                if (li >= L0 && li < L1 && (G::CT >= G::NW || ch < G::CT)) {
+                    if (G::QW == 0) {
+                        const int ri = xr / (G::NLX > 0 ? G::NLX : 1), u = xr % (G::NLX > 0 ? G::NLX : 1);
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(src.rx, CONVD_LDS(xbuf + ch * G::PX + ri * G::RP + u * 64), 4, src.vx[u],
+                                                                 ch * plane_x + src.sx[ri], 0, 0);
+                    } else if (G::DUAL_X) {
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(src.rx, CONVD_LDS(xbuf + ch * G::PX + 2 * xr * G::PXR), 4, src.vd[xr],
+                                                                 ch * plane_x + src.sx[2 * xr], 0, 0);
+                    } else {
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(src.rx, CONVD_LDS(xbuf + ch * G::PX + xr * G::PXR), 4, vd_first,
+                                                                 ch * plane_x + src.sx[xr], 0, 0);
+                    }
+                }
+            }
+        }
+    };
+
     dma_floatx16 acc[G::NBLK];
 #pragma unroll
     for (int b = 0; b < G::NBLK; ++b)
@@ -314,7 +449,8 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
     // registers (one set per buffer, the chunk loop is unrolled over the two buffers), the step's
     // part into the immediate -- no vector ALU work per fetch, which a wave between its own MFMAs
     // would wait some 20 clocks for each time.
-    const int aoff = (wk * 32 + j) * G::PA + h;              // lane (k = j, pixel parity h)
+    // lane (k = j, pixel parity h; small maps, all-rows variants: pixel half h); the slack behind the rows of the waves before
+    const int aoff = (wk * 32 + j) * G::PA + h * ((G::QW != 0 && G::AR != 0) ? (G::NPX + 1) / 2 : 1) + ((wk * 32 + j) / G::RPWV) * G::ASL;
     // LDS offset of the lane's B operand of block b at pixel pair 0: column j of the block is input
     // channel cb*32 + j at filter column s (b = cb*S + s), or the packed pair (c, s) = divmod(b*32 + j, S)
     int xoff[G::NBLK];
@@ -328,7 +464,9 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
             // (packed: the columns are all C*S*S (channel, tap) pairs; those past them read any valid position)
             const int colb = (wb + G::WB * b) * 32 + j;               // (blocks dealt out to WB waves)
             const int col = ((!G::PACK || colb < C * SS) && colb < G::NCOLB * 32) ? colb : 0, tap = col % SS;
-            xoff[b] = (wc * 32 * G::CBW + col / SS) * G::PX + (tap / G::SB) * (G::QW ? G::PXR : G::RP) + tap % G::SB + (G::QW ? 0 : h * G::ST);
+            const int chn = wc * 32 * G::CBW + col / SS;             // channel of the workgroup's CT
+            xoff[b] = chn * G::PX + (chn / G::CPWV) * G::XSL + (tap / G::SB) * (G::QW ? G::PXR : G::RP) + tap % G::SB +
+                      (G::QW ? h * (((G::NPX + 1) / 2) / (G::QW ? G::QW : 1)) * G::PXR : h * G::ST);   // (small maps: the lane's half of the rows)
         } else {
             xoff[b] = ((wc * G::CBW + b / G::SB) * 32 + j) * G::PX + b % G::SB + (G::QW ? 0 : h * st);
         }
@@ -342,9 +480,18 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
         for (int bb = 0; bb < G::NBLK; ++bb) xoffB[bf][bb] = bf * G::BUF + G::ABUF + xoff[bb];
     }
     constexpr int NST = (G::NPX + 1) / 2;
+    // Small maps, all-rows variants: the two k-lanes of step t take pixels t and t + NST of the chunk (not 2t and
+    // 2t + 1): with whole rows in each half (NST a multiple of QW) the second pixel lies a constant number of LDS
+    // rows below the first, so the lane's half is part of its base address and a step adds a compile-time constant.
+    constexpr bool HALVES = G::QW != 0 && G::AR != 0;
+    static_assert(!HALVES || (NST % (G::QW ? G::QW : 1) == 0 && G::NPX % 2 == 0), "small-map chunks: an even number of whole rows");
     auto pix_off = [&](int t) {
         // LDS offset of the step's two pixels: along the row, or (small maps) row and column of
         // pixels 2t and 2t+1 of the chunk, the lane's one picked by its pixel parity
+        if (HALVES) {
+            constexpr int QWc = G::QW ? G::QW : 1;
+            return (t / QWc) * G::PXR + (t % QWc) * G::ST;
+        }
         if (G::QW) {
             constexpr int QWc = G::QW ? G::QW : 1;
             const int o0 = (2 * t / QWc) * G::PXR + (2 * t % QWc) * G::ST;
@@ -384,20 +531,59 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
                 acc[bb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[bb], acc[bb], 0, 0, 0);
         }
     };
-    if (n < N) stage(0, n, p, q0);
     if constexpr (G::AR != 0) {
         // One loop body for both buffers (the buffer's base is added to the per-lane offsets once per
         // chunk): with nine accumulator blocks a loop unrolled over the two buffers, whose second half
         // can be left early, costs a second set of accumulator registers.
+        {
+            ArSrc src;
+            ar_source(src, n, p, q0, n < N);
+            ar_stage(IntTag<0>{}, IntTag<1>{}, 0, src);
+        }
         int bf = 0;
         while (n < N) {
             int xoffc[G::NBLK];
 #pragma unroll
             for (int bb = 0; bb < G::NBLK; ++bb) xoffc[bb] = xoff[bb] + bf * G::BUF + G::ABUF;
-            chunk_body(bf, aoff + bf * G::BUF, xoffc);
+            const int aoffc = aoff + bf * G::BUF;
+            wait_vmem_done();  // this wave's loads of chunk bf (the only ones in flight) have landed
+            __syncthreads();   // chunk bf is complete and every wave has left the other buffer
+            ArSrc src;
+            // operands of step t+1 are fetched from LDS while step t multiplies; the next chunk's loads go out a few per
+            // step from step 1 on, their scalar preparation (which chunk comes next, where it lies) behind the MFMAs of step 0
+            float an = lds[aoffc], bn[G::NBLK];
+            {
+                const int po = pix_off(0);
+#pragma unroll
+                for (int bb = 0; bb < G::NBLK; ++bb) bn[bb] = lds[xoffc[bb] + po];
+            }
+            static_for<0, NST>([&](auto t_tag) {
+                constexpr int t = decltype(t_tag)::value;
+                const float av = an;
+                float bv[G::NBLK];
+#pragma unroll
+                for (int bb = 0; bb < G::NBLK; ++bb) bv[bb] = bn[bb];
+                if (t + 1 < NST) {
+                    an = lds[aoffc + (HALVES ? 1 : 2) * (t + 1)];
+                    const int po = pix_off(t + 1);
+#pragma unroll
+                    for (int bb = 0; bb < G::NBLK; ++bb) bn[bb] = lds[xoffc[bb] + po];
+                }
+                if constexpr (t > 0) ar_stage(IntTag<t - 1>{}, IntTag<NST - 1>{}, bf ^ 1, src);
+#pragma unroll
+                for (int bb = 0; bb < G::NBLK; ++bb)
+                    acc[bb] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[bb], acc[bb], 0, 0, 0);
+                if constexpr (t == 0) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    advance();                                    // (n, p, q0) is now the next chunk
+                    ar_source(src, n, p, q0, n < N);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            });
             bf ^= 1;
         }
     } else {
+        if (n < N) stage(0, n, p, q0);
         // (the loop is unrolled over the two buffers, whose offsets are then constants of each half)
         while (n < N) {
             chunk_body(0, aoffB[0], xoffB[0]);
