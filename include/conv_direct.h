@@ -217,7 +217,8 @@ int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, 
  *
  * Two launches (a fill that clears dw, then the reduction, whose workgroups add their
  * partial sums into dw with fp32 atomics): no workspace, but the order of the additions
- * is not fixed, so the last bits of dw can differ between runs.  A wgrad plan can only be
+ * is not fixed, so the last bits of dw can differ between runs (see
+ * conv_direct_create_wgrad_deterministic for a plan without that).  A wgrad plan can only be
  * passed to conv_direct_run_wgrad, _plan_info, _workspace_bytes and _destroy;
  * CONV_DIRECT_EUNSUPPORTED for strides above 4.
  * ------------------------------------------------------------------------ */
@@ -230,6 +231,17 @@ int conv_direct_create_wgrad(conv_direct_plan **plan,
                              int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 int conv_direct_run_wgrad(const conv_direct_plan *plan,
                           const float *x, const float *dy, float *dw, void *stream);
+/* A weight-gradient plan whose result is the same bit for bit on every run: every tile of dw is reduced by ONE
+ * workgroup, which stores it plainly (one launch, no fill, no atomics).  Slower than conv_direct_create_wgrad's plan
+ * where the tiles of dw are fewer than the chip's compute units. */
+int conv_direct_create_wgrad_deterministic(conv_direct_plan **plan,
+                                           int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+/* Testing / tuning aid: conv_direct_create_wgrad with the kernel variant forced (variant = NULL asks the planner;
+ * CONV_DIRECT_EUNSUPPORTED if the variant is unknown or cannot run the shape); conv_direct_wgrad_variant_name(i)
+ * enumerates the names (NULL past the end). */
+int conv_direct_create_wgrad_ex(conv_direct_plan **plan, const char *variant,
+                                int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+const char *conv_direct_wgrad_variant_name(int index);
 
 /*
  * For callers that cannot allocate device memory -- code under HIP graph capture, tight

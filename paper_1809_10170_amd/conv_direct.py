@@ -78,6 +78,12 @@ def lib():
             getattr(l, nm).restype = i
         l.conv_direct_create_wgrad.argtypes = [pp] + [i] * 9
         l.conv_direct_create_wgrad.restype = i
+        l.conv_direct_create_wgrad_ex.argtypes = [pp, cp] + [i] * 9
+        l.conv_direct_create_wgrad_ex.restype = i
+        l.conv_direct_create_wgrad_deterministic.argtypes = [pp] + [i] * 9
+        l.conv_direct_create_wgrad_deterministic.restype = i
+        l.conv_direct_wgrad_variant_name.argtypes = [i]
+        l.conv_direct_wgrad_variant_name.restype = cp
         l.conv_direct_run_wgrad.argtypes = [vp, vp, vp, vp, vp]
         l.conv_direct_run_wgrad.restype = i
         l.conv_direct_create_dgrad.argtypes = [pp] + [i] * 9
@@ -99,6 +105,16 @@ def lib():
 
 def strerror(code: int) -> str:
     return lib().conv_direct_strerror(code).decode()
+
+
+def wgrad_variant_names():
+    out, i = [], 0
+    while True:
+        nm = lib().conv_direct_wgrad_variant_name(i)
+        if nm is None:
+            return out
+        out.append(nm.decode())
+        i += 1
 
 
 def variant_names():
@@ -195,13 +211,17 @@ class Plan:
             raise ConvDirectError(rc, "conv_direct_run_dgrad_static")
 
     @classmethod
-    def wgrad(cls, N, C, H, W, K, R, S, stride, pad):
-        """Plan of the weight gradient of the forward layer: run_wgrad(x [N,C,H,W], dy [N,K,P,Q], dw [K,C,R,S])."""
+    def wgrad(cls, N, C, H, W, K, R, S, stride, pad, variant: str | None = None, deterministic: bool = False):
+        """Plan of the weight gradient of the forward layer: run_wgrad(x [N,C,H,W], dy [N,K,P,Q], dw [K,C,R,S]).
+        deterministic: one workgroup per tile of dw (plain stores, the same bits every run)."""
         self = cls.__new__(cls)
         self._p = ctypes.c_void_p()
         self.in_layout = self.out_layout = PLAIN
         dims = [int(v) for v in (N, C, H, W, K, R, S, stride, pad)]
-        rc = lib().conv_direct_create_wgrad(ctypes.byref(self._p), *dims)
+        if deterministic:
+            rc = lib().conv_direct_create_wgrad_deterministic(ctypes.byref(self._p), *dims)
+        else:
+            rc = lib().conv_direct_create_wgrad_ex(ctypes.byref(self._p), variant.encode() if variant else None, *dims)
         if rc != OK:
             self._p = ctypes.c_void_p()
             raise ConvDirectError(rc, "conv_direct_create_wgrad")

@@ -557,6 +557,33 @@ int conv_direct_tuning_size(void) { return (int)g_tuned.size(); }
 int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W, int K, int R, int S, int stride,
                              int pad)
 {
+    return conv_direct_create_wgrad_ex(plan, nullptr, N, C, H, W, K, R, S, stride, pad);
+}
+
+const char *conv_direct_wgrad_variant_name(int index)
+{
+    int count = 0;
+    const convd::WgradVariant *table = convd::wgrad_table(&count);
+    return (index >= 0 && index < count) ? table[index].name : nullptr;
+}
+
+static int create_wgrad(conv_direct_plan **plan, const char *variant, bool one_split, int N, int C, int H, int W, int K, int R, int S,
+                        int stride, int pad);
+
+int conv_direct_create_wgrad_ex(conv_direct_plan **plan, const char *variant, int N, int C, int H, int W, int K, int R, int S,
+                                int stride, int pad)
+{
+    return create_wgrad(plan, variant, false, N, C, H, W, K, R, S, stride, pad);
+}
+
+int conv_direct_create_wgrad_deterministic(conv_direct_plan **plan, int N, int C, int H, int W, int K, int R, int S, int stride, int pad)
+{
+    return create_wgrad(plan, nullptr, true, N, C, H, W, K, R, S, stride, pad);
+}
+
+static int create_wgrad(conv_direct_plan **plan, const char *variant, bool one_split, int N, int C, int H, int W, int K, int R, int S,
+                        int stride, int pad)
+{
     if (!plan) return CONV_DIRECT_EINVAL;
     *plan = nullptr;
     Shape s;
@@ -571,6 +598,7 @@ int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W
     double best_score = 0.0;
     for (int i = 0; i < count; ++i) {
         const convd::WgradVariant &v = table[i];
+        if (variant && std::strcmp(variant, v.name) != 0) continue;
         if (v.S == 0 ? stride > v.stride : (v.S != S || v.stride != stride)) continue;   // S = 0: the fallback
         if (v.pack && !v.allr && (C * S > 32 * v.pack || C > 32 * v.CBW)) continue;
         if (v.pack && v.allr && (C * R * S > 32 * v.pack || C > 4)) continue;
@@ -611,7 +639,7 @@ int conv_direct_create_wgrad(conv_direct_plan **plan, int N, int C, int H, int W
     const int64_t slots = (int64_t)kNumCU * best->per_cu;
     int64_t splits = 1;
     double best_clk = 0.0;
-    for (int64_t sp = 1; sp <= units && sp <= 4096; ++sp) {
+    for (int64_t sp = 1; sp <= units && sp <= (one_split ? 1 : 4096); ++sp) {
         const double clk = (double)cdiv64(tiles * sp, slots) * ((double)cdiv64(units, sp) * chunks_per_unit * chunk_clk + atomics_clk);
         if (sp == 1 || clk < best_clk) {
             best_clk = clk;
@@ -629,7 +657,8 @@ int conv_direct_run_wgrad(const conv_direct_plan *plan, const float *x, const fl
     if (!plan || !plan->wv || !x || !dy || !dw) return CONV_DIRECT_EINVAL;
     if (((uintptr_t)x | (uintptr_t)dy | (uintptr_t)dw) & 3u) return CONV_DIRECT_EALIGN;
     const Shape &s = plan->s;
-    hipError_t e = convd::wgrad_clear(dw, (long long)s.K * s.C * s.R * s.S, (hipStream_t)stream);
+    // (one workgroup per result tile stores its sums plainly: nothing to clear)
+    hipError_t e = plan->wg_splits == 1 ? hipSuccess : convd::wgrad_clear(dw, (long long)s.K * s.C * s.R * s.S, (hipStream_t)stream);
     if (e == hipSuccess) {
         convd::WgradArgs a;
         a.x = x;

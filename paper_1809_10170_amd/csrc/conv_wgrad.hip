@@ -21,7 +21,9 @@
 // The reduction over all N*P*Q pixels is split over `splits` workgroups per result tile
 // (each takes every splits-th image) so that the grid fills the chip; their partial sums
 // meet in dw itself by fp32 atomic adds (dw is cleared by a fill kernel first).  No
-// workspace, but the order of those additions, and with it the last bits, varies.
+// workspace, but the order of those additions, and with it the last bits, varies.  With
+// splits = 1 (the deterministic plans) a result tile has one workgroup, which stores it
+// plainly: no fill, no atomics, the same bits every run.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -96,7 +98,7 @@ struct WgGeom {
                                  : QW ? RPC * PXR + 1 : NLX * 64 + 1;
     static_assert(!AR || (!RT && (QW == 0 || (ST == 1 && PACK == 0))), "all-rows mode: small-map chunks at stride 1, unpacked");
     static_assert(WC == 1 || (PACK == 0 && 32 % WC == 0), "channel groups of waves: whole dy rows per wave");
-    static_assert(WB == 1 || (AR && PACK == 0 && WC == 1 && 32 % WB == 0), "column blocks dealt out to waves: all-rows mode");
+    static_assert(WB == 1 || (AR && WC == 1 && 32 % WB == 0), "column blocks dealt out to waves: all-rows mode");
     static_assert(!QW || (WX <= PXR && RPC >= 1 && PACK == 0), "small-map chunks: an input row fits 32 words");
     // small-map chunks: one 64-lane load stages TWO input rows of a channel (the second starts PXR words on)
     static constexpr bool DUAL_X = QW_ != 0 && XROWS % 2 == 0 && WX + PXR <= 64;
@@ -605,7 +607,11 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int k = k0 + wk * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-                if (k < K && cok) unsafeAtomicAdd(dwp + ((size_t)k * C + c0 + wc * 32 * G::CBW) * (G::SB * G::NR) + col, acc[b][v]);
+                if (k < K && cok) {
+                    float *d = dwp + ((size_t)k * C + c0 + wc * 32 * G::CBW) * (G::SB * G::NR) + col;
+                    if (splits == 1) *d = acc[b][v];          // the tile's only workgroup: a plain store, the same bits every run
+                    else unsafeAtomicAdd(d, acc[b][v]);
+                }
             }
         }
         return;
@@ -618,7 +624,11 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int k = k0 + wk * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-            if (k < K && c < C) unsafeAtomicAdd(dwp + ((size_t)k * C + c) * RS + r * SF + s, acc[b][v]);
+            if (k < K && c < C) {
+                float *d = dwp + ((size_t)k * C + c) * RS + r * SF + s;
+                if (splits == 1) *d = acc[b][v];
+                else unsafeAtomicAdd(d, acc[b][v]);
+            }
         }
     }
 }
@@ -686,6 +696,12 @@ static WgradVariant g_wgrad[] = {
     make_wg<WgGeom<11, 4, 1, 4, 32, 12, 0, 1>>("w11s4_arpack12_k128_p32"),
     make_wg<WgGeom<11, 4, 1, 4, 28, 12, 0, 1>>("w11s4_arpack12_k128_p28"),
     make_wg<WgGeom<3, 1, 1, 4, 32, 1, 0, 1>>("w3s1_arpack1_k128_p32"),
+    // ... their column blocks dealt out to two waves per k-block (more waves per CU: a lone wave per SIMD has nobody to cover its waits)
+    make_wg<WgGeom<7, 2, 1, 2, 56, 5, 0, 1, 1, 2>>("w7s2_arpack5_k64_p56b2"),
+    make_wg<WgGeom<7, 2, 1, 2, 28, 5, 0, 1, 1, 2>>("w7s2_arpack5_k64_p28b2"),
+    make_wg<WgGeom<11, 4, 1, 3, 28, 12, 0, 1, 1, 2>>("w11s4_arpack12_k96_p28b2"),
+    make_wg<WgGeom<11, 4, 1, 4, 28, 12, 0, 1, 1, 2>>("w11s4_arpack12_k128_p28b2"),
+    make_wg<WgGeom<3, 1, 1, 2, 28, 0, 0, 1, 2>>("w3s1_ar_c64_k64_p28"),
     make_wg<WgGeom<3, 1, 1, 4, 56, 0, 7, 1>>("w3s1_ar_c32_k128_q7"),
     make_wg<WgGeom<3, 1, 1, 4, 32, 0, 13, 1>>("w3s1_ar_c32_k128_q13h"),
     make_wg<WgGeom<3, 1, 1, 4, 32, 0, 14, 1>>("w3s1_ar_c32_k128_q14h"),

@@ -9,10 +9,10 @@ from paper_1809_10170_amd import workloads
 pytestmark = pytest.mark.gpu
 
 
-def _wgrad(x, dy, R, S, st, pd):
+def _wgrad(x, dy, R, S, st, pd, variant=None):
     N, C, H, W = x.shape
     K = dy.shape[1]
-    plan = cd.Plan.wgrad(N, C, H, W, K, R, S, st, pd)
+    plan = cd.Plan.wgrad(N, C, H, W, K, R, S, st, pd, variant=variant)
     assert plan.workspace_bytes() == 0
     dw = torch.full((K, C, R, S), float("nan"), device="cuda")
     plan.run_wgrad(torch.from_numpy(x).cuda(), torch.from_numpy(dy).cuda(), dw)
@@ -69,7 +69,7 @@ def test_small_shapes_random_inputs(oracle, shape):
     assert err <= tol, (info["variant"], err)
 
 
-@pytest.mark.parametrize("shape,variant", [
+ALL_ROWS_CASES = [
     ((2, 40, 20, 64, 48, 3, 3, 1, 1), "w3s1_ar_c64_k64_p32"),       # waves spread over two channel groups
     ((2, 20, 9, 56, 70, 3, 3, 1, 1), "w3s1_ar_c32_k128_p28"),       # rows of two 28-pixel chunks
     ((2, 70, 11, 64, 130, 3, 3, 1, 1), "w3s1_ar_c32_k128_p32"),     # three channel groups, two k tiles
@@ -98,16 +98,29 @@ def test_small_shapes_random_inputs(oracle, shape):
     ((2, 3, 75, 230, 64, 7, 7, 2, 3), "w7s2_arpack5_k64_p64"),
     ((2, 3, 99, 227, 96, 11, 11, 4, 0), "w11s4_arpack12_k128_p28"),
     ((1, 3, 51, 135, 40, 11, 11, 4, 0), "w11s4_arpack12_k128_p32"),
-])
+    ((2, 3, 75, 230, 64, 7, 7, 2, 3), "w7s2_arpack5_k64_p56b2"),     # packed columns dealt out to two waves per k-block
+    ((2, 2, 61, 120, 70, 7, 7, 2, 3), "w7s2_arpack5_k64_p28b2"),
+    ((2, 3, 99, 227, 96, 11, 11, 4, 0), "w11s4_arpack12_k96_p28b2"),  # three k-blocks per workgroup
+    ((2, 3, 67, 227, 100, 11, 11, 4, 0), "w11s4_arpack12_k96_p28b2"),
+    ((1, 3, 99, 227, 130, 11, 11, 4, 0), "w11s4_arpack12_k128_p28b2"),
+    ((2, 40, 20, 56, 48, 3, 3, 1, 1), "w3s1_ar_c64_k64_p28"),
+]
+
+def test_every_all_rows_variant_has_a_case():
+    names = {n for n in cd.wgrad_variant_names() if "_ar" in n}
+    assert names and names <= {v for _, v in ALL_ROWS_CASES}, names - {v for _, v in ALL_ROWS_CASES}
+
+
+@pytest.mark.parametrize("shape,variant", ALL_ROWS_CASES)
 def test_all_rows_variants_integer_inputs_bit_exact(oracle, shape, variant):
-    """Every variant whose waves own all filter rows (columns = consecutive floats of dw), on a shape
-    the planner gives to it."""
+    """Every variant whose waves own all filter rows (columns = consecutive floats of dw), forced, on a
+    shape with ragged edges in the dimensions the variant tiles."""
     N, C, H, W, K, R, S, st, pd = shape
     rng = np.random.default_rng(1000 + sum(shape))
     x = rng.integers(-2, 3, (N, C, H, W)).astype(np.float32)
     P, Q = oracle.out_dim(H, R, st, pd), oracle.out_dim(W, S, st, pd)
     dy = rng.integers(-2, 3, (N, K, P, Q)).astype(np.float32)
-    got, info = _wgrad(x, dy, R, S, st, pd)
+    got, info = _wgrad(x, dy, R, S, st, pd, variant=variant)
     assert info["variant"] == variant
     assert np.array_equal(got.astype(np.float64), oracle.conv_wgrad(x, dy, R, S, st, pd))
 
@@ -173,3 +186,28 @@ def test_benchmark_layers_full_size_sampled(oracle, name):
     tol = 1e-4 * np.sqrt(l.N * l.P * l.Q)
     err = np.abs(got[ks].astype(np.float64) - want).max()
     assert err <= tol, (info["variant"], err)
+
+
+@pytest.mark.parametrize("shape", [(3, 40, 20, 56, 70, 3, 3, 1, 1), (4, 33, 13, 13, 40, 3, 3, 1, 1), (2, 3, 75, 230, 64, 7, 7, 2, 3),
+                                   (3, 5, 20, 70, 6, 5, 3, 1, 1)])
+def test_deterministic_plan_same_bits_every_run(oracle, shape):
+    """One workgroup per tile of dw: plain stores into a buffer that was not cleared, and the same bits on every run
+    (random inputs, whose sums do depend on the order of the additions)."""
+    N, C, H, W, K, R, S, st, pd = shape
+    rng = np.random.default_rng(1300 + sum(shape))
+    x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    P, Q = oracle.out_dim(H, R, st, pd), oracle.out_dim(W, S, st, pd)
+    dy = rng.uniform(-1, 1, (N, K, P, Q)).astype(np.float32)
+    plan = cd.Plan.wgrad(*shape, deterministic=True)
+    assert plan.info()["splits"] == 1
+    xd, dyd = torch.from_numpy(x).cuda(), torch.from_numpy(dy).cuda()
+    runs = []
+    for fill in (float("nan"), 7.0, -1e30):
+        dw = torch.full((K, C, R, S), fill, device="cuda")
+        plan.run_wgrad(xd, dyd, dw)
+        torch.cuda.synchronize()
+        runs.append(dw.cpu().numpy())
+    plan.destroy()
+    assert np.array_equal(runs[0], runs[1]) and np.array_equal(runs[0], runs[2])
+    err = np.abs(runs[0].astype(np.float64) - oracle.conv_wgrad(x, dy, R, S, st, pd)).max()
+    assert err <= 1e-4 * np.sqrt(N * P * Q), err
