@@ -350,7 +350,7 @@ int conv_direct_run_fused(const conv_direct_plan *plan, const float *in, const f
     a.bias = bias;
     a.residual = residual;
     a.relu = relu ? 1 : 0;
-    a.ost = a.onb = a.ooh = a.oow = a.OH = a.OW = 0;
+    a.ost = a.onb = a.ooh = a.oow = a.OH = a.OW = a.ofr = 0;
     if (plan->ph_stride) {
         // data gradient of a strided layer: clear dx (positions no window of the forward pass touches stay
         // zero), then one stride-1 convolution of dy per phase, each storing to its own positions of dx
@@ -363,6 +363,7 @@ int conv_direct_run_fused(const conv_direct_plan *plan, const float *in, const f
         a.OH = plan->ph_H;
         a.OW = plan->ph_W;
         a.ooh = a.oow = -plan->ph_pad;
+        a.ofr = plan->fwd_R;
         (void)RT;
         if (e == hipSuccess) e = plan->v->launch(a, plan->grid * (unsigned)(nb * nb), (hipStream_t)stream);
         return launched(e);

@@ -530,9 +530,6 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
         //     issued, and the operand fetch of chunk i+1's first steps follows under the
         //     last MFMAs of chunk i, so the matrix pipe sees no gap at a chunk boundary.
         // Within a chunk the B operands of step t+PF are fetched while step t multiplies.
-        constexpr int TY = G::STEPS - G::PF - 1 > G::STEPS / 2 ? G::STEPS - G::PF - 1 : G::STEPS / 2;
-        constexpr int TX = TY * 3 / 5;
-        static_assert(TX < TY && TY + G::PF <= G::STEPS, "arrive, check, then fetch the next chunk");
         constexpr int NW = G::NWG;
         unsigned *meet = reinterpret_cast<unsigned *>(lds + goffs + 3 * G::BUF);  // arrivals so far, all chunks
         auto arrive = [&]() {
@@ -574,41 +571,6 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
             return (g < nch ? g : nch - 1) * G::CB;
         };
         float bq[G::PF][PBW];   // B operands of the next PF steps, oldest first
-        auto chunk = [&](int i, const float *bufc, const float *bufn, float *bufnn, const float (&acr)[G::NA],
-                         float (&ann)[G::NA]) {
-            float ac[G::NA];
-            mask_a(ac, acr, chan0(i));
-    #pragma unroll
-            for (int t = 0; t < G::STEPS; ++t) {
-                if (t == TX) arrive();
-                if (t == TY) {
-                    all_arrived((unsigned)NW * (unsigned)(i + 1));
-                    // past the last chunk the last one is staged again, into a buffer and a
-                    // register set that nothing reads any more (no special case)
-                    const int cn = chan0(i + 2);
-                    stage_b(bufnn, cn);
-                    load_a(ann, cn);
-                }
-                float bnew[PBW];
-                if (t + G::PF < G::STEPS) fetch(bufc, t + G::PF, bnew);
-                else fetch(bufn, t + G::PF - G::STEPS, bnew);   // past the last chunk: stale but in-bounds, never used
-    #pragma unroll
-                for (int pb = 0; pb < PBW; ++pb)
-                    acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac[t], bq[0][pb], acc[pb], 0, 0, 0);
-    #pragma unroll
-                for (int pb = 0; pb < PBW; ++pb) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-                }
-    #pragma unroll
-                for (int pb = 0; pb < PBW; ++pb) {
-    #pragma unroll
-                    for (int d = 0; d + 1 < G::PF; ++d) bq[d][pb] = bq[d + 1][pb];
-                    bq[G::PF - 1][pb] = bnew[pb];
-                }
-            }
-        };
-
         float a0[G::NA], a1[G::NA], a2[G::NA];
         float *b0 = lds, *b1 = lds + G::BUF, *b2 = lds + 2 * G::BUF;   // (+ goffs, added where they are used)
         if (tid == 0) *meet = 0u;
@@ -618,12 +580,77 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
         load_a(a1, chan0(1));
         wait_vmem_done();   // this wave's part of the first two stage buffers has landed
         __syncthreads();
+
+        // The chunk loop, compiled for the taps that carry weights.  A forward pass uses all R*S of them.  The phases
+        // of a strided layer's data gradient (output re-mapping) share one padded RT x RT filter shape, and a phase whose
+        // first filter row and/or column is padding (all zeros) leaves those taps out of its reduction: SKIP = 2*row + column.
+        auto run = [&](auto skip_tag) __attribute__((always_inline)) {
+            constexpr int SKR = decltype(skip_tag)::value / 2, SKC = decltype(skip_tag)::value % 2;
+            constexpr int NRV = G::R - SKR, NSV = G::S - SKC;        // filter rows and columns in use
+            constexpr int NV = G::BLK ? G::STEPS : G::HC * NRV * NSV;   // reduction steps of a chunk
+            static_assert(!G::BLK || (SKR == 0 && SKC == 0), "the blocked layouts run whole filters");
+            // i-th step in use -> step of the full filter (which register of the chunk's filter values, which tap offset)
+            auto vt = [](int i) {
+                if (G::BLK) return i;
+                const int cc = i / (NRV * NSV), rem = i - cc * (NRV * NSV);
+                return cc * G::RS + (rem / NSV + SKR) * G::S + rem % NSV + SKC;
+            };
+            constexpr int TY = NV - G::PF - 1 > NV / 2 ? NV - G::PF - 1 : NV / 2;
+            constexpr int TX = TY * 3 / 5;
+            static_assert(TX < TY && TY + G::PF <= NV && 2 * G::PF < NV, "arrive, check, then fetch the next chunk");
+            auto chunk = [&](int i, const float *bufc, const float *bufn, float *bufnn, const float (&acr)[G::NA],
+                             float (&ann)[G::NA]) {
+                float ac[G::NA];
+                mask_a(ac, acr, chan0(i));
     #pragma unroll
-        for (int d = 0; d < G::PF; ++d) fetch(b0, d, bq[d]);
-        for (int ci = 0; ci < nchl; ci += 3) {
-            chunk(ci, b0, b1, b2, a0, a2);
-            if (ci + 1 < nchl) chunk(ci + 1, b1, b2, b0, a1, a0);
-            if (ci + 2 < nchl) chunk(ci + 2, b2, b0, b1, a2, a1);
+                for (int t = 0; t < NV; ++t) {
+                    if (t == TX) arrive();
+                    if (t == TY) {
+                        all_arrived((unsigned)NW * (unsigned)(i + 1));
+                        // past the last chunk the last one is staged again, into a buffer and a
+                        // register set that nothing reads any more (no special case)
+                        const int cn = chan0(i + 2);
+                        stage_b(bufnn, cn);
+                        load_a(ann, cn);
+                    }
+                    float bnew[PBW];
+                    if (t + G::PF < NV) fetch(bufc, vt(t + G::PF), bnew);
+                    else fetch(bufn, vt(t + G::PF - NV), bnew);   // past the last chunk: stale but in-bounds, never used
+    #pragma unroll
+                    for (int pb = 0; pb < PBW; ++pb)
+                        acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac[vt(t)], bq[0][pb], acc[pb], 0, 0, 0);
+    #pragma unroll
+                    for (int pb = 0; pb < PBW; ++pb) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                    }
+    #pragma unroll
+                    for (int pb = 0; pb < PBW; ++pb) {
+    #pragma unroll
+                        for (int d = 0; d + 1 < G::PF; ++d) bq[d][pb] = bq[d + 1][pb];
+                        bq[G::PF - 1][pb] = bnew[pb];
+                    }
+                }
+            };
+    #pragma unroll
+            for (int d = 0; d < G::PF; ++d) fetch(b0, vt(d), bq[d]);
+            for (int ci = 0; ci < nchl; ci += 3) {
+                chunk(ci, b0, b1, b2, a0, a2);
+                if (ci + 1 < nchl) chunk(ci + 1, b1, b2, b0, a1, a0);
+                if (ci + 2 < nchl) chunk(ci + 2, b2, b0, b1, a2, a1);
+            }
+        };
+        if constexpr (REMAP && G::R > 1 && G::S > 1) {
+            // phase (pa, pb) of the input positions has ceil((ofr - pa) / ost) filter rows; the padded shape has R
+            const int nbp = a.onb, pa = ph / nbp, pb_ = ph - pa * nbp;
+            const int skr = G::R - (a.ofr - pa + a.ost - 1) / a.ost, skc = G::S - (a.ofr - pb_ + a.ost - 1) / a.ost;
+            const int sk = __builtin_amdgcn_readfirstlane((skr > 0 ? 2 : 0) + (skc > 0 ? 1 : 0));
+            if (sk == 0) run(IntTag<0>{});
+            else if (sk == 1) run(IntTag<1>{});
+            else if (sk == 2) run(IntTag<2>{});
+            else run(IntTag<3>{});
+        } else {
+            run(IntTag<0>{});
         }
 
         if (G::SC > 1) {

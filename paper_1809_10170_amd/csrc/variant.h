@@ -32,6 +32,8 @@ struct KernelArgs {
     // fill), written this way in ONE launch: the grid is onb*onb times the tiles, workgroup id % (onb*onb) is the
     // phase ph = a*onb + b, whose filter is w + ph*K*C*R*S and whose offsets are ooh + a, oow + b.
     int ost, onb, ooh, oow, OH, OW;
+    int ofr;                      // ... and the forward layer's (square) filter extent: phase a has ceil((ofr - a) / ost) taps per
+                                  // dimension, the first rows / columns of its padded filter are zeros and are skipped
 };
 
 // which reduction index the two k-lanes of one MFMA span: two input channels, or
