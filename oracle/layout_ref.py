@@ -81,3 +81,29 @@ def conv_forward_blocked(xb: np.ndarray, wb: np.ndarray, C: int, K: int, stride:
     cb = xb.shape[-1]
     out = conv_ref.conv_forward(unpack_activations(xb, C), unpack_weights(wb, K, C), stride, pad)
     return pack_activations(out, out_cb or cb)
+
+
+def conv_dgrad_blocked(dyb: np.ndarray, w: np.ndarray, H: int, W: int, stride: int = 1, pad: int = 0,
+                       out_cb: int | None = None) -> np.ndarray:
+    """Data gradient (the adjoint of the forward map in its input; the paper's closing
+    section names the backward pass without an algorithm) with the activations in the
+    blocked layout of Section 4.1: dy [N][ceil(K/cb)][P][Q][cb], weights plain
+    [K][C][R][S]; float64 dx [N][ceil(C/out_cb)][H][W][out_cb].  Same function of the
+    same numbers: unpack, plain definition (conv_ref.conv_dgrad), pack."""
+    K = w.shape[0]
+    cb = dyb.shape[-1]
+    dx = conv_ref.conv_dgrad(unpack_activations(dyb, K), w, H, W, stride, pad)
+    return pack_activations(dx, out_cb or cb)
+
+
+def conv_wgrad_blocked(xb: np.ndarray, dyb: np.ndarray, C: int, K: int, R: int, S: int, stride: int = 1,
+                       pad: int = 0, cb: int | None = None, kb: int | None = None) -> np.ndarray:
+    """Weight gradient (the adjoint in the filter) of blocked activations x
+    [N][ceil(C/.)][H][W][.] and dy [N][ceil(K/.)][P][Q][.]; float64 dw, plain [K][C][R][S],
+    or in the blocked weight layout of Section 4.2 when both cb and kb are given."""
+    dw = conv_ref.conv_wgrad(unpack_activations(xb, C), unpack_activations(dyb, K), R, S, stride, pad)
+    if cb is None and kb is None:
+        return dw
+    if cb is None or kb is None:
+        raise ValueError("give both block sizes, or neither")
+    return pack_weights(dw, cb, kb)
