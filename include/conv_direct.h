@@ -202,9 +202,15 @@ int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, 
  * runtime-shape kernel (dy read as if zeros stood between its elements), with the
  * stride-1 form of wt.  conv_direct_output_dims of the plan gives (H, W).  A fused tail
  * is refused for a phase plan (CONV_DIRECT_EINVAL).
- * In the blocked layouts the stride-1 data gradient is served by the layout-aware forward
- * entry points as it stands: conv_direct_create_layout(&plan, N, K, P, Q, C, R, S, 1, R-1-pad,
- * BLOCKED, BLOCKED), wt from conv_direct_dgrad_filter re-arranged by conv_direct_pack_w(wt, wtb, C, K, R, S).
+ * Blocked layouts (the paper's Section 4): conv_direct_create_dgrad_layout takes the layout of
+ * dy ([N][ceil(K/4)][P][Q][4] when blocked) and of dx ([N][ceil(C/4)][H][W][4]; the spare
+ * channels of a last pencil are written as zeros) and serves every shape the plain entry point
+ * serves, strided layers included.  The weights stay plain [K][C][R][S] (the master copy a
+ * weight update writes); conv_direct_dgrad_prepare writes wt in the layout the plan's kernels read
+ * -- for a blocked dy the blocked weight layout of the forward problem over dy,
+ *   wt[phase][c/32][k/4][j][l][k%4][c%32]  (zeros where the tap or the channel does not exist),
+ * conv_direct_dgrad_wt_elems(plan) floats -- so wt is opaque to the caller: always size it with
+ * _dgrad_wt_elems and fill it with _dgrad_prepare of the SAME plan.
  *
  * Weight gradient (the backward pass with respect to the filter), plain layouts, any
  * filter, strides up to 4 (compiled variants for the filter widths and strides of the forward
@@ -224,6 +230,9 @@ int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, 
  * ------------------------------------------------------------------------ */
 int conv_direct_create_dgrad(conv_direct_plan **plan,
                              int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+int conv_direct_create_dgrad_layout(conv_direct_plan **plan,
+                                    int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                    int dy_layout, int dx_layout);   /* CONV_DIRECT_LAYOUT_* */
 int conv_direct_dgrad_filter(const float *w, float *wt, int K, int C, int R, int S, void *stream);
 size_t conv_direct_dgrad_wt_elems(const conv_direct_plan *plan);   /* 0 for a plan that is no data gradient */
 int conv_direct_dgrad_prepare(const conv_direct_plan *plan, const float *w, float *wt, void *stream);

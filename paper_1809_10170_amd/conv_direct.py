@@ -88,6 +88,8 @@ def lib():
         l.conv_direct_run_wgrad.restype = i
         l.conv_direct_create_dgrad.argtypes = [pp] + [i] * 9
         l.conv_direct_create_dgrad.restype = i
+        l.conv_direct_create_dgrad_layout.argtypes = [pp] + [i] * 11
+        l.conv_direct_create_dgrad_layout.restype = i
         l.conv_direct_dgrad_wt_elems.argtypes = [vp]
         l.conv_direct_dgrad_wt_elems.restype = ctypes.c_size_t
         l.conv_direct_dgrad_prepare.argtypes = [vp, vp, vp, vp]
@@ -165,13 +167,15 @@ class Plan:
         return self
 
     @classmethod
-    def dgrad(cls, N, C, H, W, K, R, S, stride, pad):
+    def dgrad(cls, N, C, H, W, K, R, S, stride, pad, dy_layout: int = PLAIN, dx_layout: int = PLAIN):
         """Plan of the data gradient of the forward layer (N, C, H, W, K, R, S, stride, pad):
-        run(dy [N,K,P,Q], wt [C,K,R,S] from dgrad_filter, dx [N,C,H,W])."""
+        run(dy [N,K,P,Q], wt from dgrad_prepare (dgrad_wt_elems() floats), dx [N,C,H,W]); dy and dx plain or in
+        the blocked activation layout ([N, ceil(K/4), P, Q, 4], [N, ceil(C/4), H, W, 4])."""
         self = cls.__new__(cls)
         self._p = ctypes.c_void_p()
-        self.in_layout = self.out_layout = PLAIN
-        rc = lib().conv_direct_create_dgrad(ctypes.byref(self._p), *[int(v) for v in (N, C, H, W, K, R, S, stride, pad)])
+        self.in_layout, self.out_layout = int(dy_layout), int(dx_layout)
+        rc = lib().conv_direct_create_dgrad_layout(ctypes.byref(self._p), *[int(v) for v in (N, C, H, W, K, R, S, stride, pad)],
+                                                   int(dy_layout), int(dx_layout))
         if rc != OK:
             self._p = ctypes.c_void_p()
             raise ConvDirectError(rc, "conv_direct_create_dgrad")
@@ -203,7 +207,10 @@ class Plan:
         the transformed filter held in the library's static device array (nothing is allocated)."""
         import torch
         N, C, H, W, K, R, S, _, _ = self.fwd_dims
-        for t, shape, nm in ((dy, self.dims[:4], "dy"), (w, (K, C, R, S), "w"), (dx, (N, C, H, W), "dx")):
+        n_, k_, p_, q_ = self.dims[:4]
+        dys = (n_, k_, p_, q_) if self.in_layout == PLAIN else (n_, -(-k_ // ACT_BLOCK), p_, q_, ACT_BLOCK)
+        dxs = (N, C, H, W) if self.out_layout == PLAIN else (N, -(-C // ACT_BLOCK), H, W, ACT_BLOCK)
+        for t, shape, nm in ((dy, dys, "dy"), (w, (K, C, R, S), "w"), (dx, dxs, "dx")):
             if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == tuple(shape)):
                 raise ValueError(f"{nm}: need a contiguous fp32 device tensor of shape {tuple(shape)}")
         rc = lib().conv_direct_run_dgrad_static(self._p, dy.data_ptr(), w.data_ptr(), dx.data_ptr(), _stream(stream))

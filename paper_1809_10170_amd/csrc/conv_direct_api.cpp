@@ -356,7 +356,8 @@ int conv_direct_run_fused(const conv_direct_plan *plan, const float *in, const f
         // zero), then one stride-1 convolution of dy per phase, each storing to its own positions of dx
         if (bias || residual || relu) return CONV_DIRECT_EINVAL;
         const int st = plan->ph_stride, RT = plan->s.R;
-        hipError_t e = convd::launch_fill_zero(out, (long long)plan->s.N * plan->s.K * plan->ph_H * plan->ph_W, (hipStream_t)stream);
+        const int KO = plan->out_blocked ? (plan->s.K + 3) / 4 * 4 : plan->s.K;   // channels an image of dx occupies
+        hipError_t e = convd::launch_fill_zero(out, (long long)plan->s.N * KO * plan->ph_H * plan->ph_W, (hipStream_t)stream);
         const int nb = st < plan->fwd_R ? st : plan->fwd_R;   // phases per dimension that have a tap
         a.ost = st;                                       // (the channel-pair kernels' output re-mapping, see KernelArgs)
         a.onb = nb;
@@ -677,14 +678,25 @@ int conv_direct_run_wgrad(const conv_direct_plan *plan, const float *x, const fl
 int conv_direct_create_dgrad(conv_direct_plan **plan, int N, int C, int H, int W, int K, int R, int S, int stride,
                              int pad)
 {
+    return conv_direct_create_dgrad_layout(plan, N, C, H, W, K, R, S, stride, pad, CONV_DIRECT_LAYOUT_PLAIN,
+                                           CONV_DIRECT_LAYOUT_PLAIN);
+}
+
+int conv_direct_create_dgrad_layout(conv_direct_plan **plan, int N, int C, int H, int W, int K, int R, int S, int stride,
+                                    int pad, int dy_layout, int dx_layout)
+{
     if (!plan) return CONV_DIRECT_EINVAL;
     *plan = nullptr;
+    if ((dy_layout != CONV_DIRECT_LAYOUT_PLAIN && dy_layout != CONV_DIRECT_LAYOUT_BLOCKED) ||
+        (dx_layout != CONV_DIRECT_LAYOUT_PLAIN && dx_layout != CONV_DIRECT_LAYOUT_BLOCKED))
+        return CONV_DIRECT_EINVAL;
+    const int dyb = dy_layout == CONV_DIRECT_LAYOUT_BLOCKED, dxb = dx_layout == CONV_DIRECT_LAYOUT_BLOCKED;
     Shape fwd;
     const int rc = validate(N, C, H, W, K, R, S, stride, pad, &fwd);
     if (rc != CONV_DIRECT_OK) return rc;
     if (stride == 1 && R == S && pad <= R - 1) {
         // the forward problem that computes dx: input dy [N][K][P][Q], C output channels
-        const int rc1 = make_plan(plan, nullptr, N, K, fwd.P, fwd.Q, C, R, S, 1, R - 1 - pad);
+        const int rc1 = make_plan(plan, nullptr, N, K, fwd.P, fwd.Q, C, R, S, 1, R - 1 - pad, dyb, dxb);
         if (rc1 == CONV_DIRECT_OK) {
             (*plan)->fwd_K = K;  (*plan)->fwd_C = C;  (*plan)->fwd_R = R;  (*plan)->fwd_S = S;
             return rc1;
@@ -692,7 +704,8 @@ int conv_direct_create_dgrad(conv_direct_plan **plan, int N, int C, int H, int W
         if (rc1 != CONV_DIRECT_EUNSUPPORTED) return rc1;
         // (no variant serves that forward problem: the runtime-shape path below)
     }
-    if (stride > 1 && R == S && (int64_t)N * C * H * W < kMaxElems) {
+    // (the kernels' output re-mapping is compiled for filters of up to 4x4 taps a phase)
+    if (stride > 1 && R == S && (R + stride - 1) / stride <= 4 && (int64_t)N * ((C + 3) / 4 * 4) * H * W < kMaxElems) {
         // Strided layer, square filter.  With t = h + pad = stride*u + a, only the taps r = a + stride*i reach
         // row h: dx[h] = sum_i dy[u - i] * w[a + stride*i], a stride-1 convolution of dy with the RT = ceil(R/stride)
         // taps of phase a (zeros where a + stride*i >= R), padding RT - 1, whose result u belongs at
@@ -700,7 +713,7 @@ int conv_direct_create_dgrad(conv_direct_plan **plan, int N, int C, int H, int W
         // which store with that re-mapping; no workspace.
         const int RT = cdiv(R, stride);
         conv_direct_plan *sub = nullptr;
-        if (make_plan(&sub, nullptr, N, K, fwd.P, fwd.Q, C, RT, RT, 1, RT - 1, 0, 0, true, stride) == CONV_DIRECT_OK) {
+        if (make_plan(&sub, nullptr, N, K, fwd.P, fwd.Q, C, RT, RT, 1, RT - 1, dyb, dxb, true, stride) == CONV_DIRECT_OK) {
             sub->ph_stride = stride;
             sub->ph_pad = pad;
             sub->ph_H = H;
@@ -725,6 +738,8 @@ int conv_direct_create_dgrad(conv_direct_plan **plan, int N, int C, int H, int W
     conv_direct_plan *p = new (std::nothrow) conv_direct_plan();
     if (!p) return CONV_DIRECT_ENOMEM;
     fill(p, s, *generic);
+    p->in_blocked = dyb;
+    p->out_blocked = dxb;
     p->dil = stride;
     p->pad_h = R - 1 - pad;
     p->pad_w = S - 1 - pad;
@@ -736,17 +751,23 @@ int conv_direct_create_dgrad(conv_direct_plan **plan, int N, int C, int H, int W
 size_t conv_direct_dgrad_wt_elems(const conv_direct_plan *plan)
 {
     if (!plan || !plan->v || !plan->fwd_K) return 0;
+    // (blocked: whole blocks of 32 layer-input channels and pencils of 4 layer-output channels, see conv_direct_pack_w)
+    const size_t kc = plan->in_blocked ? (size_t)((plan->fwd_C + 31) / 32 * 32) * (size_t)((plan->fwd_K + 3) / 4 * 4)
+                                       : (size_t)plan->fwd_C * plan->fwd_K;
     if (plan->ph_stride) {
         const int nb = plan->ph_stride < plan->fwd_R ? plan->ph_stride : plan->fwd_R;
-        return (size_t)nb * nb * plan->fwd_C * plan->fwd_K * plan->s.R * plan->s.S;
+        return (size_t)nb * nb * kc * plan->s.R * plan->s.S;
     }
-    return (size_t)plan->fwd_K * plan->fwd_C * plan->fwd_R * plan->fwd_S;
+    return kc * plan->fwd_R * plan->fwd_S;
 }
 
 int conv_direct_dgrad_prepare(const conv_direct_plan *plan, const float *w, float *wt, void *stream)
 {
     if (!plan || !plan->v || !plan->fwd_K || !w || !wt) return CONV_DIRECT_EINVAL;
     if (((uintptr_t)w | (uintptr_t)wt) & 3u) return CONV_DIRECT_EALIGN;
+    if (plan->in_blocked)   // the kernels of this plan read blocked weights
+        return launched(convd::launch_dgrad_filter_blocked(w, wt, plan->fwd_K, plan->fwd_C, plan->fwd_R, plan->fwd_S,
+                                                           plan->ph_stride ? plan->ph_stride : 1, (hipStream_t)stream));
     if (plan->ph_stride)
         return launched(convd::launch_dgrad_phase_filter(w, wt, plan->fwd_K, plan->fwd_C, plan->fwd_R, plan->fwd_S,
                                                          plan->ph_stride, (hipStream_t)stream));

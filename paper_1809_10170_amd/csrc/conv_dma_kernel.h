@@ -354,7 +354,8 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
         ph = (int)(bid % nph);
         bid /= nph;
     }
-    const float *const wp_ = a.w + (REMAP ? (size_t)ph * K * C * G::RS : 0);   // the filter of this workgroup
+    // the filter of this workgroup (blocked weights: whole blocks of 32 output channels and pencils of 4 input channels)
+    const float *const wp_ = a.w + (REMAP ? (size_t)ph * (G::BLK ? (size_t)((K + 31) / 32 * 32) * CI : (size_t)K * C) * G::RS : 0);
     const int kt = bid % a.ktiles;  bid /= a.ktiles;
     const int k0 = kt * G::KT;
     // rectangular: image n, tile origin (p0, q0).  flat: first pixel m0 of M, which
@@ -640,7 +641,7 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
                 if (ci + 2 < nchl) chunk(ci + 2, b2, b0, b1, a2, a1);
             }
         };
-        if constexpr (REMAP && G::R > 1 && G::S > 1) {
+        if constexpr (REMAP && G::R > 1 && G::S > 1 && G::BLK == 0) {   // (the blocked variants multiply the padded taps too)
             // phase (pa, pb) of the input positions has ceil((ofr - pa) / ost) filter rows; the padded shape has R
             const int nbp = a.onb, pa = ph / nbp, pb_ = ph - pa * nbp;
             const int skr = G::R - (a.ofr - pa + a.ost - 1) / a.ost, skc = G::S - (a.ofr - pb_ + a.ost - 1) / a.ost;
@@ -793,8 +794,8 @@ static hipError_t launch_dma_tf(const KernelArgs &a, unsigned grid, hipStream_t 
 template <class G, bool TAILC>
 static hipError_t launch_dma_t(const KernelArgs &a, unsigned grid, hipStream_t stream)
 {
-    if (a.ost) {   // output re-mapping: compiled for the plain-layout stride-1 variants of small filters only
-        if constexpr (G::BLK == 0 && G::ST == 1 && G::R <= 4) {
+    if (a.ost) {   // output re-mapping: compiled for the stride-1 variants of small filters only
+        if constexpr (G::ST == 1 && G::R <= 4) {
             return has_tail(a) ? hipErrorInvalidValue : launch_dma_remap<G, TAILC>(a, grid, stream);
         } else {
             return hipErrorInvalidValue;

@@ -98,6 +98,31 @@ __global__ void __launch_bounds__(256) dgrad_phase_filter_kernel(const float *__
     }
 }
 
+// The same filters in the blocked weight layout of the forward problem that computes dx (its 32 "output" channels a
+// block are the layer's input channels c, its pencils of 4 "input" channels the layer's output channels k):
+//   wt[ph][c/32][k/4][j][l][k%4][c%32] = w[k][c][a + stride*(RTR-1-j)][b + stride*(RTS-1-l)]
+// (stride 1: one phase, RTR x RTS = R x S, the flipped filter), zeros where the tap or the channel does not exist;
+// one thread per destination element
+__global__ void __launch_bounds__(256) dgrad_filter_blocked_kernel(const float *__restrict__ src, float *__restrict__ dst,
+                                                                   int K, int C, int R, int S, int st, int RTR, int RTS,
+                                                                   int nb, long long elems)
+{
+    const int K4 = (K + 3) / 4, C32 = (C + 31) / 32;
+    for (long long t = blockIdx.x * 256ll + threadIdx.x; t < elems; t += gridDim.x * 256ll) {
+        long long u = t;
+        const int ci = (int)(u % 32);  u /= 32;
+        const int ki = (int)(u % 4);   u /= 4;
+        const int l = (int)(u % RTS);  u /= RTS;
+        const int j = (int)(u % RTR);  u /= RTR;
+        const int kb = (int)(u % K4);  u /= K4;
+        const int cb = (int)(u % C32);
+        const int ph = (int)(u / C32);
+        const int k = kb * 4 + ki, c = cb * 32 + ci;
+        const int r = ph / nb + st * (RTR - 1 - j), s = ph % nb + st * (RTS - 1 - l);
+        dst[t] = (k < K && c < C && r < R && s < S) ? src[(((long long)k * C + c) * R + r) * S + s] : 0.f;
+    }
+}
+
 __global__ void __launch_bounds__(256) fill_zero_kernel(float *dst, long long elems)
 {
     for (long long t = blockIdx.x * 256ll + threadIdx.x; t < elems; t += gridDim.x * 256ll) dst[t] = 0.f;
@@ -144,6 +169,16 @@ hipError_t launch_dgrad_phase_filter(const float *w, float *wt, int K, int C, in
     const long long elems = (long long)nb * nb * C * K * RT * RT;
     hipLaunchKernelGGL(dgrad_phase_filter_kernel, dim3(blocks_for(elems)), dim3(256), 0, stream, w, wt, K, C, R, S, stride, RT,
                        nb, elems);
+    return hipGetLastError();
+}
+
+hipError_t launch_dgrad_filter_blocked(const float *w, float *wt, int K, int C, int R, int S, int stride, hipStream_t stream)
+{
+    const int RTR = (R + stride - 1) / stride, RTS = (S + stride - 1) / stride;
+    const int nb = stride < R ? stride : R;
+    const long long elems = (long long)nb * nb * ((C + 31) / 32 * 32) * ((K + 3) / 4 * 4) * RTR * RTS;
+    hipLaunchKernelGGL(dgrad_filter_blocked_kernel, dim3(blocks_for(elems)), dim3(256), 0, stream, w, wt, K, C, R, S, stride,
+                       RTR, RTS, nb, elems);
     return hipGetLastError();
 }
 

@@ -308,3 +308,20 @@ def test_plan_info_states_the_data_gradient_s_extra_buffer():
     fwd = cd.Plan(2, 8, 20, 20, 9, 3, 3, 1, 1)
     assert fwd.info()["extra_caller_bytes"] == 0 and fwd.info()["workspace_bytes"] == 0
     fwd.destroy()
+
+
+def test_data_gradient_plans_take_layouts_and_size_the_filter_in_whole_blocks():
+    """conv_direct_create_dgrad_layout: the blocked transformed filter holds whole blocks of 32 layer-input channels and
+    pencils of 4 layer-output channels per phase; bad layouts are refused; a phase filter of more than 4x4 taps goes to
+    the runtime-shape kernel (no compiled kernel re-maps its output)."""
+    p = cd.Plan.dgrad(2, 40, 29, 29, 70, 3, 3, 2, 1, dy_layout=cd.BLOCKED, dx_layout=cd.BLOCKED)
+    i = p.info()
+    assert i["dgrad_phases"] == 4 and i["in_layout"] == "blocked" and i["out_layout"] == "blocked"
+    assert p.dgrad_wt_elems() == 4 * 64 * 72 * 2 * 2 and i["extra_caller_bytes"] == 4 * p.dgrad_wt_elems()
+    q = cd.Plan.dgrad(2, 40, 29, 29, 70, 3, 3, 2, 1)
+    assert q.dgrad_wt_elems() == 4 * 40 * 70 * 2 * 2
+    plan = ctypes.c_void_p(1)
+    assert cd.lib().conv_direct_create_dgrad_layout(ctypes.byref(plan), 2, 40, 29, 29, 70, 3, 3, 2, 1, 2, 0) == cd.EINVAL
+    assert plan.value is None
+    big = cd.Plan.dgrad(1, 8, 20, 20, 8, 9, 9, 2, 4)
+    assert big.info()["dgrad_phases"] == 0 and big.info()["variant"].startswith("generic")

@@ -153,3 +153,66 @@ def test_strided_benchmark_layer_full_size_whole_images(oracle):
         want = oracle.conv_dgrad(np.ascontiguousarray(dy[n:n + 1]), w, l.H, l.W, l.stride, l.pad)
         err = np.abs(dx[n:n + 1].cpu().numpy().astype(np.float64) - want).max()
         assert err <= oracle.tolerance(l.K, l.R, l.S), err
+
+
+# ---- blocked layouts (dy [N][K/4][P][Q][4], dx [N][C/4][H][W][4]; the weights stay plain) ----
+BLOCKED_CASES = [s[:7] + (1, s[7]) for s in SMALL] + GENERAL
+
+
+@pytest.mark.parametrize("layouts", [(cd.BLOCKED, cd.BLOCKED), (cd.BLOCKED, cd.PLAIN), (cd.PLAIN, cd.BLOCKED)],
+                         ids=["blocked-blocked", "blocked-plain", "plain-blocked"])
+@pytest.mark.parametrize("shape", BLOCKED_CASES)
+def test_blocked_layouts_integer_inputs_bit_exact(oracle, shape, layouts):
+    """Every case of the plain-layout tests with dy and/or dx in the blocked activation layout, against the
+    layout oracle (unpack, adjoint definition, pack); the spare channels of dx's last pencil must be zeros."""
+    from oracle import layout_ref as L
+    N, C, H, W, K, R, S, st, pd = shape
+    dyl, dxl = layouts
+    rng = np.random.default_rng(660 + sum(shape))
+    w = rng.integers(-4, 5, (K, C, R, S)).astype(np.float32)
+    P, Q = oracle.out_dim(H, R, st, pd), oracle.out_dim(W, S, st, pd)
+    dy = rng.integers(-4, 5, (N, K, P, Q)).astype(np.float32)
+    assert K * R * S * 16 < 2 ** 24
+    plan = cd.Plan.dgrad(*shape, dy_layout=dyl, dx_layout=dxl)
+    info = plan.info()
+    assert plan.output_dims() == (H, W) and plan.workspace_bytes() == 0
+    assert info["in_layout"] == ("blocked" if dyl == cd.BLOCKED else "plain")
+    assert info["out_layout"] == ("blocked" if dxl == cd.BLOCKED else "plain")
+    dy_in = L.pack_activations(dy, 4) if dyl == cd.BLOCKED else dy
+    wt = torch.full((plan.dgrad_wt_elems(),), float("nan"), device="cuda")
+    plan.dgrad_prepare(torch.from_numpy(w).cuda(), wt)
+    dx = torch.full((N, -(-C // 4), H, W, 4) if dxl == cd.BLOCKED else (N, C, H, W), float("nan"), device="cuda")
+    plan.run(torch.from_numpy(dy_in).cuda(), wt, dx)
+    torch.cuda.synchronize()
+    plan.destroy()
+    want = oracle.conv_dgrad(dy, w, H, W, st, pd)
+    if dxl == cd.BLOCKED:
+        want = L.pack_activations(want, 4)
+        assert np.array_equal(want, L.conv_dgrad_blocked(L.pack_activations(dy, 4), w, H, W, st, pd))
+    assert np.array_equal(dx.cpu().numpy().astype(np.float64), want), info["variant"]
+
+
+def test_blocked_layouts_strided_benchmark_layer_full_size(oracle):
+    """The suite's 3x3 stride-2 layer in the blocked layouts at full size: the phases run on a compiled blocked
+    variant; three whole images against the oracle."""
+    from oracle import layout_ref as L
+    l = workloads.BY_NAME["s2_c128_56_k256_3x3_n64"]
+    _, w = workloads.make_inputs(l)
+    rng = np.random.default_rng(13)
+    dy = rng.uniform(-1, 1, (l.N, l.K, l.P, l.Q)).astype(np.float32)
+    plan = cd.Plan.dgrad(*l.dims(), dy_layout=cd.BLOCKED, dx_layout=cd.BLOCKED)
+    info = plan.info()
+    assert info["dgrad_phases"] == 4 and info["variant"].startswith("b2s1_flat28_k128") and plan.workspace_bytes() == 0
+    wt = torch.empty((plan.dgrad_wt_elems(),), device="cuda")
+    plan.dgrad_prepare(torch.from_numpy(w).cuda(), wt)
+    dyb = torch.empty((l.N, l.K // 4, l.P, l.Q, 4), device="cuda")
+    cd.pack_act(torch.from_numpy(dy).cuda(), dyb)
+    dxb = torch.full((l.N, l.C // 4, l.H, l.W, 4), float("nan"), device="cuda")
+    plan.run(dyb, wt, dxb)
+    torch.cuda.synchronize()
+    plan.destroy()
+    assert torch.isfinite(dxb).all()
+    for n in (0, l.N // 2, l.N - 1):
+        want = L.conv_dgrad_blocked(L.pack_activations(np.ascontiguousarray(dy[n:n + 1]), 4), w, l.H, l.W, l.stride, l.pad)
+        err = np.abs(dxb[n:n + 1].cpu().numpy().astype(np.float64) - want).max()
+        assert err <= oracle.tolerance(l.K, l.R, l.S), err
