@@ -153,12 +153,19 @@ class Runner:
         for l in layers:
             xd, wd = tensors(l)
             if direction == "wgrad":
-                plan = cd.Plan.wgrad(*l.dims())
-                self.items.append(dict(layer=l, plan=plan, x=xd, dy=self._dy(l, dev), dw=torch.empty((l.K, l.C, l.R, l.S), device=dev)))
+                # blocked: dy and dw in their blocked layouts, x too unless it is a first layer's image (kept plain)
+                lx = cd.BLOCKED if blocked and l.C >= 4 else cd.PLAIN
+                lo = cd.BLOCKED if blocked else cd.PLAIN
+                plan = cd.Plan.wgrad(*l.dims(), x_layout=lx, dy_layout=lo, dw_layout=lo)
+                dyp = self._dy(l, dev)
+                self.items.append(dict(layer=l, plan=plan, x=self._act(xd, lx), dy=self._act(dyp, lo), x_plain=xd, dy_plain=dyp,
+                                       dw=torch.empty((-(-l.K // 32), -(-l.C // 4), l.R, l.S, 4, 32) if blocked else (l.K, l.C, l.R, l.S), device=dev)))
             elif direction == "dgrad":
-                plan = cd.Plan.dgrad(*l.dims())
-                self.items.append(dict(layer=l, plan=plan, dy=self._dy(l, dev), w=wd, wt=torch.empty((plan.dgrad_wt_elems(),), device=dev),
-                                       dx=torch.empty((l.N, l.C, l.H, l.W), device=dev)))
+                lo = cd.BLOCKED if blocked else cd.PLAIN
+                plan = cd.Plan.dgrad(*l.dims(), dy_layout=lo, dx_layout=lo)
+                dyp = self._dy(l, dev)
+                self.items.append(dict(layer=l, plan=plan, dy=self._act(dyp, lo), dy_plain=dyp, w=wd, wt=torch.empty((plan.dgrad_wt_elems(),), device=dev),
+                                       dx=torch.empty((l.N, -(-l.C // 4), l.H, l.W, 4) if blocked else (l.N, l.C, l.H, l.W), device=dev)))
             else:
                 li = cd.BLOCKED if blocked and l.C >= 4 else cd.PLAIN
                 lo = cd.BLOCKED if blocked else cd.PLAIN
@@ -172,6 +179,17 @@ class Runner:
                 oshape = (l.N, -(-l.K // 4), l.P, l.Q, 4) if lo == cd.BLOCKED else (l.N, l.K, l.P, l.Q)
                 self.items.append(dict(layer=l, plan=plan, x=xin, w=win, out=torch.empty(oshape, device=dev), x_plain=xd, w_plain=wd))
         torch.cuda.synchronize()
+
+    def _act(self, plain, layout):
+        # an activation tensor in the given layout (re-arranged once, outside the timed region)
+        if layout == self.cd.PLAIN:
+            return plain
+        n, c, h, w = plain.shape
+        return self.cd.pack_act(plain, self.torch.empty((n, -(-c // 4), h, w, 4), device=plain.device))
+
+    def _plain(self, t, shape):
+        # a (possibly blocked) activation tensor as a plain one
+        return t if tuple(t.shape) == tuple(shape) else self.cd.unpack_act(t, self.torch.empty(shape, device=t.device))
 
     def _dy(self, l, dev):
         # dy stands in for the next layer's gradient: U[-1,1], seeded
@@ -237,22 +255,26 @@ class Runner:
         if self.direction == "wgrad":
             # three output channels of dw in full (each costs the oracle a forward pass of one channel)
             ks = sorted({0, l.K - 1, l.K // 2})
-            want = oracle.conv_wgrad(it["x"].cpu().numpy(), np.ascontiguousarray(it["dy"].cpu().numpy()[:, ks]), l.R, l.S, l.stride, l.pad)
-            err = float(np.abs(it["dw"].cpu().numpy()[ks].astype(np.float64) - want).max())
+            want = oracle.conv_wgrad(it["x_plain"].cpu().numpy(), np.ascontiguousarray(it["dy_plain"].cpu().numpy()[:, ks]), l.R, l.S, l.stride, l.pad)
+            dw = it["dw"].cpu().numpy()
+            if dw.ndim == 6:   # blocked [K/32][C/4][R][S][4][32] -> [K][C][R][S]
+                dw = dw.transpose(0, 5, 1, 4, 2, 3).reshape(dw.shape[0] * 32, dw.shape[1] * 4, l.R, l.S)[:l.K, :l.C]
+            err = float(np.abs(dw[ks].astype(np.float64) - want).max())
             return err, 1e-4 * (l.N * l.P * l.Q) ** 0.5, f"dw[{ks}] in full"
         if self.direction == "dgrad":
             if not (l.stride == 1 and l.R == l.S and l.pad <= l.R - 1):
                 # no single-element form for these: the last image in full against the oracle's adjoint
                 n = l.N - 1
-                want = oracle.conv_dgrad(np.ascontiguousarray(it["dy"][n:n + 1].cpu().numpy()), it["w"].cpu().numpy(), l.H, l.W, l.stride, l.pad)
-                err = float(np.abs(it["dx"][n:n + 1].cpu().numpy().astype(np.float64) - want).max())
+                want = oracle.conv_dgrad(np.ascontiguousarray(it["dy_plain"][n:n + 1].cpu().numpy()), it["w"].cpu().numpy(), l.H, l.W, l.stride, l.pad)
+                dx = self._plain(it["dx"], (l.N, l.C, l.H, l.W))
+                err = float(np.abs(dx[n:n + 1].cpu().numpy().astype(np.float64) - want).max())
                 return err, oracle.tolerance(l.K, l.R, l.S), f"image {n} of dx in full"
             # sampled dx elements through the flipped-filter identity (pinned on the CPU against the adjoint definition)
             rng = np.random.default_rng(5)
             pts = np.stack([rng.integers(0, d, npts) for d in (l.N, l.C, l.H, l.W)], axis=1).astype(np.int32)
             wt = np.ascontiguousarray(it["w"].cpu().numpy()[:, :, ::-1, ::-1].transpose(1, 0, 2, 3))
-            want = oracle.conv_forward_points(it["dy"].cpu().numpy(), wt, pts, 1, l.R - 1 - l.pad)
-            got = self._gather(it["dx"], pts)
+            want = oracle.conv_forward_points(it["dy_plain"].cpu().numpy(), wt, pts, 1, l.R - 1 - l.pad)
+            got = self._gather(self._plain(it["dx"], (l.N, l.C, l.H, l.W)), pts)
             return float(np.abs(got - want).max()), oracle.tolerance(l.K, l.R, l.S), f"{npts} sampled elements of dx"
         pts = self.workloads.sample_points(l, npts)
         want = oracle.conv_forward_points(it["x_plain"].cpu().numpy(), it["w_plain"].cpu().numpy(), pts, l.stride, l.pad)
@@ -334,8 +356,6 @@ def main():
     cd.lib()   # fail loudly if the HIP library is missing
     layers = suite(args.workload, workloads)
     blocked = args.layout == "blocked"
-    if args.direction != "forward" and blocked:
-        sys.exit("bench.py: the gradients run in plain layouts")
 
     def dgrad_layers(ls):
         # a suite: the layers whose data gradient runs on the compiled kernels (stride 1, or a strided layer as one
@@ -407,7 +427,8 @@ def main():
         # the other paths over the same suite, each timed as whole passes like the headline step
         other = {}
         for name, direction, blk, ls in (("forward_blocked", "forward", True, layers), ("dgrad", "dgrad", False, dgrad_layers(layers)),
-                                         ("wgrad", "wgrad", False, layers)):
+                                         ("wgrad", "wgrad", False, layers), ("dgrad_blocked", "dgrad", True, dgrad_layers(layers)),
+                                         ("wgrad_blocked", "wgrad", True, layers)):
             run = Runner(cd, torch, workloads, tensors, ls, direction, blk)
             ms, tms = run.time_step(args.steps, args.warmup, stream)
             fl = sum(l.flops for l in ls)

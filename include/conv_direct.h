@@ -212,7 +212,7 @@ int conv_direct_pack_w(const float *plain, float *blocked, int K, int C, int R, 
  * conv_direct_dgrad_wt_elems(plan) floats -- so wt is opaque to the caller: always size it with
  * _dgrad_wt_elems and fill it with _dgrad_prepare of the SAME plan.
  *
- * Weight gradient (the backward pass with respect to the filter), plain layouts, any
+ * Weight gradient (the backward pass with respect to the filter), any
  * filter, strides up to 4 (compiled variants for the filter widths and strides of the forward
  * variants, a slower run-time-shape variant for the rest):
  *
@@ -250,6 +250,15 @@ int conv_direct_create_wgrad_deterministic(conv_direct_plan **plan,
  * enumerates the names (NULL past the end). */
 int conv_direct_create_wgrad_ex(conv_direct_plan **plan, const char *variant,
                                 int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+/* The weight gradient with tensors in the blocked layouts of the paper's Section 4 (each one CONV_DIRECT_LAYOUT_PLAIN
+ * or _BLOCKED): x [N][ceil(C/4)][H][W][4], dy [N][ceil(K/4)][P][Q][4] (spare channels of a last pencil must hold
+ * zeros or any finite value: they only meet results that are dropped), dw [ceil(K/32)][ceil(C/4)][R][S][4][32] (what
+ * conv_direct_pack_w would make of the plain gradient; its spare channels are written as zeros).  variant (NULL: the
+ * planner's choice) and deterministic (non-zero: one workgroup per tile of dw, the same bits every run) as in
+ * conv_direct_create_wgrad_ex / _deterministic.  Every shape the plain entry points serve. */
+int conv_direct_create_wgrad_layout(conv_direct_plan **plan, const char *variant, int deterministic,
+                                    int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                    int x_layout, int dy_layout, int dw_layout);
 const char *conv_direct_wgrad_variant_name(int index);
 
 /*

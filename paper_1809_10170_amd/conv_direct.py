@@ -82,6 +82,8 @@ def lib():
         l.conv_direct_create_wgrad_ex.restype = i
         l.conv_direct_create_wgrad_deterministic.argtypes = [pp] + [i] * 9
         l.conv_direct_create_wgrad_deterministic.restype = i
+        l.conv_direct_create_wgrad_layout.argtypes = [pp, cp, i] + [i] * 12
+        l.conv_direct_create_wgrad_layout.restype = i
         l.conv_direct_wgrad_variant_name.argtypes = [i]
         l.conv_direct_wgrad_variant_name.restype = cp
         l.conv_direct_run_wgrad.argtypes = [vp, vp, vp, vp, vp]
@@ -218,14 +220,19 @@ class Plan:
             raise ConvDirectError(rc, "conv_direct_run_dgrad_static")
 
     @classmethod
-    def wgrad(cls, N, C, H, W, K, R, S, stride, pad, variant: str | None = None, deterministic: bool = False):
-        """Plan of the weight gradient of the forward layer: run_wgrad(x [N,C,H,W], dy [N,K,P,Q], dw [K,C,R,S]).
-        deterministic: one workgroup per tile of dw (plain stores, the same bits every run)."""
+    def wgrad(cls, N, C, H, W, K, R, S, stride, pad, variant: str | None = None, deterministic: bool = False,
+              x_layout: int = PLAIN, dy_layout: int = PLAIN, dw_layout: int = PLAIN):
+        """Plan of the weight gradient of the forward layer: run_wgrad(x [N,C,H,W], dy [N,K,P,Q], dw [K,C,R,S]), each
+        tensor plain or in its blocked layout.  deterministic: one workgroup per tile of dw (plain stores, the same
+        bits every run)."""
         self = cls.__new__(cls)
         self._p = ctypes.c_void_p()
-        self.in_layout = self.out_layout = PLAIN
+        self.in_layout, self.dy_layout, self.out_layout = int(x_layout), int(dy_layout), int(dw_layout)
         dims = [int(v) for v in (N, C, H, W, K, R, S, stride, pad)]
-        if deterministic:
+        if (self.in_layout, self.dy_layout, self.out_layout) != (PLAIN, PLAIN, PLAIN):
+            rc = lib().conv_direct_create_wgrad_layout(ctypes.byref(self._p), variant.encode() if variant else None,
+                                                       1 if deterministic else 0, *dims, self.in_layout, self.dy_layout, self.out_layout)
+        elif deterministic:
             rc = lib().conv_direct_create_wgrad_deterministic(ctypes.byref(self._p), *dims)
         else:
             rc = lib().conv_direct_create_wgrad_ex(ctypes.byref(self._p), variant.encode() if variant else None, *dims)
@@ -240,7 +247,11 @@ class Plan:
         N, C, H, W, K, R, S, st, pd = self.dims
         i = self.info()
         P, Q = i["P"], i["Q"]
-        for t, shape, nm in ((x, (N, C, H, W), "x"), (dy, (N, K, P, Q), "dy"), (dw, (K, C, R, S), "dw")):
+        cb, kb = ACT_BLOCK, W_KBLOCK
+        xs = (N, C, H, W) if self.in_layout == PLAIN else (N, -(-C // cb), H, W, cb)
+        ys = (N, K, P, Q) if self.dy_layout == PLAIN else (N, -(-K // cb), P, Q, cb)
+        ws = (K, C, R, S) if self.out_layout == PLAIN else (-(-K // kb), -(-C // cb), R, S, cb, kb)
+        for t, shape, nm in ((x, xs, "x"), (dy, ys, "dy"), (dw, ws, "dw")):
             if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == shape):
                 raise ValueError(f"{nm}: need a contiguous fp32 device tensor of shape {shape}")
         rc = lib().conv_direct_run_wgrad(self._p, x.data_ptr(), dy.data_ptr(), dw.data_ptr(), _stream(stream))

@@ -36,6 +36,7 @@ struct conv_direct_plan {
     int fwd_K, fwd_C, fwd_R, fwd_S;      // data-gradient plans: the forward layer's filter dims (0 otherwise)
     const convd::WgradVariant *wv; // weight-gradient plans only (v is then NULL)
     int wg_cgroups, wg_splits;
+    int wg_dy_blocked;             // weight-gradient plans: layout of dy (in_blocked: of x, out_blocked: of dw)
 };
 
 namespace {
@@ -400,9 +401,11 @@ int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
         const Shape &s = plan->s;
         return std::snprintf(buf, n,
                              "variant=%s kind=wgrad N=%d C=%d H=%d W=%d K=%d R=%d S=%d stride=%d pad=%d P=%d Q=%d "
-                             "ktiles=%d cgroups=%d splits=%d grid=%u threads=%d workspace_bytes=0",
+                             "ktiles=%d cgroups=%d splits=%d grid=%u threads=%d x_layout=%s dy_layout=%s dw_layout=%s workspace_bytes=0",
                              plan->wv->name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, plan->ktiles,
-                             plan->wg_cgroups, plan->wg_splits, plan->grid, 64 * plan->wv->WK * plan->wv->WC * plan->wv->WB);
+                             plan->wg_cgroups, plan->wg_splits, plan->grid, 64 * plan->wv->WK * plan->wv->WC * plan->wv->WB,
+                             plan->in_blocked ? "blocked" : "plain", plan->wg_dy_blocked ? "blocked" : "plain",
+                             plan->out_blocked ? "blocked" : "plain");
     }
     const Variant &v = *plan->v;
     const Shape &s = plan->s;
@@ -570,7 +573,19 @@ const char *conv_direct_wgrad_variant_name(int index)
 }
 
 static int create_wgrad(conv_direct_plan **plan, const char *variant, bool one_split, int N, int C, int H, int W, int K, int R, int S,
-                        int stride, int pad);
+                        int stride, int pad, int xb = 0, int yb = 0, int wb = 0);
+
+int conv_direct_create_wgrad_layout(conv_direct_plan **plan, const char *variant, int deterministic, int N, int C, int H, int W,
+                                    int K, int R, int S, int stride, int pad, int x_layout, int dy_layout, int dw_layout)
+{
+    for (int l : {x_layout, dy_layout, dw_layout})
+        if (l != CONV_DIRECT_LAYOUT_PLAIN && l != CONV_DIRECT_LAYOUT_BLOCKED) {
+            if (plan) *plan = nullptr;
+            return CONV_DIRECT_EINVAL;
+        }
+    return create_wgrad(plan, variant, deterministic != 0, N, C, H, W, K, R, S, stride, pad, x_layout == CONV_DIRECT_LAYOUT_BLOCKED,
+                        dy_layout == CONV_DIRECT_LAYOUT_BLOCKED, dw_layout == CONV_DIRECT_LAYOUT_BLOCKED);
+}
 
 int conv_direct_create_wgrad_ex(conv_direct_plan **plan, const char *variant, int N, int C, int H, int W, int K, int R, int S,
                                 int stride, int pad)
@@ -584,7 +599,7 @@ int conv_direct_create_wgrad_deterministic(conv_direct_plan **plan, int N, int C
 }
 
 static int create_wgrad(conv_direct_plan **plan, const char *variant, bool one_split, int N, int C, int H, int W, int K, int R, int S,
-                        int stride, int pad)
+                        int stride, int pad, int xb, int yb, int wb)
 {
     if (!plan) return CONV_DIRECT_EINVAL;
     *plan = nullptr;
@@ -592,7 +607,9 @@ static int create_wgrad(conv_direct_plan **plan, const char *variant, bool one_s
     const int rc = validate(N, C, H, W, K, R, S, stride, pad, &s);
     if (rc != CONV_DIRECT_OK) return rc;
     // offsets inside one image and one chunk's channel range are 32-bit
-    if ((int64_t)K * s.P * s.Q * 4 >= ((int64_t)1 << 31) || (int64_t)C * H * W * 4 >= ((int64_t)1 << 31))
+    // (blocked activations: whole pencils of 4 channels; a blocked dw: whole blocks of 32 x 4 channels)
+    if ((int64_t)(K + 3) * s.P * s.Q * 4 >= ((int64_t)1 << 31) || (int64_t)(C + 3) * H * W * 4 >= ((int64_t)1 << 31) ||
+        (int64_t)(K + 31) * (C + 3) * R * S >= kMaxElems)
         return CONV_DIRECT_EUNSUPPORTED;
     int count = 0;
     const convd::WgradVariant *table = convd::wgrad_table(&count);
@@ -649,6 +666,9 @@ static int create_wgrad(conv_direct_plan **plan, const char *variant, bool one_s
         }
     }
     p->wg_splits = (int)splits;
+    p->in_blocked = xb;
+    p->wg_dy_blocked = yb;
+    p->out_blocked = wb;
     p->grid = (unsigned)(tiles * splits);
     *plan = p;
     return CONV_DIRECT_OK;
@@ -659,13 +679,19 @@ int conv_direct_run_wgrad(const conv_direct_plan *plan, const float *x, const fl
     if (!plan || !plan->wv || !x || !dy || !dw) return CONV_DIRECT_EINVAL;
     if (((uintptr_t)x | (uintptr_t)dy | (uintptr_t)dw) & 3u) return CONV_DIRECT_EALIGN;
     const Shape &s = plan->s;
-    // (one workgroup per result tile stores its sums plainly: nothing to clear)
-    hipError_t e = plan->wg_splits == 1 ? hipSuccess : convd::wgrad_clear(dw, (long long)s.K * s.C * s.R * s.S, (hipStream_t)stream);
+    // (one workgroup per result tile stores its sums plainly: nothing to clear, except the spare channels that complete
+    // the blocks of a blocked dw)
+    const long long dw_elems = plan->out_blocked ? (long long)conv_direct_blocked_w_elems(s.K, s.C, s.R, s.S) : (long long)s.K * s.C * s.R * s.S;
+    const bool clear = plan->wg_splits != 1 || (plan->out_blocked && (s.K % 32 != 0 || s.C % 4 != 0));
+    hipError_t e = clear ? convd::wgrad_clear(dw, dw_elems, (hipStream_t)stream) : hipSuccess;
     if (e == hipSuccess) {
         convd::WgradArgs a;
         a.x = x;
         a.dy = dy;
         a.dw = dw;
+        a.x_blocked = plan->in_blocked;
+        a.dy_blocked = plan->wg_dy_blocked;
+        a.dw_blocked = plan->out_blocked;
         a.s = s;
         a.ktiles = plan->ktiles;
         a.cgroups = plan->wg_cgroups;

@@ -121,6 +121,12 @@ struct WgGeom {
     static constexpr int WPE = PER_CU * NW >= 4 ? PER_CU * NW / 4 : 1;   // waves per SIMD the register budget must allow
 };
 
+// element (k, c, tap) of dw in the blocked weight layout [K/32][C/4][R][S][4][32] (RS taps per channel pair)
+__device__ inline size_t dw_blocked_index(int k, int c, int tap, int C, int RS)
+{
+    return ((((size_t)(k >> 5) * ((C + 3) / 4) + (c >> 2)) * RS + tap) * 4 + (c & 3)) * 32 + (k & 31);
+}
+
 template <class G>
 __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradArgs a)
 {
@@ -137,6 +143,17 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
     const float *const xp = a.x, *const dyp = a.dy;
     float *const dwp = a.dw;
     const int splits = a.splits, cgroups = a.cgroups, ktiles = a.ktiles, SFILT = a.s.S;
+    // Layouts (run-time flags; the staging transposes either into the same LDS arrays).  Blocked activations
+    // [N][channels/4][rows][cols][4]: a pixel step is 4 floats, a channel step inside a group of 4 one float, and a
+    // step of 4 channels 4 planes -- the same as in the plain layout.
+    const int xbl = a.x_blocked, ybl = a.dy_blocked, wbl = a.dw_blocked;
+    const int CI = xbl ? (C + 3) / 4 * 4 : C, KI = ybl ? (K + 3) / 4 * 4 : K;   // channels an image occupies in memory
+    const int xpx = xbl ? 4 : 1, ypx = ybl ? 4 : 1;                             // floats from one pixel to the next
+    const int plane_dy = P * Q * 4, plane_x = H * W * 4;                        // bytes of a channel plane (plain layout)
+    const int y_c1 = ybl ? 4 : plane_dy, x_c1 = xbl ? 4 : plane_x;              // bytes from a channel to the next (inside a group of 4)
+    // byte offset of channel ch, counted from a channel that is a multiple of 4 (k0, c0)
+    auto ych = [&](int ch) { return (ch >> 2) * (4 * plane_dy) + (ch & 3) * y_c1; };
+    auto xch = [&](int ch) { return (ch >> 2) * (4 * plane_x) + (ch & 3) * x_c1; };
 
     // workgroup -> (pixel split, filter row, channel group, k tile); neighbours share dy
     // (consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2: regroup
@@ -203,37 +220,35 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
         {
             // pixels of the chunk that exist: the rest of the row, or whole rows down to the image's last
             const int npix = G::QW ? (P - sp < G::RPC ? P - sp : G::RPC) * G::QW : Q - sq0;
-            const unsigned voff = lane < npix ? (unsigned)lane * 4u : 0x80000000u;
-            const float *base = dyp + (((size_t)sn * K + k0) * P + sp) * Q + sq0;
+            const unsigned voff = lane < npix ? (unsigned)(lane * ypx) * 4u : 0x80000000u;
+            const float *base = dyp + ((size_t)sn * KI + k0) * P * Q + (size_t)(sp * Q + sq0) * ypx;
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
-            const int plane = P * Q * 4;
             if constexpr (G::DUAL_A) {
                 const int l2 = lane - G::PA;                      // lane's pixel in the second row of its pair
                 const int np = npix < G::NPX ? npix : G::NPX;     // (the rest of a long row is more than a chunk)
-                const unsigned voff2 = lane < np ? (unsigned)lane * 4u
-                                       : (l2 >= 0 && l2 < np) ? (unsigned)plane + (unsigned)l2 * 4u : 0x80000000u;
+                const unsigned voff2 = lane < np ? (unsigned)(lane * ypx) * 4u
+                                       : (l2 >= 0 && l2 < np) ? (unsigned)y_c1 + (unsigned)(l2 * ypx) * 4u : 0x80000000u;   // (the pair's second row: an odd channel)
 #pragma unroll
                 for (int i = 0; i < G::KT / G::NW / 2; ++i) {
                     const int row = (i * G::NW + wave) * 2;
                     if (k0 + row < K)   // (a second row past K is not loaded: the single-row offsets)
                         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(abuf + row * G::PA), 4,
-                                                                 k0 + row + 1 < K ? voff2 : voff, row * plane, 0, 0);
+                                                                 k0 + row + 1 < K ? voff2 : voff, ych(row), 0, 0);
                 }
             } else if (!G::HALF_A || lane < 32) {   // (a disabled lane writes nothing: rows 33 words apart do not overlap)
 #pragma unroll
                 for (int i = 0; i < G::KT / G::NW; ++i) {
                     const int row = i * G::NW + wave;
                     if (k0 + row < K)
-                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(abuf + row * G::PA), 4, voff, row * plane, 0, 0);
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(abuf + row * G::PA), 4, voff, ych(row), 0, 0);
                 }
             }
         }
         if constexpr (G::QW != 0) {
             // RPC input rows per channel, 32 words apart: only the first 32 lanes take part in a load
             // (a disabled lane writes nothing), lanes past the row's columns or outside the image load zeros
-            const float *base = xp + ((size_t)sn * C + c0) * H * W;
+            const float *base = xp + ((size_t)sn * CI + c0) * H * W;
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
-            const int plane = H * W * 4;
             const int iw = lane - pad;
             const bool colok = lane < G::WX && (unsigned)iw < (unsigned)W;
             if constexpr (G::DUAL_X) {
@@ -247,11 +262,11 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
                         for (int ri = 0; ri < G::XROWS; ri += 2) {
                             const int ih0 = (sp + ri) * G::ST + r - pad, ih1 = ih0 + G::ST;
                             const bool ok0 = (unsigned)ih0 < (unsigned)H, ok1 = (unsigned)ih1 < (unsigned)H;
-                            const unsigned voff = (colok && ok0)    ? (unsigned)(ih0 * W + iw) * 4u
-                                                  : (colok2 && ok1) ? (unsigned)(ih1 * W + iw2) * 4u
+                            const unsigned voff = (colok && ok0)    ? (unsigned)((ih0 * W + iw) * xpx) * 4u
+                                                  : (colok2 && ok1) ? (unsigned)((ih1 * W + iw2) * xpx) * 4u
                                                                     : 0x80000000u;
                             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(xbuf + ch * G::PX + ri * G::PXR), 4, voff,
-                                                                     ch * plane, 0, 0);
+                                                                     xch(ch), 0, 0);
                         }
                     }
                 }
@@ -264,40 +279,10 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
                         for (int ri = 0; ri < G::XROWS; ++ri) {   // (all-rows mode: the halo rows of all taps too)
                             const int ih = (sp + ri) * G::ST + r - pad;
                             const bool rowok = (unsigned)ih < (unsigned)H;
-                            const unsigned voff = (colok && rowok) ? (unsigned)iw * 4u : 0x80000000u;
+                            const unsigned voff = (colok && rowok) ? (unsigned)(iw * xpx) * 4u : 0x80000000u;
                             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(xbuf + ch * G::PX + ri * G::PXR), 4, voff,
-                                                                     ch * plane + (rowok ? ih : 0) * W * 4, 0, 0);
+                                                                     xch(ch) + (rowok ? ih : 0) * W * xpx * 4, 0, 0);
                         }
-                    }
-                }
-            }
-        } else if constexpr (G::AR != 0) {
-            // S input rows per channel, RP words apart; lanes past a row's RP words take no part (a disabled
-            // lane writes nothing), columns or rows outside the image load zeros
-            const int iw0 = sq0 * G::ST - pad;
-            const float *base = xp + ((size_t)sn * C + c0) * H * W;
-            __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
-            const int plane = H * W * 4;
-            unsigned voff[G::NLX];
-#pragma unroll
-            for (int u = 0; u < G::NLX; ++u) {
-                const int col = u * 64 + lane, iw = iw0 + col;
-                voff[u] = (col < G::WX && (unsigned)iw < (unsigned)W) ? (unsigned)iw * 4u : 0x80000000u;
-            }
-#pragma unroll
-            for (int i = 0; i < G::CT / G::NW; ++i) {
-                const int ch = i * G::NW + wave;
-                if (c0 + ch < C) {
-#pragma unroll
-                    for (int ri = 0; ri < G::NR; ++ri) {
-                        const int ih = sp * G::ST + ri - pad;
-                        const bool rowok = (unsigned)ih < (unsigned)H;
-#pragma unroll
-                        for (int u = 0; u < G::NLX; ++u)
-                            if (u * 64 + lane < G::RP)
-                                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(xbuf + ch * G::PX + ri * G::RP + u * 64), 4,
-                                                                         rowok ? voff[u] : 0x80000000u,
-                                                                         ch * plane + (rowok ? ih : 0) * W * 4, 0, 0);
                     }
                 }
             }
@@ -305,14 +290,13 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
             const int ih = sp * st + r - pad;              // exists (the chunk list skips rows without one)
             const int iw0 = sq0 * st - pad + s0;
             const int wx = (G::PXC - 1) * st + G::SB;      // columns the chunk needs
-            const float *base = xp + (((size_t)sn * C + c0) * H + ih) * W;
+            const float *base = xp + ((size_t)sn * CI + c0) * H * W + (size_t)ih * W * xpx;
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(base), 0, 0x7fffffff, 0x00020000);
-            const int plane = H * W * 4;
             unsigned voff[G::NLX];
 #pragma unroll
             for (int u = 0; u < G::NLX; ++u) {
                 const int col = u * 64 + lane, iw = iw0 + col;
-                voff[u] = (col < wx && (unsigned)iw < (unsigned)W) ? (unsigned)iw * 4u : 0x80000000u;
+                voff[u] = (col < wx && (unsigned)iw < (unsigned)W) ? (unsigned)(iw * xpx) * 4u : 0x80000000u;
             }
 #pragma unroll
             for (int i = 0; i < G::CT / G::NW; ++i) {
@@ -321,7 +305,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
 #pragma unroll
                     for (int u = 0; u < G::NLX; ++u)
                         __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, CONVD_LDS(xbuf + ch * G::PX + u * 64), 4, voff[u],
-                                                                 ch * plane, 0, 0);
+                                                                 xch(ch), 0, 0);
                 }
             }
         }
@@ -345,14 +329,13 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
                                                 // row outside the image the resource's size, which sends the load out of range
         unsigned vd[G::XROWS / 2 > 0 ? G::XROWS / 2 : 1];   // small maps, two rows per load: the lane's offset per row pair
     };
-    const int plane_dy = P * Q * 4, plane_x = H * W * 4;
     // per-lane constants of the dy loads: the lane's pixel, full chunk / ragged last chunk of a row or image
     auto dy_voff = [&](int np) -> unsigned {
         if (G::DUAL_A) {
             const int l2 = lane - G::PA;
-            return lane < np ? (unsigned)lane * 4u : (l2 >= 0 && l2 < np) ? (unsigned)plane_dy + (unsigned)l2 * 4u : 0x80000000u;
+            return lane < np ? (unsigned)(lane * ypx) * 4u : (l2 >= 0 && l2 < np) ? (unsigned)y_c1 + (unsigned)(l2 * ypx) * 4u : 0x80000000u;
         }
-        return lane < np ? (unsigned)lane * 4u : 0x80000000u;
+        return lane < np ? (unsigned)(lane * ypx) * 4u : 0x80000000u;
     };
     const int np_rag = G::QW ? (P % G::RPC) * G::QW : Q % G::PXC;       // pixels of a ragged last chunk (0: there is none)
     const unsigned va_full = dy_voff(G::NPX), va_rag = dy_voff(np_rag);
@@ -362,37 +345,37 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
         const int iw = lane - pad, l2 = lane - G::PXR, iw2 = l2 - pad;
         const bool c1 = lane < G::WX && lane < G::PXR && (unsigned)iw < (unsigned)W;
         const bool c2 = l2 >= 0 && l2 < G::WX && (unsigned)iw2 < (unsigned)W;
-        vd_first = c1 ? (unsigned)iw * 4u : 0x80000000u;
-        vd_second = (G::DUAL_X && c2) ? (unsigned)(G::ST * W + iw2) * 4u : 0x80000000u;
+        vd_first = c1 ? (unsigned)(iw * xpx) * 4u : 0x80000000u;
+        vd_second = (G::DUAL_X && c2) ? (unsigned)((G::ST * W + iw2) * xpx) * 4u : 0x80000000u;
         vd_both = c1 ? vd_first : vd_second;
     }
     // (offsets inside one image fit 31 bits: conv_direct_create_wgrad refuses layers whose K*P*Q*4 or C*H*W*4 does not)
-    const int img_dy = (K - k0) * P * Q, img_x = (C - c0) * H * W;     // floats from the workgroup's first channel to the image's end
+    const int img_dy = (KI - k0) * P * Q, img_x = (CI - c0) * H * W;   // floats from the workgroup's first channel to the image's end
     auto ar_source = [&](ArSrc &src, int sn, int sp, int sq0, bool more) __attribute__((always_inline)) {
         // dy: from (sn, k0, sp, sq0) to the end of the image's last channel
-        const int a_in = sp * Q + sq0;
-        src.ra = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(dyp + ((size_t)sn * K + k0) * P * Q + a_in), 0, more ? (img_dy - a_in) * 4 : 0,
+        const int a_in = (sp * Q + sq0) * ypx;
+        src.ra = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(dyp + ((size_t)sn * KI + k0) * P * Q + a_in), 0, more ? (img_dy - a_in) * 4 : 0,
                                                    0x00020000);
         const int npix = G::QW ? (P - sp < G::RPC ? P - sp : G::RPC) * G::QW : Q - sq0;
         src.va = npix >= G::NPX ? va_full : va_rag;
         // input: from row ih0 (possibly above the image), column iw0 (row chunks: possibly left of it: the lanes there are
         // sent out of range) of channel c0, to the end of the image's last channel
         const int ih0 = sp * G::ST - pad, iw0 = G::QW ? 0 : sq0 * G::ST - pad;
-        const int x_in = ih0 * W + iw0;                                    // (may be negative)
+        const int x_in = (ih0 * W + iw0) * xpx;                            // (may be negative)
         const unsigned nrx = more ? (unsigned)(img_x - x_in) * 4u : 0u;
-        src.rx = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(xp + ((long long)sn * C + c0) * H * W + x_in), 0, (int)nrx, 0x00020000);
+        src.rx = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(xp + ((long long)sn * CI + c0) * H * W + x_in), 0, (int)nrx, 0x00020000);
         bool okx[G::XROWS];
 #pragma unroll
         for (int ri = 0; ri < G::XROWS; ++ri) {
             const int ih = ih0 + ri * (G::QW ? G::ST : 1);
             okx[ri] = (unsigned)ih < (unsigned)H;
-            src.sx[ri] = (okx[ri] || (G::QW && G::DUAL_X)) ? (unsigned)(ih - ih0) * (unsigned)W * 4u : nrx;
+            src.sx[ri] = (okx[ri] || (G::QW && G::DUAL_X)) ? (unsigned)(ih - ih0) * (unsigned)(W * xpx) * 4u : nrx;
         }
         if (G::QW == 0) {
 #pragma unroll
             for (int u = 0; u < G::NLX; ++u) {
                 const int col = u * 64 + lane, iw = iw0 + col;
-                src.vx[u] = (col < G::WX && (unsigned)iw < (unsigned)W) ? (unsigned)col * 4u : 0x80000000u;
+                src.vx[u] = (col < G::WX && (unsigned)iw < (unsigned)W) ? (unsigned)(col * xpx) * 4u : 0x80000000u;
             }
         } else if (G::DUAL_X) {
 #pragma unroll
@@ -416,7 +399,7 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
         for (int i = 0; i < AR_NA; ++i)
             if (i >= L0 && i < L1) {
                 const int row = (wave * AR_NA + i) * (G::DUAL_A ? 2 : 1);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(src.ra, CONVD_LDS(abuf + row * G::PA), 4, src.va, row * plane_dy, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(src.ra, CONVD_LDS(abuf + row * G::PA), 4, src.va, ych(row), 0, 0);
             }
 #pragma unroll
         for (int i = 0; i < G::CPWV; ++i) {
@@ -428,13 +411,13 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
                     if (G::QW == 0) {
                         const int ri = xr / (G::NLX > 0 ? G::NLX : 1), u = xr % (G::NLX > 0 ? G::NLX : 1);
                         __builtin_amdgcn_raw_ptr_buffer_load_lds(src.rx, CONVD_LDS(xbuf + ch * G::PX + ri * G::RP + u * 64), 4, src.vx[u],
-                                                                 ch * plane_x + src.sx[ri], 0, 0);
+                                                                 xch(ch) + src.sx[ri], 0, 0);
                     } else if (G::DUAL_X) {
                         __builtin_amdgcn_raw_ptr_buffer_load_lds(src.rx, CONVD_LDS(xbuf + ch * G::PX + 2 * xr * G::PXR), 4, src.vd[xr],
-                                                                 ch * plane_x + src.sx[2 * xr], 0, 0);
+                                                                 xch(ch) + src.sx[2 * xr], 0, 0);
                     } else {
                         __builtin_amdgcn_raw_ptr_buffer_load_lds(src.rx, CONVD_LDS(xbuf + ch * G::PX + xr * G::PXR), 4, vd_first,
-                                                                 ch * plane_x + src.sx[xr], 0, 0);
+                                                                 xch(ch) + src.sx[xr], 0, 0);
                     }
                 }
             }
@@ -597,6 +580,47 @@ __global__ void __launch_bounds__(G::NT, G::WPE) conv_wgrad_kernel(const WgradAr
     // partial sums of this pixel split -> dw (cleared before the launch)
     const int SF = G::RT ? SFILT : G::S;             // filter width
     const int RS = R * SF;
+    if (wbl) {
+        // Blocked dw [K/32][C/4][R][S][4][32]: the 32 output channels of a block are the contiguous index, but an
+        // accumulator row (32 lanes) holds 32 columns of ONE output channel, 128 bytes or more apart.  Each wave
+        // turns its blocks round through LDS (the stage buffers, free now) so that 32 lanes hold the 32 output
+        // channels of one column: an atomic instruction then covers two 128-byte lines instead of 32.
+        static_assert(2 * G::BUF >= G::NW * 32 * 33, "the stage buffers hold one 32 x 33 tile per wave");
+        wait_vmem_done();    // (the loads issued for a chunk past the end write zeros into the stage buffers)
+        __syncthreads();     // every wave has left the chunk loop
+        float *tb = lds + wave * (32 * 33);
+        const int k = k0 + wk * 32 + j;
+#pragma unroll
+        for (int b = 0; b < G::NBLK; ++b) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) tb[(8 * (v >> 2) + 4 * h + (v & 3)) * 33 + j] = acc[b][v];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int jc = 2 * i + h;                       // column of the block this lane handles now
+                const float val = tb[j * 33 + jc];              // (the wave's LDS operations complete in order)
+                int c, tap;
+                bool ok;
+                if (G::AR) {
+                    constexpr int SS = G::SB * G::NR;
+                    const int col = (wb + G::WB * b) * 32 + jc;
+                    c = c0 + wc * 32 * G::CBW + col / SS;       // (packed first layers: c0 = wc = 0)
+                    tap = col % SS;
+                    ok = col < G::NCOLB * 32 && (G::PACK ? col < C * SS : c < C);
+                } else {
+                    const int col = b * 32 + jc;
+                    c = G::PACK ? col / G::SB : c0 + (wc * G::CBW + b / G::SB) * 32 + jc;
+                    tap = r * SF + (G::PACK ? col % G::SB : G::RT ? s0 : b % G::SB);
+                    ok = c < C;
+                }
+                if (k < K && ok) {
+                    float *d = dwp + dw_blocked_index(k, c, tap, C, RS);
+                    if (splits == 1) *d = val;
+                    else unsafeAtomicAdd(d, val);
+                }
+            }
+        }
+        return;
+    }
     if constexpr (G::AR != 0) {
         // column b*32 + j is float b*32 + j of the run dw[k][c0 .. c0 + CT)[.][.]
 #pragma unroll

@@ -7,9 +7,11 @@
 namespace convd {
 
 struct WgradArgs {
-    const float *x;     // [N][C][H][W]
-    const float *dy;    // [N][K][P][Q]
-    float *dw;          // [K][C][R][S], cleared before the launch, added to atomically
+    const float *x;     // [N][C][H][W], or blocked [N][C/4][H][W][4]
+    const float *dy;    // [N][K][P][Q], or blocked [N][K/4][P][Q][4]
+    float *dw;          // [K][C][R][S], or blocked [K/32][C/4][R][S][4][32]; cleared before the launch and added to atomically
+                        // (one split: stored plainly; blocked: still cleared, for the spare channels of its blocks)
+    int x_blocked, dy_blocked, dw_blocked;
     Shape s;
     int ktiles, cgroups, splits;   // grid = splits * ktiles * R * cgroups workgroups (all-rows variants: without R)
 };

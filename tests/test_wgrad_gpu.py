@@ -211,3 +211,86 @@ def test_deterministic_plan_same_bits_every_run(oracle, shape):
     assert np.array_equal(runs[0], runs[1]) and np.array_equal(runs[0], runs[2])
     err = np.abs(runs[0].astype(np.float64) - oracle.conv_wgrad(x, dy, R, S, st, pd)).max()
     assert err <= 1e-4 * np.sqrt(N * P * Q), err
+
+
+# ---- blocked layouts (x [N][C/4][H][W][4], dy [N][K/4][P][Q][4], dw [K/32][C/4][R][S][4][32]) ----
+FALLBACK_SHAPES = [(2, 9, 21, 30, 40, 3, 4, 1, 1), (2, 70, 17, 19, 33, 2, 2, 2, 0), (1, 5, 30, 41, 8, 4, 6, 3, 2), (2, 6, 33, 37, 9, 3, 3, 4, 1)]
+BLOCKED_SHAPES = sorted(set(SMALL) | {s for s, _ in ALL_ROWS_CASES} | set(FALLBACK_SHAPES))
+B, PL = cd.BLOCKED, cd.PLAIN
+
+
+def _spare_nan(a, channels):
+    """The spare channels that complete the last pencil of a blocked activation tensor, set to NaN."""
+    a = a.copy()
+    if channels % 4:
+        a[:, -1, :, :, channels % 4:] = np.nan
+    return a
+
+
+@pytest.mark.parametrize("shape", BLOCKED_SHAPES)
+def test_blocked_layouts_every_variant_that_serves_the_shape(oracle, shape):
+    """Integer inputs, bit-exact against the layout oracle, for the planner's choice in several layout mixes (also the
+    one-workgroup-per-tile plan) and for EVERY compiled variant that accepts the shape, all tensors blocked.  The spare
+    channels of x's and dy's last pencils hold NaN: they may only meet results that are dropped; those of dw must
+    come back as zeros."""
+    from oracle import layout_ref as L
+    N, C, H, W, K, R, S, st, pd = shape
+    rng = np.random.default_rng(1400 + sum(shape))
+    x = rng.integers(-2, 3, (N, C, H, W)).astype(np.float32)
+    P, Q = oracle.out_dim(H, R, st, pd), oracle.out_dim(W, S, st, pd)
+    dy = rng.integers(-2, 3, (N, K, P, Q)).astype(np.float32)
+    want = oracle.conv_wgrad(x, dy, R, S, st, pd)
+    xb, dyb = L.pack_activations(x, 4), L.pack_activations(dy, 4)
+    wantb = L.conv_wgrad_blocked(xb, dyb, C, K, R, S, st, pd, cb=4, kb=32)
+    assert np.array_equal(wantb, L.pack_weights(want, 4, 32))
+    dev = {PL: (torch.from_numpy(x).cuda(), torch.from_numpy(dy).cuda()),
+           B: (torch.from_numpy(_spare_nan(xb, C)).cuda(), torch.from_numpy(_spare_nan(dyb, K)).cuda())}
+    cases = [(None, False, lay) for lay in ((B, B, B), (B, B, PL), (PL, B, B), (B, PL, PL), (PL, PL, B))]
+    cases += [(None, True, (B, B, B))] + [(v, False, (B, B, B)) for v in cd.wgrad_variant_names()]
+    ran = 0
+    for variant, det, (xl, yl, wl) in cases:
+        try:
+            plan = cd.Plan.wgrad(*shape, variant=variant, deterministic=det, x_layout=xl, dy_layout=yl, dw_layout=wl)
+        except cd.ConvDirectError as e:
+            assert variant is not None and e.code == cd.EUNSUPPORTED, (variant, e.code)
+            continue
+        info = plan.info()
+        assert (info["x_layout"], info["dy_layout"], info["dw_layout"]) == tuple("blocked" if v == B else "plain" for v in (xl, yl, wl))
+        dw = torch.full(wantb.shape if wl == B else want.shape, float("nan"), device="cuda")
+        plan.run_wgrad(dev[xl][0], dev[yl][1], dw)
+        torch.cuda.synchronize()
+        plan.destroy()
+        assert np.array_equal(dw.cpu().numpy().astype(np.float64), wantb if wl == B else want), (info["variant"], det, xl, yl, wl)
+        ran += 1
+    assert ran >= 7
+
+
+@pytest.mark.parametrize("name", [l.name for l in workloads.ALL_LAYERS if l.N >= 32])
+def test_blocked_layouts_benchmark_layers_full_size_sampled(oracle, name):
+    """Full-size layers with dy and dw blocked, x blocked unless it is a first layer's image (3 channels, kept
+    plain as the forward pass keeps it): a sample of dw's output channels in full against the oracle."""
+    from oracle import layout_ref as L
+    l = workloads.BY_NAME[name]
+    x, _ = workloads.make_inputs(l)
+    rng = np.random.default_rng(14)
+    dy = rng.uniform(-1, 1, (l.N, l.K, l.P, l.Q)).astype(np.float32)
+    xl = PL if l.C < 4 else B
+    plan = cd.Plan.wgrad(*l.dims(), x_layout=xl, dy_layout=B, dw_layout=B)
+    xd = torch.from_numpy(x).cuda()
+    if xl == B:
+        xp = torch.empty((l.N, -(-l.C // 4), l.H, l.W, 4), device="cuda")
+        cd.pack_act(xd, xp)
+        xd = xp
+    dyb = torch.empty((l.N, -(-l.K // 4), l.P, l.Q, 4), device="cuda")
+    cd.pack_act(torch.from_numpy(dy).cuda(), dyb)
+    dwb = torch.full((-(-l.K // 32), -(-l.C // 4), l.R, l.S, 4, 32), float("nan"), device="cuda")
+    plan.run_wgrad(xd, dyb, dwb)
+    torch.cuda.synchronize()
+    info = plan.info()
+    plan.destroy()
+    got = L.unpack_weights(dwb.cpu().numpy(), l.K, l.C)
+    assert not np.isnan(got).any()
+    ks = sorted({0, l.K - 1, int(rng.integers(0, l.K))})
+    want = oracle.conv_wgrad(x, np.ascontiguousarray(dy[:, ks]), l.R, l.S, l.stride, l.pad)
+    err = np.abs(got[ks].astype(np.float64) - want).max()
+    assert err <= 1e-4 * np.sqrt(l.N * l.P * l.Q), (info["variant"], err)
