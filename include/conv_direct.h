@@ -233,6 +233,11 @@ int conv_direct_create_dgrad(conv_direct_plan **plan,
 int conv_direct_create_dgrad_layout(conv_direct_plan **plan,
                                     int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                                     int dy_layout, int dx_layout);   /* CONV_DIRECT_LAYOUT_* */
+/* Testing / tuning aid: the same with the kernel variant forced (NULL: the planner's choice); CONV_DIRECT_EUNSUPPORTED
+ * if that variant cannot run the data gradient of this layer. */
+int conv_direct_create_dgrad_ex(conv_direct_plan **plan, const char *variant,
+                                int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                int dy_layout, int dx_layout);
 int conv_direct_dgrad_filter(const float *w, float *wt, int K, int C, int R, int S, void *stream);
 size_t conv_direct_dgrad_wt_elems(const conv_direct_plan *plan);   /* 0 for a plan that is no data gradient */
 int conv_direct_dgrad_prepare(const conv_direct_plan *plan, const float *w, float *wt, void *stream);

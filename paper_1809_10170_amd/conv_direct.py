@@ -92,6 +92,8 @@ def lib():
         l.conv_direct_create_dgrad.restype = i
         l.conv_direct_create_dgrad_layout.argtypes = [pp] + [i] * 11
         l.conv_direct_create_dgrad_layout.restype = i
+        l.conv_direct_create_dgrad_ex.argtypes = [pp, cp] + [i] * 11
+        l.conv_direct_create_dgrad_ex.restype = i
         l.conv_direct_dgrad_wt_elems.argtypes = [vp]
         l.conv_direct_dgrad_wt_elems.restype = ctypes.c_size_t
         l.conv_direct_dgrad_prepare.argtypes = [vp, vp, vp, vp]
@@ -169,15 +171,15 @@ class Plan:
         return self
 
     @classmethod
-    def dgrad(cls, N, C, H, W, K, R, S, stride, pad, dy_layout: int = PLAIN, dx_layout: int = PLAIN):
+    def dgrad(cls, N, C, H, W, K, R, S, stride, pad, dy_layout: int = PLAIN, dx_layout: int = PLAIN, variant: str | None = None):
         """Plan of the data gradient of the forward layer (N, C, H, W, K, R, S, stride, pad):
         run(dy [N,K,P,Q], wt from dgrad_prepare (dgrad_wt_elems() floats), dx [N,C,H,W]); dy and dx plain or in
         the blocked activation layout ([N, ceil(K/4), P, Q, 4], [N, ceil(C/4), H, W, 4])."""
         self = cls.__new__(cls)
         self._p = ctypes.c_void_p()
         self.in_layout, self.out_layout = int(dy_layout), int(dx_layout)
-        rc = lib().conv_direct_create_dgrad_layout(ctypes.byref(self._p), *[int(v) for v in (N, C, H, W, K, R, S, stride, pad)],
-                                                   int(dy_layout), int(dx_layout))
+        rc = lib().conv_direct_create_dgrad_ex(ctypes.byref(self._p), variant.encode() if variant else None,
+                                               *[int(v) for v in (N, C, H, W, K, R, S, stride, pad)], int(dy_layout), int(dx_layout))
         if rc != OK:
             self._p = ctypes.c_void_p()
             raise ConvDirectError(rc, "conv_direct_create_dgrad")

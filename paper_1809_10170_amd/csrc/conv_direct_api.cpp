@@ -118,7 +118,8 @@ void fill(conv_direct_plan *p, const Shape &s, const Variant &v)
 {
     p->s = s;
     p->v = &v;
-    p->ktiles = cdiv(s.K, v.KT);
+    // (merged phases: the eight k-waves of a workgroup are four phases of two 32-channel blocks)
+    p->ktiles = v.merged ? cdiv(s.K, 64) : cdiv(s.K, v.KT);
     p->pw_flat = pointwise_flat(v, s) ? 1 : 0;
     if (p->pw_flat) {
         p->tilesP = 1;
@@ -175,13 +176,16 @@ double cost(const conv_direct_plan &p)
     const Variant &v = *p.v;
     const Shape &s = p.s;
     const int wpw = v.threads / 64;                                // waves per workgroup
-    const int64_t grid = (int64_t)p.grid * (p.ph_stride ? p.ph_stride * p.ph_stride : 1);   // (at most: phases without a tap are not launched)   // (a data gradient's phases: one launch)
+    // (a data gradient's phases: one launch; at most so many: phases without a tap are not launched; merged: the phases
+    // are waves of one workgroup)
+    const int64_t grid = (int64_t)p.grid * ((p.ph_stride && !v.merged) ? p.ph_stride * p.ph_stride : 1);
     const double useful = (double)s.N * s.K * s.P * s.Q * ((double)s.C * s.R * s.S);
     const double mfma_per_wave = useful / p.mfma_efficiency / p.grid / wpw / 2048.0;   // 32*32*2 MACs each
     auto round_time = [&](int wgs_per_cu) {
         const int waves_per_simd = cdiv(wgs_per_cu * wpw, 4);      // the busiest SIMD
         const double eff = waves_per_simd >= 2 ? 0.96 : 0.80;
-        return mfma_per_wave * 64.0 * waves_per_simd / eff;
+        // (merged phases: the padded count has 4 taps per wave; the busiest SIMD runs a four-tap and a one-tap wave)
+        return mfma_per_wave * (v.merged ? 0.625 : 1.0) * 64.0 * waves_per_simd / eff;
     };
     int occ = v.occupancy;
     const int lds_fit = (int)(kLdsPerCU / (p.lds_bytes ? p.lds_bytes : 1));
@@ -276,6 +280,7 @@ int make_plan(conv_direct_plan **plan, const char *forced, int N, int C, int H, 
         if (forced && std::strcmp(forced, v.name) != 0) continue;
         if (!applicable(v, s, in_blocked, out_blocked)) continue;
         if (pair_family_only && (v.pair != convd::PAIR_C || v.pointwise || v.R == 0)) continue;
+        if (v.merged && phase_stride != 2) continue;   // (serves only the four phases of a stride-2 layer's data gradient)
         conv_direct_plan cand{};
         fill(&cand, s, v);
         cand.in_blocked = in_blocked;
@@ -358,8 +363,15 @@ int conv_direct_run_fused(const conv_direct_plan *plan, const float *in, const f
         if (bias || residual || relu) return CONV_DIRECT_EINVAL;
         const int st = plan->ph_stride, RT = plan->s.R;
         const int KO = plan->out_blocked ? (plan->s.K + 3) / 4 * 4 : plan->s.K;   // channels an image of dx occupies
-        hipError_t e = convd::launch_fill_zero(out, (long long)plan->s.N * KO * plan->ph_H * plan->ph_W, (hipStream_t)stream);
         const int nb = st < plan->fwd_R ? st : plan->fwd_R;   // phases per dimension that have a tap
+        // Position h of dx belongs to phase (h + pad) % st, result row (h + pad) / st.  When every phase is launched and
+        // the phases' result rows and columns (plan->s.P x plan->s.Q of them) reach the last position, every element of dx
+        // is stored by exactly one phase and there is nothing to clear (blocked dx: the spare channels of a last pencil
+        // are stored as zeros with their pencil).
+        const bool covered = nb == st && (plan->ph_H - 1 + plan->ph_pad) / st <= plan->s.P - 1 &&
+                             (plan->ph_W - 1 + plan->ph_pad) / st <= plan->s.Q - 1;
+        hipError_t e = covered ? hipSuccess
+                               : convd::launch_fill_zero(out, (long long)plan->s.N * KO * plan->ph_H * plan->ph_W, (hipStream_t)stream);
         a.ost = st;                                       // (the channel-pair kernels' output re-mapping, see KernelArgs)
         a.onb = nb;
         a.OH = plan->ph_H;
@@ -367,7 +379,7 @@ int conv_direct_run_fused(const conv_direct_plan *plan, const float *in, const f
         a.ooh = a.oow = -plan->ph_pad;
         a.ofr = plan->fwd_R;
         (void)RT;
-        if (e == hipSuccess) e = plan->v->launch(a, plan->grid * (unsigned)(nb * nb), (hipStream_t)stream);
+        if (e == hipSuccess) e = plan->v->launch(a, plan->v->merged ? plan->grid : plan->grid * (unsigned)(nb * nb), (hipStream_t)stream);
         return launched(e);
     }
     const hipError_t e = plan->v->launch(a, plan->grid, (hipStream_t)stream);
@@ -415,7 +427,7 @@ int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
                          "threads=%d lds_bytes=%zu occupancy=%d flat=%d pointwise=%d mfma_efficiency=%.6g in_layout=%s "
                          "out_layout=%s dgrad_phases=%d extra_caller_bytes=%zu workspace_bytes=0",
                          v.name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, v.TP, v.TQ,
-                         v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : v.pair == convd::PAIR_R ? "r" : "t", plan->tilesP,
+                         v.merged ? 64 : v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : v.pair == convd::PAIR_R ? "r" : "t", plan->tilesP,
                          plan->tilesQ, plan->ktiles, plan->grid, v.threads, plan->lds_bytes, v.occupancy,
                          (v.img != 0 || plan->pw_flat) ? 1 : 0, v.pointwise, plan->mfma_efficiency, plan->in_blocked ? "blocked" : "plain",
                          plan->out_blocked ? "blocked" : "plain",
@@ -711,6 +723,12 @@ int conv_direct_create_dgrad(conv_direct_plan **plan, int N, int C, int H, int W
 int conv_direct_create_dgrad_layout(conv_direct_plan **plan, int N, int C, int H, int W, int K, int R, int S, int stride,
                                     int pad, int dy_layout, int dx_layout)
 {
+    return conv_direct_create_dgrad_ex(plan, nullptr, N, C, H, W, K, R, S, stride, pad, dy_layout, dx_layout);
+}
+
+int conv_direct_create_dgrad_ex(conv_direct_plan **plan, const char *variant, int N, int C, int H, int W, int K, int R, int S,
+                                int stride, int pad, int dy_layout, int dx_layout)
+{
     if (!plan) return CONV_DIRECT_EINVAL;
     *plan = nullptr;
     if ((dy_layout != CONV_DIRECT_LAYOUT_PLAIN && dy_layout != CONV_DIRECT_LAYOUT_BLOCKED) ||
@@ -722,7 +740,7 @@ int conv_direct_create_dgrad_layout(conv_direct_plan **plan, int N, int C, int H
     if (rc != CONV_DIRECT_OK) return rc;
     if (stride == 1 && R == S && pad <= R - 1) {
         // the forward problem that computes dx: input dy [N][K][P][Q], C output channels
-        const int rc1 = make_plan(plan, nullptr, N, K, fwd.P, fwd.Q, C, R, S, 1, R - 1 - pad, dyb, dxb);
+        const int rc1 = make_plan(plan, variant, N, K, fwd.P, fwd.Q, C, R, S, 1, R - 1 - pad, dyb, dxb);
         if (rc1 == CONV_DIRECT_OK) {
             (*plan)->fwd_K = K;  (*plan)->fwd_C = C;  (*plan)->fwd_R = R;  (*plan)->fwd_S = S;
             return rc1;
@@ -739,7 +757,7 @@ int conv_direct_create_dgrad_layout(conv_direct_plan **plan, int N, int C, int H
         // which store with that re-mapping; no workspace.
         const int RT = cdiv(R, stride);
         conv_direct_plan *sub = nullptr;
-        if (make_plan(&sub, nullptr, N, K, fwd.P, fwd.Q, C, RT, RT, 1, RT - 1, dyb, dxb, true, stride) == CONV_DIRECT_OK) {
+        if (make_plan(&sub, variant, N, K, fwd.P, fwd.Q, C, RT, RT, 1, RT - 1, dyb, dxb, true, stride) == CONV_DIRECT_OK) {
             sub->ph_stride = stride;
             sub->ph_pad = pad;
             sub->ph_H = H;
@@ -757,7 +775,7 @@ int conv_direct_create_dgrad_layout(conv_direct_plan **plan, int N, int C, int H
     const Variant *generic = nullptr;
     for (int i = 0; i < count; ++i)
         if (table[i]->R == 0) generic = table[i];
-    if (!generic) return CONV_DIRECT_EUNSUPPORTED;
+    if (!generic || (variant && std::strcmp(variant, generic->name) != 0)) return CONV_DIRECT_EUNSUPPORTED;
     if ((int64_t)N * K * fwd.P * fwd.Q >= kMaxElems) return CONV_DIRECT_EUNSUPPORTED;
     Shape s{N, K, fwd.P, fwd.Q, C, R, S, 1, 0, H, W};   // in = dy, K' = C, P' x Q' = H x W
     if (generic->lds_bytes(s) > kLdsPerCU) return CONV_DIRECT_EUNSUPPORTED;

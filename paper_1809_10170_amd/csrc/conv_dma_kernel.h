@@ -348,16 +348,27 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
     }
     // output re-mapping: the phases are one more grid dimension, fastest, so that the workgroups that read the same
     // tile of the input run side by side; phase ph has a filter of its own and its own offsets
+    // Merged phases (eight k-waves, stride 2: four phases): a workgroup runs ALL phases of its pixel tile for two blocks
+    // of 32 output channels, one (phase, block) per wave, so that the input window is staged once for the four phases
+    // (as separate workgroups the phases with one or two taps are bound by their staging).  Waves 0..3 take phases
+    // 0..3 of the first block, waves 4..7 phases 3..0 of the second: the SIMD that has the four-tap phase of one block
+    // has the one-tap phase of the other.
+    constexpr bool MERGED = REMAP && G::WK == 8;
     int ph = 0;
-    if constexpr (REMAP) {
+    if constexpr (REMAP && !MERGED) {
         const unsigned nb = (unsigned)a.onb, nph = nb * nb;      // phases per dimension that have a tap at all
         ph = (int)(bid % nph);
         bid /= nph;
     }
-    // the filter of this workgroup (blocked weights: whole blocks of 32 output channels and pencils of 4 input channels)
-    const float *const wp_ = a.w + (REMAP ? (size_t)ph * (G::BLK ? (size_t)((K + 31) / 32 * 32) * CI : (size_t)K * C) * G::RS : 0);
     const int kt = bid % a.ktiles;  bid /= a.ktiles;
     const int k0 = kt * G::KT;
+    int kwv = k0 + wk * 32;                          // first output channel of this wave
+    if constexpr (MERGED) {
+        ph = (wk & 4) ? 3 - (wk & 3) : (wk & 3);
+        kwv = (2 * kt + (wk >> 2)) * 32;
+    }
+    // the filter of this wave's phase (blocked weights: whole blocks of 32 output channels and pencils of 4 input channels)
+    const float *const wp_ = a.w + (REMAP ? (size_t)ph * (G::BLK ? (size_t)((K + 31) / 32 * 32) * CI : (size_t)K * C) * G::RS : 0);
     // rectangular: image n, tile origin (p0, q0).  flat: first pixel m0 of M, which
     // lies in output row g0 (rows of all images numbered through) of image n
     int n, p0 = 0, q0 = 0, m0 = 0, g0 = 0, M = 0;
@@ -437,7 +448,7 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
 
     // Filter values of this lane: output channel k0 + wk*32 + j (clamped: rows past K
     // are computed and discarded), input channels c0 + h*HC .. + HC, all taps.
-    int krow = k0 + wk * 32 + j;
+    int krow = kwv + j;
     krow = krow < K ? krow : K - 1;
     const float *w_lane = wp_ + ((size_t)krow * C + h * G::HC) * G::RS;
     const long long w_total = (long long)K * C * G::RS;
@@ -447,7 +458,7 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
     // [R][S][4][32] block of (kb, c0/4): a per-lane constant plus a compile-time offset
     const unsigned wb_lane = (unsigned)((2 * h * 32 + j) * 4);
     // (a wave whose 32 channels all lie past K reads the last block that exists; its results are discarded)
-    const int kblk = (k0 + wk * 32) / 32 < (K + 31) / 32 ? (k0 + wk * 32) / 32 : (K + 31) / 32 - 1;
+    const int kblk = kwv / 32 < (K + 31) / 32 ? kwv / 32 : (K + 31) / 32 - 1;
     const float *wb_row = wp_ + (size_t)kblk * (CI / 4) * (G::RS * 128);
     auto load_a = [&](float (&dst)[G::NA], int c0) {
         if constexpr (G::BLK != 0) {
@@ -695,7 +706,7 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[pb][v] = __builtin_nanf("");
         }
-        const int kw = k0 + wk * 32;
+        const int kw = kwv;
         const int KO = a.out_blocked ? (K + 3) / 4 * 4 : K;      // channels an output image occupies
         // output re-mapping, see KernelArgs
         const int ost = REMAP ? a.ost : 0, nb = REMAP ? a.onb : 1, OH = REMAP ? a.OH : 0, OW = REMAP ? a.OW : 0;
@@ -821,7 +832,7 @@ template <class G>
 constexpr Variant make_dma_variant(const char *name)
 {
     return Variant{name, G::R, G::S, G::ST, G::TP, G::FLAT ? 0 : G::TQ, G::KT, G::NPB, G::CB, G::PAIR, G::NT, G::OCC,
-                   G::CHF / G::CB, G::IMG, G::PADC, &lds_dma<G>, &launch_dma<G>, 0, G::BLK};
+                   G::CHF / G::CB, G::IMG, G::PADC, &lds_dma<G>, &launch_dma<G>, 0, G::BLK, (G::WK == 8 && G::ST == 1 && G::R <= 4) ? 1 : 0};
 }
 
 }  // namespace convd

@@ -61,6 +61,8 @@ struct Variant {
                           // ALL images numbered through (for images that are not a multiple of the tile)
     int in_blocked;       // 1: input and weights in the blocked layouts (paper, Section 4): in [N][C/4][H][W][4],
                           // w [K/32][C/4][R][S][4][32]
+    int merged;           // 1: eight k-waves; serves only the data gradient of a stride-2 layer, all four phases of a
+                          // pixel tile in one workgroup (a workgroup then covers 64 output channels, not KT)
 };
 
 // The compiled variants (host table of pointers; lives beside the fallback kernel).

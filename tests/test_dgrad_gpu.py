@@ -133,7 +133,8 @@ def test_benchmark_layers_full_size_sampled(oracle, name):
 
 
 def test_strided_benchmark_layer_full_size_whole_images(oracle):
-    """The 3x3 stride-2 layer of the suite at full size (four 2x2 phase convolutions on the flat tiling):
+    """The 3x3 stride-2 layer of the suite at full size (four 2x2 phase convolutions, merged into the waves of one
+    workgroup per tile, on the flat tiling):
     three whole images of dx against the oracle's adjoint (images are independent)."""
     l = workloads.BY_NAME["s2_c128_56_k256_3x3_n64"]
     _, w = workloads.make_inputs(l)
@@ -141,7 +142,7 @@ def test_strided_benchmark_layer_full_size_whole_images(oracle):
     dy = rng.uniform(-1, 1, (l.N, l.K, l.P, l.Q)).astype(np.float32)
     plan = cd.Plan.dgrad(*l.dims())
     info = plan.info()
-    assert info["dgrad_phases"] == 4 and info["variant"].startswith("d2s1_flat28_k128") and plan.workspace_bytes() == 0
+    assert info["dgrad_phases"] == 4 and info["variant"].startswith("d2s1_flat28_k64m") and plan.workspace_bytes() == 0
     wt = torch.empty((plan.dgrad_wt_elems(),), device="cuda")
     plan.dgrad_prepare(torch.from_numpy(w).cuda(), wt)
     dx = torch.full((l.N, l.C, l.H, l.W), float("nan"), device="cuda")
@@ -216,3 +217,50 @@ def test_blocked_layouts_strided_benchmark_layer_full_size(oracle):
         want = L.conv_dgrad_blocked(L.pack_activations(np.ascontiguousarray(dy[n:n + 1]), 4), w, l.H, l.W, l.stride, l.pad)
         err = np.abs(dxb[n:n + 1].cpu().numpy().astype(np.float64) - want).max()
         assert err <= oracle.tolerance(l.K, l.R, l.S), err
+
+
+MERGED_CASES = [
+    # all four phases of a stride-2 layer in one workgroup (eight waves = phase x two blocks of 32 channels), forced
+    ((2, 40, 29, 29, 70, 3, 3, 2, 1), "d2s1_8x28_k64m"),        # second channel block with 8 channels, ragged chunks
+    ((2, 9, 30, 33, 12, 4, 4, 2, 1), "d2s1_8x28_k64m"),         # 4x4: every phase has all four taps; no second block
+    ((3, 100, 20, 24, 33, 3, 3, 2, 1), "d2s1_8x28_k64m"),       # two channel tiles, the second with one block and a bit
+    ((2, 6, 21, 20, 8, 3, 3, 2, 0), "d2s1_8x28_k64m"),          # trailing rows no window reaches: dx is cleared first
+    ((3, 16, 56, 56, 33, 3, 3, 2, 1), "d2s1_flat28_k64m_b7"),
+    ((2, 70, 56, 56, 40, 4, 4, 2, 1), "d2s1_flat28_k64m_b7"),
+    ((16, 64, 28, 28, 70, 3, 3, 2, 1), "d2s1_flat14_k64m_b7"),
+    ((5, 130, 28, 28, 24, 3, 3, 2, 1), "d2s1_flat14_k64m_b7"),
+    ((16, 64, 14, 14, 70, 3, 3, 2, 1), "d2s1_flat7_k64m_b4"),
+]
+
+
+def test_every_merged_phase_variant_has_a_case():
+    names = {n for n in cd.variant_names() if n.endswith("m") or "k64m_" in n}
+    assert names and names == {v for _, v in MERGED_CASES}
+
+
+@pytest.mark.parametrize("shape,variant", MERGED_CASES)
+def test_merged_phase_variants_integer_inputs_bit_exact(oracle, shape, variant):
+    N, C, H, W, K, R, S, st, pd = shape
+    rng = np.random.default_rng(670 + sum(shape))
+    w = rng.integers(-4, 5, (K, C, R, S)).astype(np.float32)
+    P, Q = oracle.out_dim(H, R, st, pd), oracle.out_dim(W, S, st, pd)
+    dy = rng.integers(-4, 5, (N, K, P, Q)).astype(np.float32)
+    plan = cd.Plan.dgrad(*shape, variant=variant)
+    info = plan.info()
+    assert info["variant"] == variant and info["dgrad_phases"] == 4 and plan.output_dims() == (H, W)
+    wt = torch.full((plan.dgrad_wt_elems(),), float("nan"), device="cuda")
+    plan.dgrad_prepare(torch.from_numpy(w).cuda(), wt)
+    dx = torch.full((N, C, H, W), float("nan"), device="cuda")
+    plan.run(torch.from_numpy(dy).cuda(), wt, dx)
+    torch.cuda.synchronize()
+    plan.destroy()
+    assert np.array_equal(dx.cpu().numpy().astype(np.float64), oracle.conv_dgrad(dy, w, H, W, st, pd))
+
+
+def test_a_merged_phase_variant_serves_only_stride_two():
+    with pytest.raises(cd.ConvDirectError) as e:
+        cd.Plan.dgrad(1, 5, 25, 26, 7, 5, 5, 3, 2, variant="d2s1_8x28_k64m")     # stride 3: nine phases
+    assert e.value.code == cd.EUNSUPPORTED
+    with pytest.raises(cd.ConvDirectError) as e:
+        cd.Plan(2, 16, 20, 20, 32, 2, 2, 1, 0, variant="d2s1_8x28_k64m")          # a forward layer
+    assert e.value.code == cd.EUNSUPPORTED
