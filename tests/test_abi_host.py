@@ -139,10 +139,11 @@ def test_every_variant_plans_a_matching_shape():
         blocked = nm.startswith("b")               # variants for the blocked input / weight layouts
         if "k64m" in nm:
             # all phases of a stride-2 layer's data gradient in one workgroup: serves that, and no forward layer
+            lay = cd.BLOCKED if blocked else cd.PLAIN
             with pytest.raises(cd.ConvDirectError) as e:
-                cd.Plan(2, C, H, W, 70, R, R, st, R // 2, variant=nm)
+                cd.Plan(2, C, H, W, 70, R, R, st, R // 2, variant=nm, in_layout=lay, out_layout=lay)
             assert e.value.code == cd.EUNSUPPORTED
-            plan = cd.Plan.dgrad(2, 70, 2 * H, 2 * W, C, 3, 3, 2, 1, variant=nm)   # (dy is H x W)
+            plan = cd.Plan.dgrad(2, 70, 2 * H, 2 * W, C, 3, 3, 2, 1, variant=nm, dy_layout=lay, dx_layout=lay)   # (dy is H x W)
             info = plan.info()
             assert info["variant"] == nm and info["dgrad_phases"] == 4 and info["ktiles"] == 2
             _check_cover(info, exhaustive=True)

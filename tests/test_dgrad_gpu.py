@@ -203,7 +203,7 @@ def test_blocked_layouts_strided_benchmark_layer_full_size(oracle):
     dy = rng.uniform(-1, 1, (l.N, l.K, l.P, l.Q)).astype(np.float32)
     plan = cd.Plan.dgrad(*l.dims(), dy_layout=cd.BLOCKED, dx_layout=cd.BLOCKED)
     info = plan.info()
-    assert info["dgrad_phases"] == 4 and info["variant"].startswith("b2s1_flat28_k128") and plan.workspace_bytes() == 0
+    assert info["dgrad_phases"] == 4 and info["variant"].startswith("b2s1_flat28_k64m") and plan.workspace_bytes() == 0
     wt = torch.empty((plan.dgrad_wt_elems(),), device="cuda")
     plan.dgrad_prepare(torch.from_numpy(w).cuda(), wt)
     dyb = torch.empty((l.N, l.K // 4, l.P, l.Q, 4), device="cuda")
@@ -230,6 +230,9 @@ MERGED_CASES = [
     ((16, 64, 28, 28, 70, 3, 3, 2, 1), "d2s1_flat14_k64m_b7"),
     ((5, 130, 28, 28, 24, 3, 3, 2, 1), "d2s1_flat14_k64m_b7"),
     ((16, 64, 14, 14, 70, 3, 3, 2, 1), "d2s1_flat7_k64m_b4"),
+    ((2, 40, 29, 29, 70, 3, 3, 2, 1), "b2s1_8x28_k64m"),        # blocked dy and dx (the padded taps are multiplied too)
+    ((3, 100, 20, 24, 33, 4, 4, 2, 1), "b2s1_8x28_k64m"),
+    ((3, 16, 56, 56, 33, 3, 3, 2, 1), "b2s1_flat28_k64m_b7"),
 ]
 
 
@@ -245,16 +248,22 @@ def test_merged_phase_variants_integer_inputs_bit_exact(oracle, shape, variant):
     w = rng.integers(-4, 5, (K, C, R, S)).astype(np.float32)
     P, Q = oracle.out_dim(H, R, st, pd), oracle.out_dim(W, S, st, pd)
     dy = rng.integers(-4, 5, (N, K, P, Q)).astype(np.float32)
-    plan = cd.Plan.dgrad(*shape, variant=variant)
+    blocked = variant.startswith("b")
+    lay = cd.BLOCKED if blocked else cd.PLAIN
+    plan = cd.Plan.dgrad(*shape, variant=variant, dy_layout=lay, dx_layout=lay)
     info = plan.info()
     assert info["variant"] == variant and info["dgrad_phases"] == 4 and plan.output_dims() == (H, W)
     wt = torch.full((plan.dgrad_wt_elems(),), float("nan"), device="cuda")
     plan.dgrad_prepare(torch.from_numpy(w).cuda(), wt)
-    dx = torch.full((N, C, H, W), float("nan"), device="cuda")
+    want = oracle.conv_dgrad(dy, w, H, W, st, pd)
+    if blocked:
+        from oracle import layout_ref as L
+        dy, want = L.pack_activations(dy, 4), L.pack_activations(want, 4)
+    dx = torch.full(want.shape, float("nan"), device="cuda")
     plan.run(torch.from_numpy(dy).cuda(), wt, dx)
     torch.cuda.synchronize()
     plan.destroy()
-    assert np.array_equal(dx.cpu().numpy().astype(np.float64), oracle.conv_dgrad(dy, w, H, W, st, pd))
+    assert np.array_equal(dx.cpu().numpy().astype(np.float64), want)
 
 
 def test_a_merged_phase_variant_serves_only_stride_two():
