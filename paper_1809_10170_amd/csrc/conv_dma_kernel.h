@@ -599,11 +599,13 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
         auto run = [&](auto skip_tag) __attribute__((always_inline)) {
             constexpr int SKR = decltype(skip_tag)::value / 2, SKC = decltype(skip_tag)::value % 2;
             constexpr int NRV = G::R - SKR, NSV = G::S - SKC;        // filter rows and columns in use
-            constexpr int NV = G::BLK ? G::STEPS : G::HC * NRV * NSV;   // reduction steps of a chunk
-            static_assert(!G::BLK || (SKR == 0 && SKC == 0), "the blocked layouts run whole filters");
+            constexpr int NV = G::BLK ? 2 * NRV * NSV : G::HC * NRV * NSV;   // reduction steps of a chunk
             // i-th step in use -> step of the full filter (which register of the chunk's filter values, which tap offset)
             auto vt = [](int i) {
-                if (G::BLK) return i;
+                if (G::BLK) {   // (a blocked chunk takes tap after tap, two channels of the lane's half per step)
+                    const int u = i / 2;
+                    return ((u / NSV + SKR) * G::S + u % NSV + SKC) * 2 + i % 2;
+                }
                 const int cc = i / (NRV * NSV), rem = i - cc * (NRV * NSV);
                 return cc * G::RS + (rem / NSV + SKR) * G::S + rem % NSV + SKC;
             };
@@ -652,15 +654,18 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
                 if (ci + 2 < nchl) chunk(ci + 2, b2, b0, b1, a2, a1);
             }
         };
-        if constexpr (REMAP && G::R > 1 && G::S > 1 && G::BLK == 0) {   // (the blocked variants multiply the padded taps too)
+        if constexpr (REMAP && G::R > 1 && G::S > 1) {
             // phase (pa, pb) of the input positions has ceil((ofr - pa) / ost) filter rows; the padded shape has R
             const int nbp = a.onb, pa = ph / nbp, pb_ = ph - pa * nbp;
             const int skr = G::R - (a.ofr - pa + a.ost - 1) / a.ost, skc = G::S - (a.ofr - pb_ + a.ost - 1) / a.ost;
             const int sk = __builtin_amdgcn_readfirstlane((skr > 0 ? 2 : 0) + (skc > 0 ? 1 : 0));
+            // (a blocked chunk has two steps per tap: a single tap is too short a chunk for the meeting protocol, so the
+            // 2 x 2 filter's one-tap phase leaves out its padded row only and multiplies one padded tap)
+            constexpr bool BOTH = !(G::BLK && (G::R - 1) * (G::S - 1) < 2);
             if (sk == 0) run(IntTag<0>{});
             else if (sk == 1) run(IntTag<1>{});
-            else if (sk == 2) run(IntTag<2>{});
-            else run(IntTag<3>{});
+            else if (sk == 2 || !BOTH) run(IntTag<2>{});
+            else run(IntTag<(BOTH ? 3 : 2)>{});
         } else {
             run(IntTag<0>{});
         }
