@@ -51,8 +51,16 @@ typedef float dma_f2u __attribute__((ext_vector_type(2), aligned(4)));
 //     touch, the rows of one image after those of the previous one.  No MFMA column
 //     is wasted on tile edges and the grid can be cut to fit the machine.
 template <int R_, int S_, int ST_, int TP_, int TQ_, int PBW_, int WK_, int WP_, int CB_, int OCC_, int IMG_ = 0,
-          int PADC_ = 0, int PF_ = 1, int SC_ = 1, int PBW2_ = 0, int BLK_ = 0>
+          int PADC_ = 0, int PF_ = 1, int SC_ = 1, int PBW2_ = 0, int BLK_ = 0, int SL_ = 0>
 struct DmaGeom {
+    // SL = 1 (flat tiling, eight pixel groups, one 32-channel block): the tile has 8*PBW + 1 blocks.  Pixel groups 0..3
+    // own PBW blocks each; groups 4..7 own PBW blocks each and SHARE the last block of the tile: group 4 + q adds to it
+    // only in the reduction steps t of a chunk with t % 4 == q, a quarter of the reduction in EVERY chunk (the waves of a
+    // workgroup meet once per chunk, so the extra work has to be even within a chunk), and the four partial sums meet
+    // through LDS at the end.  Wave w runs on SIMD w % 4, so every SIMD carries 2*PBW + 1/4 blocks: a layer whose blocks per SIMD
+    // are a whole number and a quarter (12.25 for 512 x 28 x 28 at batch 32: 13 with two unequal waves) fills the
+    // matrix pipes without idle columns, and its 16 x 16 tiles are exactly 256 workgroups.
+    static constexpr int SL = SL_;
     // BLK = 1: input and weights in the paper's blocked layouts (Section 4) with pencils of
     // 4 input channels and weight blocks of 4 input x 32 output channels:
     //   in [N][C/4][H][W][4]      w [K/32][C/4][R][S][4][32]
@@ -81,7 +89,7 @@ struct DmaGeom {
     static constexpr bool FLAT = IMG_ > 0;
     static constexpr int OQ = FLAT ? (IMG + 2 * PADC - S) / ST + 1 : 0;       // flat: output width
     static constexpr int OP = FLAT ? (IMG + 2 * PADC - R) / ST + 1 : 0;       // flat: output height
-    static constexpr int NPB = PBW2_ ? PBW_ + PBW2_ : PBW_ * WP_;              // 32-pixel blocks per workgroup
+    static constexpr int NPB = PBW2_ ? PBW_ + PBW2_ : PBW_ * WP_ + (SL_ ? 1 : 0);   // 32-pixel blocks per workgroup
     static constexpr int NPIXF = 32 * NPB;                                     // flat: pixels per workgroup
     static constexpr int NRMAX = FLAT ? (NPIXF + OQ - 2) / OQ + 1 : 0;         // flat: output rows a tile can touch
     static constexpr int NSI = FLAT ? (NRMAX + OP - 2) / OP + 1 : 1;           // flat: images a tile can touch
@@ -116,6 +124,7 @@ struct DmaGeom {
     static_assert(CB % 2 == 0, "channel pairing needs an even chunk");
     static_assert(!BLK || CB == 4, "blocked layout: a chunk is one block of 4 channels");
     static_assert(PBW2 == 0 || (FLAT && WP == 2 && SC == 1 && PBW2 < PBW), "unequal waves: flat tiling, two pixel groups");
+    static_assert(!SL || (FLAT && WP == 8 && WK == 1 && SC == 1 && PBW2 == 0), "shared last block: flat tiling, eight pixel groups of one k-block");
     static_assert(!FLAT || R >= ST, "flat tiling stacks image windows R - ST rows apart");
     static_assert(PF >= 1 && 2 * PF < STEPS, "operand fetches for the next chunk must follow the meeting point");
     static_assert(NPB * 32 >= NPIX, "pixel blocks must cover the tile");
@@ -500,13 +509,16 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
     // Everything below depends on how many pixel blocks the wave owns: PBW, or PBW2 for
     // the second pixel group of a variant with unequal waves (same protocol, same number
     // of chunks and meetings, fewer MFMAs per step).
-    auto body = [&](auto pbw_tag) __attribute__((always_inline)) {
+    auto body = [&](auto pbw_tag, auto sh_tag) __attribute__((always_inline)) {
         constexpr int PBW = decltype(pbw_tag)::value;
+        constexpr bool SH = decltype(sh_tag)::value != 0;   // the wave's last block is the tile's shared block (see SL)
+        constexpr int shq = SH ? decltype(sh_tag)::value - 1 : 0;   // ... to which it adds in the steps t with t % 4 == shq
         // per-lane LDS read offsets (floats): pixel position plus the kk half
         int bbase[PBW];
     #pragma unroll
         for (int pb = 0; pb < PBW; ++pb) {
-            const int t = (wp * G::PBW + pb) * 32 + j;   // (the first pixel group always owns G::PBW blocks)
+            // (the first pixel group always owns G::PBW blocks; a shared block is the tile's last)
+            const int t = ((SH && pb == PBW - 1) ? G::WP * G::PBW : wp * G::PBW + pb) * 32 + j;
             int pix;
             if constexpr (G::FLAT) {
                 int m = m0 + t;
@@ -613,7 +625,7 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
             constexpr int TX = TY * 3 / 5;
             static_assert(TX < TY && TY + G::PF <= NV && 2 * G::PF < NV, "arrive, check, then fetch the next chunk");
             auto chunk = [&](int i, const float *bufc, const float *bufn, float *bufnn, const float (&acr)[G::NA],
-                             float (&ann)[G::NA]) {
+                             float (&ann)[G::NA]) __attribute__((always_inline)) {
                 float ac[G::NA];
                 mask_a(ac, acr, chan0(i));
     #pragma unroll
@@ -630,14 +642,17 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
                     float bnew[PBW];
                     if (t + G::PF < NV) fetch(bufc, vt(t + G::PF), bnew);
                     else fetch(bufn, vt(t + G::PF - NV), bnew);   // past the last chunk: stale but in-bounds, never used
+                    const bool last = !SH || (t & 3) == shq;   // (a shared last block: this wave's quarter of the steps)
     #pragma unroll
                     for (int pb = 0; pb < PBW; ++pb)
-                        acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac[vt(t)], bq[0][pb], acc[pb], 0, 0, 0);
+                        if (pb < PBW - 1 || last)
+                            acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(ac[vt(t)], bq[0][pb], acc[pb], 0, 0, 0);
     #pragma unroll
-                    for (int pb = 0; pb < PBW; ++pb) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-                    }
+                    for (int pb = 0; pb < PBW; ++pb)
+                        if (pb < PBW - 1 || last) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                        }
     #pragma unroll
                     for (int pb = 0; pb < PBW; ++pb) {
     #pragma unroll
@@ -670,6 +685,28 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
             run(IntTag<0>{});
         }
 
+        if constexpr (G::SL != 0) {
+            // The shared block: pixel groups 5, 6, 7 hand their quarter sums to group 4 through LDS (the stage
+            // buffers, free once every wave is here and its re-staged loads have landed), added in a fixed order.
+            // Every wave of the workgroup passes both barriers, whichever body it runs.
+            wait_vmem_done();
+            __syncthreads();
+            if constexpr (SH) {
+                if (shq > 0) {
+    #pragma unroll
+                    for (int v = 0; v < 16; ++v) lds[((shq - 1) * 16 + v) * 64 + lane] = acc[PBW - 1][v];
+                }
+            }
+            __syncthreads();
+            if constexpr (SH) {
+                if (shq == 0) {
+    #pragma unroll
+                    for (int g = 0; g < 3; ++g)
+    #pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[PBW - 1][v] += lds[(g * 16 + v) * 64 + lane];
+                }
+            }
+        }
         if (G::SC > 1) {
             // Sum the split groups' partial tiles into group 0, as a tree: at every level the upper half of
             // the groups still in play write their tiles to LDS (the stage buffers are free once every wave
@@ -723,7 +760,8 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
         const Tail tail{a.bias, a.residual ? a.residual + (size_t)n * KO * OPQ : nullptr, a.relu};
 #pragma unroll
         for (int pb = 0; pb < PBW; ++pb) {
-            const int t = (wp * G::PBW + pb) * 32 + j;   // (the first pixel group always owns G::PBW blocks)
+            if (SH && pb == PBW - 1 && shq != 0) continue;   // (the shared block is stored by the group that summed it)
+            const int t = ((SH && pb == PBW - 1) ? G::WP * G::PBW : wp * G::PBW + pb) * 32 + j;
             bool live;
             int ni = 0, pix;      // image of the pixel relative to n, pixel index inside its image
             if constexpr (G::FLAT) {
@@ -747,8 +785,17 @@ __device__ __forceinline__ void conv_dma_body(const KernelArgs &a)
             write_block<FUSED>(a.out_blocked != 0, fast, orsrc, out_n, K, OPQ, kw, h, live, ni, pix, acc[pb], tail);
         }
     };
-    if (G::PBW2 > 0 && wp == 1) body(IntTag<(G::PBW2 > 0 ? G::PBW2 : G::PBW)>{});
-    else body(IntTag<G::PBW>{});
+    if constexpr (G::SL != 0) {
+        // (one instantiation of the body per quarter: which steps a wave adds to the shared block is then fixed at compile time)
+        if (wp < 4) body(IntTag<G::PBW>{}, IntTag<0>{});
+        else if (wp == 4) body(IntTag<G::PBW + 1>{}, IntTag<1>{});
+        else if (wp == 5) body(IntTag<G::PBW + 1>{}, IntTag<2>{});
+        else if (wp == 6) body(IntTag<G::PBW + 1>{}, IntTag<3>{});
+        else body(IntTag<G::PBW + 1>{}, IntTag<4>{});
+    } else {
+        if (G::PBW2 > 0 && wp == 1) body(IntTag<(G::PBW2 > 0 ? G::PBW2 : G::PBW)>{}, IntTag<0>{});
+        else body(IntTag<G::PBW>{}, IntTag<0>{});
+    }
 }
 
 template <class G, bool TAILC, bool FUSED>
@@ -811,7 +858,7 @@ template <class G, bool TAILC>
 static hipError_t launch_dma_t(const KernelArgs &a, unsigned grid, hipStream_t stream)
 {
     if (a.ost) {   // output re-mapping: compiled for the stride-1 variants of small filters only
-        if constexpr (G::ST == 1 && G::R <= 4) {
+        if constexpr (G::ST == 1 && G::R <= 4 && G::SL == 0) {
             return has_tail(a) ? hipErrorInvalidValue : launch_dma_remap<G, TAILC>(a, grid, stream);
         } else {
             return hipErrorInvalidValue;
