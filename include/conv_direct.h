@@ -75,7 +75,9 @@ int conv_direct_run(const conv_direct_plan *plan,
  *   bias     : device pointer, K floats, or NULL
  *   residual : device pointer, a tensor of out's layout and size (it may not overlap out), or NULL
  *   relu     : nonzero applies max(., 0) last
- * All NULL / 0 is conv_direct_run.  Still one kernel launch and no workspace.
+ * All NULL / 0 is conv_direct_run.  Still one kernel launch and no workspace.  A few kernel variants have no
+ * registers to spare for the tail; a plan that chose one runs calls that bring a tail on its second choice
+ * (plan_info: tail_variant), calls without one on its first.
  */
 int conv_direct_run_fused(const conv_direct_plan *plan,
                           const float *in, const float *w, const float *bias, const float *residual,
@@ -93,7 +95,8 @@ size_t conv_direct_workspace_bytes(const conv_direct_plan *plan);
 /*
  * Write a one-line, space-separated key=value description of the plan into buf
  * (variant name, tile, grid, LDS bytes, threads ...; for a data-gradient plan also
- * extra_caller_bytes, the size of the transformed-filter buffer wt the caller provides),
+ * extra_caller_bytes, the size of the transformed-filter buffer wt the caller provides; tail_variant: the variant
+ * that calls with a fused tail run on, "same" unless the plan's variant has no tail),
  * NUL-terminated and truncated to n bytes.  Returns the untruncated length, or a negative error code.
  */
 int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n);

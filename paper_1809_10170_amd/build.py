@@ -48,7 +48,7 @@ def _units(only=None):
     for name, family, params in variants():
         if only and name not in only:
             continue
-        header = {"DMA": "conv_dma_kernel.h", "ROWS": "conv_rows_kernel.h", "PW": "conv_pw_kernel.h",
+        header = {"DMA": "conv_dma_kernel.h", "ROWS": "conv_rows_kernel.h", "PW": "conv_pw_kernel.h", "PWK": "conv_pwk_kernel.h",
                   "TAPS": "conv_taps_kernel.h"}[family]
         units.append((f"tile_{name}", "conv_variant.hip",
                       [f"-DV_NAME={name}", f"-DV_FAMILY={family}", f"-DV_PARAMS={params}"],

@@ -37,6 +37,8 @@ struct conv_direct_plan {
     const convd::WgradVariant *wv; // weight-gradient plans only (v is then NULL)
     int wg_cgroups, wg_splits;
     int wg_dy_blocked;             // weight-gradient plans: layout of dy (in_blocked: of x, out_blocked: of dw)
+    conv_direct_plan *tail_plan;   // forward plans whose variant cannot fuse a point-wise tail: the plan that calls with a
+                                   // tail run on instead (owned; NULL otherwise)
 };
 
 namespace {
@@ -93,7 +95,9 @@ bool applicable(const Variant &v, const Shape &s, int in_blocked, int out_blocke
     if ((v.pair == convd::PAIR_R || v.pair == convd::PAIR_T) && s.C > v.CB) return false;   // stages all channels at once
     if (v.img != 0 && (s.H != v.img || s.W != v.img || s.pad != v.pad)) return false;   // flat tiling
     if (v.pointwise && s.pad != 0) return false;
-    if (v.pointwise == 2 && (!pointwise_flat(v, s) || ((int64_t)s.H * s.W) % v.TQ == 0)) return false;
+    if (v.pointwise == 2 && (!pointwise_flat(v, s) || (!v.kloop && ((int64_t)s.H * s.W) % v.TQ == 0))) return false;
+    // (its lanes take pixels in fours; whole channel blocks only; pointwise_flat() above bounds its byte offsets)
+    if (v.kloop && (s.C != v.CB || ((int64_t)s.H * s.W) % 4 != 0 || s.K % v.KT != 0)) return false;
     if (v.lds_bytes(s) > kLdsPerCU) return false;
     if (v.R != 0) {
         // the compiled kernels address the input with 31-bit byte offsets from the first
@@ -108,7 +112,7 @@ bool applicable(const Variant &v, const Shape &s, int in_blocked, int out_blocke
     }
     const int64_t grid = v.img != 0
                              ? (int64_t)cdiv(s.K, v.KT) * ((((int64_t)s.N * s.P * s.Q) + v.NPB * 32 - 1) / (v.NPB * 32))
-                         : pointwise_flat(v, s) ? (int64_t)cdiv(s.K, v.KT) * cdiv64((int64_t)s.N * s.P * s.Q, v.TQ)
+                         : pointwise_flat(v, s) ? (int64_t)(v.kloop ? 1 : cdiv(s.K, v.KT)) * cdiv64((int64_t)s.N * s.P * s.Q, v.TQ)
                          : v.pointwise ? (int64_t)cdiv(s.K, v.KT) * cdiv64((int64_t)s.P * s.Q, v.TQ) * s.N
                                        : (int64_t)cdiv(s.K, v.KT) * cdiv(s.P, v.TP) * cdiv(s.Q, v.TQ) * s.N;
     return grid > 0 && grid < kMaxElems;
@@ -119,7 +123,7 @@ void fill(conv_direct_plan *p, const Shape &s, const Variant &v)
     p->s = s;
     p->v = &v;
     // (merged phases: the eight k-waves of a workgroup are four phases of two 32-channel blocks)
-    p->ktiles = v.merged ? cdiv(s.K, 64) : cdiv(s.K, v.KT);
+    p->ktiles = v.merged ? cdiv(s.K, 64) : v.kloop ? 1 : cdiv(s.K, v.KT);
     p->pw_flat = pointwise_flat(v, s) ? 1 : 0;
     if (p->pw_flat) {
         p->tilesP = 1;
@@ -154,7 +158,7 @@ void fill(conv_direct_plan *p, const Shape &s, const Variant &v)
     } else {
         red = (double)s.C * (2 * ((s.R + 1) / 2)) * s.S;
     }
-    const double issued = (double)p->grid * v.KT * (v.NPB * 32.0) * red;
+    const double issued = (double)p->grid * (v.kloop ? cdiv(s.K, v.KT) * v.KT : v.KT) * (v.NPB * 32.0) * red;
     const double useful = (double)s.N * s.K * s.P * s.Q * ((double)s.C * s.R * s.S);
     p->mfma_efficiency = useful / issued;
 }
@@ -204,7 +208,8 @@ double cost(const conv_direct_plan &p)
         // burst, behind which the operand loads of its CU neighbours wait.  Smaller workgroups, more of them per CU,
         // spread the bursts (measured on 64 -> 256 channels at 56x56: 6 % for 57 KB instead of 115 KB a burst).
         const double in_b = (double)s.N * s.C * s.H * s.W * 4.0, out_b = (double)s.N * s.K * s.P * s.Q * 4.0;
-        if (out_b > in_b) c += (double)cdiv64(grid, slots) * (out_b / (double)grid) / 4.0 / occ;
+        // (a workgroup that walks all output channels stores block by block along the way)
+        if (out_b > in_b && !v.kloop) c += (double)cdiv64(grid, slots) * (out_b / (double)grid) / 4.0 / occ;
     }
     // input staging traffic
     double staged;   // floats one workgroup stages in total
@@ -219,7 +224,7 @@ double cost(const conv_direct_plan &p)
     // filter traffic: every wave fetches the whole filter slice of its 32-channel blocks,
     // however few pixels it owns (what makes very small pixel tiles expensive)
     if (v.R != 0) {
-        c += (double)grid * wpw * 32.0 * s.C * s.R * s.S * 4.0 / 16384.0;
+        c += (double)grid * wpw * (v.kloop ? cdiv(s.K, v.KT) : 1) * 32.0 * s.C * s.R * s.S * 4.0 / 16384.0;
     }
     if (v.R == 0) c *= 3.0;   // the runtime-shape fallback synchronises far more often
     return c;
@@ -253,7 +258,8 @@ void tuned_store(const int (&key)[11], const char *variant)
 }
 
 int make_plan(conv_direct_plan **plan, const char *forced, int N, int C, int H, int W, int K, int R,
-              int S, int stride, int pad, int in_blocked = 0, int out_blocked = 0, bool pair_family_only = false, int phase_stride = 0)
+              int S, int stride, int pad, int in_blocked = 0, int out_blocked = 0, bool pair_family_only = false, int phase_stride = 0,
+              bool tail_capable_only = false)
 {
     if (!plan) return CONV_DIRECT_EINVAL;
     *plan = nullptr;
@@ -281,6 +287,7 @@ int make_plan(conv_direct_plan **plan, const char *forced, int N, int C, int H, 
         if (!applicable(v, s, in_blocked, out_blocked)) continue;
         if (pair_family_only && (v.pair != convd::PAIR_C || v.pointwise || v.R == 0)) continue;
         if (v.merged && phase_stride != 2) continue;   // (serves only the four phases of a stride-2 layer's data gradient)
+        if (tail_capable_only && v.no_tail) continue;
         conv_direct_plan cand{};
         fill(&cand, s, v);
         cand.in_blocked = in_blocked;
@@ -296,6 +303,15 @@ int make_plan(conv_direct_plan **plan, const char *forced, int N, int C, int H, 
     if (!have) return CONV_DIRECT_EUNSUPPORTED;
     conv_direct_plan *p = new (std::nothrow) conv_direct_plan(best);
     if (!p) return CONV_DIRECT_ENOMEM;
+    if (best.v->no_tail && !phase_stride) {
+        // the second choice, among the variants that can fuse a tail (the runtime-shape kernel is one: there always is one)
+        const int rc2 = make_plan(&p->tail_plan, nullptr, N, C, H, W, K, R, S, stride, pad, in_blocked, out_blocked, pair_family_only,
+                                  0, true);
+        if (rc2 != CONV_DIRECT_OK) {
+            delete p;
+            return rc2;
+        }
+    }
     *plan = p;
     return CONV_DIRECT_OK;
 }
@@ -339,6 +355,7 @@ int conv_direct_run_fused(const conv_direct_plan *plan, const float *in, const f
     if (!plan || !in || !w || !out || !plan->v) return CONV_DIRECT_EINVAL;
     if (((uintptr_t)in | (uintptr_t)w | (uintptr_t)out | (uintptr_t)bias | (uintptr_t)residual) & 3u)
         return CONV_DIRECT_EALIGN;
+    if ((bias || residual || relu) && plan->tail_plan) plan = plan->tail_plan;   // (same problem, a variant that fuses tails)
 
     convd::KernelArgs a;
     a.in = in;
@@ -392,6 +409,7 @@ int conv_direct_run_fused(const conv_direct_plan *plan, const float *in, const f
 
 int conv_direct_destroy(conv_direct_plan *plan)
 {
+    if (plan) delete plan->tail_plan;
     delete plan;
     return CONV_DIRECT_OK;
 }
@@ -425,14 +443,14 @@ int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
                          "variant=%s N=%d C=%d H=%d W=%d K=%d R=%d S=%d stride=%d pad=%d P=%d Q=%d "
                          "TP=%d TQ=%d KT=%d NPB=%d CB=%d pair=%s tilesP=%d tilesQ=%d ktiles=%d grid=%u "
                          "threads=%d lds_bytes=%zu occupancy=%d flat=%d pointwise=%d mfma_efficiency=%.6g in_layout=%s "
-                         "out_layout=%s dgrad_phases=%d extra_caller_bytes=%zu workspace_bytes=0",
+                         "out_layout=%s dgrad_phases=%d extra_caller_bytes=%zu tail_variant=%s workspace_bytes=0",
                          v.name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, v.TP, v.TQ,
-                         v.merged ? 64 : v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : v.pair == convd::PAIR_R ? "r" : "t", plan->tilesP,
+                         v.merged ? 64 : v.kloop ? cdiv(plan->s.K, v.KT) * v.KT : v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : v.pair == convd::PAIR_R ? "r" : "t", plan->tilesP,
                          plan->tilesQ, plan->ktiles, plan->grid, v.threads, plan->lds_bytes, v.occupancy,
                          (v.img != 0 || plan->pw_flat) ? 1 : 0, v.pointwise, plan->mfma_efficiency, plan->in_blocked ? "blocked" : "plain",
                          plan->out_blocked ? "blocked" : "plain",
                          plan->ph_stride ? (plan->ph_stride < plan->fwd_R ? plan->ph_stride : plan->fwd_R) * (plan->ph_stride < plan->fwd_R ? plan->ph_stride : plan->fwd_R) : 0,
-                         conv_direct_dgrad_wt_elems(plan) * sizeof(float));
+                         conv_direct_dgrad_wt_elems(plan) * sizeof(float), plan->tail_plan ? plan->tail_plan->v->name : "same");
 }
 
 const char *conv_direct_strerror(int code)

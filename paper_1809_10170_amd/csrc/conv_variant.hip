@@ -1,14 +1,15 @@
 // One compiled kernel variant per translation unit, so that the variants build in
-// parallel.  The build passes V_NAME (the variant's name), V_FAMILY (DMA, ROWS, TAPS or PW) and
+// parallel.  The build passes V_NAME (the variant's name), V_FAMILY (DMA, ROWS, TAPS, PW or PWK) and
 // V_PARAMS (the geometry's template arguments) from the matching row of variants.def.
 #if !defined(V_NAME) || !defined(V_PARAMS) || !defined(V_FAMILY)
-#error "compile with -DV_NAME=<name> -DV_FAMILY=<DMA|ROWS|TAPS|PW> -DV_PARAMS=<geometry template arguments>"
+#error "compile with -DV_NAME=<name> -DV_FAMILY=<DMA|ROWS|TAPS|PW|PWK> -DV_PARAMS=<geometry template arguments>"
 #endif
 
 #define CONVD_FAMILY_DMA 2
 #define CONVD_FAMILY_ROWS 3
 #define CONVD_FAMILY_PW 4
 #define CONVD_FAMILY_TAPS 5
+#define CONVD_FAMILY_PWK 6
 #define CONVD_CAT_(a, b) a##b
 #define CONVD_CAT(a, b) CONVD_CAT_(a, b)
 #define CONVD_STR_(a) #a
@@ -23,6 +24,9 @@
 #elif CONVD_CAT(CONVD_FAMILY_, V_FAMILY) == CONVD_FAMILY_PW
 #include "conv_pw_kernel.h"
 #define CONVD_MAKE make_pw_variant<PwGeom<V_PARAMS>>
+#elif CONVD_CAT(CONVD_FAMILY_, V_FAMILY) == CONVD_FAMILY_PWK
+#include "conv_pwk_kernel.h"
+#define CONVD_MAKE make_pwk_variant<PwkGeom<V_PARAMS>>
 #elif CONVD_CAT(CONVD_FAMILY_, V_FAMILY) == CONVD_FAMILY_TAPS
 #include "conv_taps_kernel.h"
 #define CONVD_MAKE make_taps_variant<TapGeom<V_PARAMS>>

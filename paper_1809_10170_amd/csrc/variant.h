@@ -63,6 +63,10 @@ struct Variant {
                           // w [K/32][C/4][R][S][4][32]
     int merged;           // 1: eight k-waves; serves only the data gradient of a stride-2 layer, all four phases of a
                           // pixel tile in one workgroup (a workgroup then covers 64 output channels, not KT)
+    int kloop;            // 1: a workgroup walks ALL output channels of its pixel tile, KT at a time (the grid has no channel
+                          // tiles); the variant takes exactly CB input channels, K a multiple of KT, H*W a multiple of 4
+    int no_tail;          // 1: the variant has no instantiation with the fused point-wise tail (its registers are spoken
+                          // for): a plan that chooses it carries a second choice for calls that bring a tail
 };
 
 // The compiled variants (host table of pointers; lives beside the fallback kernel).

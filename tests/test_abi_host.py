@@ -149,14 +149,26 @@ def test_every_variant_plans_a_matching_shape():
             _check_cover(info, exhaustive=True)
             plan.destroy()
             continue
-        plan = cd.Plan(2, C, H, W, 70, R, R, st, R // 2, variant=nm,
+        K = 70
+        walk = re.search(r"_c(\d+)_kall", nm)
+        if walk:
+            # all output channels per workgroup, the input in registers: exactly that many input channels, whole blocks
+            # of 32 output channels, pixels in fours; anything else is another variant's
+            C, K, H, W = int(walk.group(1)), 96, 36, 41
+            for bad in ((2, C, H, W, 70, 1, 1, 1, 0), (2, C, 37, 41, K, 1, 1, 1, 0), (2, C + 2, H, W, K, 1, 1, 1, 0)):
+                with pytest.raises(cd.ConvDirectError) as e:
+                    cd.Plan(*bad, variant=nm)
+                assert e.value.code == cd.EUNSUPPORTED
+        plan = cd.Plan(2, C, H, W, K, R, R, st, R // 2, variant=nm,
                        in_layout=cd.BLOCKED if blocked else cd.PLAIN, out_layout=cd.BLOCKED if blocked else cd.PLAIN)
         info = plan.info()
         assert info["variant"] == nm
+        # a variant without the fused tail comes with a second choice that has one
+        assert (info["tail_variant"] != "same") == ("_sl" in nm and nm[0] in "pb" and nm[1] == "1")
         assert info["in_layout"] == info["out_layout"] == ("blocked" if blocked else "plain")
         if not blocked and not nm.startswith("generic"):   # a compiled variant serves one input layout only
             with pytest.raises(cd.ConvDirectError) as e:
-                cd.Plan(2, C, H, W, 70, R, R, st, R // 2, variant=nm, in_layout=cd.BLOCKED)
+                cd.Plan(2, C, H, W, K, R, R, st, R // 2, variant=nm, in_layout=cd.BLOCKED)
             assert e.value.code == cd.EUNSUPPORTED
         _check_cover(info, exhaustive=True)
         plan.destroy()

@@ -89,9 +89,10 @@ def _variant_shape(name):
 
 
 # (variants for the blocked layouts, named b..., have their own tests in test_layout_gpu.py; the merged-phase variants,
-# ...k64m..., serve only the data gradient of stride-2 layers and are tested in test_dgrad_gpu.py)
+# ...k64m..., serve only the data gradient of stride-2 layers and are tested in test_dgrad_gpu.py; the pointwise walk over all
+# output channels, ..._kall, takes one channel count and whole channel blocks only: test_pointwise_forms_gpu.py)
 @pytest.mark.parametrize("channels", ["ragged", "whole"])
-@pytest.mark.parametrize("name", [n for n in cd.variant_names() if not n.startswith("b") and "k64m" not in n])
+@pytest.mark.parametrize("name", [n for n in cd.variant_names() if not n.startswith("b") and "k64m" not in n and "_kall" not in n])
 def test_every_variant_on_ragged_shape(oracle, name, channels):
     """Each compiled variant, forced, on a shape that leaves ragged tiles in every
     dimension (K, rows, columns) and spans several tiles.  Two passes over the input
