@@ -28,6 +28,13 @@
 // their results (G1 * 128 and G2 * 128 contiguous bytes per half-wave).  The shared block is 32 consecutive
 // pixels, one per lane.  This needs H*W to be a multiple of 4 (no group of pixels reaches over two images).
 //
+// BLK = 1: input and weights in the blocked layouts (paper, Section 4): in [N][C/4][H*W][4], w [K/32][C/4][4][32].
+// The reduction then runs block by block, two steps per block as in the other pointwise kernels: in step (cb, cc)
+// the k-lanes take channels 4cb + cc and 4cb + 2 + cc, a lane's B operands of both steps are 8 adjacent bytes of its
+// pixel's pencil (one load; the two halves of the wave take the two halves of the same pencils), and a step's filter
+// values are 32 consecutive floats per k-lane half.  Here every block keeps its own 32 consecutive pixels, one per
+// lane (wide pixel groups would scatter a load over 64-byte strides), and the plain-output stores are 4 bytes a lane.
+//
 // Same MFMA mapping as the other kernels otherwise (rows = output channels, columns = pixels); the two
 // k-lanes of v_mfma_f32_32x32x2_f32 take channels s and s + C/2.
 #pragma once
@@ -36,11 +43,16 @@
 namespace convd {
 
 // CH: reduction steps = C/2 (the variant serves exactly C = 2 * CH channels); PBW own blocks per wave, WP waves
-template <int CH_, int PBW_, int WP_>
+template <int CH_, int PBW_, int WP_, int BLK_ = 0>
 struct PwkGeom {
     static constexpr int R = 1, S = 1, ST = 1;
-    static constexpr int PBW = PBW_, CH = CH_, WP = WP_;
-    static constexpr int G1 = PBW == 6 ? 4 : 2, G2 = PBW - G1;     // pixels a lane holds in the two parts
+    static constexpr int PBW = PBW_, CH = CH_, WP = WP_, BLK = BLK_;
+    static constexpr int G1 = PBW == 6 ? 4 : 2, G2 = PBW - G1;     // pixels a lane holds in the two parts (plain input)
+    // The wave's blocks come in parts: a part is GS blocks whose column j are GS adjacent pixels of lane j.
+    static constexpr int NPART = BLK ? PBW + 1 : 3;               // (the last part is the shared block)
+    static constexpr int part_size(int p) { return BLK ? 1 : p == 0 ? G1 : p == 1 ? G2 : 1; }
+    static constexpr int part_first(int p) { return BLK ? p : p == 0 ? 0 : p == 1 ? G1 : PBW; }   // its first block
+    static constexpr int part_of(int pb) { return BLK ? pb : pb < G1 ? 0 : pb < PBW ? 1 : 2; }
     static constexpr int PAIR = PAIR_C;
     static constexpr int CB = 2 * CH;                    // reported: the channel count the variant takes
     static constexpr int NT = 64 * WP, OCC = 1;
@@ -82,10 +94,11 @@ __global__ void __launch_bounds__(G::NT, 1) conv_pwk_kernel(const KernelArgs a)
     const int mt = (int)bid * G::TQ;                                  // first pixel of the tile, of all N*H*W
     const int n = __builtin_amdgcn_readfirstlane((int)(((long long)mt) / HW));   // the image the tile starts in
     const int M = a.s.N * HW;                                         // (a multiple of 4)
-    const int mw = mt + Q * (G::PBW * 32);                            // first of the wave's own 192 pixels
+    const int mw = mt + Q * (G::PBW * 32);                            // first of the wave's own 32 * PBW pixels
     // the lane's pixel in block pb
     auto pixel = [&](int pb) {
-        return pb < G1 ? mw + G1 * j + pb : pb < G::PBW ? mw + 32 * G1 + G2 * j + (pb - G1) : mt + G::WP * G::PBW * 32 + j;
+        const int p = G::part_of(pb);
+        return pb < G::PBW ? mw + 32 * G::part_first(p) + G::part_size(p) * j + (pb - G::part_first(p)) : mt + G::WP * G::PBW * 32 + j;
     };
     // pixel m -> image relative to n, pixel in the image
     auto locate = [&](int m, int &ni, int &ml) {
@@ -98,15 +111,22 @@ __global__ void __launch_bounds__(G::NT, 1) conv_pwk_kernel(const KernelArgs a)
     // computed, not stored).  There is one register per step: the values of steps 4u .. 4u+3 for the next channel
     // block are fetched into the registers of this block's as soon as its MFMAs of those steps are issued, a whole
     // channel block ahead of their use.
+    // Blocked weights: step s = (cb, cc) of channel block kb is w[kb][cb][cc + 2h][j], 32 consecutive floats per k-lane half.
     float av[CH];
     auto a_row = [&](int kb) {
+        if constexpr (G::BLK != 0) return a.w + (size_t)kb * (C / 4 * 128) + 2 * h * 32 + j;
         int krow = kb * 32 + j;
         krow = krow < K ? krow : K - 1;
         return a.w + (size_t)krow * C + h * CH;
     };
     auto load_a4 = [&](const float *p, int u) {
-        const dma_f4u v = *reinterpret_cast<const dma_f4u *>(p + 4 * u);
-        av[4 * u] = v[0]; av[4 * u + 1] = v[1]; av[4 * u + 2] = v[2]; av[4 * u + 3] = v[3];
+        if constexpr (G::BLK != 0) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) av[4 * u + e] = p[(2 * u + e / 2) * 128 + (e % 2) * 32];
+        } else {
+            const dma_f4u v = *reinterpret_cast<const dma_f4u *>(p + 4 * u);
+            av[4 * u] = v[0]; av[4 * u + 1] = v[1]; av[4 * u + 2] = v[2]; av[4 * u + 3] = v[3];
+        }
     };
     {
         const float *p = a_row(0);
@@ -116,16 +136,17 @@ __global__ void __launch_bounds__(G::NT, 1) conv_pwk_kernel(const KernelArgs a)
 
     // B: lane (j, h) holds in[n'][s + h*CH][its pixel of block pb] for every step s.  Groups past the last pixel
     // (the last tile) read the tensor's last group instead (computed, not stored).
-    unsigned boff[3];   // byte offsets of the lane's first pixel in the two parts, and of its shared pixel, in channel h*CH
+    // Blocked input: bytes 8h .. 8h+7 of the pixel's pencil in channel block 0; one load is two steps.
+    unsigned boff[G::NPART];   // byte offsets of the lane's first pixel of every part in channel h*CH
 #pragma unroll
-    for (int g = 0; g < 3; ++g) {
-        int m = pixel(g == 0 ? 0 : g == 1 ? G1 : G::PBW);
+    for (int g = 0; g < G::NPART; ++g) {
+        int m = pixel(G::part_first(g));
         m = m < M ? m : M - 4;
         int ni, ml;
         locate(m, ni, ml);
-        boff[g] = (unsigned)((ni * C + h * CH) * HW + ml) * 4u;
+        boff[g] = G::BLK ? (unsigned)((ni * (C / 4) * HW + ml) * 4 + 2 * h) * 4u : (unsigned)((ni * C + h * CH) * HW + ml) * 4u;
     }
-    const unsigned plane = (unsigned)HW * 4u;
+    const unsigned plane = (unsigned)HW * (G::BLK ? 16u : 4u);      // bytes of one channel (blocked: channel block) of one image
     // (the tile's pixels lie in several images: the resource runs on past image n; every pixel read exists)
     __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(a.in + (size_t)n * C * HW), 0, 0x7fffffff, 0x00020000);
@@ -148,11 +169,23 @@ __global__ void __launch_bounds__(G::NT, 1) conv_pwk_kernel(const KernelArgs a)
             dst[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, soff, 0));
         }
     };
+    if constexpr (G::BLK != 0) {
 #pragma unroll
-    for (int s = 0; s < CH; ++s) {
-        load_part(IntTag<G1>{}, rsrc, boff[0], s * (int)plane, &b[s][0]);
-        load_part(IntTag<G2>{}, rsrc, boff[1], s * (int)plane, &b[s][G1]);
-        load_part(IntTag<1>{}, rsrc, boff[2], s * (int)plane, &b[s][G::PBW]);
+        for (int cb = 0; cb < CH / 2; ++cb)
+#pragma unroll
+            for (int pb = 0; pb < NB; ++pb) {
+                float two[2];
+                load_part(IntTag<2>{}, rsrc, boff[pb], cb * (int)plane, two);
+                b[2 * cb][pb] = two[0];
+                b[2 * cb + 1][pb] = two[1];
+            }
+    } else {
+#pragma unroll
+        for (int s = 0; s < CH; ++s) {
+            load_part(IntTag<G1>{}, rsrc, boff[0], s * (int)plane, &b[s][0]);
+            load_part(IntTag<G2>{}, rsrc, boff[1], s * (int)plane, &b[s][G1]);
+            load_part(IntTag<1>{}, rsrc, boff[2], s * (int)plane, &b[s][G::PBW]);
+        }
     }
 
     // output addressing (see write_block)
@@ -161,11 +194,11 @@ __global__ void __launch_bounds__(G::NT, 1) conv_pwk_kernel(const KernelArgs a)
     __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(out_n), 0, 0x7fffffff, 0x00020000);
     const Tail tail{a.bias, a.residual ? a.residual + (size_t)n * KO * HW : nullptr, a.relu};
     const unsigned oplane = (unsigned)HW * 4u;
-    unsigned voff[MODE == 0 ? 3 : 1];     // bare stores: byte offsets of the lane's two groups and shared pixel in channel 4h
+    unsigned voff[MODE == 0 ? G::NPART : 1];     // bare stores: byte offsets of the lane's first pixel of every part in channel 4h
     if constexpr (MODE == 0) {
 #pragma unroll
-        for (int g = 0; g < 3; ++g) {
-            const int m = pixel(g == 0 ? 0 : g == 1 ? G1 : G::PBW);
+        for (int g = 0; g < G::NPART; ++g) {
+            const int m = pixel(G::part_first(g));
             int ni, ml;
             locate(m < M ? m : M - 4, ni, ml);
             const size_t o = (size_t)ni * K * HW + ml;
@@ -211,9 +244,10 @@ __global__ void __launch_bounds__(G::NT, 1) conv_pwk_kernel(const KernelArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int soff = (kw + 8 * (v >> 2) + (v & 3)) * (int)oplane;
-                store_part(IntTag<G1>{}, voff[0], soff, 0, v);
-                store_part(IntTag<G2>{}, voff[1], soff, G1, v);
-                if constexpr (NBK == NB) store_part(IntTag<1>{}, voff[2], soff, NB - 1, v);
+                static_for<0, G::NPART>([&](auto p_tag) {
+                    constexpr int p = decltype(p_tag)::value;
+                    if constexpr (G::part_first(p) < NBK) store_part(IntTag<G::part_size(p)>{}, voff[p], soff, G::part_first(p), v);
+                });
             }
         } else {
 #pragma unroll
@@ -251,7 +285,7 @@ template <class G>
 constexpr Variant make_pwk_variant(const char *name)
 {
     return Variant{name, 1, 1, 1, G::TP, G::TQ, G::KT, G::NPB, G::CB, G::PAIR, G::NT, G::OCC,
-                   G::TQ, 0, 0, &lds_pwk<G>, &launch_pwk<G>, 2, 0, 0, 1};
+                   G::TQ, 0, 0, &lds_pwk<G>, &launch_pwk<G>, 2, G::BLK, 0, 1};
 }
 
 }  // namespace convd

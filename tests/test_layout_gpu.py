@@ -71,8 +71,9 @@ def test_weight_rearranger_bit_exact(K, C, R, S):
 
 
 def _blocked_variants():
-    # (merged-phase variants, ...k64m..., serve only the data gradient of stride-2 layers: tests/test_dgrad_gpu.py)
-    return [n for n in cd.variant_names() if n.startswith("b") and "k64m" not in n]
+    # (merged-phase variants, ...k64m..., serve only the data gradient of stride-2 layers: tests/test_dgrad_gpu.py; the walk
+    # over all output channels, ..._kall, takes one channel count only: tests/test_pointwise_forms_gpu.py)
+    return [n for n in cd.variant_names() if n.startswith("b") and "k64m" not in n and "_kall" not in n]
 
 
 def _shape_for(nm, C):

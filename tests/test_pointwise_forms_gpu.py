@@ -19,12 +19,14 @@ def test_the_forms_exist():
     assert WALK and SHARED
 
 
-def _run(plan, x, w, K, blocked, bias=None, residual=None, relu=False):
+def _run(plan, x, w, K, blocked, bias=None, residual=None, relu=False, in_blocked=False):
     N, _, H, W = x.shape
     out = torch.full((N, -(-K // 4), H, W, 4) if blocked else (N, K, H, W), float("nan"), device="cuda")
     rd = None
     if residual is not None:
         rd = torch.from_numpy(L.pack_activations(residual, 4) if blocked else residual).cuda()
+    if in_blocked:
+        x, w = L.pack_activations(x, 4), L.pack_weights(w, 4, 32)
     plan.run(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), out,
              bias=torch.from_numpy(bias).cuda() if bias is not None else None, residual=rd, relu=relu)
     torch.cuda.synchronize()
@@ -51,10 +53,11 @@ def test_walk_over_all_output_channels_bit_exact_on_integers(oracle, name, shape
     b = rng.integers(-50, 51, (K,)).astype(np.float32) if tail else None
     r = rng.integers(-50, 51, (N, K, H, W)).astype(np.float32) if tail else None
     assert C * 16 + 100 < 2 ** 24
-    plan = cd.Plan(N, C, H, W, K, 1, 1, 1, 0, variant=name, out_layout=out_layout)
+    inb = name.startswith("b")          # the variant for blocked input and weights
+    plan = cd.Plan(N, C, H, W, K, 1, 1, 1, 0, variant=name, in_layout=cd.BLOCKED if inb else cd.PLAIN, out_layout=out_layout)
     info = plan.info()
     assert info["variant"] == name and info["ktiles"] == 1 and info["tail_variant"] == "same"
-    got = _run(plan, x, w, K, out_layout == cd.BLOCKED, b, r, tail)
+    got = _run(plan, x, w, K, out_layout == cd.BLOCKED, b, r, tail, in_blocked=inb)
     plan.destroy()
     want = oracle.conv_forward_fused(x, w, 1, 0, bias=b, residual=r, relu=tail) if tail else oracle.conv_forward(x, w, 1, 0)
     assert np.array_equal(got.astype(np.float64), want)
@@ -67,8 +70,9 @@ def test_walk_random_inputs_within_tolerance(oracle, name):
     rng = np.random.default_rng(4200)
     x = rng.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
     w = rng.uniform(-1, 1, (K, C, 1, 1)).astype(np.float32)
-    plan = cd.Plan(N, C, H, W, K, 1, 1, 1, 0, variant=name)
-    got = _run(plan, x, w, K, False)
+    inb = name.startswith("b")
+    plan = cd.Plan(N, C, H, W, K, 1, 1, 1, 0, variant=name, in_layout=cd.BLOCKED if inb else cd.PLAIN)
+    got = _run(plan, x, w, K, False, in_blocked=inb)
     plan.destroy()
     assert np.abs(got - oracle.conv_forward(x, w, 1, 0)).max() <= oracle.tolerance(C, 1, 1)
 
@@ -124,4 +128,7 @@ def test_benchmark_pointwise_layers_take_the_two_forms():
     p.destroy()
     p = cd.Plan(64, 256, 56, 56, 64, 1, 1, 1, 0)
     assert "_sl" in p.info()["variant"]
+    p.destroy()
+    p = cd.Plan(64, 64, 56, 56, 256, 1, 1, 1, 0, in_layout=cd.BLOCKED, out_layout=cd.BLOCKED)
+    assert "_kall" in p.info()["variant"]
     p.destroy()
