@@ -6,9 +6,10 @@ conv_direct_run per layer) on seeded synthetic tensors already resident in HBM.
 The default workload is the batched AlexNet-/VGG-shaped layer suite; `--workload
 NAME` times a single layer (names: paper_1809_10170_amd/workloads.py).
 
-Prints ONE JSON line: whole-workload TFLOP/s (2*N*K*C*R*S*P*Q per layer / time),
-per-layer figures (average, median and minimum launch time from HIP events on the launch
-stream, fraction of the nominal fp32 MFMA peak and of the peak at the clock a bare-MFMA
+Prints ONE JSON line: whole-workload TFLOP/s (2*N*K*C*R*S*P*Q per layer / time of the timed
+passes, which carry HIP events around the launches of one layer only: the one that takes the
+most time), per-layer figures (average, median and minimum launch time from HIP events on the
+launch stream in as many further passes behind the timed ones, fraction of the nominal fp32 MFMA peak and of the peak at the clock a bare-MFMA
 probe measures in the same run, error of sampled outputs against the CPU oracle), the
 roofline record of the kernel that takes the most time, and the CPU oracle timed on a
 bounded sample of the same workload on this host.  The default run (forward, plain
@@ -205,29 +206,44 @@ class Runner:
         else:
             it["plan"].run(it["x"], it["w"], it["out"], stream)
 
-    def time_step(self, steps, warmup, stream):
-        """Whole passes over the layers: returns (ms per pass from the host clock around `steps` passes,
-        per-layer sorted launch times from events on the launch stream)."""
+    def _passes(self, count, stream, bracket):
+        """`count` passes over the layers with a pair of events around the launches of the layers in `bracket`:
+        (host seconds, {layer index: sorted launch times in ms})."""
         torch = self.torch
-        for _ in range(warmup):
-            for it in self.items:
-                self.launch(it, stream.cuda_stream)
-        torch.cuda.synchronize()
-        alloc_before = torch.cuda.memory_allocated()
-        ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-               for _ in self.items] for _ in range(steps)]
+        ev = {i: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(count)] for i in bracket}
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for s in range(steps):
+        for s in range(count):
             for i, it in enumerate(self.items):
-                ev[s][i][0].record(stream)
+                if i in ev:
+                    ev[i][s][0].record(stream)
                 self.launch(it, stream.cuda_stream)
-                ev[s][i][1].record(stream)
+                if i in ev:
+                    ev[i][s][1].record(stream)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
+        return wall, {i: sorted(e0.elapsed_time(e1) for e0, e1 in pairs) for i, pairs in ev.items()}
+
+    def time_step(self, steps, warmup, stream):
+        """Whole passes over the layers.  A pair of events around every launch costs the pass about 2 % (28 markers between
+        14 kernels), so the timed passes carry events around ONE layer only, the one that takes the most time (found in
+        the warm-up passes, which carry them all); the per-layer times come from a further `steps` passes behind the
+        timed region.  Returns (ms per pass from the host clock around the `steps` timed passes, per-layer sorted
+        launch times of the further passes, index of the layer that takes the most time, its sorted launch times in the
+        timed passes)."""
+        torch = self.torch
+        everything = range(len(self.items))
+        _, warm = self._passes(warmup, stream, everything)
+        if warmup:
+            dom = max(everything, key=lambda i: sum(warm[i]))
+        else:
+            dom = max(everything, key=lambda i: self.items[i]["layer"].flops)
+        alloc_before = torch.cuda.memory_allocated()
+        wall, dom_times = self._passes(steps, stream, [dom])
         assert torch.cuda.memory_allocated() == alloc_before, "device memory was allocated during the timed region"
-        times = [sorted(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(steps)) for i in range(len(self.items))]
-        return wall * 1e3 / steps, times
+        wall_ev, times = self._passes(steps, stream, everything)
+        self.ms_per_pass_with_events = wall_ev * 1e3 / steps
+        return wall * 1e3 / steps, [times[i] for i in everything], dom, dom_times[dom]
 
     def time_each(self, steps, warmup, stream):
         """Every layer alone in a loop of its own (for layers that are no part of a step): per-layer sorted
@@ -383,19 +399,25 @@ def main():
     clock_mhz = clock["clock_mhz"] if clock else None
 
     main_run = Runner(cd, torch, workloads, tensors, layers, args.direction, blocked, args.variant)
-    ms_per_step, times = main_run.time_step(args.steps, args.warmup, stream)
+    ms_per_step, times, dom_index, dom_times = main_run.time_step(args.steps, args.warmup, stream)
     per_layer = main_run.records(times, clock_mhz, check)
     total_flops = sum(l.flops for l in layers)
     value = total_flops / (ms_per_step * 1e-3) / 1e12
 
-    dom = max(per_layer, key=lambda r: r["ms_avg"])
+    # the layer that takes the most time, from the events around its launches inside the timed passes
+    dom = dict(per_layer[dom_index])
+    dom["ms_avg"] = round(sum(dom_times) / len(dom_times), 5)
+    dom["tflops"] = round(layers[dom_index].flops / (dom["ms_avg"] * 1e-3) / 1e12, 3)
+    if clock_mhz:
+        dom["frac_at_measured_clock"] = round(dom["tflops"] / (PEAK_FP32_MFMA_TFLOPS * clock_mhz / PEAK_CLOCK_MHZ), 4)
     kern = {"r": "conv_rows_kernel", "p": "conv_pw_kernel", "w": "conv_wgrad_kernel"}.get(dom["variant"][0], "conv_dma_kernel")
     traffic = measured_traffic(dom["layer"], dom["variant"])
     roofline = {"bound": "mfma", "kernel": f"{kern}<{dom['variant']}>", "layer": dom["layer"],
                 "achieved": dom["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(dom["tflops"] / PEAK_FP32_MFMA_TFLOPS, 4),
                 "frac_at_measured_clock": dom["frac_at_measured_clock"],
-                "launch_ms": dom["ms_avg"], "traffic": traffic,
+                "launch_ms": dom["ms_avg"], "launch_ms_source": f"HIP events around this layer's {len(dom_times)} launches in the timed passes, on the launch stream",
+                "traffic": traffic,
                 "traffic_source": (f"{TRAFFIC_SOURCE}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this layer with this "
                                    "variant, scaled by the copy calibration stated there; not measured in this run") if traffic else None,
                 "algorithmic_bytes": workloads.BY_NAME[dom["layer"]].algorithmic_bytes}
@@ -410,7 +432,10 @@ def main():
         "config": {"workload": args.workload, "direction": args.direction, "layout": args.layout, "layers": [l.name for l in layers],
                    "frac_fp32_mfma_peak": round(value / PEAK_FP32_MFMA_TFLOPS, 4),
                    "frac_at_measured_clock": round(value / (PEAK_FP32_MFMA_TFLOPS * clock_mhz / PEAK_CLOCK_MHZ), 4) if clock_mhz else None,
-                   "workspace_bytes": sum(r["workspace_bytes"] for r in per_layer)},
+                   "workspace_bytes": sum(r["workspace_bytes"] for r in per_layer),
+                   "layer_times": f"per-layer figures: {args.steps} further passes behind the timed ones, with HIP events around every launch "
+                                  "(kept out of the timed passes, which they slow by about 2 %)",
+                   "ms_per_pass_with_layer_events": round(main_run.ms_per_pass_with_events, 4)},
         "roofline": roofline,
         "clock": clock,
         "layers": per_layer,
@@ -430,7 +455,7 @@ def main():
                                          ("wgrad", "wgrad", False, layers), ("dgrad_blocked", "dgrad", True, dgrad_layers(layers)),
                                          ("wgrad_blocked", "wgrad", True, layers)):
             run = Runner(cd, torch, workloads, tensors, ls, direction, blk)
-            ms, tms = run.time_step(args.steps, args.warmup, stream)
+            ms, tms, _, _ = run.time_step(args.steps, args.warmup, stream)
             fl = sum(l.flops for l in ls)
             recs = run.records(tms, clock_mhz, check)
             other[name] = {"value": round(fl / (ms * 1e-3) / 1e12, 3), "unit": "TFLOP/s", "ms_per_step": round(ms, 4),
