@@ -15,7 +15,8 @@ roofline record of the kernel that takes the most time, and the CPU oracle timed
 bounded sample of the same workload on this host.  The default run (forward, plain
 layouts, batched suite) also times, outside the headline step, the single-image layers
 and the toy layer (`layers_single`) and the library's other paths over the same suite
-(`other_paths`: blocked layouts, data gradient, weight gradient).
+(`other_paths`: blocked layouts, data gradient, weight gradient) and over the GoogLeNet-shaped
+layers (`other_paths.inception_forward*`).
 """
 from __future__ import annotations
 
@@ -453,7 +454,9 @@ def main():
         other = {}
         for name, direction, blk, ls in (("forward_blocked", "forward", True, layers), ("dgrad", "dgrad", False, dgrad_layers(layers)),
                                          ("wgrad", "wgrad", False, layers), ("dgrad_blocked", "dgrad", True, dgrad_layers(layers)),
-                                         ("wgrad_blocked", "wgrad", True, layers)):
+                                         ("wgrad_blocked", "wgrad", True, layers),
+                                         ("inception_forward", "forward", False, suite("suite_inception", workloads)),
+                                         ("inception_forward_blocked", "forward", True, suite("suite_inception", workloads))):
             run = Runner(cd, torch, workloads, tensors, ls, direction, blk)
             ms, tms, _, _ = run.time_step(args.steps, args.warmup, stream)
             fl = sum(l.flops for l in ls)
