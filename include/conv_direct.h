@@ -96,7 +96,8 @@ size_t conv_direct_workspace_bytes(const conv_direct_plan *plan);
  * Write a one-line, space-separated key=value description of the plan into buf
  * (variant name, tile, grid, LDS bytes, threads ...; for a data-gradient plan also
  * extra_caller_bytes, the size of the transformed-filter buffer wt the caller provides; tail_variant: the variant
- * that calls with a fused tail run on, "same" unless the plan's variant has no tail),
+ * that calls with a fused tail run on, "same" unless the plan's variant has no tail; model_clocks: the planner's
+ * estimate of the run time in shader clocks, the figure that ranked the variants),
  * NUL-terminated and truncated to n bytes.  Returns the untruncated length, or a negative error code.
  */
 int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n);

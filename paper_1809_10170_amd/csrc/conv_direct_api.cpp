@@ -28,6 +28,7 @@ struct conv_direct_plan {
     unsigned grid;
     size_t lds_bytes;
     double mfma_efficiency;   // useful / issued multiply-accumulates
+    double model_clocks;      // the planner's estimate of the run time in shader clocks (what ranked the variants)
     int in_blocked, out_blocked;   // layouts of in + w, and of out (paper, Section 4)
     int pw_flat;                   // pointwise kernels: tiles run over the pixels of all images
     int dil, pad_h, pad_w;         // data gradients on the runtime-shape kernel (dil >= 1), see variant.h
@@ -294,6 +295,7 @@ int make_plan(conv_direct_plan **plan, const char *forced, int N, int C, int H, 
         cand.out_blocked = out_blocked;
         cand.ph_stride = phase_stride;
         const double c = cost(cand);
+        cand.model_clocks = c;
         if (!have || c < best_cost) {
             best = cand;
             best_cost = c;
@@ -443,14 +445,14 @@ int conv_direct_plan_info(const conv_direct_plan *plan, char *buf, size_t n)
                          "variant=%s N=%d C=%d H=%d W=%d K=%d R=%d S=%d stride=%d pad=%d P=%d Q=%d "
                          "TP=%d TQ=%d KT=%d NPB=%d CB=%d pair=%s tilesP=%d tilesQ=%d ktiles=%d grid=%u "
                          "threads=%d lds_bytes=%zu occupancy=%d flat=%d pointwise=%d mfma_efficiency=%.6g in_layout=%s "
-                         "out_layout=%s dgrad_phases=%d extra_caller_bytes=%zu tail_variant=%s workspace_bytes=0",
+                         "out_layout=%s dgrad_phases=%d extra_caller_bytes=%zu tail_variant=%s model_clocks=%.0f workspace_bytes=0",
                          v.name, s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.P, s.Q, v.TP, v.TQ,
                          v.merged ? 64 : v.kloop ? cdiv(plan->s.K, v.KT) * v.KT : v.KT, v.NPB, v.CB, v.pair == convd::PAIR_C ? "c" : v.pair == convd::PAIR_R ? "r" : "t", plan->tilesP,
                          plan->tilesQ, plan->ktiles, plan->grid, v.threads, plan->lds_bytes, v.occupancy,
                          (v.img != 0 || plan->pw_flat) ? 1 : 0, v.pointwise, plan->mfma_efficiency, plan->in_blocked ? "blocked" : "plain",
                          plan->out_blocked ? "blocked" : "plain",
                          plan->ph_stride ? (plan->ph_stride < plan->fwd_R ? plan->ph_stride : plan->fwd_R) * (plan->ph_stride < plan->fwd_R ? plan->ph_stride : plan->fwd_R) : 0,
-                         conv_direct_dgrad_wt_elems(plan) * sizeof(float), plan->tail_plan ? plan->tail_plan->v->name : "same");
+                         conv_direct_dgrad_wt_elems(plan) * sizeof(float), plan->tail_plan ? plan->tail_plan->v->name : "same", plan->model_clocks);
 }
 
 const char *conv_direct_strerror(int code)
