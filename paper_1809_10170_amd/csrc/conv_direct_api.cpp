@@ -272,7 +272,10 @@ int make_plan(conv_direct_plan **plan, const char *forced, int N, int C, int H, 
         const int key[11] = {N, C, H, W, K, R, S, stride, pad, in_blocked, out_blocked};
         if (const TunedEntry *e = tuned_lookup(key)) {
             const std::string name = e->variant;   // (a copy: the recursion below does not touch the table, but be safe)
-            if (make_plan(plan, name.c_str(), N, C, H, W, K, R, S, stride, pad, in_blocked, out_blocked) == CONV_DIRECT_OK)
+            // (a second choice for calls with a tail must have one: otherwise the measured name does not count here,
+            // and a plan for it would ask for a second choice of its own without end)
+            if (make_plan(plan, name.c_str(), N, C, H, W, K, R, S, stride, pad, in_blocked, out_blocked, false, 0, tail_capable_only) ==
+                CONV_DIRECT_OK)
                 return CONV_DIRECT_OK;
         }
     }
@@ -525,7 +528,7 @@ int conv_direct_create_tuned(conv_direct_plan **plan, int N, int C, int H, int W
         if (r == CONV_DIRECT_OK && (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
                                     hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
             r = CONV_DIRECT_EHIP;
-        delete cand;
+        conv_direct_destroy(cand);   // (with its second choice, if it has one)
         if (r != CONV_DIRECT_OK) {
             rc = r;
             best.clear();

@@ -231,6 +231,23 @@ def test_tuning_table_round_trip_and_override(tmp_path):
     assert cd.tuning_size() == 0 and cd.Plan(*shape).info()["variant"] == default
 
 
+def test_measured_choice_of_a_variant_without_tail_still_gets_a_second_plan(tmp_path):
+    """A tuning-table entry that names a variant without the fused tail: the plan is that variant, its second
+    choice (for calls with a tail) comes from the model among the variants that have one, and planning ends."""
+    cd.tuning_clear()
+    shape = (4, 256, 56, 56, 64, 1, 1, 1, 0)
+    names = [n for n in cd.variant_names() if n.startswith("p1s1") and "_sl" in n]
+    assert names
+    f = tmp_path / "tuned.txt"
+    f.write_text(" ".join(map(str, shape)) + f" 0 0 {names[0]}\n")
+    cd.tuning_load(str(f))
+    plan = cd.Plan(*shape)
+    info = plan.info()
+    assert info["variant"] == names[0] and info["tail_variant"] not in ("same", names[0])
+    plan.destroy()
+    cd.tuning_clear()
+
+
 def test_layout_gradient_and_tail_entry_points_check_arguments_before_any_launch():
     L = cd.lib()
     import ctypes

@@ -13,6 +13,10 @@ pytestmark = pytest.mark.gpu
     ((4, 32, 28, 28, 96, 3, 3, 1, 1), (cd.PLAIN, cd.PLAIN)),
     ((4, 32, 28, 28, 96, 3, 3, 1, 1), (cd.BLOCKED, cd.BLOCKED)),
     ((2, 3, 64, 64, 32, 7, 7, 2, 3), (cd.PLAIN, cd.BLOCKED)),
+    # pointwise layers: among the candidates are the tiles with a shared last block (no fused tail: the plan for them
+    # comes with a second choice) and the walk over all output channels
+    ((8, 256, 56, 56, 64, 1, 1, 1, 0), (cd.PLAIN, cd.PLAIN)),
+    ((8, 64, 56, 56, 96, 1, 1, 1, 0), (cd.PLAIN, cd.PLAIN)),
 ])
 def test_tuned_plan_is_correct_and_remembered(oracle, shape, layouts):
     from oracle import layout_ref as L
