@@ -127,6 +127,55 @@ def test_plan_for_odd_shapes(shape):
     plan.destroy()
 
 
+def _seeded_shapes(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        kind = rng.integers(0, 4)
+        if kind == 0:      # pointwise, channel counts around the special forms' conditions
+            R = S = 1
+            st, pd = 1, 0
+            C = int(rng.choice([64, 63, 65, 128, 256, 24]))
+            K = int(rng.choice([32, 64, 96, 256, 70, 33]))
+        else:
+            R = int(rng.integers(1, 8))
+            S = R if rng.random() < 0.7 else int(rng.integers(1, 8))
+            st, pd = int(rng.integers(1, 4)), int(rng.integers(0, 4))
+            C, K = int(rng.integers(1, 300)), int(rng.integers(1, 300))
+        H, W = int(rng.integers(1, 120)), int(rng.integers(1, 120))
+        if rng.random() < 0.3:
+            H = W = int(rng.choice([7, 13, 14, 27, 28, 56]))
+        if H + 2 * pd < R or W + 2 * pd < S:
+            continue
+        out.append((int(rng.integers(1, 70)), C, H, W, K, R, S, st, pd))
+    return out
+
+
+def test_planner_on_seeded_random_shapes():
+    """Plans of every kind for a few hundred seeded shapes: each is created, describes a grid that covers its
+    output, names a second choice exactly when its variant has no fused tail, and is destroyed."""
+    for shape in _seeded_shapes(300, 77):
+        N, C, H, W, K, R, S, st, pd = shape
+        for li, lo in ((cd.PLAIN, cd.PLAIN), (cd.BLOCKED, cd.BLOCKED), (cd.PLAIN, cd.BLOCKED)):
+            plan = cd.Plan(*shape, in_layout=li, out_layout=lo)
+            info = plan.info()
+            _check_cover(info, exhaustive=False)
+            assert (info["tail_variant"] != "same") == ("_sl" in info["variant"] and info["variant"][1] == "1"), (shape, info["variant"])
+            assert info["model_clocks"] > 0
+            plan.destroy()
+        if R == S or st == 1:
+            plan = cd.Plan.dgrad(*shape)
+            assert plan.info()["workspace_bytes"] == 0 and plan.dgrad_wt_elems() > 0
+            plan.destroy()
+        try:
+            plan = cd.Plan.wgrad(*shape)
+        except cd.ConvDirectError as e:
+            assert e.code == cd.EUNSUPPORTED, shape      # (filter shapes the weight gradient has no variant for)
+        else:
+            assert plan.info()["kind"] == "wgrad"
+            plan.destroy()
+
+
 def test_every_variant_plans_a_matching_shape():
     names = cd.variant_names()
     assert len(names) == len(set(names)) and any(n.startswith("generic") for n in names)
